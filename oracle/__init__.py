@@ -1,0 +1,235 @@
+"""ctypes front-end of the CPU oracle (oracle/st_oracle.c).
+
+TEST INFRASTRUCTURE.  Only tests/, the smoke check and the benchmark's cpu_baseline leg may
+import this package; the product (paper_2003_10735_amd) never does.  All arrays are numpy,
+float64 unless said otherwise, NCHW / OIHW, C-contiguous.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+class Desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("c_in", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
+                ("c1", C.c_int32), ("c2", C.c_int32), ("n_classes", C.c_int32),
+                ("ignore_index", C.c_int32), ("bf16_operands", C.c_int32)]
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build(force=True)
+        _LIB = C.CDLL(path)
+        _LIB.sto_softmax_ce.restype = C.c_double
+        _LIB.sto_loss_and_grad.restype = C.c_double
+        _LIB.sto_num_params.restype = C.c_int64
+        _LIB.sto_miou.restype = C.c_int
+        _LIB.sto_train.restype = C.c_int
+        _LIB.sto_num_threads.restype = C.c_int
+    return _LIB
+
+
+def num_threads() -> int:
+    return int(lib().sto_num_threads())
+
+
+def _d(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double)) if a is not None else None
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(C.POINTER(ty)) if a is not None else None
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def desc(n, c_in, h, w, c1, c2, n_classes, ignore_index=-1, bf16_operands=False) -> Desc:
+    return Desc(n, c_in, h, w, c1, c2, n_classes, ignore_index, 1 if bf16_operands else 0)
+
+
+def desc_of(wl, bf16_operands: bool | None = None) -> Desc:
+    """Descriptor of a workloads.Workload; bf16-operand rounding follows its compute type."""
+    q = (wl.compute == "bf16") if bf16_operands is None else bf16_operands
+    return desc(wl.n, wl.c_in, wl.h, wl.w, wl.c1, wl.c2, wl.n_classes, wl.ignore_index, q)
+
+
+# ------------------------------------------------------------------ single operations
+def conv_fwd(x, W, b=None):
+    x, W = _f64(x), _f64(W)
+    n, ci, h, w = x.shape
+    co, ci2, k, k2 = W.shape
+    assert ci == ci2 and k == k2 and k in (1, 3)
+    b = _f64(b) if b is not None else None
+    y = np.empty((n, co, h, w))
+    lib().sto_conv_fwd(_d(x), _d(W), _d(b), _d(y), n, ci, co, h, w, k)
+    return y
+
+
+def conv_dgrad(dy, W):
+    dy, W = _f64(dy), _f64(W)
+    n, co, h, w = dy.shape
+    co2, ci, k, _ = W.shape
+    assert co == co2
+    dx = np.empty((n, ci, h, w))
+    lib().sto_conv_dgrad(_d(dy), _d(W), _d(dx), n, ci, co, h, w, k)
+    return dx
+
+
+def conv_wgrad(x, dy, k):
+    x, dy = _f64(x), _f64(dy)
+    n, ci, h, w = x.shape
+    co = dy.shape[1]
+    dW = np.empty((co, ci, k, k))
+    db = np.empty(co)
+    lib().sto_conv_wgrad(_d(x), _d(dy), _d(dW), _d(db), n, ci, co, h, w, k)
+    return dW, db
+
+
+def round_bf16(x):
+    y = _f64(x).copy()
+    lib().sto_round_bf16(_d(y), C.c_int64(y.size))
+    return y
+
+
+def upsample8(z):
+    z = _f64(z)
+    n, c, h, w = z.shape
+    Z = np.empty((n, c, 8 * h, 8 * w))
+    lib().sto_upsample8(_d(z), _d(Z), n * c, h, w)
+    return Z
+
+
+def upsample8_f32(z):
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    n, c, h, w = z.shape
+    Z = np.empty((n, c, 8 * h, 8 * w), dtype=np.float32)
+    lib().sto_upsample8_f32(_p(z, C.c_float), _p(Z, C.c_float), n * c, h, w)
+    return Z
+
+
+def upsample8_adjoint(G):
+    G = _f64(G)
+    n, c, H, W = G.shape
+    g = np.empty((n, c, H // 8, W // 8))
+    lib().sto_upsample8_adjoint(_d(G), _d(g), n * c, H // 8, W // 8)
+    return g
+
+
+def argmax_f32(Zf):
+    Zf = np.ascontiguousarray(Zf, dtype=np.float32)
+    n, c, H, W = Zf.shape
+    pred = np.empty((n, H, W), dtype=np.uint8)
+    lib().sto_argmax_f32(_p(Zf, C.c_float), _p(pred, C.c_uint8), n, c, C.c_int64(H * W))
+    return pred
+
+
+def predict_from_logits(z_f32):
+    """pred [n,8h,8w] from float32 low-resolution logits: float32 interpolation, argmax."""
+    return argmax_f32(upsample8_f32(z_f32))
+
+
+def softmax_ce(Z, labels, ignore_index=-1, want_grad=True):
+    Z = _f64(Z)
+    n, c, H, W = Z.shape
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    G = np.empty_like(Z) if want_grad else None
+    nv = C.c_int64(0)
+    loss = lib().sto_softmax_ce(_d(Z), _p(labels, C.c_int32), _d(G), n, c, C.c_int64(H * W),
+                                ignore_index, C.byref(nv))
+    return float(loss), G, int(nv.value)
+
+
+def confusion(pred, labels, n_classes, ignore_index=-1):
+    pred = np.ascontiguousarray(pred, dtype=np.uint8).ravel()
+    labels = np.ascontiguousarray(labels, dtype=np.int32).ravel()
+    conf = np.empty((n_classes, n_classes), dtype=np.int64)
+    lib().sto_confusion(_p(pred, C.c_uint8), _p(labels, C.c_int32), C.c_int64(pred.size),
+                        n_classes, ignore_index, _p(conf, C.c_int64))
+    return conf
+
+
+def miou(conf):
+    conf = np.ascontiguousarray(conf, dtype=np.int64)
+    out = C.c_double(0.0)
+    present = lib().sto_miou(_p(conf, C.c_int64), conf.shape[0], C.byref(out))
+    return float(out.value), int(present)
+
+
+def sgd(theta, grad, vel, lr, mu):
+    theta, grad = _f64(theta).copy(), _f64(grad)
+    vel = _f64(vel).copy() if vel is not None else None
+    lib().sto_sgd(_d(theta), _d(grad), _d(vel), C.c_int64(theta.size), C.c_double(lr),
+                  C.c_double(mu))
+    return theta, vel
+
+
+# ------------------------------------------------------------------ the head
+def num_params(d: Desc) -> int:
+    return int(lib().sto_num_params(C.byref(d)))
+
+
+def head_forward(d: Desc, features, params, want_pred=True):
+    features, params = _f64(features), _f64(params)
+    z = np.empty((d.n, d.n_classes, d.h, d.w))
+    pred = np.empty((d.n, 8 * d.h, 8 * d.w), dtype=np.uint8) if want_pred else None
+    lib().sto_head_forward(C.byref(d), _d(features), _d(params), _d(z), _p(pred, C.c_uint8))
+    return z, pred
+
+
+def loss_and_grad(d: Desc, features, labels, params, want_grad=True, want_metric=True):
+    features, params = _f64(features), _f64(params)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    grad = np.empty_like(params) if want_grad else None
+    Cn = d.n_classes
+    pred = np.empty((d.n, 8 * d.h, 8 * d.w), dtype=np.uint8) if want_metric else None
+    conf = np.empty((d.n, Cn, Cn), dtype=np.int64) if want_metric else None
+    mi = np.empty(d.n) if want_metric else None
+    loss = lib().sto_loss_and_grad(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params),
+                                   _d(grad), _p(pred, C.c_uint8), _p(conf, C.c_int64), _d(mi))
+    return float(loss), grad, pred, conf, mi
+
+
+def partial_distill(d: Desc, features, labels, params, steps, lr, momentum=0.0, velocity=None):
+    """k fixed steps.  Returns dict(params, velocity, losses[k+1], mious[k+1,n], conf[n,C,C],
+    pred[n,8h,8w])."""
+    features = _f64(features)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    params = _f64(params).copy()
+    vel = (_f64(velocity).copy() if velocity is not None else np.zeros_like(params))
+    losses = np.empty(steps + 1)
+    mious = np.empty((steps + 1, d.n))
+    conf = np.empty((d.n, d.n_classes, d.n_classes), dtype=np.int64)
+    pred = np.empty((d.n, 8 * d.h, 8 * d.w), dtype=np.uint8)
+    lib().sto_partial_distill(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params),
+                              _d(vel), steps, C.c_double(lr), C.c_double(momentum), _d(losses),
+                              _d(mious), _p(conf, C.c_int64), _p(pred, C.c_uint8))
+    return dict(params=params, velocity=vel, losses=losses, mious=mious, conf=conf, pred=pred)
+
+
+def train(d: Desc, features, labels, params, max_updates, lr, threshold, momentum=0.0,
+          velocity=None, strict_break=True):
+    """Student training with the skip / best-tracking / early-exit rules.
+    Returns dict(params=best, best_metric, updates, metrics[0..updates])."""
+    features = _f64(features)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    params = _f64(params).copy()
+    vel = (_f64(velocity).copy() if velocity is not None else np.zeros_like(params))
+    bm = C.c_double(0.0)
+    metrics = np.full(max_updates + 1, np.nan)
+    upd = lib().sto_train(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params), _d(vel),
+                          max_updates, C.c_double(lr), C.c_double(momentum),
+                          C.c_double(threshold), 1 if strict_break else 0, C.byref(bm),
+                          _d(metrics))
+    return dict(params=params, velocity=vel, best_metric=float(bm.value), updates=int(upd),
+                metrics=metrics[:upd + 1])
