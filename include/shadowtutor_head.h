@@ -1,0 +1,187 @@
+/*
+ * shadowtutor_head.h -- C ABI of the MI355X (gfx950) partial-distillation library.
+ *
+ * The library runs, on one GPU, the server-side student-training step of ShadowTutor
+ * restricted to the trainable tail ("head") of the student segmentation network:
+ *
+ *   Forward          head convolutions + x8 bilinear up-sampling to the frame's resolution
+ *                    (Algorithm 1, "Forward"; Section 2.2: output has the input's spatial size)
+ *   ComputeMetric    mean IoU of the predicted class map against the teacher's labels (Eq. 1)
+ *   ComputeLoss      mean per-pixel cross-entropy against the teacher's hard labels
+ *                    (Algorithm 1, "ComputeLoss"; Section 5.2, without the x5 object weighting)
+ *   PartialBackward  chain rule from the loss down to the first trainable layer and no
+ *                    further: the frozen front part's output (the feature map) is an input
+ *                    and never receives a gradient (Section 4.2)
+ *   OptimStep        gradient descent, optionally with momentum (Algorithm 1, "OptimStep")
+ *
+ * The head is  conv3x3(c_in->c1)+bias+ReLU,  conv3x3(c1->c2)+bias+ReLU,  conv1x1(c2->n_classes)
+ * +bias,  x8 bilinear up-sampling (pixel centres at half-integers, edge replication).
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless it says HOST.  The
+ *     library neither frees nor keeps any of them after the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     Calls return without synchronising, except st_partial_distill with a positive
+ *     `threshold`, whose loop exits are decided on the host (one small device-to-host read per
+ *     iteration) and which has finished when it returns.
+ *   - Dense row-major layouts: features [n, c_in, h, w]; labels / pred [n, 8h, 8w];
+ *     low-resolution logits [n, n_classes, h, w].
+ *   - head_params is one flat float32 vector: W1 (OIHW) | b1 | W2 (OIHW) | b2 | W3 (OI) | b3.
+ *     It is what the server sends back to the client after training ("UpdatedPart").
+ *   - Every function returns ST_OK (0) or a negative st_status; nothing throws or aborts.
+ *     Arguments are validated on the host before any GPU work is enqueued.
+ *   - `workspace` is caller-owned device scratch of at least st_workspace_bytes(desc) bytes,
+ *     256-byte aligned; its contents on entry do not matter and two calls may not share one
+ *     workspace concurrently.
+ */
+#ifndef SHADOWTUTOR_HEAD_H
+#define SHADOWTUTOR_HEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum st_status {
+    ST_OK = 0,
+    ST_ERR_NULL = -1,      /* a required pointer is NULL */
+    ST_ERR_SHAPE = -2,     /* non-positive or unsupported dimension, upscale != 8 */
+    ST_ERR_ARG = -3,       /* steps < 0, non-finite lr / momentum, bad enum value */
+    ST_ERR_WORKSPACE = -4, /* workspace NULL or misaligned */
+    ST_ERR_HIP = -5,       /* a HIP runtime call failed (st_last_hip_error() tells which) */
+    ST_ERR_NO_DEVICE = -6  /* no usable GPU in this process */
+} st_status;
+
+enum { ST_F32 = 0, ST_BF16 = 1 };                 /* st_head_desc.feat_dtype */
+enum { ST_NCHW = 0 };                             /* st_head_desc.feat_layout */
+enum { ST_COMPUTE_F32 = 0, ST_COMPUTE_BF16 = 1 }; /* st_head_desc.compute */
+
+/* Shape of one training problem.
+ * compute = ST_COMPUTE_F32: every convolution in float32 (reference-precision path).
+ * compute = ST_COMPUTE_BF16: convolution operands (features, weights, activations and the
+ *   back-propagated gradients) are rounded to bfloat16, products accumulate in float32 on the
+ *   matrix cores; master weights, optimiser arithmetic, logits, loss and weight gradients stay
+ *   float32.  Requires c_in, c1, c2 to be multiples of 32 and n_classes <= 32.
+ * Limits: upscale == 8; 2 <= n_classes <= 64; labels outside [0, n_classes) are skipped like
+ * ignore_index (they count neither in the loss nor in the metric). */
+typedef struct st_head_desc {
+    int32_t n, c_in, h, w;     /* feature map [n, c_in, h, w]                         */
+    int32_t c1, c2, n_classes; /* conv3x3 c_in->c1, conv3x3 c1->c2, conv1x1 c2->classes */
+    int32_t upscale;           /* 8                                                   */
+    int32_t feat_dtype;        /* ST_F32 | ST_BF16: element type of `features`        */
+    int32_t feat_layout;       /* ST_NCHW                                             */
+    int32_t compute;           /* ST_COMPUTE_F32 | ST_COMPUTE_BF16                    */
+    int32_t ignore_index;      /* label value to skip; -1 = none                      */
+} st_head_desc;
+
+/* Options of st_partial_distill (NULL = plain gradient descent, fixed step count). */
+typedef struct st_distill_opts {
+    float momentum;       /* mu in v <- mu v + g, theta <- theta - lr v; 0 = plain descent   */
+    float* velocity;      /* in/out, st_num_params floats, same order as head_params;
+                             required when momentum != 0 (zero it before the first key frame) */
+    double threshold;     /* THRESHOLD of Algorithm 1 (compared with the float64 metric);
+                             <= 0 runs exactly `steps` updates                               */
+    int32_t strict_break; /* 1: leave the loop when metric > threshold (as printed);
+                             0: when metric >= threshold                                     */
+    int32_t return_best;  /* with threshold > 0 -- 1: head_params receives best_student of
+                             Algorithm 1 (strictly-better rule); 0: the last parameters      */
+} st_distill_opts;
+
+/* Outputs of st_partial_distill.  The struct lives in HOST memory; the arrays are DEVICE
+ * pointers and each may be NULL.  Entry i of losses / mious describes the parameters before
+ * update i+1, entry `steps_taken` the returned ones (k updates = k+1 forwards). */
+typedef struct st_distill_result {
+    float* losses;       /* [steps + 1]                                     */
+    double* mious;       /* [steps + 1, n]  per-frame mean IoU              */
+    int64_t* confusion;  /* [n, C, C] of the last forward; row = label, column = prediction */
+    uint8_t* pred;       /* [n, 8h, 8w] class map of the last forward       */
+    int32_t steps_taken; /* HOST, written by the call (== steps unless threshold > 0) */
+    double best_metric;  /* HOST, written only when threshold > 0           */
+} st_distill_result;
+
+/* Number of float32 values in head_params:
+ * c1*c_in*9 + c1 + c2*c1*9 + c2 + n_classes*c2 + n_classes.  0 if desc is NULL or invalid. */
+size_t st_num_params(const st_head_desc* desc);
+
+/* Bytes of device scratch the calls below need for this shape.  0 if desc is invalid. */
+size_t st_workspace_bytes(const st_head_desc* desc);
+
+/* Forward (Algorithm 1, "Forward"): features -> low-resolution logits and/or the predicted
+ * class map (lowest index among the largest up-sampled logits).
+ *   features       [n, c_in, h, w], float32 or bfloat16 as desc says; read only
+ *   head_params    st_num_params floats; read only
+ *   logits_lowres  [n, n_classes, h, w] float32, or NULL
+ *   pred           [n, 8h, 8w] uint8, or NULL                                              */
+int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
+                    float* logits_lowres, uint8_t* pred, void* workspace, void* stream);
+
+/* Student training on one key frame (Algorithm 1 restricted to the head, Section 4.2):
+ * `steps` times { loss, partial backward, optimiser step }, with a forward + metric before the
+ * first and after every update.  features are never written and get no gradient.
+ *   teacher_labels [n, 8h, 8w] int32 hard labels (the teacher's segmentation result)
+ *   head_params    in/out, updated in place
+ *   steps          >= 0 (0: forward + metric only; MAX_UPDATES when threshold > 0)
+ *   lr             learning rate, finite
+ * The loss is the mean over all valid pixels of all n frames; the metric is per frame (the
+ * loop exits of Algorithm 1 use the mean over frames). */
+int st_partial_distill(const st_head_desc* desc, const void* features,
+                       const int32_t* teacher_labels, float* head_params, int32_t steps,
+                       float lr, const st_distill_opts* opts, st_distill_result* out,
+                       void* workspace, void* stream);
+
+/* Mean IoU (Eq. 1) of a class map against labels: IoU_c = |pred_c & label_c| / |pred_c | label_c|
+ * averaged over the classes present in the labels (0 when none is).
+ *   pred [n_pixels] uint8, labels [n_pixels] int32
+ *   confusion [C, C] int64 out (row = label, column = prediction), overwritten; may be NULL
+ *             only if workspace is given (C*C*8 bytes are then taken from it)
+ *   miou  one double out (device)                                                          */
+int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_t n_classes,
+            int32_t ignore_index, int64_t* confusion, double* miou, void* stream);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* st_strerror(int status);
+
+/* The hipError_t (as int) of the most recent ST_ERR_HIP on this thread, else 0. */
+int st_last_hip_error(void);
+
+/* Library version, "major.minor". */
+const char* st_version(void);
+
+/* ---- introspection for tests and tools (no part of the training path) -------------------- */
+
+/* Byte offsets of the library's internal buffers inside `workspace`, so that a test can look
+ * at intermediate tensors after a call.  Offsets are 0 for buffers this shape does not use. */
+typedef struct st_workspace_layout {
+    size_t feat;      /* features, position-major [n, h+2, w+2, c_in] with a zero border    */
+    size_t a1, a2;    /* activations after ReLU, same layout, c1 / c2 channels              */
+    size_t da1, da2;  /* back-propagated gradients (after the ReLU mask), same layout       */
+    size_t z;         /* low-resolution logits [n, C, h, w] float32                         */
+    size_t g;         /* d loss / d z        [n, C, h, w] float32                           */
+    size_t theta;     /* master parameters, internal order (3x3 weights as [o][kh][kw][i])  */
+    size_t grad;      /* parameter gradient, internal order                                 */
+    size_t elem_size; /* bytes per activation element: 4 (float32 path) or 2 (bfloat16)     */
+    size_t total;     /* == st_workspace_bytes                                              */
+} st_workspace_layout;
+
+int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out);
+
+/* Per-kernel timing: when enabled, every kernel launch of the calls above is bracketed by a
+ * pair of HIP events on the caller's stream.  st_profile_read synchronises those events and
+ * returns, for each kernel name, the launch count and the summed duration since the last
+ * st_profile_reset.  Off by default; switching it on adds event overhead to every launch. */
+typedef struct st_kernel_stat {
+    char name[48];
+    int64_t launches;
+    double total_ms;
+} st_kernel_stat;
+
+void st_profile_enable(int on);
+void st_profile_reset(void);
+int st_profile_read(st_kernel_stat* stats, int max_stats); /* returns the number written, <0 on error */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHADOWTUTOR_HEAD_H */

@@ -1,0 +1,229 @@
+"""Thin Python binding of libshadowtutor_head.so (hand-written HIP for MI355X / gfx950).
+
+Argument marshalling only: torch tensors supply device memory and the stream; every step of
+the partial-distillation path runs inside the library's kernels.  There is no CPU fallback:
+if the shared library is missing, importing the entry points raises.
+
+Function names mirror the C ABI declared in include/shadowtutor_head.h.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshadowtutor_head.so")
+
+ST_OK = 0
+ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_DEVICE = -1, -2, -3, -4, -5, -6
+ST_F32, ST_BF16 = 0, 1
+ST_NCHW = 0
+ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
+
+EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
+           "st_miou", "st_strerror", "st_last_hip_error", "st_version",
+           "st_get_workspace_layout", "st_profile_enable", "st_profile_reset", "st_profile_read"]
+
+
+class StHeadDesc(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n", "c_in", "h", "w", "c1", "c2", "n_classes", "upscale",
+                                          "feat_dtype", "feat_layout", "compute", "ignore_index")]
+
+
+class StDistillOpts(C.Structure):
+    _fields_ = [("momentum", C.c_float), ("velocity", C.c_void_p), ("threshold", C.c_double),
+                ("strict_break", C.c_int32), ("return_best", C.c_int32)]
+
+
+class StDistillResult(C.Structure):
+    _fields_ = [("losses", C.c_void_p), ("mious", C.c_void_p), ("confusion", C.c_void_p),
+                ("pred", C.c_void_p), ("steps_taken", C.c_int32), ("best_metric", C.c_double)]
+
+
+class StWorkspaceLayout(C.Structure):
+    _fields_ = [(k, C.c_size_t) for k in ("feat", "a1", "a2", "da1", "da2", "z", "g", "theta",
+                                           "grad", "elem_size", "total")]
+
+
+class StKernelStat(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double)]
+
+
+class StError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().st_strerror(status).decode()
+        extra = f" (hipError {lib().st_last_hip_error()})" if status == ST_ERR_HIP else ""
+        super().__init__(f"{where}: {msg}{extra} [status {status}]")
+
+
+_LIB = None
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built (no fallback exists)."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2003_10735_amd.build` "
+                "(hipcc, gfx950).  There is no CPU fallback.")
+        L = C.CDLL(LIB_PATH)
+        L.st_num_params.restype = C.c_size_t
+        L.st_num_params.argtypes = [C.POINTER(StHeadDesc)]
+        L.st_workspace_bytes.restype = C.c_size_t
+        L.st_workspace_bytes.argtypes = [C.POINTER(StHeadDesc)]
+        L.st_head_forward.restype = C.c_int
+        L.st_head_forward.argtypes = [C.POINTER(StHeadDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.st_partial_distill.restype = C.c_int
+        L.st_partial_distill.argtypes = [C.POINTER(StHeadDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_int32, C.c_float, C.POINTER(StDistillOpts),
+                                         C.POINTER(StDistillResult), C.c_void_p, C.c_void_p]
+        L.st_miou.restype = C.c_int
+        L.st_miou.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
+                              C.c_void_p, C.c_void_p]
+        L.st_strerror.restype = C.c_char_p
+        L.st_strerror.argtypes = [C.c_int]
+        L.st_last_hip_error.restype = C.c_int
+        L.st_version.restype = C.c_char_p
+        L.st_get_workspace_layout.restype = C.c_int
+        L.st_get_workspace_layout.argtypes = [C.POINTER(StHeadDesc), C.POINTER(StWorkspaceLayout)]
+        L.st_profile_enable.argtypes = [C.c_int]
+        L.st_profile_read.restype = C.c_int
+        L.st_profile_read.argtypes = [C.POINTER(StKernelStat), C.c_int]
+        _LIB = L
+    return _LIB
+
+
+@dataclass
+class HeadDesc:
+    n: int
+    c_in: int
+    h: int
+    w: int
+    c1: int
+    c2: int
+    n_classes: int
+    feat_dtype: int = ST_BF16
+    compute: int = ST_COMPUTE_BF16
+    ignore_index: int = -1
+    upscale: int = 8
+    feat_layout: int = ST_NCHW
+
+    def c(self) -> StHeadDesc:
+        return StHeadDesc(self.n, self.c_in, self.h, self.w, self.c1, self.c2, self.n_classes,
+                          self.upscale, self.feat_dtype, self.feat_layout, self.compute,
+                          self.ignore_index)
+
+    @staticmethod
+    def of(wl) -> "HeadDesc":
+        """Descriptor of a workloads.Workload."""
+        return HeadDesc(wl.n, wl.c_in, wl.h, wl.w, wl.c1, wl.c2, wl.n_classes,
+                        ST_BF16 if wl.feat_dtype == "bf16" else ST_F32,
+                        ST_COMPUTE_BF16 if wl.compute == "bf16" else ST_COMPUTE_F32,
+                        wl.ignore_index)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != ST_OK:
+        raise StError(status, where)
+
+
+def st_num_params(desc: HeadDesc) -> int:
+    d = desc.c()
+    return int(lib().st_num_params(C.byref(d)))
+
+
+def st_workspace_bytes(desc: HeadDesc) -> int:
+    d = desc.c()
+    return int(lib().st_workspace_bytes(C.byref(d)))
+
+
+def st_get_workspace_layout(desc: HeadDesc) -> dict:
+    d, out = desc.c(), StWorkspaceLayout()
+    _check(lib().st_get_workspace_layout(C.byref(d), C.byref(out)), "st_get_workspace_layout")
+    return {k: int(getattr(out, k)) for k, _ in StWorkspaceLayout._fields_}
+
+
+def new_workspace(desc: HeadDesc, device="cuda"):
+    """A device buffer of st_workspace_bytes(desc) bytes (torch allocations are 256-byte aligned)."""
+    import torch
+    nbytes = st_workspace_bytes(desc)
+    if nbytes == 0:
+        raise StError(ST_ERR_SHAPE, "st_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def st_head_forward(desc: HeadDesc, features, head_params, logits_lowres=None, pred=None,
+                    workspace=None, stream=None):
+    """features [n,c_in,h,w] (float32 or bfloat16 cuda tensor), head_params float32 [num_params].
+    Fills logits_lowres [n,C,h,w] float32 and/or pred [n,8h,8w] uint8 when given."""
+    d = desc.c()
+    ws = workspace if workspace is not None else new_workspace(desc, features.device)
+    _check(lib().st_head_forward(C.byref(d), _ptr(features), _ptr(head_params), _ptr(logits_lowres),
+                                 _ptr(pred), _ptr(ws), _stream(stream)), "st_head_forward")
+    return logits_lowres, pred
+
+
+def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, steps: int, lr: float,
+                       momentum: float = 0.0, velocity=None, threshold: float = 0.0,
+                       strict_break: bool = True, return_best: bool = False, losses=None,
+                       mious=None, confusion=None, pred=None, workspace=None, stream=None):
+    """Runs the library's st_partial_distill; head_params (and velocity) are updated in place.
+    Returns (steps_taken, best_metric or None)."""
+    d = desc.c()
+    ws = workspace if workspace is not None else new_workspace(desc, features.device)
+    use_opts = momentum != 0.0 or threshold > 0.0 or velocity is not None
+    opts = StDistillOpts(momentum, _ptr(velocity), threshold, 1 if strict_break else 0,
+                         1 if return_best else 0)
+    res = StDistillResult(_ptr(losses), _ptr(mious), _ptr(confusion), _ptr(pred), 0, 0.0)
+    st = lib().st_partial_distill(C.byref(d), _ptr(features), _ptr(teacher_labels), _ptr(head_params),
+                                  steps, lr, C.byref(opts) if use_opts else None, C.byref(res),
+                                  _ptr(ws), _stream(stream))
+    _check(st, "st_partial_distill")
+    return int(res.steps_taken), (float(res.best_metric) if threshold > 0.0 else None)
+
+
+def st_miou(pred, labels, n_classes: int, ignore_index: int = -1, confusion=None, miou=None,
+            stream=None):
+    """pred uint8 [..], labels int32 [..] cuda tensors.  Returns (confusion int64 [C,C], miou float64 [1])."""
+    import torch
+    if confusion is None:
+        confusion = torch.empty((n_classes, n_classes), dtype=torch.int64, device=pred.device)
+    if miou is None:
+        miou = torch.empty(1, dtype=torch.float64, device=pred.device)
+    _check(lib().st_miou(_ptr(pred), _ptr(labels), pred.numel(), n_classes, ignore_index,
+                         _ptr(confusion), _ptr(miou), _stream(stream)), "st_miou")
+    return confusion, miou
+
+
+def st_profile_enable(on: bool):
+    lib().st_profile_enable(1 if on else 0)
+
+
+def st_profile_reset():
+    lib().st_profile_reset()
+
+
+def st_profile_read(max_stats: int = 64) -> dict:
+    arr = (StKernelStat * max_stats)()
+    n = lib().st_profile_read(arr, max_stats)
+    if n < 0:
+        raise StError(n, "st_profile_read")
+    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms)) for i in range(n)}
+
+
+def st_version() -> str:
+    return lib().st_version().decode()

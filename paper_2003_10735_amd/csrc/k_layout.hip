@@ -1,0 +1,121 @@
+// Layout kernels: zero fill, feature packing (caller's NCHW -> padded position-major), and the
+// permutation between the caller's parameter order (OIHW) and the internal one ([o][kh][kw][i]).
+#include "st_kernels.hpp"
+
+namespace st {
+
+__global__ void __launch_bounds__(256) k_zero16(uint4* p, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (; i < n16; i += stride) p[i] = z;
+}
+
+void zero_bytes(Ctx& c, void* p, size_t bytes)
+{
+    // all workspace regions are 256-byte aligned and padded to 256 bytes
+    const size_t n16 = (bytes + 15) / 16;
+    if (n16 == 0) return;
+    int blocks = (int)((n16 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    ST_LAUNCH(c, "zero_fill", k_zero16, dim3(blocks), dim3(256), 0, (uint4*)p, n16);
+}
+
+// features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
+// featT != nullptr, a channel-major padded copy [n, c_in, Hp, WpT] for the weight-gradient.
+// One block transposes a 32-channel x 32-column tile of one row through LDS so that both the
+// read (along x) and the write (along c) are contiguous.
+template <class Tin, class E>
+__global__ void __launch_bounds__(256)
+k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ outT, Geo g, int WpT)
+{
+    __shared__ float tile[32][33];
+    const int x0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int img = blockIdx.z / g.h, y = blockIdx.z % g.h;
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+    for (int k = ty; k < 32; k += 8) {
+        const int c = c0 + k, x = x0 + tx;
+        float v = 0.f;
+        if (c < g.c_in && x < g.w) v = to_f32(f[(((size_t)img * g.c_in + c) * g.h + y) * g.w + x]);
+        tile[k][tx] = v;
+        if (outT && c < g.c_in && x < g.w)
+            outT[(((size_t)img * g.c_in + c) * g.Hp + y + 1) * WpT + x + 1] = from_f32<E>(v);
+    }
+    __syncthreads();
+    for (int k = ty; k < 32; k += 8) {
+        const int x = x0 + k, c = c0 + tx;
+        if (c < g.c_in && x < g.w)
+            out[(((size_t)img * g.Hp + y + 1) * g.Wp + x + 1) * g.c_in + c] = from_f32<E>(tile[tx][k]);
+    }
+}
+
+__global__ void __launch_bounds__(256) k_zero8(unsigned long long* p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0ull;
+}
+
+void zero_u64(Ctx& c, unsigned long long* p, size_t n)
+{
+    if (n == 0) return;
+    int blocks = (int)((n + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    ST_LAUNCH(c, "zero_fill", k_zero8, dim3(blocks), dim3(256), 0, p, n);
+}
+
+void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, char* ws)
+{
+    const Geo& g = p.g;
+    dim3 grid(cdiv(g.w, 32), cdiv(g.c_in, 32), g.n * g.h);
+    if (p.bf16) {
+        bf16* out = (bf16*)(ws + p.feat);
+        bf16* outT = p.featT ? (bf16*)(ws + p.featT) : nullptr;
+        if (feat_dtype == ST_BF16)
+            ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, bf16>), grid, dim3(256), 0,
+                      (const bf16*)features, out, outT, g, p.WpT);
+        else
+            ST_LAUNCH(c, "pack_features", (k_pack_features<float, bf16>), grid, dim3(256), 0,
+                      (const float*)features, out, outT, g, p.WpT);
+    } else {
+        float* out = (float*)(ws + p.feat);
+        if (feat_dtype == ST_BF16)
+            ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, float>), grid, dim3(256), 0,
+                      (const bf16*)features, out, (float*)nullptr, g, 0);
+        else
+            ST_LAUNCH(c, "pack_features", (k_pack_features<float, float>), grid, dim3(256), 0,
+                      (const float*)features, out, (float*)nullptr, g, 0);
+    }
+}
+
+// Parameter permutation.  dir = 0: external (OIHW) -> internal; dir = 1: internal -> external.
+// Thread j walks the internal index; inside a 3x3 weight block
+//   internal (o*9 + tap)*ci + i   <->   external (o*ci + i)*9 + tap.
+__global__ void __launch_bounds__(256)
+k_permute_params(const float* __restrict__ src, float* __restrict__ dst, ParamOffsets po,
+                 int ci1, int ci2, int dir)
+{
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= po.total) return;
+    size_t e = j;
+    if (j < po.b1) {
+        const size_t r = j - po.W1;
+        const size_t i = r % ci1, tap = (r / ci1) % 9, o = r / ((size_t)ci1 * 9);
+        e = po.W1 + (o * ci1 + i) * 9 + tap;
+    } else if (j >= po.W2 && j < po.b2) {
+        const size_t r = j - po.W2;
+        const size_t i = r % ci2, tap = (r / ci2) % 9, o = r / ((size_t)ci2 * 9);
+        e = po.W2 + (o * ci2 + i) * 9 + tap;
+    }
+    if (dir == 0) dst[j] = src[e];
+    else dst[e] = src[j];
+}
+
+void permute_params(Ctx& c, const Plan& p, const float* src, float* dst, int dir)
+{
+    ST_LAUNCH(c, dir == 0 ? "params_to_internal" : "params_from_internal", k_permute_params,
+              dim3(cdiv(p.po.total, 256)), dim3(256), 0, src, dst, p.po, p.g.c_in, p.g.c1, dir);
+}
+
+}  // namespace st

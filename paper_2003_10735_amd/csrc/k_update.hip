@@ -1,0 +1,206 @@
+// Optimiser step over the flat parameter buffer (fused with the sum of the partial weight
+// gradients and the bfloat16 operand copies of the new weights), the per-step bookkeeping
+// kernel (loss, per-frame mean IoU) and the stand-alone confusion-matrix / mean-IoU kernels.
+#include "st_kernels.hpp"
+
+namespace st {
+
+// theta <- theta - lr * v,  v <- mu * v + g  (mu == 0: v is not touched),  g = sum of the
+// `splits` partial gradients in ascending order.  Also refreshes the bfloat16 copies:
+//   wq[j]  : same (internal) order as theta, for the forward convolutions
+//   wq2t   : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
+struct UpdateArgs {
+    float* theta; float* vel; const float* grad; size_t grad_stride; int splits;
+    bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
+    ParamOffsets po; int c1, c2;
+    float lr, mu;
+    int do_step;   // 0: only refresh the bfloat16 copies
+};
+
+__global__ void __launch_bounds__(256) k_update(UpdateArgs a)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.po.total) return;
+    float w = a.theta[j];
+    if (a.do_step) {
+        float g = a.grad[j];
+        for (int s = 1; s < a.splits; ++s) g += a.grad[(size_t)s * a.grad_stride + j];
+        if (a.mu != 0.f) {
+            const float v = __builtin_fmaf(a.mu, a.vel[j], g);
+            a.vel[j] = v;
+            g = v;
+        }
+        w = __builtin_fmaf(-a.lr, g, w);
+        a.theta[j] = w;
+    }
+    if (a.wq1) {
+        const bf16 q = (bf16)w;
+        if (j < a.po.b1) a.wq1[j - a.po.W1] = q;
+        else if (j >= a.po.W2 && j < a.po.b2) {
+            const size_t r = j - a.po.W2;
+            a.wq2[r] = q;
+            if (a.wq2t) {
+                const size_t i = r % a.c1, tap = (r / a.c1) % 9, o = r / ((size_t)a.c1 * 9);
+                a.wq2t[(i * 9 + (8 - tap)) * a.c2 + o] = q;
+            }
+        } else if (j >= a.po.W3 && j < a.po.b3) a.wq3[j - a.po.W3] = q;
+    }
+}
+
+void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step)
+{
+    UpdateArgs a;
+    a.theta = (float*)(ws + p.theta);
+    a.vel = (float*)(ws + p.vel);
+    a.grad = (const float*)(ws + p.grad);
+    a.grad_stride = p.po.total;
+    a.splits = 1;
+    a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
+    a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
+    a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
+    a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
+    a.po = p.po; a.c1 = p.g.c1; a.c2 = p.g.c2;
+    a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;
+    if (!do_step && !p.bf16) return;
+    ST_LAUNCH(c, do_step ? "sgd_update" : "weights_to_bf16", k_update, dim3(cdiv(p.po.total, 256)), dim3(256),
+              0, a);
+}
+
+// ------------------------------------------------------------------ mean IoU from counts
+// IoU_c = conf[c][c] / (row_c + col_c - conf[c][c]) for classes with row_c > 0, summed in
+// ascending c in float64, divided by their number; 0 when no class is present.
+__device__ double miou_of(const unsigned long long* conf, int C)
+{
+    double sum = 0.0;
+    int present = 0;
+    for (int c = 0; c < C; ++c) {
+        unsigned long long row = 0, col = 0;
+        for (int k = 0; k < C; ++k) { row += conf[c * C + k]; col += conf[k * C + c]; }
+        if (row == 0) continue;
+        const unsigned long long inter = conf[c * C + c];
+        sum += (double)inter / (double)(row + col - inter);
+        ++present;
+    }
+    return present ? sum / present : 0.0;
+}
+
+// One block closes a forward pass: sums the tile losses in order (float64), divides by the
+// number of valid pixels, computes the per-frame mean IoU, copies the counts out when asked
+// and clears them for the next pass.
+__global__ void __launch_bounds__(256)
+k_finish_pass(const float* __restrict__ loss_part, int n_part, const unsigned long long* __restrict__ n_valid,
+              unsigned long long* __restrict__ conf, int n, int C, float* loss_out, double* miou_out,
+              long long* conf_out, double* metric_mean_out)
+{
+    __shared__ double part[256];
+    __shared__ double miou_s[64];
+    double acc = 0.0;
+    // contiguous chunks per thread, then a fixed tree: independent of anything but n_part
+    const int per = (n_part + 255) / 256;
+    for (int i = threadIdx.x * per; i < min(n_part, (threadIdx.x + 1) * per); ++i) acc += (double)loss_part[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && loss_out) {
+        const unsigned long long nv = *n_valid;
+        *loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
+    }
+    for (int f = threadIdx.x; f < n; f += 256) {
+        const double m = miou_of(conf + (size_t)f * C * C, C);
+        if (miou_out) miou_out[f] = m;
+        if (f < 64) miou_s[f] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && metric_mean_out) {
+        double s = 0.0;
+        for (int f = 0; f < n; ++f) s += (f < 64) ? miou_s[f] : miou_of(conf + (size_t)f * C * C, C);
+        *metric_mean_out = s / n;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n * C * C; i += 256) {
+        if (conf_out) conf_out[i] = (long long)conf[i];
+        conf[i] = 0ull;
+    }
+}
+
+void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                 double* metric_mean_out)
+{
+    ST_LAUNCH(c, "finish_pass", k_finish_pass, dim3(1), dim3(256), 0, (const float*)(ws + p.loss_part),
+              loss_blocks(p.g), (const unsigned long long*)(ws + p.counters),
+              (unsigned long long*)(ws + p.conf), p.g.n, p.g.C, loss_out, miou_out, conf_out, metric_mean_out);
+}
+
+// ------------------------------------------------------------------ stand-alone metric
+// Confusion counts of a class map against labels.  Each block keeps its own C x C table in
+// LDS.  Label maps are piecewise constant, so most wavefronts hold a single (label, prediction)
+// pair: the wavefront first agrees on one bin by ballot and a single lane adds the population
+// count; the few mixed wavefronts repeat that for each distinct bin.  Integer counts, so the
+// order of additions does not matter.
+template <bool LDS_TABLE>
+__global__ void __launch_bounds__(256)
+k_confusion(const uint8_t* __restrict__ pred, const int32_t* __restrict__ labels, long long P, int C,
+            int ignore, unsigned long long* __restrict__ conf)
+{
+    extern __shared__ unsigned int table[];
+    if (LDS_TABLE) {
+        for (int i = threadIdx.x; i < C * C; i += 256) table[i] = 0;
+        __syncthreads();
+    }
+    const long long stride = (long long)gridDim.x * 256;
+    const long long n_iter = (P + stride - 1) / stride;
+    for (long long it = 0; it < n_iter; ++it) {
+        const long long i = it * stride + (long long)blockIdx.x * 256 + threadIdx.x;
+        int bin = -1;
+        if (i < P) {
+            const int y = labels[i];
+            const int q = pred[i];
+            if (y != ignore && y >= 0 && y < C && q < C) bin = y * C + q;
+        }
+        // wavefront-level aggregation
+        unsigned long long todo = __ballot(bin >= 0);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int lbin = __shfl(bin, leader, 64);
+            const unsigned long long same = __ballot(bin == lbin);
+            if ((int)(threadIdx.x & 63) == leader) {
+                const unsigned int cnt = (unsigned int)__popcll(same);
+                if (LDS_TABLE) atomicAdd(&table[lbin], cnt);
+                else atomicAdd(&conf[lbin], (unsigned long long)cnt);
+            }
+            todo &= ~same;
+        }
+    }
+    if (LDS_TABLE) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < C * C; i += 256)
+            if (table[i]) atomicAdd(&conf[i], (unsigned long long)table[i]);
+    }
+}
+
+__global__ void k_miou_single(const unsigned long long* conf, int C, double* out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = miou_of(conf, C);
+}
+
+void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
+                        long long* conf, double* miou)
+{
+    zero_u64(c, (unsigned long long*)conf, (size_t)C * C);
+    int blocks = cdiv(P, 256 * 16);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    const size_t lds = (size_t)C * C * 4;
+    if (lds <= 64 * 1024)
+        ST_LAUNCH(c, "confusion", (k_confusion<true>), dim3(blocks), dim3(256), lds, pred, labels, P, C, ignore,
+                  (unsigned long long*)conf);
+    else
+        ST_LAUNCH(c, "confusion", (k_confusion<false>), dim3(blocks), dim3(256), 0, pred, labels, P, C, ignore,
+                  (unsigned long long*)conf);
+    ST_LAUNCH(c, "miou", k_miou_single, dim3(1), dim3(64), 0, (const unsigned long long*)conf, C, miou);
+}
+
+}  // namespace st

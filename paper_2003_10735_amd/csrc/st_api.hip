@@ -1,0 +1,362 @@
+// C ABI of the partial-distillation library: argument validation, workspace planning and the
+// order in which the kernels of one call are enqueued.  No kernel lives here.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "st_kernels.hpp"
+
+namespace st {
+
+// ------------------------------------------------------------------ errors
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+#define ST_HIP(ctx, call)                                                                   \
+    do {                                                                                    \
+        if ((ctx).status == ST_OK) {                                                        \
+            hipError_t e_ = (call);                                                         \
+            if (e_ != hipSuccess) { st::set_hip_error(e_); (ctx).status = ST_ERR_HIP; }     \
+        }                                                                                   \
+    } while (0)
+
+// ------------------------------------------------------------------ event profile
+struct ProfRec { const char* name; hipEvent_t start, stop; };
+static std::mutex g_prof_mutex;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+static std::vector<hipEvent_t> g_event_pool;
+static thread_local const char* g_prof_name = nullptr;
+static thread_local hipEvent_t g_prof_start = nullptr;
+
+static hipEvent_t get_event()
+{
+    if (!g_event_pool.empty()) { hipEvent_t e = g_event_pool.back(); g_event_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(Ctx& c, const char* name)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    g_prof_name = name;
+    g_prof_start = get_event();
+    if (g_prof_start) (void)hipEventRecord(g_prof_start, c.stream);
+}
+
+void prof_end(Ctx& c)
+{
+    if (!g_prof_on || !g_prof_start) return;
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    hipEvent_t stop = get_event();
+    if (stop) {
+        (void)hipEventRecord(stop, c.stream);
+        g_prof.push_back(ProfRec{g_prof_name, g_prof_start, stop});
+    } else {
+        g_event_pool.push_back(g_prof_start);
+    }
+    g_prof_start = nullptr;
+}
+
+// ------------------------------------------------------------------ validation and plan
+static int validate(const st_head_desc* d)
+{
+    if (!d) return ST_ERR_NULL;
+    if (d->n <= 0 || d->c_in <= 0 || d->h <= 0 || d->w <= 0 || d->c1 <= 0 || d->c2 <= 0) return ST_ERR_SHAPE;
+    if (d->upscale != UP) return ST_ERR_SHAPE;
+    if (d->n_classes < 2 || d->n_classes > 32) return ST_ERR_SHAPE;
+    if (d->feat_dtype != ST_F32 && d->feat_dtype != ST_BF16) return ST_ERR_ARG;
+    if (d->feat_layout != ST_NCHW) return ST_ERR_ARG;
+    if (d->compute != ST_COMPUTE_F32 && d->compute != ST_COMPUTE_BF16) return ST_ERR_ARG;
+    if (d->ignore_index < -1) return ST_ERR_ARG;
+    // 32-bit indexing inside the kernels
+    const long long cmax = std::max(std::max(d->c_in, d->c1), std::max(d->c2, d->n_classes));
+    const long long pp = (long long)d->n * (d->h + 2) * (d->w + 2 + 8);
+    if (pp * cmax >= (1ll << 31)) return ST_ERR_SHAPE;
+    if ((long long)d->n * d->h * d->w * UP * UP >= (1ll << 31)) return ST_ERR_SHAPE;
+    if ((long long)d->c1 * d->c_in * 9 >= (1ll << 28) || (long long)d->c2 * d->c1 * 9 >= (1ll << 28))
+        return ST_ERR_SHAPE;
+    return ST_OK;
+}
+
+static size_t take(size_t& off, size_t bytes)
+{
+    const size_t at = off;
+    off += (bytes + 255) / 256 * 256;
+    return at;
+}
+
+Plan make_plan(const st_head_desc& d)
+{
+    Plan p;
+    memset(&p, 0, sizeof(p));
+    p.g = make_geo(d);
+    p.po = param_offsets(p.g);
+    p.lt = loss_tiling(p.g);
+    p.bf16 = d.compute == ST_COMPUTE_BF16;
+    p.esz = p.bf16 ? 2 : 4;
+    p.wgrad_splits = 1;
+    p.WpT = (p.g.Wp + 7) / 8 * 8;
+    const Geo& g = p.g;
+    const size_t PP = (size_t)g.padded_positions();
+    size_t off = 256;   // offset 0 is kept unused so that "0" can mean "absent"
+    // position-major activations; kept adjacent so that one fill clears all their borders
+    p.feat = take(off, PP * g.c_in * p.esz);
+    p.a1 = take(off, PP * g.c1 * p.esz);
+    p.a2 = take(off, PP * g.c2 * p.esz);
+    p.da1 = take(off, PP * g.c1 * p.esz);
+    p.da2 = take(off, PP * g.c2 * p.esz);
+    const size_t hw = (size_t)g.h * g.w;
+    p.z = take(off, (size_t)g.n * g.C * hw * 4);
+    p.gz = take(off, (size_t)g.n * g.C * hw * 4);
+    p.g_slots = take(off, loss_slot_floats(g) * 4);
+    p.theta = take(off, p.po.total * 4);
+    p.vel = take(off, p.po.total * 4);
+    p.grad = take(off, p.po.total * 4 * p.wgrad_splits);
+    p.best = take(off, p.po.total * 4);
+    if (p.bf16) {
+        p.wq1 = take(off, (p.po.b1 - p.po.W1) * 2);
+        p.wq2 = take(off, (p.po.b2 - p.po.W2) * 2);
+        p.wq2t = take(off, (p.po.b2 - p.po.W2) * 2);
+        p.wq3 = take(off, (p.po.b3 - p.po.W3) * 2);
+    }
+    p.loss_part = take(off, (size_t)loss_blocks(g) * 4);
+    p.counters = take(off, 256);                       // [0] number of valid pixels
+    p.conf = take(off, (size_t)g.n * g.C * g.C * 8);
+    p.scal = take(off, 256);                           // [0] mean metric of the last pass (double)
+    p.total = off;
+    return p;
+}
+
+static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// clears everything a call relies on being zero: activation borders and the counters
+static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
+{
+    zero_bytes(c, ws + p.feat, p.z - p.feat);
+    zero_bytes(c, ws + p.counters, 256);
+    zero_bytes(c, ws + p.conf, (size_t)p.g.n * p.g.C * p.g.C * 8);
+}
+
+static void forward(Ctx& c, const Plan& p, char* ws, float* z) { generic_forward(c, p, ws, z); }
+static void backward(Ctx& c, const Plan& p, char* ws) { generic_backward(c, p, ws); }
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" {
+
+size_t st_num_params(const st_head_desc* desc)
+{
+    if (validate(desc) != ST_OK) return 0;
+    return param_offsets(make_geo(*desc)).total;
+}
+
+size_t st_workspace_bytes(const st_head_desc* desc)
+{
+    if (validate(desc) != ST_OK) return 0;
+    return make_plan(*desc).total;
+}
+
+int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out)
+{
+    if (!out) return ST_ERR_NULL;
+    const int v = validate(desc);
+    if (v != ST_OK) return v;
+    const Plan p = make_plan(*desc);
+    out->feat = p.feat; out->a1 = p.a1; out->a2 = p.a2; out->da1 = p.da1; out->da2 = p.da2;
+    out->z = p.z; out->g = p.gz; out->theta = p.theta; out->grad = p.grad;
+    out->elem_size = p.esz; out->total = p.total;
+    return ST_OK;
+}
+
+int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
+                    float* logits_lowres, uint8_t* pred, void* workspace, void* stream)
+{
+    const int v = validate(desc);
+    if (v != ST_OK) return v;
+    if (!features || !head_params) return ST_ERR_NULL;
+    if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
+    const Plan p = make_plan(*desc);
+    char* ws = (char*)workspace;
+    Ctx c{as_stream(stream), ST_OK};
+    prepare_workspace(c, p, ws);
+    pack_features(c, p, features, desc->feat_dtype, ws);
+    permute_params(c, p, head_params, (float*)(ws + p.theta), 0);
+    update_params(c, p, ws, 0.f, 0.f, false);
+    float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
+    forward(c, p, ws, z);
+    if (pred)
+        loss_pass(c, p.g, z, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false);
+    return c.status;
+}
+
+int st_partial_distill(const st_head_desc* desc, const void* features, const int32_t* teacher_labels,
+                       float* head_params, int32_t steps, float lr, const st_distill_opts* opts,
+                       st_distill_result* out, void* workspace, void* stream)
+{
+    const int v = validate(desc);
+    if (v != ST_OK) return v;
+    if (!features || !teacher_labels || !head_params) return ST_ERR_NULL;
+    if (steps < 0 || !isfinite(lr)) return ST_ERR_ARG;
+    float mu = 0.f;
+    double threshold = 0.0;
+    float* velocity = nullptr;
+    bool strict = true, return_best = false;
+    if (opts) {
+        if (!isfinite(opts->momentum) || opts->momentum < 0.f || isnan(opts->threshold)) return ST_ERR_ARG;
+        mu = opts->momentum;
+        velocity = opts->velocity;
+        if (mu != 0.f && !velocity) return ST_ERR_NULL;
+        threshold = opts->threshold;
+        strict = opts->strict_break != 0;
+        return_best = opts->return_best != 0;
+    }
+    if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
+    const bool early_exit = threshold > 0.0;
+
+    const Plan p = make_plan(*desc);
+    const Geo& g = p.g;
+    char* ws = (char*)workspace;
+    Ctx c{as_stream(stream), ST_OK};
+
+    float* theta = (float*)(ws + p.theta);
+    float* z = (float*)(ws + p.z);
+    unsigned long long* n_valid = (unsigned long long*)(ws + p.counters);
+    unsigned long long* conf = (unsigned long long*)(ws + p.conf);
+    double* metric_dev = (double*)(ws + p.scal);
+
+    prepare_workspace(c, p, ws);
+    pack_features(c, p, features, desc->feat_dtype, ws);
+    permute_params(c, p, head_params, theta, 0);
+    if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
+    update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
+    count_valid(c, g, teacher_labels, n_valid);
+
+    double best_metric = -1.0;
+    int taken = 0;
+    bool have_best = false;
+    for (int it = 0; it <= steps; ++it) {
+        const bool last = it == steps;
+        forward(c, p, ws, z);
+        loss_pass(c, g, z, teacher_labels, (out && (last || early_exit)) ? out->pred : nullptr,
+                  (float*)(ws + p.g_slots),
+                  (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last);
+        finish_pass(c, p, ws, (out && out->losses) ? out->losses + it : nullptr,
+                    (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr,
+                    (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr,
+                    metric_dev);
+        bool stop = last;
+        if (early_exit) {
+            // Algorithm 1 decides its exits on the metric: one small read-back per iteration
+            double metric = 0.0;
+            ST_HIP(c, hipMemcpyAsync(&metric, metric_dev, sizeof(double), hipMemcpyDeviceToHost, c.stream));
+            ST_HIP(c, hipStreamSynchronize(c.stream));
+            if (c.status != ST_OK) break;
+            if (it == 0) {
+                best_metric = metric;
+                if (return_best) {
+                    ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
+                    have_best = true;
+                }
+                if (!(metric < threshold)) stop = true;   // already good enough: no update at all
+            } else {
+                if (metric > best_metric) {
+                    best_metric = metric;
+                    if (return_best)
+                        ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
+                }
+                if (strict ? metric > threshold : metric >= threshold) stop = true;
+            }
+        }
+        if (stop) break;
+        backward(c, p, ws);
+        update_params(c, p, ws, lr, mu, true);
+        ++taken;
+    }
+    if (early_exit && return_best && have_best)
+        ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
+    permute_params(c, p, theta, head_params, 1);
+    if (mu != 0.f) permute_params(c, p, (const float*)(ws + p.vel), velocity, 1);
+    if (early_exit) ST_HIP(c, hipStreamSynchronize(c.stream));
+    if (out) {
+        out->steps_taken = taken;
+        if (early_exit) out->best_metric = best_metric;
+    }
+    return c.status;
+}
+
+int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_t n_classes,
+            int32_t ignore_index, int64_t* confusion, double* miou, void* stream)
+{
+    if (n_pixels < 0 || n_classes < 1 || n_classes > 256) return ST_ERR_SHAPE;
+    if (((!pred || !labels) && n_pixels > 0) || !confusion || !miou) return ST_ERR_NULL;
+    Ctx c{as_stream(stream), ST_OK};
+    confusion_and_miou(c, pred, labels, n_pixels, n_classes, ignore_index, (long long*)confusion, miou);
+    return c.status;
+}
+
+const char* st_strerror(int status)
+{
+    switch (status) {
+    case ST_OK: return "ok";
+    case ST_ERR_NULL: return "a required pointer is NULL";
+    case ST_ERR_SHAPE: return "unsupported or non-positive dimension";
+    case ST_ERR_ARG: return "invalid argument value";
+    case ST_ERR_WORKSPACE: return "workspace missing or not 256-byte aligned";
+    case ST_ERR_HIP: return "a HIP runtime call failed";
+    case ST_ERR_NO_DEVICE: return "no usable GPU";
+    default: return "unknown status";
+    }
+}
+
+int st_last_hip_error(void) { return g_last_hip_error; }
+
+const char* st_version(void) { return "0.1"; }
+
+void st_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    g_prof_on = on != 0;
+}
+
+void st_profile_reset(void)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    for (auto& r : g_prof) { g_event_pool.push_back(r.start); g_event_pool.push_back(r.stop); }
+    g_prof.clear();
+}
+
+int st_profile_read(st_kernel_stat* stats, int max_stats)
+{
+    if (!stats || max_stats <= 0) return ST_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    int n = 0;
+    for (auto& r : g_prof) {
+        if (hipEventSynchronize(r.stop) != hipSuccess) return ST_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return ST_ERR_HIP;
+        int k = 0;
+        for (; k < n; ++k)
+            if (strncmp(stats[k].name, r.name, sizeof(stats[k].name) - 1) == 0) break;
+        if (k == n) {
+            if (n == max_stats) continue;
+            memset(&stats[k], 0, sizeof(stats[k]));
+            strncpy(stats[k].name, r.name, sizeof(stats[k].name) - 1);
+            ++n;
+        }
+        stats[k].launches += 1;
+        stats[k].total_ms += ms;
+    }
+    return n;
+}
+
+}  // extern "C"

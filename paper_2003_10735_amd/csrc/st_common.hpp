@@ -1,0 +1,138 @@
+// Shared declarations of the partial-distillation library: geometry, workspace plan, launch
+// bookkeeping and small device helpers.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/shadowtutor_head.h"
+
+namespace st {
+
+constexpr int UP = 8;  // up-sampling factor of the head's last stage
+
+typedef __bf16 bf16;
+
+// ------------------------------------------------------------------ geometry
+// Activations live position-major ("NHWC") on a grid padded by one zero cell on every side, so
+// a 3x3 tap is a plain offset and needs no bounds test:
+//   element (img, y, x, c)  ->  ((img * Hp + y + 1) * Wp + x + 1) * C + c
+struct Geo {
+    int n, h, w;     // frames and low-resolution grid
+    int Hp, Wp;      // padded grid: h + 2, w + 2
+    int H, W;        // frame resolution: 8h, 8w
+    int c_in, c1, c2, C;
+    int ignore_index;
+    __host__ __device__ int positions() const { return n * h * w; }
+    __host__ __device__ int padded_positions() const { return n * Hp * Wp; }
+    __host__ __device__ long long pixels() const { return (long long)n * H * W; }
+};
+
+inline Geo make_geo(const st_head_desc& d)
+{
+    Geo g;
+    g.n = d.n; g.h = d.h; g.w = d.w;
+    g.Hp = d.h + 2; g.Wp = d.w + 2;
+    g.H = d.h * UP; g.W = d.w * UP;
+    g.c_in = d.c_in; g.c1 = d.c1; g.c2 = d.c2; g.C = d.n_classes;
+    g.ignore_index = d.ignore_index;
+    return g;
+}
+
+// Offsets (in floats) of the six parameter blocks; identical in the caller's flat vector and in
+// the internal one.  Only the order *inside* W1 and W2 differs: OIHW outside, [o][kh][kw][i]
+// inside (reduction index contiguous for the implicit GEMMs).
+struct ParamOffsets {
+    size_t W1, b1, W2, b2, W3, b3, total;
+};
+
+inline ParamOffsets param_offsets(const Geo& g)
+{
+    ParamOffsets o;
+    o.W1 = 0;
+    o.b1 = o.W1 + (size_t)g.c1 * g.c_in * 9;
+    o.W2 = o.b1 + g.c1;
+    o.b2 = o.W2 + (size_t)g.c2 * g.c1 * 9;
+    o.W3 = o.b2 + g.c2;
+    o.b3 = o.W3 + (size_t)g.C * g.c2;
+    o.total = o.b3 + g.C;
+    return o;
+}
+
+// ------------------------------------------------------------------ loss-kernel tiling
+// The fused up-sample + cross-entropy kernel works on tiles of LOSS_TY x LOSS_TX groups of 8x8
+// frame pixels (one thread per pixel column).  A tile touches (LOSS_TY + 2) x (LOSS_TX + 2)
+// low-resolution cells and leaves its share of d loss / d z for them in a slot of its own.
+constexpr int LOSS_TX = 32;             // 8-pixel column groups per tile (256 threads)
+constexpr int LOSS_TY = 2;              // 8-pixel row groups per tile
+constexpr int LOSS_CW = LOSS_TX + 2;    // cells per tile row
+constexpr int LOSS_CH = LOSS_TY + 2;    // cell rows per tile
+
+struct LossTiling {
+    int tiles_x, tiles_y;   // per frame
+    __host__ __device__ int tiles() const { return tiles_x * tiles_y; }
+};
+
+inline LossTiling loss_tiling(const Geo& g)
+{
+    LossTiling t;
+    t.tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
+    t.tiles_y = (g.h + LOSS_TY - 1) / LOSS_TY;
+    return t;
+}
+
+// ------------------------------------------------------------------ workspace plan
+struct Plan {
+    Geo g;
+    ParamOffsets po;
+    LossTiling lt;
+    bool bf16;          // compute path
+    size_t esz;         // bytes per activation element
+    int wgrad_splits;   // partial weight-gradient copies summed by the update kernel
+    // byte offsets
+    size_t feat, a1, a2, da1, da2;
+    size_t featT, a1T, da1T, da2T;   // channel-major copies for the MFMA weight-gradient
+    size_t z, g_slots, gz;
+    size_t theta, vel, grad, best;
+    size_t wq1, wq2, wq2t, wq3;      // bfloat16 operand copies of the weights
+    size_t loss_part, counters, conf, scal;
+    size_t losses, mious;            // staging when the caller passes no result arrays
+    size_t total;
+    int WpT;            // row pitch (elements) of the channel-major copies, multiple of 8
+};
+
+Plan make_plan(const st_head_desc& d);
+
+// ------------------------------------------------------------------ launch bookkeeping
+// Each kernel launch goes through Launch: it records the kernel's name for the optional event
+// profile and turns a launch failure into ST_ERR_HIP instead of an abort.
+struct Ctx {
+    hipStream_t stream;
+    int status;   // first failure sticks
+};
+
+void prof_begin(Ctx& c, const char* name);
+void prof_end(Ctx& c);
+void set_hip_error(hipError_t e);
+
+#define ST_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                               \
+    do {                                                                                    \
+        if ((ctx).status == ST_OK) {                                                        \
+            st::prof_begin((ctx), name);                                                    \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, (ctx).stream, __VA_ARGS__);      \
+            hipError_t e_ = hipGetLastError();                                              \
+            st::prof_end((ctx));                                                            \
+            if (e_ != hipSuccess) { st::set_hip_error(e_); (ctx).status = ST_ERR_HIP; }     \
+        }                                                                                   \
+    } while (0)
+
+// ------------------------------------------------------------------ device helpers
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <class E> __device__ __forceinline__ E from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
+
+inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+}  // namespace st

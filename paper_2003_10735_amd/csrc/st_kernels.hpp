@@ -1,0 +1,32 @@
+// Host-side launchers of the kernels, one group per source file.
+#pragma once
+#include "st_common.hpp"
+
+namespace st {
+
+// k_layout.hip
+void zero_bytes(Ctx& c, void* p, size_t bytes);            // p 16-byte aligned, region padded to 16
+void zero_u64(Ctx& c, unsigned long long* p, size_t n);
+void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, char* ws);
+void permute_params(Ctx& c, const Plan& p, const float* src, float* dst, int dir);
+
+// k_conv_generic.hip -- plain tiled kernels (float32 path; bfloat16 shapes the MFMA kernels skip)
+void generic_forward(Ctx& c, const Plan& p, char* ws, float* z);
+void generic_backward(Ctx& c, const Plan& p, char* ws);
+
+// k_loss.hip
+size_t loss_slot_floats(const Geo& g);
+int loss_blocks(const Geo& g);
+void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long* out);
+void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, uint8_t* pred, float* slots,
+               float* gz, float* loss_part, unsigned long long* conf, const unsigned long long* n_valid,
+               bool grad);
+
+// k_update.hip
+void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step);
+void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                 double* metric_mean_out);
+void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
+                        long long* conf, double* miou);
+
+}  // namespace st

@@ -1,0 +1,177 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bars: bit-exact for class maps, confusion counts and mean IoU (from the same
+low-resolution logits); 1e-4 relative for the float32 path; 2e-2 relative against the plain
+oracle for the bfloat16 path (and a tighter bar against the oracle's bf16-operand mode, where
+only the accumulation order differs)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2003_10735_amd as st
+import workloads as WL
+from gpu_util import (check_pred_against_oracle, check_staged_bit_exact, rel_err, run_gpu, run_oracle,
+                      to_dev_features)
+
+pytestmark = pytest.mark.gpu
+
+
+def inputs(wl):
+    return WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+
+
+def test_tiny_f32_end_to_end():
+    wl = WL.WORKLOADS["tiny"]
+    f, lab, p = inputs(wl)
+    gpu = run_gpu(wl, f, lab, p)
+    ora = run_oracle(wl, f, lab, p)
+    print("losses gpu", gpu["losses"], "oracle", ora["losses"], "miou", gpu["mious"].ravel())
+    assert gpu["steps_taken"] == wl.steps
+    assert rel_err(gpu["losses"], ora["losses"]) < 1e-4
+    assert rel_err(gpu["params"], ora["params"]) < 1e-4
+    assert rel_err(gpu["params"] - p, ora["params"] - p) < 1e-3      # the update itself
+    check_staged_bit_exact(wl, gpu, lab)
+    np.testing.assert_allclose(gpu["mious"], ora["mious"], atol=2e-3)
+    check_pred_against_oracle(wl, gpu, ora, f, logit_tol=1e-4)
+
+
+RAGGED = [
+    dict(n=1, c_in=8, h=5, w=7, c1=8, c2=8, n_classes=3),
+    dict(n=2, c_in=20, h=9, w=37, c1=24, c2=16, n_classes=5, ignore_index=255, ignore_fraction=0.1),
+    dict(n=1, c_in=16, h=3, w=70, c1=16, c2=40, n_classes=21, momentum=0.9),
+    dict(n=3, c_in=4, h=1, w=1, c1=4, c2=4, n_classes=2),
+]
+
+
+@pytest.mark.parametrize("compute", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+def test_ragged_shapes(case, compute):
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], steps=3, lr=0.05, compute=compute,
+                          feat_dtype="bf16" if compute == "bf16" else "f32", n_sites=7, **RAGGED[case])
+    f, lab, p = inputs(wl)
+    gpu = run_gpu(wl, f, lab, p)
+    check_staged_bit_exact(wl, gpu, lab)
+    if compute == "f32":
+        ora = run_oracle(wl, f, lab, p)
+        assert rel_err(gpu["losses"], ora["losses"]) < 1e-4
+        assert rel_err(gpu["params"], ora["params"]) < 1e-4
+        assert rel_err(gpu["params"] - p, ora["params"] - p) < 2e-3
+        if wl.momentum:
+            assert rel_err(gpu["velocity"], ora["velocity"]) < 2e-3
+    else:
+        ora = run_oracle(wl, f, lab, p, bf16_operands=False)
+        orq = run_oracle(wl, f, lab, p, bf16_operands=True)
+        assert rel_err(gpu["losses"], ora["losses"]) < 2e-2
+        assert rel_err(gpu["params"], ora["params"]) < 2e-2
+        # against the oracle that rounds the same operands: accumulation order only
+        assert rel_err(gpu["losses"], orq["losses"]) < 2e-4
+        assert rel_err(gpu["params"], orq["params"]) < 2e-4
+        assert rel_err(gpu["params"] - p, orq["params"] - p) < 2e-2
+
+
+def test_intermediate_gradient_buffers_f32():
+    """d loss / d z and the parameter gradient of one step, read back from the workspace."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], steps=1, c_in=8, h=6, w=40, c1=8, c2=8, n_classes=4,
+                          n_sites=6, lr=0.0)
+    f, lab, p = inputs(wl)
+    gpu = run_gpu(wl, f, lab, p)
+    d = O.desc_of(wl)
+    f64 = WL.features_as_f64(wl, f)
+    loss, grad, *_ = O.loss_and_grad(d, f64, lab, p.astype(np.float64))
+    z, _ = O.head_forward(d, f64, p.astype(np.float64), want_pred=False)
+    _, G, _ = O.softmax_ce(O.upsample8(z), lab)
+    g = O.upsample8_adjoint(G)
+    lay, ws = gpu["layout"], gpu["workspace"]
+    gz = ws[lay["g"]:lay["g"] + 4 * g.size].view(torch.float32).cpu().numpy().reshape(g.shape)
+    assert rel_err(gz, g) < 1e-5
+    # gradient in the internal order: 3x3 weights as [o][kh][kw][i]
+    n = p.size
+    gi = ws[lay["grad"]:lay["grad"] + 4 * n].view(torch.float32).cpu().numpy()
+    sl = WL.param_slices(wl)
+    ref = grad.copy()
+    for name, (co, ci) in (("W1", (wl.c1, wl.c_in)), ("W2", (wl.c2, wl.c1))):
+        ref[sl[name]] = grad[sl[name]].reshape(co, ci, 3, 3).transpose(0, 2, 3, 1).ravel()
+    for name in sl:
+        assert rel_err(gi[sl[name]], ref[sl[name]]) < 1e-4, name
+    assert abs(gpu["losses"][0] - loss) < 1e-5 * loss
+    np.testing.assert_array_equal(gpu["params"], p)      # lr = 0 leaves the parameters alone
+
+
+def test_head_forward_matches_oracle():
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=12, h=10, w=33, c1=16, c2=8, n_classes=6)
+    f, lab, p = inputs(wl)
+    desc = st.HeadDesc.of(wl)
+    z = torch.empty((wl.n, wl.n_classes, wl.h, wl.w), dtype=torch.float32, device="cuda")
+    pred = torch.empty((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+    st.st_head_forward(desc, to_dev_features(wl, f), torch.from_numpy(p).cuda(), z, pred)
+    torch.cuda.synchronize()
+    zo, _ = O.head_forward(O.desc_of(wl), WL.features_as_f64(wl, f), p.astype(np.float64), want_pred=False)
+    assert rel_err(z.cpu().numpy(), zo) < 1e-5
+    np.testing.assert_array_equal(pred.cpu().numpy(), O.predict_from_logits(z.cpu().numpy()))
+    # pred only / logits only
+    pred2 = torch.empty_like(pred)
+    st.st_head_forward(desc, to_dev_features(wl, f), torch.from_numpy(p).cuda(), None, pred2)
+    torch.cuda.synchronize()
+    assert torch.equal(pred, pred2)
+
+
+@pytest.mark.parametrize("P,C,ignore", [(0, 3, -1), (1, 2, -1), (1000, 19, 255), (65537, 21, 255),
+                                        (300001, 9, -1), (4097, 200, 7)])
+def test_miou_matches_oracle_bit_exact(P, C, ignore):
+    rng = np.random.default_rng(P + C)
+    pred = rng.integers(0, min(C, 256), size=P).astype(np.uint8)
+    lab = rng.integers(0, C, size=P).astype(np.int32)
+    # long constant runs, like real label maps
+    if P > 100:
+        lab[: P // 2] = lab[0]
+        pred[: P // 3] = pred[0]
+    if ignore >= 0 and P:
+        lab[rng.random(P) < 0.07] = ignore
+    conf, m = st.st_miou(torch.from_numpy(pred).cuda(), torch.from_numpy(lab).cuda(), C, ignore)
+    torch.cuda.synchronize()
+    conf_o = O.confusion(pred, lab, C, ignore)
+    np.testing.assert_array_equal(conf.cpu().numpy(), conf_o)
+    assert m.item() == O.miou(conf_o)[0]
+
+
+def test_steps_zero_and_determinism():
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=9, w=35, c1=8, c2=8, n_classes=5, steps=2)
+    f, lab, p = inputs(wl)
+    g0 = run_gpu(wl, f, lab, p, steps=0)
+    np.testing.assert_array_equal(g0["params"], p)
+    assert g0["steps_taken"] == 0
+    a = run_gpu(wl, f, lab, p)
+    b = run_gpu(wl, f, lab, p)
+    for k in ("params", "losses", "mious", "conf", "pred"):
+        np.testing.assert_array_equal(a[k], b[k])
+    assert a["losses"][0] == g0["losses"][0]
+
+
+def test_training_loop_exits():
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, n_sites=5,
+                          label_seed=5, steps=8, lr=0.05)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    trace = run_gpu(wl, f, lab, p)
+    m = trace["mious"][:, 0]
+    assert m.max() > m[0] + 0.05
+    # already at THRESHOLD: nothing happens
+    r = run_gpu(wl, f, lab, p, threshold=float(m[0]), return_best=True)
+    assert r["steps_taken"] == 0
+    np.testing.assert_array_equal(r["params"], p)
+    # unreachable THRESHOLD: every update taken, the first strict maximum returned
+    r = run_gpu(wl, f, lab, p, threshold=1.5, return_best=True)
+    assert r["steps_taken"] == 8 and r["best_metric"] == m.max()
+    best_i = int(np.argmax(m))
+    ref = run_gpu(wl, f, lab, p, steps=best_i)
+    np.testing.assert_array_equal(r["params"], ref["params"])
+    # reachable THRESHOLD: leave at the first metric strictly above it ('>'), or at it ('>=')
+    j = next(i for i in range(1, 9) if m[i] > m[0])
+    r_ge = run_gpu(wl, f, lab, p, threshold=float(m[j]), strict_break=False)
+    assert r_ge["steps_taken"] == j
+    r_gt = run_gpu(wl, f, lab, p, threshold=float(m[j]), strict_break=True)
+    assert r_gt["steps_taken"] > j or not (m[j + 1:] > m[j]).any()
+    # and the whole trace agrees with the oracle's run of Algorithm 1
+    ora = O.train(O.desc_of(wl), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 8, wl.lr, 1.5)
+    np.testing.assert_allclose(m, ora["metrics"], atol=5e-3)
