@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the partial-distillation hot path on one MI355X.
+
+One bench "step" is one st_partial_distill call on the 1280x720 key-frame workload: feature
+packing, 8 optimiser steps (9 forwards, 8 partial backwards, 8 updates) and 9 loss/metric
+passes, with all inputs already resident in HBM.  `value` is optimiser steps per second.
+
+Prints ONE JSON line.  Extra objects:
+  roofline      the kernel that takes the largest share of the call, its algorithmic work per
+                launch over its average launch duration (HIP events on the launch stream, taken
+                during the timed region), against the chip's published peak
+  cpu_baseline  the CPU oracle (test infrastructure, untuned) on the host cores of this machine
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS_BF16 = 2500.0   # MI355X dense bf16 MFMA
+PEAK_TFLOPS_F32 = 157.3     # MI355X fp32 vector / matrix
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def kernel_work(wl):
+    """Algorithmic work per launch of each kernel family: name prefix -> (bound, amount, unit).
+    Convolutions count 2 * M * N * K flops of the contraction the layer defines; streaming
+    kernels count the bytes the method must move."""
+    M = wl.n * wl.h * wl.w
+    C = wl.n_classes
+    P = wl.n * wl.H * wl.W
+    conv1 = 2.0 * M * wl.c1 * 9 * wl.c_in
+    conv2 = 2.0 * M * wl.c2 * 9 * wl.c1
+    conv3 = 2.0 * M * C * wl.c2
+    loss_bytes = 4.0 * C * M + 4.0 * P          # logits in + labels in
+    return {
+        "conv1_fwd": ("mfma", conv1), "conv1_wgrad": ("mfma", conv1),
+        "conv2_fwd": ("mfma", conv2), "conv2_wgrad": ("mfma", conv2), "conv2_dgrad": ("mfma", conv2),
+        "conv3_fwd": ("mfma", conv3), "conv3_wgrad": ("mfma", conv3), "conv3_dgrad": ("mfma", conv3),
+        "conv3_bwd": ("mfma", 2 * conv3),
+        "upsample_ce_grad": ("hbm", loss_bytes + 4.0 * C * M),
+        "upsample_ce": ("hbm", loss_bytes),
+        "sgd_update": ("hbm", (22.0 if wl.momentum else 14.0) * wl.n_params),
+        "pack_features": ("hbm", 2.0 * wl.n * wl.c_in * wl.h * wl.w * 2),
+    }
+
+
+def call_flops(wl):
+    M = wl.n * wl.h * wl.w
+    conv1 = 2.0 * M * wl.c1 * 9 * wl.c_in
+    conv2 = 2.0 * M * wl.c2 * 9 * wl.c1
+    conv3 = 2.0 * M * wl.n_classes * wl.c2
+    fwd = conv1 + conv2 + conv3
+    bwd = conv1 + 2 * conv2 + 2 * conv3     # no data-gradient for layer 1: the features are frozen
+    return (wl.steps + 1) * fwd + wl.steps * bwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="720p")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; sharding is by video stream (one head per "
+              "client per GPU, no exchange) and is not part of it. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2003_10735_amd as st
+    import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    st.lib()   # fails loudly when the HIP library has not been built
+    torch.cuda.set_device(0)
+    wl = WL.WORKLOADS[args.workload]
+    desc = st.HeadDesc.of(wl)
+
+    feats = WL.make_features(wl)
+    labels = WL.make_labels(wl)
+    params0 = WL.make_head_params(wl)
+    f = torch.from_numpy(feats.view(np.int16)).cuda().view(torch.bfloat16) if feats.dtype == np.uint16 \
+        else torch.from_numpy(feats).cuda()
+    lab = torch.from_numpy(labels).cuda()
+    p0 = torch.from_numpy(params0).cuda()
+    p = p0.clone()
+    vel = torch.zeros_like(p) if wl.momentum else None
+    losses = torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")
+    mious = torch.zeros((wl.steps + 1, wl.n), dtype=torch.float64, device="cuda")
+    conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+    ws = st.new_workspace(desc)
+    stream = torch.cuda.current_stream()
+
+    def one_call():
+        p.copy_(p0)                      # the head is re-initialised for every key frame
+        if vel is not None:
+            vel.zero_()
+        st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
+                              losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        one_call()
+    torch.cuda.synchronize()
+
+    # which kernel dominates: one untimed call with an event pair around every launch
+    st.st_profile_reset()
+    st.st_profile_filter(None)
+    st.st_profile_enable(True)
+    one_call()
+    torch.cuda.synchronize()
+    prof = st.st_profile_read()
+    st.st_profile_enable(False)
+    st.st_profile_reset()
+    work = kernel_work(wl)
+    known = {k: v for k, v in prof.items() if any(k.startswith(pre) for pre in work)}
+    dominant = max(known, key=lambda k: known[k][1])
+    breakdown = {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
+
+    # timed region; only the dominant kernel carries an event pair
+    st.st_profile_filter(dominant)
+    st.st_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_call()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom = st.st_profile_read()[dominant]
+    st.st_profile_enable(False)
+    st.st_profile_reset()
+    st.st_profile_filter(None)
+
+    elapsed = t1 - t0
+    ms_per_call = elapsed / args.steps * 1e3
+    steps_per_s = args.steps * wl.steps / elapsed
+    final_losses = losses.cpu().numpy()
+
+    pre = max((k for k in work if dominant.startswith(k)), key=len)
+    bound, amount = work[pre]
+    avg_s = dom[1] / dom[0] * 1e-3
+    if bound == "mfma":
+        peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
+        achieved, unit = amount / avg_s / 1e12, "TFLOP/s"
+    else:
+        peak, achieved, unit = PEAK_HBM_GBS, amount / avg_s / 1e9, "GB/s"
+    roofline = {"bound": bound, "kernel": dominant, "achieved": round(achieved, 3), "peak": peak,
+                "unit": unit, "frac": round(achieved / peak, 5), "traffic": None,
+                "avg_launch_us": round(avg_s * 1e6, 2), "launches": dom[0],
+                "work_per_launch": amount}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        d = O.desc_of(wl)
+        f64 = WL.features_as_f64(wl, feats)
+        k = wl.steps if wl.name in ("tiny", "720p") else 1
+        tc0 = time.perf_counter()
+        O.partial_distill(d, f64, labels, params0.astype(np.float64), k, wl.lr, momentum=wl.momentum)
+        tc1 = time.perf_counter()
+        cpu_baseline = {"value": round(k / (tc1 - tc0), 4), "unit": "steps/s", "cores": O.num_threads(),
+                        "kind": "oracle",
+                        "sample": f"the same {wl.name} key frame, {k} optimiser step(s) "
+                                  f"({k + 1} forwards), float64, {tc1 - tc0:.1f} s"}
+
+    out = {
+        "metric": "key-frame partial-distill steps/sec at 1280x720 (fwd+bwd+update)",
+        "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_call, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if wl.compute == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: features [{wl.n},{wl.c_in},{wl.h},{wl.w}] {wl.feat_dtype}, head "
+                               f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, "
+                               f"{wl.steps} SGD steps per key frame (one bench step = one key frame)",
+                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum},
+        "key_frames_per_s": round(args.steps / elapsed, 3),
+        "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
+        "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],
+        "kernel_us": breakdown,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -178,6 +178,7 @@ typedef struct st_kernel_stat {
 } st_kernel_stat;
 
 void st_profile_enable(int on);
+void st_profile_filter(const char* substring); /* only kernels whose name contains it; NULL = all */
 void st_profile_reset(void);
 int st_profile_read(st_kernel_stat* stats, int max_stats); /* returns the number written, <0 on error */
 

@@ -23,7 +23,7 @@ ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
 
 EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
            "st_miou", "st_strerror", "st_last_hip_error", "st_version",
-           "st_get_workspace_layout", "st_profile_enable", "st_profile_reset", "st_profile_read"]
+           "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read"]
 
 
 class StHeadDesc(C.Structure):
@@ -91,6 +91,7 @@ def lib():
         L.st_get_workspace_layout.restype = C.c_int
         L.st_get_workspace_layout.argtypes = [C.POINTER(StHeadDesc), C.POINTER(StWorkspaceLayout)]
         L.st_profile_enable.argtypes = [C.c_int]
+        L.st_profile_filter.argtypes = [C.c_char_p]
         L.st_profile_read.restype = C.c_int
         L.st_profile_read.argtypes = [C.POINTER(StKernelStat), C.c_int]
         _LIB = L
@@ -211,6 +212,10 @@ def st_miou(pred, labels, n_classes: int, ignore_index: int = -1, confusion=None
 
 def st_profile_enable(on: bool):
     lib().st_profile_enable(1 if on else 0)
+
+
+def st_profile_filter(substring):
+    lib().st_profile_filter(None if substring is None else substring.encode())
 
 
 def st_profile_reset():

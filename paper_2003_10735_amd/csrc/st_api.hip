@@ -27,6 +27,7 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 struct ProfRec { const char* name; hipEvent_t start, stop; };
 static std::mutex g_prof_mutex;
 static bool g_prof_on = false;
+static std::string g_prof_filter;   // empty: every kernel
 static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_event_pool;
 static thread_local const char* g_prof_name = nullptr;
@@ -44,6 +45,7 @@ void prof_begin(Ctx& c, const char* name)
 {
     if (!g_prof_on) return;
     std::lock_guard<std::mutex> lk(g_prof_mutex);
+    if (!g_prof_filter.empty() && !strstr(name, g_prof_filter.c_str())) return;
     g_prof_name = name;
     g_prof_start = get_event();
     if (g_prof_start) (void)hipEventRecord(g_prof_start, c.stream);
@@ -326,6 +328,12 @@ void st_profile_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mutex);
     g_prof_on = on != 0;
+}
+
+void st_profile_filter(const char* substring)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    g_prof_filter = substring ? substring : "";
 }
 
 void st_profile_reset(void)
