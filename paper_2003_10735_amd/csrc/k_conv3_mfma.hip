@@ -1,0 +1,203 @@
+// The 1x1 classifier layer on the matrix cores (bfloat16 operands, float32 accumulation).
+//
+// Forward:   z[img][c][pos] = b3[c] + sum_o a2[pos][o] * W3[c][o]            (float32, planar)
+// Backward:  da2[pos][o]    = [a2[pos][o] > 0] * sum_c g[c][pos] * W3[c][o]
+//            dW3[c][o]      = sum_pos g[c][pos] * a2[pos][o]
+//            db3[c]         = sum_pos g[c][pos]
+// with g = d loss / d z rounded to bfloat16 where it enters a product.  The class dimension
+// (<= 32) is padded to one 32-row MFMA tile with zeros.
+#include "st_kernels.hpp"
+#include "st_mfma.hpp"
+
+namespace st {
+
+// ------------------------------------------------------------------ forward
+// One wavefront = 32 consecutive (unpadded) positions; the weights are the A operand (rows =
+// classes), the activations the B operand, so register r of a lane is one class of one position
+// and each store instruction writes 32 consecutive positions of one class plane.
+template <int KSTEPS>   // c2 / 16
+__global__ void __launch_bounds__(256)
+k_logits_mfma(const bf16* __restrict__ a2, const bf16* __restrict__ W3q, const float* __restrict__ b3,
+              float* __restrict__ z, Geo g)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int hw = g.h * g.w, total = g.n * hw;
+    const int q = (blockIdx.x * 4 + wave) * 32 + l32;
+    const int qc = min(q, total - 1);
+    const int img = qc / hw, rr = qc - img * hw, y = rr / g.w, x = rr - y * g.w;
+    const size_t mp = ((size_t)img * g.Hp + y + 1) * g.Wp + x + 1;
+    const bf16* arow = a2 + mp * g.c2 + lhi * 8;
+    const bf16* wrow = W3q + (size_t)min(l32, g.C - 1) * g.c2 + lhi * 8;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const bf16x8 zero = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        bf16x8 wf = *(const bf16x8*)(wrow + ks * 16);
+        if (l32 >= g.C) wf = zero;
+        const bf16x8 xf = *(const bf16x8*)(arow + ks * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc, 0, 0, 0);
+    }
+    if (q < total) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
+            if (c < g.C) z[((size_t)img * g.C + c) * hw + rr] = acc[r] + b3[c];
+        }
+    }
+}
+
+bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 == 256) && C <= 32; }
+
+void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z)
+{
+    const Geo& g = p.g;
+    const dim3 grid(cdiv(g.positions(), 128));
+    switch (g.c2) {
+    case 64: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<4>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
+    case 128: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<8>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
+    case 256: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<16>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
+    default: c.status = ST_ERR_SHAPE;
+    }
+}
+
+// ------------------------------------------------------------------ backward
+// One block = 128 consecutive padded positions (g is zero on the border).  The block first
+// stages g (rounded to bfloat16) in LDS in both orientations and W3 transposed; then
+//   wavefront w computes da2 for positions 32w .. 32w+31 and all channels  (K = classes),
+//   wavefront w computes dW3 for channel tiles w, w+4, ..  over all 128 positions (K = positions),
+// so no sum crosses wavefronts.  Partial dW3 / db3 go to one slot per block; the optimiser
+// kernel adds the slots in order.
+template <int C2>
+__global__ void __launch_bounds__(256)
+k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
+                 const bf16* __restrict__ W3q, bf16* __restrict__ da2, bf16* __restrict__ da2T,
+                 float* __restrict__ part, Geo g, int PPT, int guard)
+{
+    constexpr int OT = C2 / 32;            // channel tiles
+    constexpr int GP = 128 + 8;            // pitch of g_cp rows (positions)
+    constexpr int GC = 32 + 8;             // pitch of g_pc / w3t rows (classes)
+    constexpr int OLD = C2 + 8;            // pitch of the output tile
+    __shared__ __attribute__((aligned(16))) bf16 g_cp[32 * GP];     // [class][position]
+    __shared__ __attribute__((aligned(16))) bf16 g_pc[128 * GC];    // [position][class]
+    __shared__ __attribute__((aligned(16))) bf16 w3t[C2 * GC];      // [channel][class]
+    __shared__ __attribute__((aligned(16))) bf16 Os[128 * OLD];     // da2 tile [position][channel]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int PP = g.padded_positions(), frame = g.Hp * g.Wp, hw = g.h * g.w;
+    const int m0 = blockIdx.x * 128;
+
+    // ---- stage g (both orientations) and W3^T
+    for (int i = tid; i < 32 * 128; i += 256) {
+        const int p = i & 127, c = i >> 7;
+        const int mp = m0 + p;
+        float v = 0.f;
+        if (c < g.C && mp < PP) {
+            const int img = mp / frame, rr = mp - img * frame, y = rr / g.Wp, x = rr - y * g.Wp;
+            if (y >= 1 && y <= g.h && x >= 1 && x <= g.w)
+                v = gz[((size_t)img * g.C + c) * hw + (y - 1) * g.w + (x - 1)];
+        }
+        const bf16 q = (bf16)v;
+        g_cp[c * GP + p] = q;
+        g_pc[p * GC + c] = q;
+    }
+    for (int i = tid; i < C2 * 32; i += 256) {
+        const int o = i % C2, c = i / C2;
+        w3t[o * GC + c] = c < g.C ? W3q[(size_t)c * C2 + o] : (bf16)0.f;
+    }
+    __syncthreads();
+
+    // ---- da2: D[o][pos] = sum_c W3T[o][c] * g[c][pos], two K steps cover 32 classes
+    {
+        f32x16 acc[OT];
+#pragma unroll
+        for (int t = 0; t < OT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        const int p = wave * 32 + l32;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 gf = *(const bf16x8*)(g_pc + p * GC + ks * 16 + lhi * 8);
+#pragma unroll
+            for (int t = 0; t < OT; ++t) {
+                const bf16x8 wf = *(const bf16x8*)(w3t + (t * 32 + l32) * GC + ks * 16 + lhi * 8);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, gf, acc[t], 0, 0, 0);
+            }
+        }
+        const int mp = m0 + p;
+        const bool in_range = mp < PP;
+#pragma unroll
+        for (int t = 0; t < OT; ++t)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int o = t * 32 + rg * 8 + lhi * 4;
+                bf16x4 mk = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
+                if (in_range) mk = *(const bf16x4*)(a2 + (size_t)mp * C2 + o);   // zero on the border
+                bf16x4 ov;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ov[e] = (bf16)((float)mk[e] > 0.f ? acc[t][rg * 4 + e] : 0.f);
+                *(bf16x4*)(Os + p * OLD + o) = ov;
+            }
+    }
+
+    // ---- dW3: D[c][o] = sum_pos g[c][pos] * a2[pos][o] over this block's 128 positions
+    float* slot = part + (size_t)blockIdx.x * (32 * C2 + 32);
+    for (int t = wave; t < OT; t += 4) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        const bf16* xrow = a2T + (size_t)(t * 32 + l32) * PPT + guard + m0 + lhi * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
+            const bf16x8 xf = *(const bf16x8*)(xrow + ks * 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
+            slot[c * C2 + t * 32 + l32] = acc[r];
+        }
+    }
+    if (tid < 32) {
+        float s = 0.f;
+        for (int p = 0; p < 128; ++p) s += (float)g_cp[tid * GP + p];
+        slot[32 * C2 + tid] = s;
+    }
+    __syncthreads();
+
+    // ---- write the da2 tile: position-major rows and channel-major 8-position groups
+    for (int q = tid; q < 128 * (C2 / 8); q += 256) {
+        const int p = q / (C2 / 8), part8 = q % (C2 / 8);
+        if (m0 + p < PP)
+            *(uint4*)(da2 + (size_t)(m0 + p) * C2 + part8 * 8) = *(const uint4*)(Os + p * OLD + part8 * 8);
+    }
+    for (int q = tid; q < 16 * C2; q += 256) {
+        const int o = q % C2, pg = q / C2;
+        bf16x8 ov;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ov[e] = Os[(pg * 8 + e) * OLD + o];
+        *(bf16x8*)(da2T + (size_t)o * PPT + guard + m0 + pg * 8) = ov;
+    }
+}
+
+int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions(), 128); }
+size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
+
+void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* gz, const bf16* a2, const bf16* a2T, const bf16* W3q,
+                    bf16* da2, bf16* da2T, float* part)
+{
+    const Geo& g = p.g;
+    const dim3 grid(conv3_bwd_blocks(g));
+    switch (g.c2) {
+    case 64: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<64>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
+    case 128: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<128>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
+    case 256: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<256>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
+    default: c.status = ST_ERR_SHAPE;
+    }
+}
+
+}  // namespace st

@@ -23,12 +23,13 @@ void zero_bytes(Ctx& c, void* p, size_t bytes)
 }
 
 // features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
-// featT != nullptr, a channel-major padded copy [n, c_in, Hp, WpT] for the weight-gradient.
+// outT != nullptr, a channel-major copy [c_in][PPT] (padded position mp at column guard + mp)
+// for the weight-gradient kernel.
 // One block transposes a 32-channel x 32-column tile of one row through LDS so that both the
 // read (along x) and the write (along c) are contiguous.
 template <class Tin, class E>
 __global__ void __launch_bounds__(256)
-k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ outT, Geo g, int WpT)
+k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ outT, Geo g, int PPT, int guard)
 {
     __shared__ float tile[32][33];
     const int x0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
@@ -40,7 +41,7 @@ k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ 
         if (c < g.c_in && x < g.w) v = to_f32(f[(((size_t)img * g.c_in + c) * g.h + y) * g.w + x]);
         tile[k][tx] = v;
         if (outT && c < g.c_in && x < g.w)
-            outT[(((size_t)img * g.c_in + c) * g.Hp + y + 1) * WpT + x + 1] = from_f32<E>(v);
+            outT[(size_t)c * PPT + guard + ((size_t)img * g.Hp + y + 1) * g.Wp + x + 1] = from_f32<E>(v);
     }
     __syncthreads();
     for (int k = ty; k < 32; k += 8) {
@@ -74,18 +75,18 @@ void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, 
         bf16* outT = p.featT ? (bf16*)(ws + p.featT) : nullptr;
         if (feat_dtype == ST_BF16)
             ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, bf16>), grid, dim3(256), 0,
-                      (const bf16*)features, out, outT, g, p.WpT);
+                      (const bf16*)features, out, outT, g, p.PPT, p.guard);
         else
             ST_LAUNCH(c, "pack_features", (k_pack_features<float, bf16>), grid, dim3(256), 0,
-                      (const float*)features, out, outT, g, p.WpT);
+                      (const float*)features, out, outT, g, p.PPT, p.guard);
     } else {
         float* out = (float*)(ws + p.feat);
         if (feat_dtype == ST_BF16)
             ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, float>), grid, dim3(256), 0,
-                      (const bf16*)features, out, (float*)nullptr, g, 0);
+                      (const bf16*)features, out, (float*)nullptr, g, 0, 0);
         else
             ST_LAUNCH(c, "pack_features", (k_pack_features<float, float>), grid, dim3(256), 0,
-                      (const float*)features, out, (float*)nullptr, g, 0);
+                      (const float*)features, out, (float*)nullptr, g, 0, 0);
     }
 }
 

@@ -5,12 +5,16 @@
 
 namespace st {
 
-// theta <- theta - lr * v,  v <- mu * v + g  (mu == 0: v is not touched),  g = sum of the
-// `splits` partial gradients in ascending order.  Also refreshes the bfloat16 copies:
-//   wq[j]  : same (internal) order as theta, for the forward convolutions
-//   wq2t   : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
+// theta <- theta - lr * v,  v <- mu * v + g  (mu == 0: v is not touched).  g is the sum, in
+// ascending order, of the partial gradients the backward kernels left behind: `splits1` copies
+// for W1/b1 and `splits2` for W2/b2 (position splits of the weight-gradient kernels, `stride`
+// floats apart), and `blocks3` per-block slots for W3/b3 (0: they sit in copy 0 like the rest).
+// Also refreshes the bfloat16 copies of the new weights:
+//   wq1, wq2, wq3 : same (internal) order as theta, for the forward convolutions
+//   wq2t          : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
 struct UpdateArgs {
-    float* theta; float* vel; const float* grad; size_t grad_stride; int splits;
+    float* theta; float* vel; const float* grad; size_t stride; int splits1, splits2;
+    const float* part3; int blocks3; size_t slot3;
     bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
     ParamOffsets po; int c1, c2;
     float lr, mu;
@@ -23,8 +27,17 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a)
     if (j >= a.po.total) return;
     float w = a.theta[j];
     if (a.do_step) {
-        float g = a.grad[j];
-        for (int s = 1; s < a.splits; ++s) g += a.grad[(size_t)s * a.grad_stride + j];
+        float g;
+        if (j >= a.po.W3 && a.blocks3 > 0) {
+            // slot layout: [32 classes][c2] weights, then [32] biases
+            const size_t r = j >= a.po.b3 ? (size_t)32 * a.c2 + (j - a.po.b3) : j - a.po.W3;
+            g = a.part3[r];
+            for (int s = 1; s < a.blocks3; ++s) g += a.part3[(size_t)s * a.slot3 + r];
+        } else {
+            const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
+            g = a.grad[j];
+            for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
+        }
         if (a.mu != 0.f) {
             const float v = __builtin_fmaf(a.mu, a.vel[j], g);
             a.vel[j] = v;
@@ -53,8 +66,12 @@ void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_
     a.theta = (float*)(ws + p.theta);
     a.vel = (float*)(ws + p.vel);
     a.grad = (const float*)(ws + p.grad);
-    a.grad_stride = p.po.total;
-    a.splits = 1;
+    a.stride = p.po.total;
+    a.splits1 = p.mfma ? p.splits1 : 1;
+    a.splits2 = p.mfma ? p.splits2 : 1;
+    a.part3 = (const float*)(ws + p.grad3);
+    a.blocks3 = p.mfma ? p.blocks3 : 0;
+    a.slot3 = conv3_bwd_slot_floats(p.g);
     a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
     a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;

@@ -102,24 +102,48 @@ Plan make_plan(const st_head_desc& d)
     p.lt = loss_tiling(p.g);
     p.bf16 = d.compute == ST_COMPUTE_BF16;
     p.esz = p.bf16 ? 2 : 4;
-    p.wgrad_splits = 1;
-    p.WpT = (p.g.Wp + 7) / 8 * 8;
     const Geo& g = p.g;
+    p.mfma = p.bf16 && conv3x3_mfma_supported(g.c_in, g.c1) && conv3x3_mfma_supported(g.c1, g.c2) &&
+             wgrad3x3_mfma_supported(g.c_in, g.c1) && wgrad3x3_mfma_supported(g.c1, g.c2) &&
+             conv3_mfma_supported(g.c2, g.C);
+    p.splits1 = p.mfma ? wgrad_splits_for(g, g.c_in, g.c1) : 1;
+    p.splits2 = p.mfma ? wgrad_splits_for(g, g.c1, g.c2) : 1;
+    p.blocks3 = p.mfma ? conv3_bwd_blocks(g) : 0;
+    p.grad_copies = std::max(p.splits1, p.splits2);
+    // guard: a 3x3 tap reaches Wp + 1 rows back/ahead of a tile that may overrun the grid by
+    // up to 255 positions
+    p.guard = (g.Wp + 2 + 256 + 7) / 8 * 8;
     const size_t PP = (size_t)g.padded_positions();
+    p.PPT = (int)(p.guard + (PP + 15) / 16 * 16 + p.guard);
     size_t off = 256;   // offset 0 is kept unused so that "0" can mean "absent"
-    // position-major activations; kept adjacent so that one fill clears all their borders
-    p.feat = take(off, PP * g.c_in * p.esz);
-    p.a1 = take(off, PP * g.c1 * p.esz);
-    p.a2 = take(off, PP * g.c2 * p.esz);
-    p.da1 = take(off, PP * g.c1 * p.esz);
-    p.da2 = take(off, PP * g.c2 * p.esz);
+    // position-major activations [guard + PP + guard][C]; the offsets point at position 0.
+    // Everything from zero_begin to zero_end is cleared at the start of a call (borders, guards).
+    p.zero_begin = off;
+    auto act = [&](int C) {
+        const size_t base = take(off, (PP + 2 * (size_t)p.guard) * C * p.esz);
+        return base + (size_t)p.guard * C * p.esz;
+    };
+    p.feat = act(g.c_in);
+    p.a1 = act(g.c1);
+    p.a2 = act(g.c2);
+    p.da1 = act(g.c1);
+    p.da2 = act(g.c2);
+    if (p.mfma) {
+        p.featT = take(off, (size_t)g.c_in * p.PPT * 2);
+        p.a1T = take(off, (size_t)g.c1 * p.PPT * 2);
+        p.a2T = take(off, (size_t)g.c2 * p.PPT * 2);
+        p.da1T = take(off, (size_t)g.c1 * p.PPT * 2);
+        p.da2T = take(off, (size_t)g.c2 * p.PPT * 2);
+    }
+    p.zero_end = off;
     const size_t hw = (size_t)g.h * g.w;
     p.z = take(off, (size_t)g.n * g.C * hw * 4);
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.theta = take(off, p.po.total * 4);
     p.vel = take(off, p.po.total * 4);
-    p.grad = take(off, p.po.total * 4 * p.wgrad_splits);
+    p.grad = take(off, p.po.total * 4 * p.grad_copies);
+    p.grad3 = take(off, (size_t)std::max(p.blocks3, 1) * conv3_bwd_slot_floats(g) * 4);
     p.best = take(off, p.po.total * 4);
     if (p.bf16) {
         p.wq1 = take(off, (p.po.b1 - p.po.W1) * 2);
@@ -142,13 +166,39 @@ static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 // clears everything a call relies on being zero: activation borders and the counters
 static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
 {
-    zero_bytes(c, ws + p.feat, p.z - p.feat);
+    zero_bytes(c, ws + p.zero_begin, p.zero_end - p.zero_begin);
     zero_bytes(c, ws + p.counters, 256);
     zero_bytes(c, ws + p.conf, (size_t)p.g.n * p.g.C * p.g.C * 8);
 }
 
-static void forward(Ctx& c, const Plan& p, char* ws, float* z) { generic_forward(c, p, ws, z); }
-static void backward(Ctx& c, const Plan& p, char* ws) { generic_backward(c, p, ws); }
+// one forward pass of the head: features (already packed) -> low-resolution logits z
+static void forward(Ctx& c, const Plan& p, char* ws, float* z)
+{
+    if (!p.mfma) { generic_forward(c, p, ws, z); return; }
+    const Geo& g = p.g;
+    const float* theta = (const float*)(ws + p.theta);
+    conv3x3_mfma(c, "conv1_fwd_mfma", p, (const bf16*)(ws + p.feat), (const bf16*)(ws + p.wq1), theta + p.po.b1,
+                 nullptr, (bf16*)(ws + p.a1), (bf16*)(ws + p.a1T), g.c_in, g.c1, 0);
+    conv3x3_mfma(c, "conv2_fwd_mfma", p, (const bf16*)(ws + p.a1), (const bf16*)(ws + p.wq2), theta + p.po.b2,
+                 nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0);
+    logits_mfma(c, p, (const bf16*)(ws + p.a2), (const bf16*)(ws + p.wq3), theta + p.po.b3, z);
+}
+
+// partial backward: gradients of the head's parameters only; nothing flows into the features
+static void backward(Ctx& c, const Plan& p, char* ws)
+{
+    if (!p.mfma) { generic_backward(c, p, ws); return; }
+    const Geo& g = p.g;
+    float* grad = (float*)(ws + p.grad);
+    conv3_bwd_mfma(c, p, (const float*)(ws + p.gz), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
+                   (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
+    wgrad3x3_mfma(c, "conv2_wgrad_mfma", p, (const bf16*)(ws + p.da2T), (const bf16*)(ws + p.a1T),
+                  grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2);
+    conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
+                 (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1);
+    wgrad3x3_mfma(c, "conv1_wgrad_mfma", p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT),
+                  grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1);
+}
 
 }  // namespace st
 

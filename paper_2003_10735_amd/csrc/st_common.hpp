@@ -88,17 +88,24 @@ struct Plan {
     LossTiling lt;
     bool bf16;          // compute path
     size_t esz;         // bytes per activation element
-    int wgrad_splits;   // partial weight-gradient copies summed by the update kernel
+    bool mfma;          // bf16 path on the matrix-core kernels (else the plain tiled kernels)
+    int splits1, splits2;   // position splits of the layer-1 / layer-2 weight-gradient kernels
+    int blocks3;            // per-block partial slots of the layer-3 backward kernel
+    int grad_copies;        // max(splits1, splits2): partial gradient copies the update sums
+    int guard;          // guard rows before and after every position-major activation buffer;
+                        // also the number of guard columns in front of a channel-major row
+    int PPT;            // row pitch (elements) of the channel-major copies
     // byte offsets
     size_t feat, a1, a2, da1, da2;
-    size_t featT, a1T, da1T, da2T;   // channel-major copies for the MFMA weight-gradient
+    size_t featT, a1T, a2T, da1T, da2T;   // channel-major copies [C][PPT] for the weight-gradient kernels
+    size_t grad3;                         // per-block partials of dW3 / db3
+    size_t zero_begin, zero_end;          // region cleared at the start of every call
     size_t z, g_slots, gz;
     size_t theta, vel, grad, best;
     size_t wq1, wq2, wq2t, wq3;      // bfloat16 operand copies of the weights
     size_t loss_part, counters, conf, scal;
     size_t losses, mious;            // staging when the caller passes no result arrays
     size_t total;
-    int WpT;            // row pitch (elements) of the channel-major copies, multiple of 8
 };
 
 Plan make_plan(const st_head_desc& d);

@@ -1,0 +1,14 @@
+// Vector types of the gfx950 matrix-core builtins.
+#pragma once
+#include "st_common.hpp"
+
+namespace st {
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].  Lane l supplies A[l % 32][8*(l/32) .. +7]
+// and B[8*(l/32) .. +7][l % 32]; it receives D[8*(r/4) + 4*(l/32) + r%4][l % 32] in register r.
+}  // namespace st
