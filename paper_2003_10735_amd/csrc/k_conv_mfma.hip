@@ -47,9 +47,11 @@ template <int BN, int EPI>
 __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
 {
     constexpr int TA = BN / 64;          // 32-row weight fragments per wavefront
-    constexpr int XS_ROWS = CV_BM + 2;
+    // 130 activation rows are needed; 160 are staged so that every thread moves the same
+    // number of 16-byte chunks (5) without a bounds test -- the extra rows are never read back
+    constexpr int XS_ROWS = 160;
     constexpr int XS_CHUNKS = XS_ROWS * 8, WS_CHUNKS = 3 * BN * 8;
-    constexpr int XS_PER_T = (XS_CHUNKS + 255) / 256, WS_PER_T = WS_CHUNKS / 256;
+    constexpr int XS_PER_T = XS_CHUNKS / 256, WS_PER_T = WS_CHUNKS / 256;
     constexpr int XS_ELEMS = XS_ROWS * CV_LDP, WS_ELEMS = 3 * BN * CV_LDP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Xs = (bf16*)smem_raw;                       // [2][XS_ROWS][LDP]
@@ -77,48 +79,45 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
 
     const int c_chunks = a.cin / CV_BK;
     const int n_stages = 3 * c_chunks;
-    uint4 xr[XS_PER_T], wr[WS_PER_T];
+    // prefetch registers of one stage (kept as plain unrolled register arrays)
+    u32x4 xr[XS_PER_T], wr[WS_PER_T];
 
-    auto load_stage = [&](int s) {
-        const int kh = s / c_chunks, c0 = (s % c_chunks) * CV_BK;
-        const long long row0 = (long long)m0 - 1 + (long long)(kh - 1) * a.Wp;
-#pragma unroll
-        for (int i = 0; i < XS_PER_T; ++i) {
-            const int q = tid + i * 256;
-            if (q < XS_CHUNKS) {
-                const int r = q >> 3, part = q & 7;
-                xr[i] = *(const uint4*)(a.X + (row0 + r) * a.cin + c0 + part * 8);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < WS_PER_T; ++i) {
-            const int q = tid + i * 256;
-            const int row = q >> 3, part = q & 7;
-            const int kw = row / BN, n = min(n0 + row % BN, a.cout - 1);
-            wr[i] = *(const uint4*)(a.Wq + ((size_t)n * 9 + kh * 3 + kw) * a.cin + c0 + part * 8);
-        }
-    };
-    auto store_stage = [&](int buf) {
-        bf16* xs = Xs + buf * XS_ELEMS;
-        bf16* ws = Ws + buf * WS_ELEMS;
-#pragma unroll
-        for (int i = 0; i < XS_PER_T; ++i) {
-            const int q = tid + i * 256;
-            if (q < XS_CHUNKS) *(uint4*)(xs + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[i];
-        }
-#pragma unroll
-        for (int i = 0; i < WS_PER_T; ++i) {
-            const int q = tid + i * 256;
-            *(uint4*)(ws + (q >> 3) * CV_LDP + (q & 7) * 8) = wr[i];
-        }
-    };
+#define CV_LOAD_STAGE(S)                                                                          \
+    {                                                                                             \
+        const int kh_ = (S) / c_chunks, c0_ = ((S) % c_chunks) * CV_BK;                           \
+        const long long row0_ = (long long)m0 - 1 + (long long)(kh_ - 1) * a.Wp;                  \
+        _Pragma("unroll") for (int i = 0; i < XS_PER_T; ++i) {                                    \
+            const int q = tid + i * 256;                                                          \
+            xr[i] = *(const u32x4*)(a.X + (row0_ + (q >> 3)) * a.cin + c0_ + (q & 7) * 8);        \
+        }                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < WS_PER_T; ++i) {                                    \
+            const int q = tid + i * 256;                                                          \
+            const int row = q >> 3;                                                               \
+            const int n = min(n0 + row % BN, a.cout - 1);                                         \
+            wr[i] = *(const u32x4*)(a.Wq + ((size_t)n * 9 + kh_ * 3 + row / BN) * a.cin + c0_ +   \
+                                    (q & 7) * 8);                                                 \
+        }                                                                                         \
+    }
+#define CV_STORE_STAGE(BUF)                                                                       \
+    {                                                                                             \
+        bf16* xs_ = Xs + (BUF) * XS_ELEMS;                                                        \
+        bf16* ws_ = Ws + (BUF) * WS_ELEMS;                                                        \
+        _Pragma("unroll") for (int i = 0; i < XS_PER_T; ++i) {                                    \
+            const int q = tid + i * 256;                                                          \
+            *(u32x4*)(xs_ + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[i];                             \
+        }                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < WS_PER_T; ++i) {                                    \
+            const int q = tid + i * 256;                                                          \
+            *(u32x4*)(ws_ + (q >> 3) * CV_LDP + (q & 7) * 8) = wr[i];                             \
+        }                                                                                         \
+    }
 
-    load_stage(0);
-    store_stage(0);
+    CV_LOAD_STAGE(0)
+    CV_STORE_STAGE(0)
     __syncthreads();
     for (int s = 0; s < n_stages; ++s) {
         const int buf = s & 1;
-        if (s + 1 < n_stages) load_stage(s + 1);
+        if (s + 1 < n_stages) CV_LOAD_STAGE(s + 1)
         const bf16* xs = Xs + buf * XS_ELEMS;
         const bf16* ws = Ws + buf * WS_ELEMS;
 #pragma unroll
@@ -140,9 +139,11 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
             }
         }
-        if (s + 1 < n_stages) store_stage(buf ^ 1);
+        if (s + 1 < n_stages) CV_STORE_STAGE(buf ^ 1)
         __syncthreads();
     }
+#undef CV_LOAD_STAGE
+#undef CV_STORE_STAGE
 
     // ---- epilogue: bias + ReLU (forward) or ReLU mask (data-gradient), zero outside the grid,
     //      round to bfloat16, stage the tile in LDS as [position][channel]
@@ -208,7 +209,7 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
 template <int BN>
 static size_t conv_smem_bytes()
 {
-    return (size_t)2 * ((CV_BM + 2) * CV_LDP + 3 * BN * CV_LDP) * sizeof(bf16);
+    return (size_t)2 * (160 * CV_LDP + 3 * BN * CV_LDP) * sizeof(bf16);
 }
 
 bool conv3x3_mfma_supported(int cin, int cout) { return cin % CV_BK == 0 && cout % 32 == 0 && cout >= 32; }

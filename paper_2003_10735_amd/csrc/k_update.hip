@@ -8,13 +8,12 @@ namespace st {
 // theta <- theta - lr * v,  v <- mu * v + g  (mu == 0: v is not touched).  g is the sum, in
 // ascending order, of the partial gradients the backward kernels left behind: `splits1` copies
 // for W1/b1 and `splits2` for W2/b2 (position splits of the weight-gradient kernels, `stride`
-// floats apart), and `blocks3` per-block slots for W3/b3 (0: they sit in copy 0 like the rest).
+// floats apart); W3/b3 sit in copy 0 (k_reduce3 has already added their per-block slots).
 // Also refreshes the bfloat16 copies of the new weights:
 //   wq1, wq2, wq3 : same (internal) order as theta, for the forward convolutions
 //   wq2t          : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
 struct UpdateArgs {
     float* theta; float* vel; const float* grad; size_t stride; int splits1, splits2;
-    const float* part3; int blocks3; size_t slot3;
     bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
     ParamOffsets po; int c1, c2;
     float lr, mu;
@@ -27,17 +26,9 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a)
     if (j >= a.po.total) return;
     float w = a.theta[j];
     if (a.do_step) {
-        float g;
-        if (j >= a.po.W3 && a.blocks3 > 0) {
-            // slot layout: [32 classes][c2] weights, then [32] biases
-            const size_t r = j >= a.po.b3 ? (size_t)32 * a.c2 + (j - a.po.b3) : j - a.po.W3;
-            g = a.part3[r];
-            for (int s = 1; s < a.blocks3; ++s) g += a.part3[(size_t)s * a.slot3 + r];
-        } else {
-            const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
-            g = a.grad[j];
-            for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
-        }
+        const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
+        float g = a.grad[j];
+        for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
         if (a.mu != 0.f) {
             const float v = __builtin_fmaf(a.mu, a.vel[j], g);
             a.vel[j] = v;
@@ -69,9 +60,6 @@ void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_
     a.stride = p.po.total;
     a.splits1 = p.mfma ? p.splits1 : 1;
     a.splits2 = p.mfma ? p.splits2 : 1;
-    a.part3 = (const float*)(ws + p.grad3);
-    a.blocks3 = p.mfma ? p.blocks3 : 0;
-    a.slot3 = conv3_bwd_slot_floats(p.g);
     a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
     a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
@@ -101,54 +89,101 @@ __device__ double miou_of(const unsigned long long* conf, int C)
     return present ? sum / present : 0.0;
 }
 
-// One block closes a forward pass: sums the tile losses in order (float64), divides by the
-// number of valid pixels, computes the per-frame mean IoU, copies the counts out when asked
-// and clears them for the next pass.
+// Sum of the per-block slots of the classifier layer's backward kernel into gradient copy 0.
+// One wavefront per parameter: lane l adds slots l, l+64, ... in order, then the 64 lane sums
+// are added by a fixed shuffle tree.
 __global__ void __launch_bounds__(256)
-k_finish_pass(const float* __restrict__ loss_part, int n_part, const unsigned long long* __restrict__ n_valid,
-              unsigned long long* __restrict__ conf, int n, int C, float* loss_out, double* miou_out,
-              long long* conf_out, double* metric_mean_out)
+k_reduce3(const float* __restrict__ part, int blocks, size_t slot, float* __restrict__ gW3,
+          float* __restrict__ gb3, int C, int c2)
 {
-    __shared__ double part[256];
-    __shared__ double miou_s[64];
-    double acc = 0.0;
-    // contiguous chunks per thread, then a fixed tree: independent of anything but n_part
-    const int per = (n_part + 255) / 256;
-    for (int i = threadIdx.x * per; i < min(n_part, (threadIdx.x + 1) * per); ++i) acc += (double)loss_part[i];
-    part[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0 && loss_out) {
-        const unsigned long long nv = *n_valid;
-        *loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
-    }
-    for (int f = threadIdx.x; f < n; f += 256) {
-        const double m = miou_of(conf + (size_t)f * C * C, C);
-        if (miou_out) miou_out[f] = m;
-        if (f < 64) miou_s[f] = m;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0 && metric_mean_out) {
-        double s = 0.0;
-        for (int f = 0; f < n; ++f) s += (f < 64) ? miou_s[f] : miou_of(conf + (size_t)f * C * C, C);
-        *metric_mean_out = s / n;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < n * C * C; i += 256) {
-        if (conf_out) conf_out[i] = (long long)conf[i];
-        conf[i] = 0ull;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int n_w = C * c2;
+    if (j >= n_w + C) return;
+    const size_t r = j < n_w ? (size_t)j : (size_t)32 * c2 + (j - n_w);   // slot: [32][c2] weights, [32] biases
+    float acc = 0.f;
+    for (int s = lane; s < blocks; s += 64) acc += part[(size_t)s * slot + r];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) {
+        if (j < n_w) gW3[j] = acc;
+        else gb3[j - n_w] = acc;
     }
 }
 
-void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
-                 double* metric_mean_out)
+void reduce_grad3(Ctx& c, const Plan& p, char* ws)
 {
-    ST_LAUNCH(c, "finish_pass", k_finish_pass, dim3(1), dim3(256), 0, (const float*)(ws + p.loss_part),
+    float* grad = (float*)(ws + p.grad);
+    const int n = p.g.C * p.g.c2 + p.g.C;
+    ST_LAUNCH(c, "reduce_grad3", k_reduce3, dim3(cdiv(n, 4)), dim3(256), 0, (const float*)(ws + p.grad3),
+              p.blocks3, conv3_bwd_slot_floats(p.g), grad + p.po.W3, grad + p.po.b3, p.g.C, p.g.c2);
+}
+
+// Closes a forward pass.  Block f < n: mean IoU of frame f from its confusion counts (copied out
+// when asked, then cleared for the next pass).  Block n: the tile losses added in a fixed order
+// (float64) and divided by the number of valid pixels.
+__global__ void __launch_bounds__(256)
+k_finish_pass(const float* __restrict__ loss_part, int n_part, const unsigned long long* __restrict__ n_valid,
+              unsigned long long* __restrict__ conf, int n, int C, float* loss_out, double* miou_a,
+              double* miou_b, long long* conf_out)
+{
+    __shared__ double part[256];
+    __shared__ unsigned long long cl[32 * 32];
+    __shared__ double iou[32];
+    __shared__ int present[32];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x == n) {
+        double acc = 0.0;
+        const int per = (n_part + 255) / 256;
+        for (int i = tid * per; i < min(n_part, (tid + 1) * per); ++i) acc += (double)loss_part[i];
+        part[tid] = acc;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s) part[tid] += part[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0 && loss_out) {
+            const unsigned long long nv = *n_valid;
+            *loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
+        }
+        return;
+    }
+    const int f = blockIdx.x;
+    unsigned long long* cf = conf + (size_t)f * C * C;
+    for (int i = tid; i < C * C; i += 256) {
+        const unsigned long long v = cf[i];
+        cl[i] = v;
+        if (conf_out) conf_out[(size_t)f * C * C + i] = (long long)v;
+        cf[i] = 0ull;
+    }
+    __syncthreads();
+    if (tid < C) {
+        unsigned long long row = 0, col = 0;
+        for (int k = 0; k < C; ++k) { row += cl[tid * C + k]; col += cl[k * C + tid]; }
+        const unsigned long long inter = cl[tid * C + tid];
+        present[tid] = row != 0;
+        iou[tid] = row ? (double)inter / (double)(row + col - inter) : 0.0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double sum = 0.0;
+        int cnt = 0;
+        for (int c = 0; c < C; ++c)
+            if (present[c]) { sum += iou[c]; ++cnt; }
+        const double m = cnt ? sum / cnt : 0.0;
+        if (miou_a) miou_a[f] = m;
+        if (miou_b) miou_b[f] = m;
+    }
+}
+
+// miou_ws: per-frame metric kept in the workspace (for the host-side loop exits);
+// miou_out: the caller's array (may be null)
+void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
+{
+    ST_LAUNCH(c, "finish_pass", k_finish_pass, dim3(p.g.n + 1), dim3(256), 0, (const float*)(ws + p.loss_part),
               loss_blocks(p.g), (const unsigned long long*)(ws + p.counters),
-              (unsigned long long*)(ws + p.conf), p.g.n, p.g.C, loss_out, miou_out, conf_out, metric_mean_out);
+              (unsigned long long*)(ws + p.conf), p.g.n, p.g.C, loss_out, (double*)(ws + p.scal), miou_out,
+              conf_out);
 }
 
 // ------------------------------------------------------------------ stand-alone metric

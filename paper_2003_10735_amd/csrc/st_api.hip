@@ -154,7 +154,7 @@ Plan make_plan(const st_head_desc& d)
     p.loss_part = take(off, (size_t)loss_blocks(g) * 4);
     p.counters = take(off, 256);                       // [0] number of valid pixels
     p.conf = take(off, (size_t)g.n * g.C * g.C * 8);
-    p.scal = take(off, 256);                           // [0] mean metric of the last pass (double)
+    p.scal = take(off, (size_t)g.n * 8);               // per-frame mean IoU of the last pass (double)
     p.total = off;
     return p;
 }
@@ -198,6 +198,7 @@ static void backward(Ctx& c, const Plan& p, char* ws)
                  (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1);
     wgrad3x3_mfma(c, "conv1_wgrad_mfma", p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT),
                   grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1);
+    reduce_grad3(c, p, ws);
 }
 
 }  // namespace st
@@ -294,6 +295,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     count_valid(c, g, teacher_labels, n_valid);
 
     double best_metric = -1.0;
+    std::vector<double> frame_metric;
     int taken = 0;
     bool have_best = false;
     for (int it = 0; it <= steps; ++it) {
@@ -304,15 +306,18 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last);
         finish_pass(c, p, ws, (out && out->losses) ? out->losses + it : nullptr,
                     (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr,
-                    (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr,
-                    metric_dev);
+                    (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr);
         bool stop = last;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
-            double metric = 0.0;
-            ST_HIP(c, hipMemcpyAsync(&metric, metric_dev, sizeof(double), hipMemcpyDeviceToHost, c.stream));
+            frame_metric.resize(g.n);
+            ST_HIP(c, hipMemcpyAsync(frame_metric.data(), metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost,
+                                     c.stream));
             ST_HIP(c, hipStreamSynchronize(c.stream));
             if (c.status != ST_OK) break;
+            double metric = 0.0;
+            for (int f = 0; f < g.n; ++f) metric += frame_metric[f];
+            metric /= g.n;
             if (it == 0) {
                 best_metric = metric;
                 if (return_best) {

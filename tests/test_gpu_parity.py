@@ -175,3 +175,35 @@ def test_training_loop_exits():
     # and the whole trace agrees with the oracle's run of Algorithm 1
     ora = O.train(O.desc_of(wl), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 8, wl.lr, 1.5)
     np.testing.assert_allclose(m, ora["metrics"], atol=5e-3)
+
+
+MFMA_CASES = [
+    dict(n=1, c_in=64, h=12, w=40, c1=64, c2=64, n_classes=19),
+    dict(n=2, c_in=128, h=9, w=21, c1=64, c2=128, n_classes=21, ignore_index=255, ignore_fraction=0.05,
+         momentum=0.9),
+    dict(n=1, c_in=64, h=3, w=5, c1=96, c2=256, n_classes=5),
+    dict(n=3, c_in=64, h=17, w=9, c1=32, c2=64, n_classes=32),
+]
+
+
+@pytest.mark.parametrize("case", range(len(MFMA_CASES)))
+def test_matrix_core_path_small_shapes(case):
+    """Shapes that take the MFMA kernels (channels in multiples of 64 / 32) with ragged grids:
+    several position tiles, a ragged last tile, more than one frame."""
+    wl = WL.small_variant(WL.WORKLOADS["720p"], steps=3, lr=0.02, n_sites=9, **MFMA_CASES[case])
+    f, lab, p = inputs(wl)
+    gpu = run_gpu(wl, f, lab, p)
+    check_staged_bit_exact(wl, gpu, lab)
+    ora = run_oracle(wl, f, lab, p, bf16_operands=False)
+    orq = run_oracle(wl, f, lab, p, bf16_operands=True)
+    assert rel_err(gpu["losses"], ora["losses"]) < 2e-2
+    assert rel_err(gpu["params"], ora["params"]) < 2e-2
+    assert rel_err(gpu["losses"], orq["losses"]) < 5e-4
+    assert rel_err(gpu["params"], orq["params"]) < 5e-4
+    assert rel_err(gpu["params"] - p, orq["params"] - p) < 3e-2
+    if wl.momentum:
+        assert rel_err(gpu["velocity"], orq["velocity"]) < 3e-2
+    # run twice: bit-identical (fixed-order reductions, no floating-point atomics)
+    again = run_gpu(wl, f, lab, p)
+    for k in ("params", "losses", "mious", "conf", "pred"):
+        np.testing.assert_array_equal(gpu[k], again[k])
