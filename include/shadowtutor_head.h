@@ -154,7 +154,7 @@ const char* st_version(void);
 /* Byte offsets of the library's internal buffers inside `workspace`, so that a test can look
  * at intermediate tensors after a call.  Offsets are 0 for buffers this shape does not use. */
 typedef struct st_workspace_layout {
-    size_t feat;      /* features, position-major [n, h+2, w+2, c_in] with a zero border    */
+    size_t feat;      /* features, position-major [n, h+2, row_pitch, c_in], zero border    */
     size_t a1, a2;    /* activations after ReLU, same layout, c1 / c2 channels              */
     size_t da1, da2;  /* back-propagated gradients (after the ReLU mask), same layout       */
     size_t z;         /* low-resolution logits [n, C, h, w] float32                         */
@@ -163,6 +163,7 @@ typedef struct st_workspace_layout {
     size_t grad;      /* parameter gradient, internal order                                 */
     size_t elem_size; /* bytes per activation element: 4 (float32 path) or 2 (bfloat16)     */
     size_t total;     /* == st_workspace_bytes                                              */
+    size_t row_pitch; /* cells per padded row: w + 2 rounded up to a multiple of 8          */
 } st_workspace_layout;
 
 int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out);

@@ -43,7 +43,7 @@ class StDistillResult(C.Structure):
 
 class StWorkspaceLayout(C.Structure):
     _fields_ = [(k, C.c_size_t) for k in ("feat", "a1", "a2", "da1", "da2", "z", "g", "theta",
-                                           "grad", "elem_size", "total")]
+                                           "grad", "elem_size", "total", "row_pitch")]
 
 
 class StKernelStat(C.Structure):

@@ -149,11 +149,11 @@ k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, cons
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const bf16* xrow = a2T + (size_t)(t * 32 + l32) * PPT + guard + m0 + lhi * 8;
+        const bf16* xrow = a2T + xt_index(t * 32 + l32, guard + m0 + lhi * 8, PPT / 8);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
-            const bf16x8 xf = *(const bf16x8*)(xrow + ks * 16);
+            const bf16x8 xf = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups further
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf, acc, 0, 0, 0);
         }
 #pragma unroll
@@ -180,7 +180,7 @@ k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, cons
         bf16x8 ov;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ov[e] = Os[(pg * 8 + e) * OLD + o];
-        *(bf16x8*)(da2T + (size_t)o * PPT + guard + m0 + pg * 8) = ov;
+        *(bf16x8*)(da2T + xt_index(o, guard + m0 + pg * 8, PPT / 8)) = ov;
     }
 }
 

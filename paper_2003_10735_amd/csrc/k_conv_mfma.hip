@@ -9,13 +9,16 @@
 // positions are forced to zero, which keeps the border of the output zero as well).  Guard rows
 // in front of and behind every activation buffer make all reads in-bounds without tests.
 //
-// Block = 256 threads = 4 wavefronts, tile = 128 positions x BN output channels.
+// Block = 512 threads = 8 wavefronts, tile = 128 positions x BN output channels.  Wavefronts
+// 0-3 and 4-7 cover the same 2 x 2 arrangement of sub-tiles and split the K steps of every
+// stage between them (two wavefronts per SIMD: while one waits for its LDS fragments the other
+// one's MFMAs run); their accumulators are added through LDS once, before the epilogue.
 // K loop: stages of (one kernel row kh) x (64 input channels).  A stage holds in LDS
 //   Xs: 130 activation rows (the tile's rows shifted by kh, plus one on each side) -- the three
 //       taps kw = 0,1,2 of that kernel row read the same slab at row offsets 0,1,2;
 //   Ws: 3 x BN weight rows.
-// Stages are double-buffered: the global loads of stage s+1 are in flight while the matrix
-// cores work on stage s.  LDS rows are padded by 16 bytes so that the 16-byte fragment reads of
+// Stages are pipelined three deep (global -> registers, registers -> LDS, LDS -> matrix cores),
+// so the global loads of stage s+2 are in flight while the matrix cores work on stage s.  LDS rows are padded by 16 bytes so that the 16-byte fragment reads of
 // 32 consecutive rows spread over all banks.
 //
 // The weights are the MFMA A operand (rows = output channels) and the activations the B operand
@@ -38,20 +41,21 @@ struct ConvArgs {
     const float* bias;  // EPI 0
     const bf16* mask;   // EPI 1: activation whose sign gates the gradient, [PP][cout]
     bf16* Y;            // [PP][cout] or nullptr
-    bf16* YT;           // [cout][PPT], position mp at column guard + mp, or nullptr
-    int PP, Hp, Wp, cin, cout, PPT, guard;
+    bf16* YT;           // channel-major copy, blocked layout of xt_index(), or nullptr
+    int PP, Hp, Wp, h, w, cin, cout, PPT, guard;
     int m_tiles, n_tiles, tiles_per_xcd;
 };
 
 template <int BN, int EPI>
-__global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
+__global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 {
     constexpr int TA = BN / 64;          // 32-row weight fragments per wavefront
-    // 130 activation rows are needed; 160 are staged so that every thread moves the same
-    // number of 16-byte chunks (5) without a bounds test -- the extra rows are never read back
-    constexpr int XS_ROWS = 160;
+    constexpr int NT = 512;                // threads per block
+    constexpr int XS_ROWS = CV_BM + 2;
+    // 16-byte chunks per stage; every thread moves the same number without a bounds test: the
+    // activation slots beyond the last chunk wrap around and re-copy a chunk (same bytes)
     constexpr int XS_CHUNKS = XS_ROWS * 8, WS_CHUNKS = 3 * BN * 8;
-    constexpr int XS_PER_T = XS_CHUNKS / 256, WS_PER_T = WS_CHUNKS / 256;
+    constexpr int XS_PER_T = (XS_CHUNKS + NT - 1) / NT, WS_PER_T = WS_CHUNKS / NT;
     constexpr int XS_ELEMS = XS_ROWS * CV_LDP, WS_ELEMS = 3 * BN * CV_LDP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Xs = (bf16*)smem_raw;                       // [2][XS_ROWS][LDP]
@@ -66,7 +70,7 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
     const int m0 = mt * CV_BM, n0 = nt * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave & 1, wm = wave >> 1;
+    const int wn = wave & 1, wm = (wave >> 1) & 1, kgrp = wave >> 2;
     const int l32 = lane & 31, lhi = lane >> 5;
 
     f32x16 acc[TA][2];
@@ -79,83 +83,121 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
 
     const int c_chunks = a.cin / CV_BK;
     const int n_stages = 3 * c_chunks;
-    // prefetch registers of one stage (kept as plain unrolled register arrays)
-    u32x4 xr[XS_PER_T], wr[WS_PER_T];
+    // Three-deep pipeline: while the matrix cores work on stage s out of one LDS buffer, the
+    // registers holding stage s+1 (loaded during stage s-1) are written to the other buffer and
+    // the global loads of stage s+2 are issued into the second register set.  A load therefore
+    // has a whole stage of matrix work to complete before anything waits for it.
+    u32x4 xr[2][XS_PER_T], wr[2][WS_PER_T];
 
-#define CV_LOAD_STAGE(S)                                                                          \
+#define CV_LOAD(SET, S)                                                                           \
     {                                                                                             \
         const int kh_ = (S) / c_chunks, c0_ = ((S) % c_chunks) * CV_BK;                           \
         const long long row0_ = (long long)m0 - 1 + (long long)(kh_ - 1) * a.Wp;                  \
         _Pragma("unroll") for (int i = 0; i < XS_PER_T; ++i) {                                    \
-            const int q = tid + i * 256;                                                          \
-            xr[i] = *(const u32x4*)(a.X + (row0_ + (q >> 3)) * a.cin + c0_ + (q & 7) * 8);        \
+            int q = tid + i * NT;                                                                 \
+            q = q < XS_CHUNKS ? q : q - XS_CHUNKS;                                                \
+            xr[SET][i] = *(const u32x4*)(a.X + (row0_ + (q >> 3)) * a.cin + c0_ + (q & 7) * 8);   \
         }                                                                                         \
         _Pragma("unroll") for (int i = 0; i < WS_PER_T; ++i) {                                    \
-            const int q = tid + i * 256;                                                          \
+            const int q = tid + i * NT;                                                           \
             const int row = q >> 3;                                                               \
             const int n = min(n0 + row % BN, a.cout - 1);                                         \
-            wr[i] = *(const u32x4*)(a.Wq + ((size_t)n * 9 + kh_ * 3 + row / BN) * a.cin + c0_ +   \
-                                    (q & 7) * 8);                                                 \
+            wr[SET][i] = *(const u32x4*)(a.Wq + ((size_t)n * 9 + kh_ * 3 + row / BN) * a.cin +    \
+                                         c0_ + (q & 7) * 8);                                      \
         }                                                                                         \
     }
-#define CV_STORE_STAGE(BUF)                                                                       \
+#define CV_STORE(SET, BUF)                                                                        \
     {                                                                                             \
         bf16* xs_ = Xs + (BUF) * XS_ELEMS;                                                        \
         bf16* ws_ = Ws + (BUF) * WS_ELEMS;                                                        \
         _Pragma("unroll") for (int i = 0; i < XS_PER_T; ++i) {                                    \
-            const int q = tid + i * 256;                                                          \
-            *(u32x4*)(xs_ + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[i];                             \
+            int q = tid + i * NT;                                                                 \
+            q = q < XS_CHUNKS ? q : q - XS_CHUNKS;                                                \
+            *(u32x4*)(xs_ + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[SET][i];                        \
         }                                                                                         \
         _Pragma("unroll") for (int i = 0; i < WS_PER_T; ++i) {                                    \
-            const int q = tid + i * 256;                                                          \
-            *(u32x4*)(ws_ + (q >> 3) * CV_LDP + (q & 7) * 8) = wr[i];                             \
+            const int q = tid + i * NT;                                                           \
+            *(u32x4*)(ws_ + (q >> 3) * CV_LDP + (q & 7) * 8) = wr[SET][i];                        \
+        }                                                                                         \
+    }
+#define CV_COMPUTE(BUF, KW)                                                                       \
+    {                                                                                             \
+        const bf16* xs = Xs + (BUF) * XS_ELEMS;                                                   \
+        const bf16* ws = Ws + (BUF) * WS_ELEMS;                                                   \
+        _Pragma("unroll") for (int k2 = 0; k2 < CV_BK / 32; ++k2) {                               \
+            const int col = (k2 * 2 + kgrp) * 16 + lhi * 8;                                       \
+            bf16x8 xf[2], wf[TA];                                                                 \
+            _Pragma("unroll") for (int j = 0; j < 2; ++j)                                         \
+                xf[j] = *(const bf16x8*)(xs + (wm * 64 + j * 32 + l32 + (KW)) * CV_LDP + col);    \
+            _Pragma("unroll") for (int i = 0; i < TA; ++i)                                        \
+                wf[i] = *(const bf16x8*)(ws + ((KW) * BN + wn * (BN / 2) + i * 32 + l32) * CV_LDP + col); \
+            _Pragma("unroll") for (int i = 0; i < TA; ++i)                                        \
+                _Pragma("unroll") for (int j = 0; j < 2; ++j)                                     \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0); \
         }                                                                                         \
     }
 
-    CV_LOAD_STAGE(0)
-    CV_STORE_STAGE(0)
+    CV_LOAD(0, 0)
+    if (n_stages > 1) CV_LOAD(1, 1)
+    CV_STORE(0, 0)
     __syncthreads();
-    for (int s = 0; s < n_stages; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < n_stages) CV_LOAD_STAGE(s + 1)
-        const bf16* xs = Xs + buf * XS_ELEMS;
-        const bf16* ws = Ws + buf * WS_ELEMS;
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) {
-#pragma unroll
-            for (int ks = 0; ks < CV_BK / 16; ++ks) {
-                const int col = ks * 16 + lhi * 8;
-                bf16x8 xf[2], wf[TA];
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    xf[j] = *(const bf16x8*)(xs + (wm * 64 + j * 32 + l32 + kw) * CV_LDP + col);
-#pragma unroll
-                for (int i = 0; i < TA; ++i)
-                    wf[i] = *(const bf16x8*)(ws + (kw * BN + wn * (BN / 2) + i * 32 + l32) * CV_LDP + col);
-#pragma unroll
-                for (int i = 0; i < TA; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-            }
-        }
-        if (s + 1 < n_stages) CV_STORE_STAGE(buf ^ 1)
+    for (int s = 0; s < n_stages; s += 2) {
+        // even stage s: LDS buffer 0; register set 1 holds stage s+1; set 0 is free
+        if (s + 2 < n_stages) CV_LOAD(0, s + 2)
+        CV_COMPUTE(0, 0)
+        if (s + 1 < n_stages) CV_STORE(1, 1)
+        CV_COMPUTE(0, 1)
+        CV_COMPUTE(0, 2)
+        __syncthreads();
+        if (s + 1 >= n_stages) break;
+        // odd stage s+1: LDS buffer 1; register set 0 holds stage s+2; set 1 is free
+        if (s + 3 < n_stages) CV_LOAD(1, s + 3)
+        CV_COMPUTE(1, 0)
+        if (s + 2 < n_stages) CV_STORE(0, 0)
+        CV_COMPUTE(1, 1)
+        CV_COMPUTE(1, 2)
         __syncthreads();
     }
-#undef CV_LOAD_STAGE
-#undef CV_STORE_STAGE
+#undef CV_LOAD
+#undef CV_STORE
+#undef CV_COMPUTE
 
     // ---- epilogue: bias + ReLU (forward) or ReLU mask (data-gradient), zero outside the grid,
     //      round to bfloat16, stage the tile in LDS as [position][channel]
+    // the second K group hands its accumulators to the first through LDS
+    {
+        float* red = (float*)smem_raw;   // [4 wavefronts][TA * 2 * 16][64]
+        if (kgrp == 1) {
+#pragma unroll
+            for (int i = 0; i < TA; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        red[(((wave & 3) * TA * 2 + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (kgrp == 0) {
+#pragma unroll
+            for (int i = 0; i < TA; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][j][r] += red[(((wave & 3) * TA * 2 + i * 2 + j) * 16 + r) * 64 + lane];
+        }
+        __syncthreads();
+    }
     constexpr int OLD = BN + 8;
     bf16* Os = (bf16*)smem_raw;     // [CV_BM][OLD]; all waves are past the last barrier
+    if (kgrp == 0) {
     const int frame = a.Hp * a.Wp;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int p = wm * 64 + j * 32 + l32;
         const int mp = m0 + p;
         const int rr = mp % frame, y = rr / a.Wp, x = rr - y * a.Wp;
-        const bool inside = mp < a.PP && y >= 1 && y <= a.Hp - 2 && x >= 1 && x <= a.Wp - 2;
+        const bool inside = mp < a.PP && y >= 1 && y <= a.h && x >= 1 && x <= a.w;
 #pragma unroll
         for (int i = 0; i < TA; ++i) {
 #pragma unroll
@@ -182,11 +224,12 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
             }
         }
     }
+    }
     __syncthreads();
     const int n_valid = min(BN, a.cout - n0);
     if (a.Y) {
         // position-major: 16 bytes = 8 channels of one position
-        for (int q = tid; q < CV_BM * (BN / 8); q += 256) {
+        for (int q = tid; q < CV_BM * (BN / 8); q += NT) {
             const int p = q / (BN / 8), part = q % (BN / 8);
             if (m0 + p < a.PP && part * 8 < n_valid)
                 *(uint4*)(a.Y + (size_t)(m0 + p) * a.cout + n0 + part * 8) = *(const uint4*)(Os + p * OLD + part * 8);
@@ -194,13 +237,13 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
     }
     if (a.YT) {
         // channel-major: 16 bytes = 8 consecutive positions of one channel
-        for (int q = tid; q < (CV_BM / 8) * BN; q += 256) {
+        for (int q = tid; q < (CV_BM / 8) * BN; q += NT) {
             const int c = q % BN, pg = q / BN;
             if (c < n_valid) {
                 bf16x8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = Os[(pg * 8 + e) * OLD + c];
-                *(bf16x8*)(a.YT + (size_t)(n0 + c) * a.PPT + a.guard + m0 + pg * 8) = o;
+                *(bf16x8*)(a.YT + xt_index(n0 + c, a.guard + m0 + pg * 8, a.PPT / 8)) = o;
             }
         }
     }
@@ -209,7 +252,7 @@ __global__ void __launch_bounds__(256) k_conv3x3_mfma(ConvArgs a)
 template <int BN>
 static size_t conv_smem_bytes()
 {
-    return (size_t)2 * (160 * CV_LDP + 3 * BN * CV_LDP) * sizeof(bf16);
+    return (size_t)2 * ((CV_BM + 2) * CV_LDP + 3 * BN * CV_LDP) * sizeof(bf16);
 }
 
 bool conv3x3_mfma_supported(int cin, int cout) { return cin % CV_BK == 0 && cout % 32 == 0 && cout >= 32; }
@@ -220,7 +263,8 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
 {
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
-    a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.cin = cin; a.cout = cout;
+    a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.h = p.g.h; a.w = p.g.w;
+    a.cin = cin; a.cout = cout;
     a.PPT = p.PPT; a.guard = p.guard;
     constexpr int BN = 64;
     a.m_tiles = cdiv(a.PP, CV_BM);
@@ -235,8 +279,8 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
         (void)hipFuncSetAttribute((const void*)k_conv3x3_mfma<BN, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    if (epi == 0) ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 0>), grid, dim3(256), smem, a);
-    else ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 1>), grid, dim3(256), smem, a);
+    if (epi == 0) ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 0>), grid, dim3(512), smem, a);
+    else ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 1>), grid, dim3(512), smem, a);
 }
 
 }  // namespace st

@@ -1,6 +1,7 @@
 // Layout kernels: zero fill, feature packing (caller's NCHW -> padded position-major), and the
 // permutation between the caller's parameter order (OIHW) and the internal one ([o][kh][kw][i]).
 #include "st_kernels.hpp"
+#include "st_mfma.hpp"
 
 namespace st {
 
@@ -23,8 +24,8 @@ void zero_bytes(Ctx& c, void* p, size_t bytes)
 }
 
 // features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
-// outT != nullptr, a channel-major copy [c_in][PPT] (padded position mp at column guard + mp)
-// for the weight-gradient kernel.
+// outT != nullptr, a channel-major copy in the blocked layout of xt_index() for the
+// weight-gradient kernel.
 // One block transposes a 32-channel x 32-column tile of one row through LDS so that both the
 // read (along x) and the write (along c) are contiguous.
 template <class Tin, class E>
@@ -41,7 +42,7 @@ k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ 
         if (c < g.c_in && x < g.w) v = to_f32(f[(((size_t)img * g.c_in + c) * g.h + y) * g.w + x]);
         tile[k][tx] = v;
         if (outT && c < g.c_in && x < g.w)
-            outT[(size_t)c * PPT + guard + ((size_t)img * g.Hp + y + 1) * g.Wp + x + 1] = from_f32<E>(v);
+            outT[xt_index(c, guard + (img * g.Hp + y + 1) * g.Wp + x + 1, PPT / 8)] = from_f32<E>(v);
     }
     __syncthreads();
     for (int k = ty; k < 32; k += 8) {

@@ -8,10 +8,12 @@
 // the border of the padded grid, so the sum may run over all padded positions.
 //
 // One wavefront accumulates a 32 (o) x 32 (i) x 9 (taps) block (144 accumulator registers): per
-// 16 positions it loads one dY fragment and, per kernel row kh, one 16-byte window of X plus the
-// 4 bytes on each side; the kw = 0 and kw = 2 operands are the same window shifted by one
-// element, built in registers (v_alignbyte) instead of being loaded again.  9 MFMAs per 4 wide
-// loads.  A bigger block would need fewer loads per MFMA but leaves too few blocks to fill the
+// 16 positions it loads one dY fragment and, per kernel row kh, one 16-byte window of X (the
+// row pitch of the padded grid is a multiple of 8, so all of them are aligned fragments of the
+// blocked channel-major layout and every wavefront load is one contiguous kilobyte); the kw = 0
+// and kw = 2 operands are the same window shifted by one element, built in registers
+// (v_alignbyte + a cross-lane permute for the element that enters) instead of being loaded
+// again.  9 MFMAs per 4 loads.  A bigger block would need fewer loads per MFMA but leaves too few blocks to fill the
 // chip without multiplying the partial copies.
 //
 // The four wavefronts of a block own the same output block and a quarter each of the block's
@@ -23,8 +25,8 @@
 namespace st {
 
 struct WgradArgs {
-    const bf16* dYT;   // [cout][PPT]
-    const bf16* XT;    // [cin][PPT]
+    const bf16* dYT;   // channel-major copies in the blocked layout of xt_index()
+    const bf16* XT;
     float* dW;         // [splits][stride] : this layer's weight block, [o][9][cin]
     float* db;         // [splits][stride] : this layer's bias block
     size_t split_stride;
@@ -56,38 +58,84 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
 
     const int unit0 = (split * 4 + wave) * a.units_per_wave;
     const int unit1 = min(unit0 + a.units_per_wave, a.n_units);
-    const bf16* ya = a.dYT + (size_t)(o0 + l32) * a.PPT + a.guard + lhi * 8;
-    const bf16* xb = a.XT + (size_t)(i0 + l32) * a.PPT + a.guard + lhi * 8;
+    // blocked layout: one 8-position group of 32 channels is 256 elements; lane (l32, lhi) reads
+    // channel l32 of group 2u + lhi, so a wavefront's fragment load is one contiguous kilobyte
+    const int NG = a.PPT >> 3;
+    const bf16* ya = a.dYT + (((size_t)(o0 >> 5) * NG + (a.guard >> 3) + lhi) << 8) + l32 * 8;
+    const bf16* xb = a.XT + (((size_t)(i0 >> 5) * NG + (a.guard >> 3) + lhi) << 8) + l32 * 8;
+    const int row_groups = a.Wp >> 3;   // one kernel row = this many 8-position groups
     const bool want_bias = it == 0;
+    const int swap_addr = (lane ^ 32) << 2;   // ds_bpermute address of the lane holding the other half
 
-    for (int u = unit0; u < unit1; ++u) {
-        const int mp = u * 16;
-        const bf16x8 y0 = *(const bf16x8*)(ya + mp);
-        if (want_bias) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bsum += (float)y0[e];
-        }
+    // Operand ring: the loads of unit u + 3 are issued before the MFMAs of unit u, so that an L2
+    // round trip is covered by matrix work of the same wavefront (there is only one wavefront
+    // per SIMD: the accumulators take most of the register file).
+    constexpr int DEPTH = 4;
+    u32x4 ry[DEPTH], rx[DEPTH][3];
+#define WG_LOAD(SLOT, U)                                                                        \
+    {                                                                                           \
+        const ptrdiff_t g_ = (ptrdiff_t)(U) * 2 * 256;                                          \
+        ry[SLOT] = *(const u32x4*)(ya + g_);                                                    \
+        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh)                                        \
+            rx[SLOT][kh] = *(const u32x4*)(xb + g_ + (ptrdiff_t)(kh - 1) * row_groups * 256);   \
+    }
+    // The kw = 0 / kw = 2 operands are the kw = 1 window moved by one position.  The element that
+    // enters on the left is the last one of the previous 8-position group, the one on the right
+    // the first of the next group: both sit in the *other half* of the wavefront (lane ^ 32), in
+    // this unit's registers or in the neighbouring unit's, so they are fetched with a cross-lane
+    // permute instead of being loaded again.
+    unsigned int last_prev[3];   // for lhi = 0: dword 3 of the previous unit's upper half
+    unsigned int first_cur[3];   // for lhi = 0: dword 0 of this unit's upper half (computed one unit ahead)
+#define WG_COMPUTE(SLOT, NEXT)                                                                  \
+    {                                                                                           \
+        const bf16x8 y0 = as_bf16x8(ry[SLOT]);                                                  \
+        if (want_bias) {                                                                        \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) bsum += (float)y0[e];                 \
+        }                                                                                       \
+        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
+            const u32x4 w_ = rx[SLOT][kh];                                                      \
+            const unsigned int s3_ = __builtin_amdgcn_ds_bpermute(swap_addr, w_[3]);            \
+            const unsigned int n0_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]);  \
+            const unsigned int prev_ = lhi ? s3_ : last_prev[kh];                               \
+            const unsigned int next_ = lhi ? n0_ : first_cur[kh];                               \
+            last_prev[kh] = s3_;      /* lhi = 0 lanes: upper half of this unit, used next */   \
+            first_cur[kh] = n0_;      /* lhi = 0 lanes: upper half of the next unit */          \
+            u32x4 lft, rgt;                                                                     \
+            lft[0] = __builtin_amdgcn_alignbyte(w_[0], prev_, 2);                               \
+            lft[1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                               \
+            lft[2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                               \
+            lft[3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                               \
+            rgt[0] = lft[1]; rgt[1] = lft[2]; rgt[2] = lft[3];                                  \
+            rgt[3] = __builtin_amdgcn_alignbyte(next_, w_[3], 2);                               \
+            acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(lft), acc[kh * 3 + 0], 0, 0, 0); \
+            acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(w_), acc[kh * 3 + 1], 0, 0, 0);  \
+            acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(rgt), acc[kh * 3 + 2], 0, 0, 0); \
+        }                                                                                       \
+    }
+
+    if (unit0 < unit1) {
+        // unit0 - 1 (guard columns make it readable) supplies the first left neighbours
+        WG_LOAD(DEPTH - 1, unit0 - 1)
+        WG_LOAD(0, unit0)
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh) {
-            const bf16* src = xb + mp + (kh - 1) * a.Wp;
-            u32x4 d;
-            unsigned int prev, next;
-            __builtin_memcpy(&d, src, 16);
-            __builtin_memcpy(&prev, src - 2, 4);
-            __builtin_memcpy(&next, src + 8, 4);
-            u32x4 lft, rgt;   // window shifted to start one element earlier / later
-            lft[0] = __builtin_amdgcn_alignbyte(d[0], prev, 2);
-            lft[1] = __builtin_amdgcn_alignbyte(d[1], d[0], 2);
-            lft[2] = __builtin_amdgcn_alignbyte(d[2], d[1], 2);
-            lft[3] = __builtin_amdgcn_alignbyte(d[3], d[2], 2);
-            rgt[0] = lft[1]; rgt[1] = lft[2]; rgt[2] = lft[3];
-            rgt[3] = __builtin_amdgcn_alignbyte(next, d[3], 2);
-            const bf16x8 x0 = as_bf16x8(lft), x1 = as_bf16x8(d), x2 = as_bf16x8(rgt);
-            acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, x0, acc[kh * 3 + 0], 0, 0, 0);
-            acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, x1, acc[kh * 3 + 1], 0, 0, 0);
-            acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, x2, acc[kh * 3 + 2], 0, 0, 0);
+            last_prev[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[DEPTH - 1][kh][3]);
+            first_cur[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[0][kh][0]);
+        }
+#pragma unroll
+        for (int d = 1; d < DEPTH - 1; ++d)
+            if (unit0 + d <= unit1) WG_LOAD(d, unit0 + d)
+        // unit1 itself is loaded too (readable: tail guard): it supplies the last right neighbours
+        for (int u = unit0; u < unit1; u += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                if (u + d + DEPTH - 1 <= unit1) WG_LOAD((d + DEPTH - 1) % DEPTH, u + d + DEPTH - 1)
+                if (u + d < unit1) WG_COMPUTE(d, (d + 1) % DEPTH)
+            }
         }
     }
+#undef WG_LOAD
+#undef WG_COMPUTE
 
     // ---- add the four wavefronts in the order 3, 2, 1, 0 through LDS
     for (int w = 3; w >= 1; --w) {

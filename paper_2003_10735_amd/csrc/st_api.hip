@@ -227,7 +227,7 @@ int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out)
     const Plan p = make_plan(*desc);
     out->feat = p.feat; out->a1 = p.a1; out->a2 = p.a2; out->da1 = p.da1; out->da2 = p.da2;
     out->z = p.z; out->g = p.gz; out->theta = p.theta; out->grad = p.grad;
-    out->elem_size = p.esz; out->total = p.total;
+    out->elem_size = p.esz; out->total = p.total; out->row_pitch = (size_t)p.g.Wp;
     return ST_OK;
 }
 

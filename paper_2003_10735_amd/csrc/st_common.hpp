@@ -17,9 +17,12 @@ typedef __bf16 bf16;
 // Activations live position-major ("NHWC") on a grid padded by one zero cell on every side, so
 // a 3x3 tap is a plain offset and needs no bounds test:
 //   element (img, y, x, c)  ->  ((img * Hp + y + 1) * Wp + x + 1) * C + c
+// The row pitch Wp is w + 2 rounded up to a multiple of 8 (extra zero columns on the right): a
+// step of one row is then a multiple of 16 bytes in the channel-major copies, which keeps the
+// weight-gradient kernel's 8-position windows aligned.
 struct Geo {
     int n, h, w;     // frames and low-resolution grid
-    int Hp, Wp;      // padded grid: h + 2, w + 2
+    int Hp, Wp;      // padded grid: h + 2 rows of pitch Wp >= w + 2
     int H, W;        // frame resolution: 8h, 8w
     int c_in, c1, c2, C;
     int ignore_index;
@@ -32,7 +35,7 @@ inline Geo make_geo(const st_head_desc& d)
 {
     Geo g;
     g.n = d.n; g.h = d.h; g.w = d.w;
-    g.Hp = d.h + 2; g.Wp = d.w + 2;
+    g.Hp = d.h + 2; g.Wp = (d.w + 2 + 7) / 8 * 8;
     g.H = d.h * UP; g.W = d.w * UP;
     g.c_in = d.c_in; g.c1 = d.c1; g.c2 = d.c2; g.C = d.n_classes;
     g.ignore_index = d.ignore_index;

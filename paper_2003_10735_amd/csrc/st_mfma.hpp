@@ -11,4 +11,14 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].  Lane l supplies A[l % 32][8*(l/32) .. +7]
 // and B[8*(l/32) .. +7][l % 32]; it receives D[8*(r/4) + 4*(l/32) + r%4][l % 32] in register r.
+
+// Channel-major operand copies ("XT") feed the weight-gradient kernels, whose MFMA fragments are
+// 32 channels x 8 consecutive positions.  They are stored blocked so that such a fragment is one
+// contiguous 512-byte run and a wavefront's fragment load is fully coalesced:
+//     [channel / 32][column / 8][channel % 32][column % 8],   column = guard + padded position,
+// with NG = PPT / 8 column groups per channel block.
+__host__ __device__ __forceinline__ size_t xt_index(int c, int col, int NG)
+{
+    return (((size_t)(c >> 5) * NG + (col >> 3)) << 8) + ((c & 31) << 3) + (col & 7);
+}
 }  // namespace st
