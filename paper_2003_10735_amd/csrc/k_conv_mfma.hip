@@ -137,23 +137,33 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         }                                                                                         \
     }
 
+    // (loads and LDS stores are unconditional, with the stage index clamped to the last stage:
+    //  a load under a branch would force a wait for every outstanding load at the join; the
+    //  redundant copies at the tail land in the buffer nobody reads any more)
+    const int last = n_stages - 1;
     CV_LOAD(0, 0)
-    if (n_stages > 1) CV_LOAD(1, 1)
+    CV_LOAD(1, min(1, last))
     CV_STORE(0, 0)
     __syncthreads();
     for (int s = 0; s < n_stages; s += 2) {
         // even stage s: LDS buffer 0; register set 1 holds stage s+1; set 0 is free
-        if (s + 2 < n_stages) CV_LOAD(0, s + 2)
+        CV_LOAD(0, min(s + 2, last))
+        __builtin_amdgcn_sched_barrier(0);   // keep the loads first: the scheduler would sink them
         CV_COMPUTE(0, 0)
-        if (s + 1 < n_stages) CV_STORE(1, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        CV_STORE(1, 1)
+        __builtin_amdgcn_sched_barrier(0);
         CV_COMPUTE(0, 1)
         CV_COMPUTE(0, 2)
         __syncthreads();
         if (s + 1 >= n_stages) break;
         // odd stage s+1: LDS buffer 1; register set 0 holds stage s+2; set 1 is free
-        if (s + 3 < n_stages) CV_LOAD(1, s + 3)
+        CV_LOAD(1, min(s + 3, last))
+        __builtin_amdgcn_sched_barrier(0);
         CV_COMPUTE(1, 0)
-        if (s + 2 < n_stages) CV_STORE(0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        CV_STORE(0, 0)
+        __builtin_amdgcn_sched_barrier(0);
         CV_COMPUTE(1, 1)
         CV_COMPUTE(1, 2)
         __syncthreads();

@@ -17,8 +17,10 @@
 // chip without multiplying the partial copies.
 //
 // The four wavefronts of a block own the same output block and a quarter each of the block's
-// position range; they are added in LDS in a fixed order, and the grid's position splits are
-// added by the optimiser kernel, also in a fixed order: no floating-point atomics.
+// position range; they are added through LDS in a fixed order, and the grid's position splits
+// are added by the optimiser kernel, also in a fixed order: no floating-point atomics.  The
+// bias gradient (row sums of dY) comes from one extra MFMA against a fragment of ones in the
+// blocks of the first input-channel tile.
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
 
@@ -33,7 +35,7 @@ struct WgradArgs {
     int cin, cout, PPT, guard, Wp;
     int units_per_wave;   // 16-position units per wavefront
     int n_units;          // total units
-    int o_tiles, i_tiles;
+    int o_tiles, i_tiles, splits, items_per_xcd;
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -41,20 +43,25 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    float* red = (float*)smem_raw;    // [9][16][64] accumulators of one wavefront, then [64] bias sums
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int tile = blockIdx.x % (a.o_tiles * a.i_tiles), split = blockIdx.x / (a.o_tiles * a.i_tiles);
+    // XCD-aware order: consecutive blocks go to different XCDs; give each XCD a contiguous run
+    // of work items in split-major order, so that one XCD's L2 only ever sees about 1/8 of the
+    // positions (all channels) instead of every position of a few channels
+    const int tiles = a.o_tiles * a.i_tiles;
+    const int item = (blockIdx.x % 8) * a.items_per_xcd + blockIdx.x / 8;
+    if ((int)(blockIdx.x / 8) >= a.items_per_xcd || item >= tiles * a.splits) return;
+    const int split = item / tiles, tile = item % tiles;
     const int ot = tile / a.i_tiles, it = tile % a.i_tiles;
     const int o0 = ot * 32, i0 = it * 32;
 
-    f32x16 acc[9];
+    // acc[0..8]: the nine taps; acc[9]: row sums of dY (bias gradient), only in blocks with it == 0
+    f32x16 acc[10];
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < 10; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-    float bsum = 0.f;
 
     const int unit0 = (split * 4 + wave) * a.units_per_wave;
     const int unit1 = min(unit0 + a.units_per_wave, a.n_units);
@@ -66,11 +73,16 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
     const int row_groups = a.Wp >> 3;   // one kernel row = this many 8-position groups
     const bool want_bias = it == 0;
     const int swap_addr = (lane ^ 32) << 2;   // ds_bpermute address of the lane holding the other half
+    const bf16 one = (bf16)1.0f;
+    const bf16x8 ones = {one, one, one, one, one, one, one, one};
 
-    // Operand ring: the loads of unit u + 3 are issued before the MFMAs of unit u, so that an L2
-    // round trip is covered by matrix work of the same wavefront (there is only one wavefront
-    // per SIMD: the accumulators take most of the register file).
-    constexpr int DEPTH = 4;
+    // Operand ring: the loads of unit u + DEPTH - 1 are issued before the MFMAs of unit u, so
+    // that an L2 round trip is covered by matrix work of the same wavefront (there is only one
+    // wavefront per SIMD: the accumulators take most of the register file).
+#ifndef ST_WGRAD_DEPTH
+#define ST_WGRAD_DEPTH 8
+#endif
+    constexpr int DEPTH = ST_WGRAD_DEPTH;
     u32x4 ry[DEPTH], rx[DEPTH][3];
 #define WG_LOAD(SLOT, U)                                                                        \
     {                                                                                           \
@@ -82,31 +94,39 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
     // The kw = 0 / kw = 2 operands are the kw = 1 window moved by one position.  The element that
     // enters on the left is the last one of the previous 8-position group, the one on the right
     // the first of the next group: both sit in the *other half* of the wavefront (lane ^ 32), in
-    // this unit's registers or in the neighbouring unit's, so they are fetched with a cross-lane
-    // permute instead of being loaded again.
-    unsigned int last_prev[3];   // for lhi = 0: dword 3 of the previous unit's upper half
-    unsigned int first_cur[3];   // for lhi = 0: dword 0 of this unit's upper half (computed one unit ahead)
-#define WG_COMPUTE(SLOT, NEXT)                                                                  \
+    // this unit's registers or in a neighbouring unit's, so they are fetched with a cross-lane
+    // permute instead of being loaded again.  The permutes for unit u + 1 are issued while the
+    // MFMAs of unit u run (WG_NEIGHBOURS one unit ahead of WG_COMPUTE).
+    //   up3[kh]: dword 3 of lane^32 in the unit being prepared; dn0[kh]: dword 0 of lane^32 in the
+    //   unit after it.  For a lane of the lower half (lhi = 0) the left neighbour is the upper
+    //   half of the *previous* unit (carry_prev) and the right one the upper half of this unit
+    //   (carry_next, fetched when the previous unit was prepared).
+    unsigned int prev_cur[3], next_cur[3];      // neighbours of the unit about to be computed
+    unsigned int carry_prev[3], carry_next[3];
+#define WG_NEIGHBOURS(SLOT, NEXT, OUTP, OUTN)                                                   \
+    {                                                                                           \
+        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
+            const unsigned int up3_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[SLOT][kh][3]); \
+            const unsigned int dn0_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]); \
+            OUTP[kh] = lhi ? up3_ : carry_prev[kh];                                             \
+            OUTN[kh] = lhi ? dn0_ : carry_next[kh];                                             \
+            carry_prev[kh] = up3_;                                                              \
+            carry_next[kh] = dn0_;                                                              \
+        }                                                                                       \
+    }
+#define WG_COMPUTE(SLOT)                                                                        \
     {                                                                                           \
         const bf16x8 y0 = as_bf16x8(ry[SLOT]);                                                  \
-        if (want_bias) {                                                                        \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e) bsum += (float)y0[e];                 \
-        }                                                                                       \
+        if (want_bias) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, ones, acc[9], 0, 0, 0); \
         _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
             const u32x4 w_ = rx[SLOT][kh];                                                      \
-            const unsigned int s3_ = __builtin_amdgcn_ds_bpermute(swap_addr, w_[3]);            \
-            const unsigned int n0_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]);  \
-            const unsigned int prev_ = lhi ? s3_ : last_prev[kh];                               \
-            const unsigned int next_ = lhi ? n0_ : first_cur[kh];                               \
-            last_prev[kh] = s3_;      /* lhi = 0 lanes: upper half of this unit, used next */   \
-            first_cur[kh] = n0_;      /* lhi = 0 lanes: upper half of the next unit */          \
             u32x4 lft, rgt;                                                                     \
-            lft[0] = __builtin_amdgcn_alignbyte(w_[0], prev_, 2);                               \
+            lft[0] = __builtin_amdgcn_alignbyte(w_[0], prev_cur[kh], 2);                        \
             lft[1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                               \
             lft[2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                               \
             lft[3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                               \
             rgt[0] = lft[1]; rgt[1] = lft[2]; rgt[2] = lft[3];                                  \
-            rgt[3] = __builtin_amdgcn_alignbyte(next_, w_[3], 2);                               \
+            rgt[3] = __builtin_amdgcn_alignbyte(next_cur[kh], w_[3], 2);                        \
             acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(lft), acc[kh * 3 + 0], 0, 0, 0); \
             acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(w_), acc[kh * 3 + 1], 0, 0, 0);  \
             acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(rgt), acc[kh * 3 + 2], 0, 0, 0); \
@@ -114,63 +134,69 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
     }
 
     if (unit0 < unit1) {
-        // unit0 - 1 (guard columns make it readable) supplies the first left neighbours
+        // unit0 - 1 (guard columns make it readable) supplies the first left neighbours and
+        // unit1 (tail guard) the last right neighbours
+        // (all loads are unconditional, with the unit index clamped to unit1: a load under a
+        //  branch would force the compiler to wait for every outstanding load at the join)
         WG_LOAD(DEPTH - 1, unit0 - 1)
-        WG_LOAD(0, unit0)
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) WG_LOAD(d, min(unit0 + d, unit1))
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh) {
-            last_prev[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[DEPTH - 1][kh][3]);
-            first_cur[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[0][kh][0]);
+            carry_prev[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[DEPTH - 1][kh][3]);
+            carry_next[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[0][kh][0]);
         }
-#pragma unroll
-        for (int d = 1; d < DEPTH - 1; ++d)
-            if (unit0 + d <= unit1) WG_LOAD(d, unit0 + d)
-        // unit1 itself is loaded too (readable: tail guard): it supplies the last right neighbours
+        WG_NEIGHBOURS(0, 1, prev_cur, next_cur)
         for (int u = unit0; u < unit1; u += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                if (u + d + DEPTH - 1 <= unit1) WG_LOAD((d + DEPTH - 1) % DEPTH, u + d + DEPTH - 1)
-                if (u + d < unit1) WG_COMPUTE(d, (d + 1) % DEPTH)
+                WG_LOAD((d + DEPTH - 1) % DEPTH, min(u + d + DEPTH - 1, unit1))
+                if (u + d < unit1) {
+                    unsigned int prev_nxt[3], next_nxt[3];
+                    // neighbours of unit u + d + 1 (its right neighbours come from unit u + d + 2)
+                    if (u + d + 1 < unit1) WG_NEIGHBOURS((d + 1) % DEPTH, (d + 2) % DEPTH, prev_nxt, next_nxt)
+                    WG_COMPUTE(d)
+#pragma unroll
+                    for (int kh = 0; kh < 3; ++kh) { prev_cur[kh] = prev_nxt[kh]; next_cur[kh] = next_nxt[kh]; }
+                }
             }
         }
     }
 #undef WG_LOAD
+#undef WG_NEIGHBOURS
 #undef WG_COMPUTE
 
-    // ---- add the four wavefronts in the order 3, 2, 1, 0 through LDS
-    for (int w = 3; w >= 1; --w) {
-        if (wave == w) {
-#pragma unroll
-            for (int t = 0; t < 9; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) red[(t * 16 + r) * 64 + lane] = acc[t][r];
-            if (want_bias) red[9 * 16 * 64 + lane] = bsum;
-        }
-        __syncthreads();
-        if (wave == w - 1) {
-#pragma unroll
-            for (int t = 0; t < 9; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] += red[(t * 16 + r) * 64 + lane];
-            if (want_bias) bsum += red[9 * 16 * 64 + lane];
-        }
-        __syncthreads();
-    }
-    if (wave != 0) return;
-
-    float* dW = a.dW + (size_t)split * a.split_stride;
+    // ---- every wavefront leaves its block in LDS as [tap][o][i]; then all 256 threads add the
+    //      four copies in the order ((w0 + w1) + w2) + w3 and write the result with 16-byte stores
+    float* red = (float*)smem_raw;                 // [4][9 * 32 rows][32]
+    float* redb = red + 4 * 9 * 32 * 32;           // [4][32] row sums of dY
 #pragma unroll
     for (int t = 0; t < 9; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int o = o0 + (r >> 2) * 8 + lhi * 4 + (r & 3);
-            dW[((size_t)o * 9 + t) * a.cin + i0 + l32] = acc[t][r];
+            const int ol = (r >> 2) * 8 + lhi * 4 + (r & 3);
+            red[((wave * 9 + t) * 32 + ol) * 32 + l32] = acc[t][r];
         }
-    if (want_bias) {
-        // a lane pair (l, l + 32) holds the two halves of one output channel's sum
+    if (want_bias && l32 == 0) {
+        // every column of acc[9] holds the row sums; column 0 lives in lanes 0 and 32
+#pragma unroll
+        for (int r = 0; r < 16; ++r) redb[wave * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3)] = acc[9][r];
+    }
+    __syncthreads();
+    float* dW = a.dW + (size_t)split * a.split_stride;
+    for (int q = tid; q < 9 * 32 * 8; q += 256) {
+        const int row = q >> 3, part = q & 7;
+        const f32x4 v0 = *(const f32x4*)(red + ((0 * 9 * 32 + row) * 32 + part * 4));
+        const f32x4 v1 = *(const f32x4*)(red + ((1 * 9 * 32 + row) * 32 + part * 4));
+        const f32x4 v2 = *(const f32x4*)(red + ((2 * 9 * 32 + row) * 32 + part * 4));
+        const f32x4 v3 = *(const f32x4*)(red + ((3 * 9 * 32 + row) * 32 + part * 4));
+        const f32x4 sum = ((v0 + v1) + v2) + v3;
+        const int t = row >> 5, ol = row & 31;
+        *(f32x4*)(dW + ((size_t)(o0 + ol) * 9 + t) * a.cin + i0 + part * 4) = sum;
+    }
+    if (want_bias && tid < 32) {
         float* db = a.db + (size_t)split * a.split_stride;
-        const float other = __shfl(bsum, lane ^ 32, 64);
-        if (lhi == 0) db[o0 + l32] = bsum + other;
+        db[o0 + tid] = ((redb[tid] + redb[32 + tid]) + redb[64 + tid]) + redb[96 + tid];
     }
 }
 
@@ -196,13 +222,15 @@ void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, con
     a.n_units = cdiv(p.g.padded_positions(), 16);
     a.units_per_wave = cdiv(a.n_units, splits * 4);
     a.o_tiles = cout / 32; a.i_tiles = cin / 32;
-    const size_t smem = (size_t)(9 * 16 * 64 + 64) * sizeof(float);
+    const size_t smem = (size_t)(4 * 9 * 32 * 32 + 4 * 32) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void*)k_wgrad3x3_mfma, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         attr_set = true;
     }
-    ST_LAUNCH(c, name, k_wgrad3x3_mfma, dim3(a.o_tiles * a.i_tiles * splits), dim3(256), smem, a);
+    a.splits = splits;
+    a.items_per_xcd = cdiv(a.o_tiles * a.i_tiles * splits, 8);
+    ST_LAUNCH(c, name, k_wgrad3x3_mfma, dim3(a.items_per_xcd * 8), dim3(256), smem, a);
 }
 
 }  // namespace st
