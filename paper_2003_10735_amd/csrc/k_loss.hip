@@ -9,11 +9,20 @@
 // and lerp(a, b, t) is evaluated as fma(t, b - a, a), first along x, then along y, every
 // operation rounded once in float32.  The predicted class is decided on exactly these values.
 //
+// What depends on the labels but not on the logits is computed once per call
+// (k_label_adjoint): with U the up-sampling operator and Y the one-hot label map,
+//     T = U^T Y                      (exact in float32: sums of multiples of 1/256)
+// Then, with P the softmax of the up-sampled logits on the valid pixels,
+//     d loss / d z = (U^T P - T) / N_valid
+//     loss         = ( sum_valid logsumexp  -  <T, z> ) / N_valid        (U z is linear in z)
+// so the per-step kernel needs no per-class label test at all: per pixel and class it does one
+// fma (interpolate), max/compare (prediction), fma + exp, add, and two fmas (U^T along y).
+//
 // Work split: one 256-thread block per tile of LOSS_TY x LOSS_TX groups of 8 x 8 pixels, one
 // thread per pixel column.  A tile touches (LOSS_TY + 2) x (LOSS_TX + 2) low-resolution cells;
-// its share of d loss / d z for those cells goes to a slot of its own, and a second small
-// kernel adds the (at most four) slots that meet in a cell in a fixed order.  No floating-point
-// atomics anywhere: results do not change from run to run.
+// its share of U^T P for those cells goes to a slot of its own, and the consumer adds the (at
+// most four) slots that meet in a cell in a fixed order.  No floating-point atomics anywhere:
+// results do not change from run to run.
 #include "st_kernels.hpp"
 
 namespace st {
@@ -25,14 +34,14 @@ __device__ __forceinline__ float lerp1(float a, float b, float t)
     return __builtin_fmaf(t, d, a);
 }
 
-// sum over the 8 lanes of an aligned group of 8 (all 8 lanes receive it), fixed order
-__device__ __forceinline__ float group8_sum(float v)
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
 {
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
-    return v;
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
+// sum over the 4 lanes of a quad / the 8 lanes of an aligned group of 8 (every lane gets it)
+__device__ __forceinline__ float quad_sum(float v) { return dpp_add<0x4E>(dpp_add<0xB1>(v)); }
+__device__ __forceinline__ float group8_sum(float v) { return dpp_add<0x141>(quad_sum(v)); }
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -58,15 +67,58 @@ k_count_valid(const int32_t* __restrict__ labels, long long P, int C, int ignore
     if (threadIdx.x == 0) atomicAdd(out, (unsigned long long)(part[0] + part[1] + part[2] + part[3]));
 }
 
+// weight with which frame index X (0 .. 8*len-1) contributes to cell `cell` of a line of `len`
+// cells: the tent (1, 3, .. 15, 15, .. 3, 1)/16 around the cell, plus, for the first and last
+// cell, the weight that edge replication folds back onto them
+__device__ __forceinline__ float tap_weight(int X, int cell, int len)
+{
+    const int t = X - 8 * cell + 4;   // 0 .. 15 inside the tent
+    float wgt = 0.f;
+    if (t >= 0 && t < 16) wgt = (t < 8 ? 2 * t + 1 : 31 - 2 * t) * 0.0625f;
+    if (cell == 0 && X < 4) wgt = 1.f;
+    if (cell == len - 1 && X >= 8 * len - 4) wgt = 1.f;
+    return wgt;
+}
+
+// T[img][c][cy][cx] = sum over valid pixels p with label c of wy(p, cy) * wx(p, cx).
+// One thread per cell, a private column of an LDS table per thread (dynamic class index).
+template <int CP>
+__global__ void __launch_bounds__(256)
+k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, Geo g)
+{
+    __shared__ float tab[CP][256];
+    const int tid = threadIdx.x;
+    const int hw = g.h * g.w;
+    const int cell = blockIdx.x * 256 + tid;
+#pragma unroll
+    for (int c = 0; c < CP; ++c) tab[c][tid] = 0.f;
+    if (cell < g.n * hw) {
+        const int img = cell / hw, rr = cell - img * hw, cy = rr / g.w, cx = rr - cy * g.w;
+        const int32_t* lab = labels + (size_t)img * g.H * g.W;
+        const int Y0 = max(8 * cy - 4, 0), Y1 = min(8 * cy + 12, g.H);
+        const int X0 = max(8 * cx - 4, 0), X1 = min(8 * cx + 12, g.W);
+        for (int Y = Y0; Y < Y1; ++Y) {
+            const float wy = tap_weight(Y, cy, g.h);
+            for (int X = X0; X < X1; ++X) {
+                const int y = lab[(size_t)Y * g.W + X];
+                if (y != g.ignore_index && y >= 0 && y < g.C) tab[y][tid] += wy * tap_weight(X, cx, g.w);
+            }
+        }
+        for (int c = 0; c < g.C; ++c) T[((size_t)img * g.C + c) * hw + rr] = tab[c][tid];
+    }
+}
+
 template <int CP, bool GRAD>
 __global__ void __launch_bounds__(256)
-k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, uint8_t* __restrict__ pred,
-       float* __restrict__ slots, float* __restrict__ loss_part, unsigned long long* __restrict__ conf,
-       const unsigned long long* __restrict__ n_valid, Geo g, LossTiling lt)
+k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const float* __restrict__ T,
+       uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
+       unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
 {
     constexpr int CW = LOSS_CW, CH = LOSS_CH, CWP = CW + 1;
     __shared__ float zt[CP][CH][CWP];                 // logits of the touched cells
-    __shared__ float contrib[GRAD ? CP : 1][CH][LOSS_TX][3];  // per column group: left/centre/right cell
+    // per row group and column group: what they hand to their 3 x 3 cells (left, centre, right,
+    // unused); written once, never read-modify-written
+    __shared__ __attribute__((aligned(16))) float contrib[GRAD ? LOSS_TY : 1][GRAD ? CP : 1][3][LOSS_TX][4];
     __shared__ unsigned int conf_l[32 * 32];          // label x prediction counts of this tile
     __shared__ float wsum[4];
 
@@ -91,27 +143,50 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, uint8_t*
     const bool col_ok = X < g.W;
     const float fx = (j < 4 ? 2 * j + 9 : 2 * j - 7) * 0.0625f;
     const int cl = tq + (j >= 4 ? 1 : 0);
-    const float inv_n = [&] {
-        const unsigned long long nv = n_valid ? *n_valid : 0ull;
-        return nv ? 1.0f / (float)nv : 0.f;
-    }();
-    // weights of this column towards the left / centre / right cell of its group
-    const float wl = j < 4 ? 1.f - fx : 0.f, wc = j < 4 ? fx : 1.f - fx, wr = j < 4 ? 0.f : fx;
+    // weights of this column towards its group's outer cell (left for j < 4, right for j >= 4)
+    // and towards the centre cell
+    float w_side = j < 4 ? 1.f - fx : fx, w_mid = j < 4 ? fx : 1.f - fx;
+    {
+        // edge replication: at the first / last column group the cell outside the grid is the
+        // border cell itself, so its weight goes to the centre cell
+        const int q = tile_x * LOSS_TX + tq;
+        if ((q == 0 && j < 4) || (q == g.w - 1 && j >= 4)) { w_mid += w_side; w_side = 0.f; }
+    }
 
     float loss_acc = 0.f;
     const int32_t* lab_img = labels ? labels + (size_t)img * g.H * g.W : nullptr;
     uint8_t* pred_img = pred ? pred + (size_t)img * g.H * g.W : nullptr;
 
+    // ---- minus <T, z> over the cells this tile owns (part of the loss; see the header)
+    if (T && loss_part) {
+        for (int i = tid; i < C * LOSS_TY * LOSS_TX; i += 256) {
+            const int lc = i % LOSS_TX, r = (i / LOSS_TX) % LOSS_TY, c = i / (LOSS_TX * LOSS_TY);
+            const int cx = tile_x * LOSS_TX + lc, cy = tile_y * LOSS_TY + r;
+            if (cx < g.w && cy < g.h)
+                loss_acc -= T[((size_t)img * C + c) * hw + cy * g.w + cx] * zt[c][r + 1][lc + 1];
+        }
+    }
+
 #pragma unroll 1
     for (int gy = 0; gy < LOSS_TY; ++gy) {
         const int qy = tile_y * LOSS_TY + gy;   // row group
         if (qy >= g.h) break;                   // uniform over the block
-        float Hm[CP], H0[CP], Hp[CP];           // x-interpolated logits on cell rows qy-1, qy, qy+1
+        // labels of this column's 8 pixels, fetched up front
+        int lab8[8];
+        if (lab_img) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) lab8[i] = col_ok ? lab_img[(size_t)(qy * 8 + i) * g.W + X] : -1;
+        }
+        // x-interpolated logits on cell rows qy-1, qy, qy+1 and their differences (the y
+        // interpolation is fma(fy, difference, upper row): same roundings as lerp1)
+        float Hm[CP], H0[CP], D0[CP], D1[CP];
 #pragma unroll
         for (int c = 0; c < CP; ++c) {
             Hm[c] = lerp1(zt[c][gy][cl], zt[c][gy][cl + 1], fx);
             H0[c] = lerp1(zt[c][gy + 1][cl], zt[c][gy + 1][cl + 1], fx);
-            Hp[c] = lerp1(zt[c][gy + 2][cl], zt[c][gy + 2][cl + 1], fx);
+            const float Hp = lerp1(zt[c][gy + 2][cl], zt[c][gy + 2][cl + 1], fx);
+            D0[c] = __fsub_rn(H0[c], Hm[c]);
+            D1[c] = __fsub_rn(Hp, H0[c]);
         }
         float Vm[GRAD ? CP : 1], V0[GRAD ? CP : 1], Vp[GRAD ? CP : 1];
         if (GRAD) {
@@ -124,56 +199,66 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, uint8_t*
             const int Y = qy * 8 + i;
             float Z[CP];
 #pragma unroll
-            for (int c = 0; c < CP; ++c) Z[c] = i < 4 ? lerp1(Hm[c], H0[c], fy) : lerp1(H0[c], Hp[c], fy);
-            // prediction: lowest index among the largest
+            for (int c = 0; c < CP; ++c) Z[c] = i < 4 ? __builtin_fmaf(fy, D0[c], Hm[c]) : __builtin_fmaf(fy, D1[c], H0[c]);
+            // prediction: the largest logit, lowest index among equals
             float m = Z[0];
-            int best = 0;
 #pragma unroll
-            for (int c = 1; c < CP; ++c)
-                if (Z[c] > m) { m = Z[c]; best = c; }
+            for (int c = 1; c < CP; ++c) m = fmaxf(m, Z[c]);
+            int best = CP - 1;
+#pragma unroll
+            for (int c = CP - 2; c >= 0; --c) best = Z[c] == m ? c : best;
             if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
             if (lab_img) {
-                const int y = col_ok ? lab_img[(size_t)Y * g.W + X] : -1;
-                const bool valid = col_ok && y != g.ignore_index && y >= 0 && y < C;
-                float s = 0.f, zym = 0.f;   // zym = Z_y - m
+                const int y = lab8[i];
+                const bool valid = y != g.ignore_index && y >= 0 && y < C;   // y = -1 off the frame
+                const float mb = -m * 1.44269504088896341f;
+                float s = 0.f;
 #pragma unroll
                 for (int c = 0; c < CP; ++c) {
-                    const float t = Z[c] - m;
-                    zym = (c == y) ? t : zym;
-                    Z[c] = __builtin_amdgcn_exp2f(t * 1.44269504088896341f);
+                    Z[c] = __builtin_amdgcn_exp2f(__builtin_fmaf(Z[c], 1.44269504088896341f, mb));
                     s += Z[c];
                 }
-                // -log softmax_y = log(sum exp(Z - m)) - (Z_y - m)
-                const float nll = __builtin_amdgcn_logf(s) * 0.693147180559945309f - zym;
                 if (valid) {
-                    loss_acc += nll;
+                    loss_acc += __builtin_fmaf(__builtin_amdgcn_logf(s), 0.693147180559945309f, m);
                     atomicAdd(&conf_l[y * C + best], 1u);
                 }
                 if (GRAD) {
                     const float rs = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
+                    const float wa = (1.f - fy) * rs, wb = fy * rs;
 #pragma unroll
                     for (int c = 0; c < CP; ++c) {
-                        const float G = valid ? __builtin_fmaf(Z[c], rs, c == y ? -1.f : 0.f) : 0.f;
-                        if (i < 4) { Vm[c] = fmaf(1.f - fy, G, Vm[c]); V0[c] = fmaf(fy, G, V0[c]); }
-                        else       { V0[c] = fmaf(1.f - fy, G, V0[c]); Vp[c] = fmaf(fy, G, Vp[c]); }
+                        if (i < 4) { Vm[c] = __builtin_fmaf(wa, Z[c], Vm[c]); V0[c] = __builtin_fmaf(wb, Z[c], V0[c]); }
+                        else       { V0[c] = __builtin_fmaf(wa, Z[c], V0[c]); Vp[c] = __builtin_fmaf(wb, Z[c], Vp[c]); }
                     }
                 }
             }
         }
         if (GRAD) {
-            // hand the column sums to the three cells of this column group (adjoint of the
-            // x-interpolation), reduced over the group's 8 columns
+            // same for the first / last row group: the cell row outside the grid is the border row
+            if (qy == 0) {
+#pragma unroll
+                for (int c = 0; c < CP; ++c) { V0[c] += Vm[c]; Vm[c] = 0.f; }
+            }
+            if (qy == g.h - 1) {
+#pragma unroll
+                for (int c = 0; c < CP; ++c) { V0[c] += Vp[c]; Vp[c] = 0.f; }
+            }
+            // adjoint of the x interpolation, reduced over the group's 8 columns: columns 0-3 feed
+            // the left and the centre cell, columns 4-7 the centre and the right cell
 #pragma unroll
             for (int c = 0; c < CP; ++c) {
+                float side[3], mid[3];
 #pragma unroll
                 for (int r = 0; r < 3; ++r) {
                     const float v = r == 0 ? Vm[c] : (r == 1 ? V0[c] : Vp[c]);
-                    const float L = group8_sum(v * wl), M = group8_sum(v * wc), R = group8_sum(v * wr);
-                    if (j == 0) {
-                        float* dst = &contrib[c][gy + r][tq][0];
-                        if (gy == 0 || r == 2) { dst[0] = L; dst[1] = M; dst[2] = R; }
-                        else { dst[0] += L; dst[1] += M; dst[2] += R; }
-                    }
+                    side[r] = quad_sum(v * w_side);   // lanes 0-3: left cell, lanes 4-7: right cell
+                    mid[r] = group8_sum(v * w_mid);
+                }
+                // lane 0 of the group writes (left, centre), lane 4 writes (right, unused)
+                if ((j & 3) == 0) {
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+                        *(float2*)&contrib[gy][c][r][tq][j >> 1] = make_float2(side[r], j == 0 ? mid[r] : 0.f);
                 }
             }
         }
@@ -191,53 +276,31 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, uint8_t*
     if (GRAD) {
         // rows of `contrib` a short last tile never wrote must read as zero
         const int rows_done = min(LOSS_TY, g.h - tile_y * LOSS_TY);   // row groups processed
-        // ---- cell totals: column group lc gives its left part, lc-1 its centre, lc-2 its right
         float* slot = slots + (size_t)blockIdx.x * CP * CH * CW;
-        // 1) gather into zt (reused as the output tile)
+        // cell totals: column group lc gives its left part, lc-1 its centre part, lc-2 its right
+        // part; cell row r gets row r - gy of row group gy (gy = 0 first).  Cells outside the grid
+        // received nothing (their weight went to the border cells above).
         __syncthreads();
         for (int i = tid; i < CP * CH * CW; i += 256) {
             const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
             float v = 0.f;
-            if (r < rows_done + 2) {
-                if (lc < LOSS_TX) v += contrib[c][r][lc][0];
-                if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[c][r][lc - 1][1];
-                if (lc >= 2) v += contrib[c][r][lc - 2][2];
-            }
-            zt[c][r][lc] = v;
-        }
-        __syncthreads();
-        // 2) fold cells outside the grid onto the border cell they replicate, scale, store
-        for (int i = tid; i < CP * CH * CW; i += 256) {
-            const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
-            const int cx = cx0 + lc, cy = cy0 + r;
-            float v = 0.f;
-            if (cx >= 0 && cx < g.w && cy >= 0 && cy < g.h) {
-                v = zt[c][r][lc];
-                const bool fl = cx == 0 && lc >= 1, fr = cx == g.w - 1 && lc + 1 < CW;
-                const bool fu = cy == 0 && r >= 1, fd = cy == g.h - 1 && r + 1 < CH;
-                if (fl) v += zt[c][r][lc - 1];
-                if (fr) v += zt[c][r][lc + 1];
-                if (fu) {
-                    v += zt[c][r - 1][lc];
-                    if (fl) v += zt[c][r - 1][lc - 1];
-                    if (fr) v += zt[c][r - 1][lc + 1];
-                }
-                if (fd) {
-                    v += zt[c][r + 1][lc];
-                    if (fl) v += zt[c][r + 1][lc - 1];
-                    if (fr) v += zt[c][r + 1][lc + 1];
-                }
-                v *= inv_n;
+            for (int gy = 0; gy < rows_done; ++gy) {
+                const int rr = r - gy;
+                if (rr < 0 || rr > 2) continue;
+                if (lc < LOSS_TX) v += contrib[gy][c][rr][lc][0];
+                if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[gy][c][rr][lc - 1][1];
+                if (lc >= 2) v += contrib[gy][c][rr][lc - 2][2];
             }
             slot[i] = v;
         }
     }
 }
 
-// g[img][c][cy][cx] = sum of the slots of the tiles that touch the cell, tile rows first
+// g[img][c][cy][cx] = ( sum of the slots of the tiles that touch the cell, tile rows first,  - T ) / N_valid
 template <int CP>
 __global__ void __launch_bounds__(256)
-k_assemble_g(const float* __restrict__ slots, float* __restrict__ gz, Geo g, LossTiling lt)
+k_assemble_g(const float* __restrict__ slots, const float* __restrict__ T,
+             const unsigned long long* __restrict__ n_valid, float* __restrict__ gz, Geo g, LossTiling lt)
 {
     constexpr int CW = LOSS_CW, CH = LOSS_CH;
     const int idx = blockIdx.x * 256 + threadIdx.x;
@@ -258,7 +321,9 @@ k_assemble_g(const float* __restrict__ slots, float* __restrict__ gz, Geo g, Los
             v += slots[((tile * CP + c) * CH + r) * CW + lc];
         }
     }
-    gz[idx] = v;
+    const unsigned long long nv = *n_valid;
+    const float inv_n = nv ? 1.0f / (float)nv : 0.f;
+    gz[idx] = (v - T[idx]) * inv_n;
 }
 
 static int padded_classes(int C) { return (C + 3) / 4 * 4; }
@@ -280,38 +345,52 @@ void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long
 }
 
 template <int CP>
-static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* labels, uint8_t* pred,
-                        float* slots, float* gz, float* loss_part, unsigned long long* conf,
+static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T,
+                        uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
                         const unsigned long long* n_valid, bool grad)
 {
     const LossTiling lt = loss_tiling(g);
     const int blocks = g.n * lt.tiles();
     if (grad) {
-        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(256), 0, z, labels, pred,
-                  slots, loss_part, conf, n_valid, g, lt);
+        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(256), 0, z, labels, T, pred,
+                  slots, loss_part, conf, g, lt);
         ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
-                  dim3(256), 0, (const float*)slots, gz, g, lt);
+                  dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
-        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(256), 0, z, labels, pred,
-                  slots, loss_part, conf, n_valid, g, lt);
+        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(256), 0, z, labels, T, pred, slots,
+                  loss_part, conf, g, lt);
     }
 }
 
-void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, uint8_t* pred, float* slots,
-               float* gz, float* loss_part, unsigned long long* conf, const unsigned long long* n_valid,
-               bool grad)
-{
-    switch (padded_classes(g.C)) {
-    case 4: loss_launch<4>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 8: loss_launch<8>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 12: loss_launch<12>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 16: loss_launch<16>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 20: loss_launch<20>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 24: loss_launch<24>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 28: loss_launch<28>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    case 32: loss_launch<32>(c, g, z, labels, pred, slots, gz, loss_part, conf, n_valid, grad); break;
-    default: c.status = ST_ERR_SHAPE; break;
+#define ST_FOR_CP(CALL)                                                                       \
+    switch (padded_classes(g.C)) {                                                            \
+    case 4: CALL(4); break;                                                                   \
+    case 8: CALL(8); break;                                                                   \
+    case 12: CALL(12); break;                                                                 \
+    case 16: CALL(16); break;                                                                 \
+    case 20: CALL(20); break;                                                                 \
+    case 24: CALL(24); break;                                                                 \
+    case 28: CALL(28); break;                                                                 \
+    case 32: CALL(32); break;                                                                 \
+    default: c.status = ST_ERR_SHAPE; break;                                                  \
     }
+
+// T = U^T (one-hot valid labels); once per call
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T)
+{
+    const dim3 grid(cdiv(g.positions(), 256));
+#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, T, g)
+    ST_FOR_CP(ST_CALL)
+#undef ST_CALL
+}
+
+void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
+               float* slots, float* gz, float* loss_part, unsigned long long* conf,
+               const unsigned long long* n_valid, bool grad)
+{
+#define ST_CALL(CP) loss_launch<CP>(c, g, z, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad)
+    ST_FOR_CP(ST_CALL)
+#undef ST_CALL
 }
 
 }  // namespace st

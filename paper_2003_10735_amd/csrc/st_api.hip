@@ -139,6 +139,7 @@ Plan make_plan(const st_head_desc& d)
     const size_t hw = (size_t)g.h * g.w;
     p.z = take(off, (size_t)g.n * g.C * hw * 4);
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
+    p.tadj = take(off, (size_t)g.n * g.C * hw * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.theta = take(off, p.po.total * 4);
     p.vel = take(off, p.po.total * 4);
@@ -248,7 +249,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred)
-        loss_pass(c, p.g, z, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false);
+        loss_pass(c, p.g, z, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false);
     return c.status;
 }
 
@@ -293,6 +294,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
     update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
     count_valid(c, g, teacher_labels, n_valid);
+    label_adjoint(c, g, teacher_labels, (float*)(ws + p.tadj));
 
     double best_metric = -1.0;
     std::vector<double> frame_metric;
@@ -301,7 +303,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
         forward(c, p, ws, z);
-        loss_pass(c, g, z, teacher_labels, (out && (last || early_exit)) ? out->pred : nullptr,
+        loss_pass(c, g, z, teacher_labels, (const float*)(ws + p.tadj),
+                  (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last);
         finish_pass(c, p, ws, (out && out->losses) ? out->losses + it : nullptr,

@@ -67,7 +67,10 @@ inline ParamOffsets param_offsets(const Geo& g)
 // frame pixels (one thread per pixel column).  A tile touches (LOSS_TY + 2) x (LOSS_TX + 2)
 // low-resolution cells and leaves its share of d loss / d z for them in a slot of its own.
 constexpr int LOSS_TX = 32;             // 8-pixel column groups per tile (256 threads)
-constexpr int LOSS_TY = 2;              // 8-pixel row groups per tile
+#ifndef ST_LOSS_TY
+#define ST_LOSS_TY 1
+#endif
+constexpr int LOSS_TY = ST_LOSS_TY;     // 8-pixel row groups per tile
 constexpr int LOSS_CW = LOSS_TX + 2;    // cells per tile row
 constexpr int LOSS_CH = LOSS_TY + 2;    // cell rows per tile
 
@@ -103,7 +106,7 @@ struct Plan {
     size_t featT, a1T, a2T, da1T, da2T;   // channel-major copies [C][PPT] for the weight-gradient kernels
     size_t grad3;                         // per-block partials of dW3 / db3
     size_t zero_begin, zero_end;          // region cleared at the start of every call
-    size_t z, g_slots, gz;
+    size_t z, g_slots, gz, tadj;   // tadj: U^T of the one-hot labels, [n, C, h, w] float32
     size_t theta, vel, grad, best;
     size_t wq1, wq2, wq2t, wq3;      // bfloat16 operand copies of the weights
     size_t loss_part, counters, conf, scal;

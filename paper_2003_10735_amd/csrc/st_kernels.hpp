@@ -33,9 +33,10 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* gz, const bf16* a2, cons
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
 void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long* out);
-void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, uint8_t* pred, float* slots,
-               float* gz, float* loss_part, unsigned long long* conf, const unsigned long long* n_valid,
-               bool grad);
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T);
+void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
+               float* slots, float* gz, float* loss_part, unsigned long long* conf,
+               const unsigned long long* n_valid, bool grad);
 
 // k_update.hip
 void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step);
