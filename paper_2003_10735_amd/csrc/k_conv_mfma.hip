@@ -46,7 +46,9 @@ struct ConvArgs {
     int m_tiles, n_tiles, tiles_per_xcd;
 };
 
-template <int BN, int EPI>
+// TAG only gives every call site (layer 1 forward, layer 2 forward, layer 2 data-gradient) a
+// kernel symbol of its own, so that profiles list them separately.
+template <int BN, int EPI, int TAG>
 __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 {
     constexpr int TA = BN / 64;          // 32-row weight fragments per wavefront
@@ -269,7 +271,7 @@ bool conv3x3_mfma_supported(int cin, int cout) { return cin % CV_BK == 0 && cout
 
 // epi 0: Y = relu(conv + bias); epi 1: Y = conv * [mask > 0]
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
-                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi)
+                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer)
 {
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
@@ -283,14 +285,14 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
     a.tiles_per_xcd = cdiv(tiles, 8);
     const dim3 grid(a.tiles_per_xcd * 8);
     const size_t smem = conv_smem_bytes<BN>();
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)k_conv3x3_mfma<BN, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        (void)hipFuncSetAttribute((const void*)k_conv3x3_mfma<BN, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        attr_set = true;
-    }
-    if (epi == 0) ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 0>), grid, dim3(512), smem, a);
-    else ST_LAUNCH(c, name, (k_conv3x3_mfma<BN, 1>), grid, dim3(512), smem, a);
+    // tag 1: layer-1 forward, 2: layer-2 forward, 3: layer-2 data-gradient
+    auto go = [&](auto kernel) {
+        ensure_dynamic_lds((const void*)kernel, smem);
+        ST_LAUNCH(c, name, kernel, grid, dim3(512), smem, a);
+    };
+    if (epi == 1) go(k_conv3x3_mfma<BN, 1, 3>);
+    else if (layer == 1) go(k_conv3x3_mfma<BN, 0, 1>);
+    else go(k_conv3x3_mfma<BN, 0, 2>);
 }
 
 }  // namespace st

@@ -65,6 +65,18 @@ void prof_end(Ctx& c)
     g_prof_start = nullptr;
 }
 
+// kernels that need more than 64 KB of dynamic LDS must be told once (per process)
+void ensure_dynamic_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex m;
+    static std::vector<const void*> done;
+    std::lock_guard<std::mutex> lk(m);
+    for (const void* k : done)
+        if (k == kernel) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    done.push_back(kernel);
+}
+
 // ------------------------------------------------------------------ validation and plan
 static int validate(const st_head_desc* d)
 {
@@ -179,9 +191,9 @@ static void forward(Ctx& c, const Plan& p, char* ws, float* z)
     const Geo& g = p.g;
     const float* theta = (const float*)(ws + p.theta);
     conv3x3_mfma(c, "conv1_fwd_mfma", p, (const bf16*)(ws + p.feat), (const bf16*)(ws + p.wq1), theta + p.po.b1,
-                 nullptr, (bf16*)(ws + p.a1), (bf16*)(ws + p.a1T), g.c_in, g.c1, 0);
+                 nullptr, (bf16*)(ws + p.a1), (bf16*)(ws + p.a1T), g.c_in, g.c1, 0, 1);
     conv3x3_mfma(c, "conv2_fwd_mfma", p, (const bf16*)(ws + p.a1), (const bf16*)(ws + p.wq2), theta + p.po.b2,
-                 nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0);
+                 nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0, 2);
     logits_mfma(c, p, (const bf16*)(ws + p.a2), (const bf16*)(ws + p.wq3), theta + p.po.b3, z);
 }
 
@@ -194,11 +206,11 @@ static void backward(Ctx& c, const Plan& p, char* ws)
     conv3_bwd_mfma(c, p, (const float*)(ws + p.gz), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
                    (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
     wgrad3x3_mfma(c, "conv2_wgrad_mfma", p, (const bf16*)(ws + p.da2T), (const bf16*)(ws + p.a1T),
-                  grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2);
+                  grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2, 2);
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
-                 (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1);
+                 (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
     wgrad3x3_mfma(c, "conv1_wgrad_mfma", p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT),
-                  grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1);
+                  grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1, 1);
     reduce_grad3(c, p, ws);
 }
 

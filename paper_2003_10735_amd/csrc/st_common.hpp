@@ -127,6 +127,7 @@ struct Ctx {
 void prof_begin(Ctx& c, const char* name);
 void prof_end(Ctx& c);
 void set_hip_error(hipError_t e);
+void ensure_dynamic_lds(const void* kernel, size_t bytes);
 
 #define ST_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                               \
     do {                                                                                    \

@@ -17,11 +17,11 @@ void generic_backward(Ctx& c, const Plan& p, char* ws);
 // k_conv_mfma.hip, k_wgrad_mfma.hip, k_conv3_mfma.hip -- matrix-core kernels of the bfloat16 path
 bool conv3x3_mfma_supported(int cin, int cout);
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
-                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi);
+                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer);
 bool wgrad3x3_mfma_supported(int cin, int cout);
 int wgrad_splits_for(const Geo& g, int cin, int cout);
 void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, const bf16* XT, float* dW,
-                   float* db, int cin, int cout, int splits);
+                   float* db, int cin, int cout, int splits, int layer);
 bool conv3_mfma_supported(int c2, int C);
 void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z);
 int conv3_bwd_blocks(const Geo& g);
