@@ -64,19 +64,26 @@ void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const f
 }
 
 // ------------------------------------------------------------------ backward
-// One block = 128 consecutive padded positions (g is zero on the border).  The block first
-// stages g (rounded to bfloat16) in LDS in both orientations and W3 transposed; then
+// One block = 128 consecutive padded positions (g is zero on the border).  The block first forms
+// g = d loss / d z for its cells from what the loss kernel left behind -- the per-tile slots of
+// U^T softmax (added in a fixed order: tile rows first), minus U^T of the one-hot labels, over
+// N_valid -- rounds it to bfloat16 and stages it in LDS in both orientations, with W3 transposed.
+// Then
 //   wavefront w computes da2 for positions 32w .. 32w+31 and all channels  (K = classes),
 //   wavefront w computes dW3 for channel tiles w, w+4, ..  over all 128 positions (K = positions),
 // so no sum crosses wavefronts.  Partial dW3 / db3 go to one slot per block; the optimiser
-// kernel adds the slots in order.
+// kernel adds the slots in order.  All global loads a wavefront needs later (ReLU mask, a2
+// fragments) are issued before the first barrier, so their latency overlaps the staging.
 template <int C2>
 __global__ void __launch_bounds__(256)
-k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
+k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
+                 const unsigned long long* __restrict__ n_valid, int CP, LossTiling lt,
+                 const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
                  const bf16* __restrict__ W3q, bf16* __restrict__ da2, bf16* __restrict__ da2T,
                  float* __restrict__ part, Geo g, int PPT, int guard)
 {
     constexpr int OT = C2 / 32;            // channel tiles
+    constexpr int DW = (OT + 3) / 4;       // dW3 channel tiles per wavefront
     constexpr int GP = 128 + 8;            // pitch of g_cp rows (positions)
     constexpr int GC = 32 + 8;             // pitch of g_pc / w3t rows (classes)
     constexpr int OLD = C2 + 8;            // pitch of the output tile
@@ -90,19 +97,63 @@ k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, cons
     const int PP = g.padded_positions(), frame = g.Hp * g.Wp, hw = g.h * g.w;
     const int m0 = blockIdx.x * 128;
 
+    // ---- early loads: ReLU mask of this lane's position, a2 fragments of this wavefront's tiles
+    const int pm = wave * 32 + l32;                // position (inside the block) for the da2 part
+    const size_t mrow = (size_t)min(m0 + pm, PP - 1) * C2;
+    bf16x4 mk[OT][4];
+#pragma unroll
+    for (int t = 0; t < OT; ++t)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(a2 + mrow + t * 32 + rg * 8 + lhi * 4);
+    bf16x8 xf[DW][8];
+#pragma unroll
+    for (int d = 0; d < DW; ++d) {
+        const int t = min(wave + 4 * d, OT - 1);
+        const bf16* xrow = a2T + xt_index(t * 32 + l32, guard + m0 + lhi * 8, PPT / 8);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) xf[d][ks] = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups per step
+    }
+
     // ---- stage g (both orientations) and W3^T
-    for (int i = tid; i < 32 * 128; i += 256) {
-        const int p = i & 127, c = i >> 7;
+    {
+        const int p = tid & 127, chalf = tid >> 7;     // this thread: one position, every other class
         const int mp = m0 + p;
-        float v = 0.f;
-        if (c < g.C && mp < PP) {
-            const int img = mp / frame, rr = mp - img * frame, y = rr / g.Wp, x = rr - y * g.Wp;
-            if (y >= 1 && y <= g.h && x >= 1 && x <= g.w)
-                v = gz[((size_t)img * g.C + c) * hw + (y - 1) * g.w + (x - 1)];
+        const int img = min(mp / frame, g.n - 1), rr = mp - img * frame, y = rr / g.Wp, x = rr - y * g.Wp;
+        const bool inside = mp < PP && y >= 1 && y <= g.h && x >= 1 && x <= g.w;
+        const int cy = inside ? y - 1 : 0, cx = inside ? x - 1 : 0;
+        const unsigned long long nv = *n_valid;
+        const float inv_n = (inside && nv) ? 1.0f / (float)nv : 0.f;
+        // the tiles whose cell window contains (cy, cx): up to 3 tile rows x 2 tile columns
+        const int ty_hi = min((cy + 1) / LOSS_TY, lt.tiles_y - 1), tx_hi = min((cx + 1) / LOSS_TX, lt.tiles_x - 1);
+        // slot offset of class 0 and a 0/1 weight: tiles that do not exist or do not touch the
+        // cell read slot element 0 with weight 0, so that every load is unconditional
+        int off[3][2];
+        float wgt[3][2];
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int ty = ty_hi - 2 + a, tx = tx_hi - 1 + b;
+                const int r = cy - (ty * LOSS_TY - 1), lc = cx - (tx * LOSS_TX - 1);
+                const bool ok = inside && ty >= 0 && tx >= 0 && r >= 0 && r < LOSS_CH && lc >= 0 && lc < LOSS_CW;
+                off[a][b] = ok ? (((img * lt.tiles() + ty * lt.tiles_x + tx) * CP) * LOSS_CH + r) * LOSS_CW + lc : 0;
+                wgt[a][b] = ok ? 1.f : 0.f;
+            }
+        const int cstride = LOSS_CH * LOSS_CW;
+        const size_t tbase = (size_t)img * g.C * hw + cy * g.w + cx;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int c = min(chalf + 2 * k, g.C - 1);     // classes beyond C re-read the last one, unused
+            float v = 0.f;
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) v = __builtin_fmaf(wgt[a][b], slots[(size_t)off[a][b] + (size_t)c * cstride], v);
+            v = (v - T[tbase + (size_t)c * hw]) * inv_n;
+            const bf16 q = (chalf + 2 * k < g.C) ? (bf16)v : (bf16)0.f;
+            g_cp[(chalf + 2 * k) * GP + p] = q;
+            g_pc[p * GC + chalf + 2 * k] = q;
         }
-        const bf16 q = (bf16)v;
-        g_cp[c * GP + p] = q;
-        g_pc[p * GC + c] = q;
     }
     for (int i = tid; i < C2 * 32; i += 256) {
         const int o = i % C2, c = i / C2;
@@ -117,49 +168,46 @@ k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, cons
         for (int t = 0; t < OT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-        const int p = wave * 32 + l32;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 gf = *(const bf16x8*)(g_pc + p * GC + ks * 16 + lhi * 8);
+            const bf16x8 gf = *(const bf16x8*)(g_pc + pm * GC + ks * 16 + lhi * 8);
 #pragma unroll
             for (int t = 0; t < OT; ++t) {
                 const bf16x8 wf = *(const bf16x8*)(w3t + (t * 32 + l32) * GC + ks * 16 + lhi * 8);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, gf, acc[t], 0, 0, 0);
             }
         }
-        const int mp = m0 + p;
-        const bool in_range = mp < PP;
+        // (a2 is zero on the border, and g is zero there too: border rows of da2 come out zero)
 #pragma unroll
         for (int t = 0; t < OT; ++t)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
-                const int o = t * 32 + rg * 8 + lhi * 4;
-                bf16x4 mk = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
-                if (in_range) mk = *(const bf16x4*)(a2 + (size_t)mp * C2 + o);   // zero on the border
                 bf16x4 ov;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) ov[e] = (bf16)((float)mk[e] > 0.f ? acc[t][rg * 4 + e] : 0.f);
-                *(bf16x4*)(Os + p * OLD + o) = ov;
+                for (int e = 0; e < 4; ++e) ov[e] = (bf16)((float)mk[t][rg][e] > 0.f ? acc[t][rg * 4 + e] : 0.f);
+                *(bf16x4*)(Os + pm * OLD + t * 32 + rg * 8 + lhi * 4) = ov;
             }
     }
 
     // ---- dW3: D[c][o] = sum_pos g[c][pos] * a2[pos][o] over this block's 128 positions
     float* slot = part + (size_t)blockIdx.x * (32 * C2 + 32);
-    for (int t = wave; t < OT; t += 4) {
-        f32x16 acc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const bf16* xrow = a2T + xt_index(t * 32 + l32, guard + m0 + lhi * 8, PPT / 8);
+    for (int d = 0; d < DW; ++d) {
+        const int t = wave + 4 * d;
+        if (t < OT) {
+            f32x16 acc;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
-            const bf16x8 xf = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups further
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf, acc, 0, 0, 0);
-        }
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
-            slot[c * C2 + t * 32 + l32] = acc[r];
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf[d][ks], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
+                slot[c * C2 + t * 32 + l32] = acc[r];
+            }
         }
     }
     if (tid < 32) {
@@ -187,17 +235,22 @@ k_conv3_bwd_mfma(const float* __restrict__ gz, const bf16* __restrict__ a2, cons
 int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions(), 128); }
 size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
-void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* gz, const bf16* a2, const bf16* a2T, const bf16* W3q,
+void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3q,
                     bf16* da2, bf16* da2T, float* part)
 {
     const Geo& g = p.g;
     const dim3 grid(conv3_bwd_blocks(g));
+    const int CP = (g.C + 3) / 4 * 4;   // class padding of the loss kernel's slots
+#define ST_C3B(C2) ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2>), grid, dim3(256), 0, slots, T, n_valid, CP, \
+                             p.lt, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard)
     switch (g.c2) {
-    case 64: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<64>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
-    case 128: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<128>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
-    case 256: ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<256>), grid, dim3(256), 0, gz, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard); break;
+    case 64: ST_C3B(64); break;
+    case 128: ST_C3B(128); break;
+    case 256: ST_C3B(256); break;
     default: c.status = ST_ERR_SHAPE;
     }
+#undef ST_C3B
 }
 
 }  // namespace st

@@ -347,15 +347,17 @@ void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long
 template <int CP>
 static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
-                        const unsigned long long* n_valid, bool grad)
+                        const unsigned long long* n_valid, bool grad, bool assemble)
 {
     const LossTiling lt = loss_tiling(g);
     const int blocks = g.n * lt.tiles();
     if (grad) {
         ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(256), 0, z, labels, T, pred,
                   slots, loss_part, conf, g, lt);
-        ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
-                  dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
+        // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
+        if (assemble)
+            ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
+                      dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
         ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(256), 0, z, labels, T, pred, slots,
                   loss_part, conf, g, lt);
@@ -386,9 +388,9 @@ void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T)
 
 void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
-               const unsigned long long* n_valid, bool grad)
+               const unsigned long long* n_valid, bool grad, bool assemble)
 {
-#define ST_CALL(CP) loss_launch<CP>(c, g, z, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad)
+#define ST_CALL(CP) loss_launch<CP>(c, g, z, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
 }

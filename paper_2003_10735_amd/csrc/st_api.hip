@@ -203,7 +203,8 @@ static void backward(Ctx& c, const Plan& p, char* ws)
     if (!p.mfma) { generic_backward(c, p, ws); return; }
     const Geo& g = p.g;
     float* grad = (float*)(ws + p.grad);
-    conv3_bwd_mfma(c, p, (const float*)(ws + p.gz), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
+    conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
+                   (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
                    (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
     wgrad3x3_mfma(c, "conv2_wgrad_mfma", p, (const bf16*)(ws + p.da2T), (const bf16*)(ws + p.a1T),
                   grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2, 2);
@@ -261,7 +262,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred)
-        loss_pass(c, p.g, z, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false);
+        loss_pass(c, p.g, z, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false, false);
     return c.status;
 }
 
@@ -318,7 +319,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         loss_pass(c, g, z, teacher_labels, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
-                  (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last);
+                  (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);
         finish_pass(c, p, ws, (out && out->losses) ? out->losses + it : nullptr,
                     (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr,
                     (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr);

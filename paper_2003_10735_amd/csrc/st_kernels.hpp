@@ -26,7 +26,8 @@ bool conv3_mfma_supported(int c2, int C);
 void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z);
 int conv3_bwd_blocks(const Geo& g);
 size_t conv3_bwd_slot_floats(const Geo& g);
-void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* gz, const bf16* a2, const bf16* a2T, const bf16* W3q,
+void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3q,
                     bf16* da2, bf16* da2T, float* part);
 
 // k_loss.hip
@@ -36,7 +37,7 @@ void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long
 void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T);
 void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
-               const unsigned long long* n_valid, bool grad);
+               const unsigned long long* n_valid, bool grad, bool assemble);
 
 // k_update.hip
 void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step);
