@@ -1,15 +1,25 @@
 // Optimiser step over the flat parameter buffer (fused with the sum of the partial weight
 // gradients and the bfloat16 operand copies of the new weights), the per-step bookkeeping
 // kernel (loss, per-frame mean IoU) and the stand-alone confusion-matrix / mean-IoU kernels.
+#include <string.h>
+
 #include "st_kernels.hpp"
 
 namespace st {
 
-// theta <- theta - lr * v,  v <- mu * v + g  (mu == 0: v is not touched).  g is the sum, in
-// ascending order, of the partial gradients the backward kernels left behind: `splits1` copies
-// for W1/b1 and `splits2` for W2/b2 (position splits of the weight-gradient kernels, `stride`
-// floats apart); W3/b3 sit in copy 0 (k_reduce3 has already added their per-block slots).
-// Also refreshes the bfloat16 copies of the new weights:
+// One kernel closes a training step; its blocks play three roles (block index ranges):
+//
+//  (1) optimiser step over the flat parameter buffer: theta <- theta - lr * v, v <- mu * v + g
+//      (mu == 0: v is not touched).  g is the sum, in ascending order, of the partial gradients
+//      the backward kernels left behind: `splits1` copies for W1/b1 and `splits2` for W2/b2
+//      (position splits of the weight-gradient kernels, `stride` floats apart).
+//  (2) the same for W3/b3 when the classifier's backward kernel left one slot per block: one
+//      wavefront per parameter, lane l adds slots l, l+64, .. in order, then a fixed shuffle tree.
+//  (3) bookkeeping of the forward pass that preceded the step: block f: mean IoU of frame f from
+//      its confusion counts (copied out when asked, then cleared for the next pass); one more
+//      block: the tile losses added in a fixed order (float64) over the number of valid pixels.
+//
+// Roles (1) and (2) also refresh the bfloat16 copies of the new weights:
 //   wq1, wq2, wq3 : same (internal) order as theta, for the forward convolutions
 //   wq2t          : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
 struct UpdateArgs {
@@ -17,18 +27,22 @@ struct UpdateArgs {
     bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
     ParamOffsets po; int c1, c2;
     float lr, mu;
-    int do_step;   // 0: only refresh the bfloat16 copies
+    int do_step;     // 0: only refresh the bfloat16 copies
+    // role (2)
+    const float* part3; int blocks3; size_t slot3; int C;
+    // block ranges
+    int nb_main, nb_l3, nb_finish;
 };
 
-__global__ void __launch_bounds__(256) k_update(UpdateArgs a)
+struct FinishArgs {
+    const float* loss_part; int n_part; const unsigned long long* n_valid; unsigned long long* conf;
+    int n, C; float* loss_out; double* miou_a; double* miou_b; long long* conf_out;
+};
+
+__device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, float g)
 {
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= a.po.total) return;
     float w = a.theta[j];
     if (a.do_step) {
-        const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
-        float g = a.grad[j];
-        for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
         if (a.mu != 0.f) {
             const float v = __builtin_fmaf(a.mu, a.vel[j], g);
             a.vel[j] = v;
@@ -51,112 +65,40 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a)
     }
 }
 
-void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step)
-{
-    UpdateArgs a;
-    a.theta = (float*)(ws + p.theta);
-    a.vel = (float*)(ws + p.vel);
-    a.grad = (const float*)(ws + p.grad);
-    a.stride = p.po.total;
-    a.splits1 = p.mfma ? p.splits1 : 1;
-    a.splits2 = p.mfma ? p.splits2 : 1;
-    a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
-    a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
-    a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
-    a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
-    a.po = p.po; a.c1 = p.g.c1; a.c2 = p.g.c2;
-    a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;
-    if (!do_step && !p.bf16) return;
-    ST_LAUNCH(c, do_step ? "sgd_update" : "weights_to_bf16", k_update, dim3(cdiv(p.po.total, 256)), dim3(256),
-              0, a);
-}
-
-// ------------------------------------------------------------------ mean IoU from counts
-// IoU_c = conf[c][c] / (row_c + col_c - conf[c][c]) for classes with row_c > 0, summed in
-// ascending c in float64, divided by their number; 0 when no class is present.
-__device__ double miou_of(const unsigned long long* conf, int C)
-{
-    double sum = 0.0;
-    int present = 0;
-    for (int c = 0; c < C; ++c) {
-        unsigned long long row = 0, col = 0;
-        for (int k = 0; k < C; ++k) { row += conf[c * C + k]; col += conf[k * C + c]; }
-        if (row == 0) continue;
-        const unsigned long long inter = conf[c * C + c];
-        sum += (double)inter / (double)(row + col - inter);
-        ++present;
-    }
-    return present ? sum / present : 0.0;
-}
-
-// Sum of the per-block slots of the classifier layer's backward kernel into gradient copy 0.
-// One wavefront per parameter: lane l adds slots l, l+64, ... in order, then the 64 lane sums
-// are added by a fixed shuffle tree.
-__global__ void __launch_bounds__(256)
-k_reduce3(const float* __restrict__ part, int blocks, size_t slot, float* __restrict__ gW3,
-          float* __restrict__ gb3, int C, int c2)
-{
-    const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int n_w = C * c2;
-    if (j >= n_w + C) return;
-    const size_t r = j < n_w ? (size_t)j : (size_t)32 * c2 + (j - n_w);   // slot: [32][c2] weights, [32] biases
-    float acc = 0.f;
-    for (int s = lane; s < blocks; s += 64) acc += part[(size_t)s * slot + r];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-    if (lane == 0) {
-        if (j < n_w) gW3[j] = acc;
-        else gb3[j - n_w] = acc;
-    }
-}
-
-void reduce_grad3(Ctx& c, const Plan& p, char* ws)
-{
-    float* grad = (float*)(ws + p.grad);
-    const int n = p.g.C * p.g.c2 + p.g.C;
-    ST_LAUNCH(c, "reduce_grad3", k_reduce3, dim3(cdiv(n, 4)), dim3(256), 0, (const float*)(ws + p.grad3),
-              p.blocks3, conv3_bwd_slot_floats(p.g), grad + p.po.W3, grad + p.po.b3, p.g.C, p.g.c2);
-}
-
-// Closes a forward pass.  Block f < n: mean IoU of frame f from its confusion counts (copied out
-// when asked, then cleared for the next pass).  Block n: the tile losses added in a fixed order
-// (float64) and divided by the number of valid pixels.
-__global__ void __launch_bounds__(256)
-k_finish_pass(const float* __restrict__ loss_part, int n_part, const unsigned long long* __restrict__ n_valid,
-              unsigned long long* __restrict__ conf, int n, int C, float* loss_out, double* miou_a,
-              double* miou_b, long long* conf_out)
+__device__ void finish_block(const FinishArgs& f, int block)
 {
     __shared__ double part[256];
     __shared__ unsigned long long cl[32 * 32];
     __shared__ double iou[32];
     __shared__ int present[32];
     const int tid = threadIdx.x;
-    if ((int)blockIdx.x == n) {
+    if (block == f.n) {
         double acc = 0.0;
-        const int per = (n_part + 255) / 256;
-        for (int i = tid * per; i < min(n_part, (tid + 1) * per); ++i) acc += (double)loss_part[i];
+        const int per = (f.n_part + 255) / 256;
+        for (int i = tid * per; i < min(f.n_part, (tid + 1) * per); ++i) acc += (double)f.loss_part[i];
         part[tid] = acc;
         __syncthreads();
         for (int s = 128; s > 0; s >>= 1) {
             if (tid < s) part[tid] += part[tid + s];
             __syncthreads();
         }
-        if (tid == 0 && loss_out) {
-            const unsigned long long nv = *n_valid;
-            *loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
+        if (tid == 0 && f.loss_out) {
+            const unsigned long long nv = *f.n_valid;
+            *f.loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
         }
         return;
     }
-    const int f = blockIdx.x;
-    unsigned long long* cf = conf + (size_t)f * C * C;
+    const int C = f.C;
+    unsigned long long* cf = f.conf + (size_t)block * C * C;
     for (int i = tid; i < C * C; i += 256) {
         const unsigned long long v = cf[i];
         cl[i] = v;
-        if (conf_out) conf_out[(size_t)f * C * C + i] = (long long)v;
+        if (f.conf_out) f.conf_out[(size_t)block * C * C + i] = (long long)v;
         cf[i] = 0ull;
     }
     __syncthreads();
+    // IoU_c = conf[c][c] / (row_c + col_c - conf[c][c]) for classes with row_c > 0, added in
+    // ascending c in float64, divided by their number; 0 when no class is present
     if (tid < C) {
         unsigned long long row = 0, col = 0;
         for (int k = 0; k < C; ++k) { row += cl[tid * C + k]; col += cl[k * C + tid]; }
@@ -171,19 +113,120 @@ k_finish_pass(const float* __restrict__ loss_part, int n_part, const unsigned lo
         for (int c = 0; c < C; ++c)
             if (present[c]) { sum += iou[c]; ++cnt; }
         const double m = cnt ? sum / cnt : 0.0;
-        if (miou_a) miou_a[f] = m;
-        if (miou_b) miou_b[f] = m;
+        if (f.miou_a) f.miou_a[block] = m;
+        if (f.miou_b) f.miou_b[block] = m;
     }
 }
 
-// miou_ws: per-frame metric kept in the workspace (for the host-side loop exits);
-// miou_out: the caller's array (may be null)
+__global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
+{
+    const int b = blockIdx.x;
+    if (b < a.nb_main) {
+        // role (1); W3/b3 are left to role (2) when it is active
+        const size_t j = (size_t)b * 256 + threadIdx.x;
+        const size_t limit = a.nb_l3 ? a.po.W3 : a.po.total;
+        if (j >= limit) return;
+        float g = 0.f;
+        if (a.do_step) {
+            const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
+            g = a.grad[j];
+            for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
+        }
+        apply_update(a, j, g);
+    } else if (b < a.nb_main + a.nb_l3) {
+        // role (2): slot layout [32 classes][c2] weights, then [32] biases
+        const int lane = threadIdx.x & 63;
+        const int k = (b - a.nb_main) * 4 + (threadIdx.x >> 6);
+        const int n_w = a.C * a.c2;
+        if (k >= n_w + a.C) return;
+        float acc = 0.f;
+        if (a.do_step) {
+            const size_t r = k < n_w ? (size_t)k : (size_t)32 * a.c2 + (k - n_w);
+            for (int s = lane; s < a.blocks3; s += 64) acc += a.part3[(size_t)s * a.slot3 + r];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+        }
+        if (lane == 0) apply_update(a, a.po.W3 + k, acc);
+    } else {
+        finish_block(f, b - a.nb_main - a.nb_l3);
+    }
+}
+
+static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
+{
+    FinishArgs f;
+    f.loss_part = (const float*)(ws + p.loss_part);
+    f.n_part = loss_blocks(p.g);
+    f.n_valid = (const unsigned long long*)(ws + p.counters);
+    f.conf = (unsigned long long*)(ws + p.conf);
+    f.n = p.g.n; f.C = p.g.C;
+    f.loss_out = loss_out;
+    f.miou_a = (double*)(ws + p.scal);   // per-frame metric kept in the workspace (host-side loop exits)
+    f.miou_b = miou_out;                 // the caller's array (may be null)
+    f.conf_out = conf_out;
+    return f;
+}
+
+// do_step: optimiser step (else only the bfloat16 copies are refreshed);
+// finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
+void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step, bool finish, float* loss_out,
+              double* miou_out, long long* conf_out)
+{
+    UpdateArgs a;
+    a.theta = (float*)(ws + p.theta);
+    a.vel = (float*)(ws + p.vel);
+    a.grad = (const float*)(ws + p.grad);
+    a.stride = p.po.total;
+    a.splits1 = p.mfma ? p.splits1 : 1;
+    a.splits2 = p.mfma ? p.splits2 : 1;
+    a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
+    a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
+    a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
+    a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
+    a.po = p.po; a.c1 = p.g.c1; a.c2 = p.g.c2;
+    a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;
+    a.part3 = (const float*)(ws + p.grad3);
+    a.blocks3 = p.blocks3; a.slot3 = conv3_bwd_slot_floats(p.g); a.C = p.g.C;
+    const bool params = do_step || p.bf16;
+    const bool l3 = params && p.mfma && do_step;
+    a.nb_main = params ? cdiv(l3 ? p.po.W3 : p.po.total, 256) : 0;
+    a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 4) : 0;
+    a.nb_finish = finish ? p.g.n + 1 : 0;
+    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    const int blocks = a.nb_main + a.nb_l3 + a.nb_finish;
+    if (blocks == 0) return;
+    const char* name = do_step ? (finish ? "sgd_update+finish_pass" : "sgd_update") : (params ? "weights_to_bf16" : "finish_pass");
+    ST_LAUNCH(c, name, k_step_end, dim3(blocks), dim3(256), 0, a, f);
+}
+
+void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step)
+{
+    step_end(c, p, ws, lr, mu, do_step, false, nullptr, nullptr, nullptr);
+}
+
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
 {
-    ST_LAUNCH(c, "finish_pass", k_finish_pass, dim3(p.g.n + 1), dim3(256), 0, (const float*)(ws + p.loss_part),
-              loss_blocks(p.g), (const unsigned long long*)(ws + p.counters),
-              (unsigned long long*)(ws + p.conf), p.g.n, p.g.C, loss_out, (double*)(ws + p.scal), miou_out,
-              conf_out);
+    UpdateArgs a;
+    memset(&a, 0, sizeof(a));
+    a.nb_finish = p.g.n + 1;
+    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    ST_LAUNCH(c, "finish_pass", k_step_end, dim3(a.nb_finish), dim3(256), 0, a, f);
+}
+
+__global__ void k_miou_from_counts(const unsigned long long* conf, int C, double* out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double sum = 0.0;
+    int present = 0;
+    for (int c = 0; c < C; ++c) {
+        unsigned long long row = 0, col = 0;
+        for (int k = 0; k < C; ++k) { row += conf[c * C + k]; col += conf[k * C + c]; }
+        if (row == 0) continue;
+        const unsigned long long inter = conf[c * C + c];
+        sum += (double)inter / (double)(row + col - inter);
+        ++present;
+    }
+    *out = present ? sum / present : 0.0;
 }
 
 // ------------------------------------------------------------------ stand-alone metric
@@ -233,11 +276,6 @@ k_confusion(const uint8_t* __restrict__ pred, const int32_t* __restrict__ labels
     }
 }
 
-__global__ void k_miou_single(const unsigned long long* conf, int C, double* out)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) *out = miou_of(conf, C);
-}
-
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
                         long long* conf, double* miou)
 {
@@ -252,7 +290,7 @@ void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long
     else
         ST_LAUNCH(c, "confusion", (k_confusion<false>), dim3(blocks), dim3(256), 0, pred, labels, P, C, ignore,
                   (unsigned long long*)conf);
-    ST_LAUNCH(c, "miou", k_miou_single, dim3(1), dim3(64), 0, (const unsigned long long*)conf, C, miou);
+    ST_LAUNCH(c, "miou", k_miou_from_counts, dim3(1), dim3(64), 0, (const unsigned long long*)conf, C, miou);
 }
 
 }  // namespace st

@@ -212,7 +212,6 @@ static void backward(Ctx& c, const Plan& p, char* ws)
                  (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
     wgrad3x3_mfma(c, "conv1_wgrad_mfma", p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT),
                   grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1, 1);
-    reduce_grad3(c, p, ws);
 }
 
 }  // namespace st
@@ -320,9 +319,14 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);
-        finish_pass(c, p, ws, (out && out->losses) ? out->losses + it : nullptr,
-                    (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr,
-                    (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr);
+        float* loss_out = (out && out->losses) ? out->losses + it : nullptr;
+        double* miou_out = (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr;
+        long long* conf_out = (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr;
+        // The bookkeeping of this pass (loss, per-frame mIoU, clearing the counts) normally rides
+        // along with the optimiser kernel at the end of the step; it needs a launch of its own
+        // only when no update follows or when the host must see the metric first.
+        const bool finish_now = last || early_exit;
+        if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out);
         bool stop = last;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
@@ -352,7 +356,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         }
         if (stop) break;
         backward(c, p, ws);
-        update_params(c, p, ws, lr, mu, true);
+        step_end(c, p, ws, lr, mu, true, !finish_now, loss_out, miou_out, conf_out);
         ++taken;
     }
     if (early_exit && return_best && have_best)

@@ -41,7 +41,8 @@ void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, cons
 
 // k_update.hip
 void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step);
-void reduce_grad3(Ctx& c, const Plan& p, char* ws);
+void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step, bool finish, float* loss_out,
+              double* miou_out, long long* conf_out);
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out);
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
                         long long* conf, double* miou);
