@@ -81,30 +81,47 @@ __device__ __forceinline__ float tap_weight(int X, int cell, int len)
 }
 
 // T[img][c][cy][cx] = sum over valid pixels p with label c of wy(p, cy) * wx(p, cx).
-// One thread per cell, a private column of an LDS table per thread (dynamic class index).
+// One block per cell row and run of 32 cells.  First every pixel column that can reach those
+// cells (256 + 2 x 4 columns) adds its 16 rows' y-weights into a per-column table in LDS
+// (the class index is data, so the table cannot live in registers); then one thread per
+// (class, cell) applies the x-weights of the 16 columns under the cell.  All terms are
+// multiples of 1/256 and the sums stay below 2^8, so the result is exact in float32 and does
+// not depend on the order of additions.
 template <int CP>
 __global__ void __launch_bounds__(256)
 k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, Geo g)
 {
-    __shared__ float tab[CP][256];
+    constexpr int NCOL = LOSS_TX * 8 + 8;
+    __shared__ float colsum[CP][NCOL + 1];
     const int tid = threadIdx.x;
+    const int tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
+    const int tx = blockIdx.x % tiles_x, cy = (blockIdx.x / tiles_x) % g.h, img = blockIdx.x / (tiles_x * g.h);
     const int hw = g.h * g.w;
-    const int cell = blockIdx.x * 256 + tid;
-#pragma unroll
-    for (int c = 0; c < CP; ++c) tab[c][tid] = 0.f;
-    if (cell < g.n * hw) {
-        const int img = cell / hw, rr = cell - img * hw, cy = rr / g.w, cx = rr - cy * g.w;
-        const int32_t* lab = labels + (size_t)img * g.H * g.W;
-        const int Y0 = max(8 * cy - 4, 0), Y1 = min(8 * cy + 12, g.H);
-        const int X0 = max(8 * cx - 4, 0), X1 = min(8 * cx + 12, g.W);
+    const int32_t* lab = labels + (size_t)img * g.H * g.W;
+    for (int i = tid; i < CP * (NCOL + 1); i += 256) (&colsum[0][0])[i] = 0.f;
+    __syncthreads();
+    const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
+    const int Y0 = max(8 * cy - 4, 0), Y1 = min(8 * cy + 12, g.H);
+    for (int col = tid; col < NCOL; col += 256) {
+        const int X = X0 + col;
+        if (X < 0 || X >= g.W) continue;
         for (int Y = Y0; Y < Y1; ++Y) {
-            const float wy = tap_weight(Y, cy, g.h);
-            for (int X = X0; X < X1; ++X) {
-                const int y = lab[(size_t)Y * g.W + X];
-                if (y != g.ignore_index && y >= 0 && y < g.C) tab[y][tid] += wy * tap_weight(X, cx, g.w);
-            }
+            const int y = lab[(size_t)Y * g.W + X];
+            if (y != g.ignore_index && y >= 0 && y < g.C) colsum[y][col] += tap_weight(Y, cy, g.h);
         }
-        for (int c = 0; c < g.C; ++c) T[((size_t)img * g.C + c) * hw + rr] = tab[c][tid];
+    }
+    __syncthreads();
+    for (int i = tid; i < g.C * LOSS_TX; i += 256) {
+        const int lc = i % LOSS_TX, c = i / LOSS_TX;
+        const int cx = tx * LOSS_TX + lc;
+        if (cx >= g.w) continue;
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int X = 8 * cx - 4 + t;                  // table column 8 * lc + t
+            if (X >= 0 && X < g.W) acc += tap_weight(X, cx, g.w) * colsum[c][8 * lc + t];
+        }
+        T[((size_t)img * g.C + c) * hw + cy * g.w + cx] = acc;
     }
 }
 
@@ -380,7 +397,7 @@ static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* lab
 // T = U^T (one-hot valid labels); once per call
 void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T)
 {
-    const dim3 grid(cdiv(g.positions(), 256));
+    const dim3 grid(g.n * g.h * ((g.w + LOSS_TX - 1) / LOSS_TX));
 #define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, T, g)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL

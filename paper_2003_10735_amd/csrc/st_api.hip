@@ -30,8 +30,6 @@ static bool g_prof_on = false;
 static std::string g_prof_filter;   // empty: every kernel
 static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_event_pool;
-static thread_local const char* g_prof_name = nullptr;
-static thread_local hipEvent_t g_prof_start = nullptr;
 
 static hipEvent_t get_event()
 {
@@ -41,28 +39,22 @@ static hipEvent_t get_event()
     return e;
 }
 
-void prof_begin(Ctx& c, const char* name)
+void prof_events(Ctx&, const char* name, hipEvent_t* start, hipEvent_t* stop)
 {
+    *start = nullptr;
+    *stop = nullptr;
     if (!g_prof_on) return;
     std::lock_guard<std::mutex> lk(g_prof_mutex);
     if (!g_prof_filter.empty() && !strstr(name, g_prof_filter.c_str())) return;
-    g_prof_name = name;
-    g_prof_start = get_event();
-    if (g_prof_start) (void)hipEventRecord(g_prof_start, c.stream);
-}
-
-void prof_end(Ctx& c)
-{
-    if (!g_prof_on || !g_prof_start) return;
-    std::lock_guard<std::mutex> lk(g_prof_mutex);
-    hipEvent_t stop = get_event();
-    if (stop) {
-        (void)hipEventRecord(stop, c.stream);
-        g_prof.push_back(ProfRec{g_prof_name, g_prof_start, stop});
-    } else {
-        g_event_pool.push_back(g_prof_start);
+    hipEvent_t a = get_event(), b = get_event();
+    if (!a || !b) {
+        if (a) g_event_pool.push_back(a);
+        if (b) g_event_pool.push_back(b);
+        return;
     }
-    g_prof_start = nullptr;
+    g_prof.push_back(ProfRec{name, a, b});
+    *start = a;
+    *stop = b;
 }
 
 // kernels that need more than 64 KB of dynamic LDS must be told once (per process)

@@ -2,6 +2,7 @@
 // bookkeeping and small device helpers.  gfx950 only.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -124,20 +125,26 @@ struct Ctx {
     int status;   // first failure sticks
 };
 
-void prof_begin(Ctx& c, const char* name);
-void prof_end(Ctx& c);
+// When the event profile is on and covers `name`, hands out a start/stop event pair that the
+// launch attaches to the dispatch itself (hipExtLaunchKernelGGL): the pair then times the kernel
+// only and puts no extra packet into the stream.  Otherwise both come back null.
+void prof_events(Ctx& c, const char* name, hipEvent_t* start, hipEvent_t* stop);
 void set_hip_error(hipError_t e);
 void ensure_dynamic_lds(const void* kernel, size_t bytes);
 
-#define ST_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                               \
-    do {                                                                                    \
-        if ((ctx).status == ST_OK) {                                                        \
-            st::prof_begin((ctx), name);                                                    \
-            hipLaunchKernelGGL(kernel, grid, block, shmem, (ctx).stream, __VA_ARGS__);      \
-            hipError_t e_ = hipGetLastError();                                              \
-            st::prof_end((ctx));                                                            \
-            if (e_ != hipSuccess) { st::set_hip_error(e_); (ctx).status = ST_ERR_HIP; }     \
-        }                                                                                   \
+#define ST_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                                   \
+    do {                                                                                        \
+        if ((ctx).status == ST_OK) {                                                            \
+            hipEvent_t e0_ = nullptr, e1_ = nullptr;                                            \
+            st::prof_events((ctx), name, &e0_, &e1_);                                           \
+            if (e0_)                                                                            \
+                hipExtLaunchKernelGGL(kernel, grid, block, shmem, (ctx).stream, e0_, e1_, 0,    \
+                                      __VA_ARGS__);                                             \
+            else                                                                                \
+                hipLaunchKernelGGL(kernel, grid, block, shmem, (ctx).stream, __VA_ARGS__);      \
+            hipError_t err_ = hipGetLastError();                                                \
+            if (err_ != hipSuccess) { st::set_hip_error(err_); (ctx).status = ST_ERR_HIP; }     \
+        }                                                                                       \
     } while (0)
 
 // ------------------------------------------------------------------ device helpers
