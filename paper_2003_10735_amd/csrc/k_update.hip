@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "st_kernels.hpp"
+#include "st_mfma.hpp"
 
 namespace st {
 
@@ -20,12 +21,16 @@ namespace st {
 //      block: the tile losses added in a fixed order (float64) over the number of valid pixels.
 //
 // Roles (1) and (2) also refresh the bfloat16 copies of the new weights:
-//   wq1, wq2, wq3 : same (internal) order as theta, for the forward convolutions
-//   wq2t          : W2 as [i][tap'][o] with tap' the mirrored tap, for the data-gradient of layer 2
+//   wq1, wq2, wq3 : for the forward convolutions
+//   wq2t          : W2 with the roles of o and i exchanged and the taps mirrored (tap' = 8 - tap),
+//                   for the data-gradient of layer 2 run as a forward convolution
+// wq3 has theta's order.  So do wq1 and wq2 for the plain tiled kernels (frag == 0); the
+// matrix-core convolutions read wq1, wq2 and wq2t in fragment order (wfrag_index).
 struct UpdateArgs {
     float* theta; float* vel; const float* grad; size_t stride; int splits1, splits2;
     bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
-    ParamOffsets po; int c1, c2;
+    ParamOffsets po; int c_in, c1, c2;
+    int frag;        // wq1 / wq2 / wq2t in fragment order
     float lr, mu;
     int do_step;     // 0: only refresh the bfloat16 copies
     // role (2)
@@ -53,14 +58,19 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
     }
     if (a.wq1) {
         const bf16 q = (bf16)w;
-        if (j < a.po.b1) a.wq1[j - a.po.W1] = q;
-        else if (j >= a.po.W2 && j < a.po.b2) {
+        if (j < a.po.b1) {
+            const size_t r = j - a.po.W1;
+            if (a.frag) {
+                const int i = (int)(r % a.c_in), tap = (int)((r / a.c_in) % 9), o = (int)(r / ((size_t)a.c_in * 9));
+                a.wq1[wfrag_index(o, tap, i, a.c_in)] = q;
+            } else a.wq1[r] = q;
+        } else if (j >= a.po.W2 && j < a.po.b2) {
             const size_t r = j - a.po.W2;
-            a.wq2[r] = q;
-            if (a.wq2t) {
-                const size_t i = r % a.c1, tap = (r / a.c1) % 9, o = r / ((size_t)a.c1 * 9);
-                a.wq2t[(i * 9 + (8 - tap)) * a.c2 + o] = q;
-            }
+            if (a.frag) {
+                const int i = (int)(r % a.c1), tap = (int)((r / a.c1) % 9), o = (int)(r / ((size_t)a.c1 * 9));
+                a.wq2[wfrag_index(o, tap, i, a.c1)] = q;
+                a.wq2t[wfrag_index(i, 8 - tap, o, a.c2)] = q;
+            } else a.wq2[r] = q;
         } else if (j >= a.po.W3 && j < a.po.b3) a.wq3[j - a.po.W3] = q;
     }
 }
@@ -183,7 +193,8 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step,
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
     a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
     a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
-    a.po = p.po; a.c1 = p.g.c1; a.c2 = p.g.c2;
+    a.po = p.po; a.c_in = p.g.c_in; a.c1 = p.g.c1; a.c2 = p.g.c2;
+    a.frag = p.mfma ? 1 : 0;
     a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;
     a.part3 = (const float*)(ws + p.grad3);
     a.blocks3 = p.blocks3; a.slot3 = conv3_bwd_slot_floats(p.g); a.C = p.g.C;

@@ -21,4 +21,13 @@ __host__ __device__ __forceinline__ size_t xt_index(int c, int col, int NG)
 {
     return (((size_t)(c >> 5) * NG + (col >> 3)) << 8) + ((c & 31) << 3) + (col & 7);
 }
+
+// Weights of the 3x3 matrix-core convolutions, [rows][9 taps][K], are kept in the order in which
+// that kernel's wavefronts consume them: one A fragment (32 rows x 16 k of one tap, lane l holding
+// row l % 32, k 8*(l/32) .. +7) is one contiguous 1 KB run,
+//     [row / 32][tap][k / 16][(k / 8) % 2][row % 32][k % 8].
+__host__ __device__ __forceinline__ size_t wfrag_index(int row, int tap, int k, int K)
+{
+    return ((((size_t)(row >> 5) * 9 + tap) * (K >> 4) + (k >> 4)) * 64 + ((k >> 3) & 1) * 32 + (row & 31)) * 8 + (k & 7);
+}
 }  // namespace st
