@@ -65,10 +65,10 @@ template <int EPI, int TAG>
 __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 {
     constexpr int NT = 512;                // threads per block
-    // 16-byte chunks per stage; every thread moves the same number without a bounds test: the
-    // slots beyond the last chunk wrap around and re-copy a chunk (same bytes)
+    // 16-byte chunks per stage: XS_FULL per thread and one more for the first XS_REST threads
     constexpr int XS_CHUNKS = CV_XS_ROWS * 8;
-    constexpr int XS_PER_T = (XS_CHUNKS + NT - 1) / NT;
+    constexpr int XS_FULL = XS_CHUNKS / NT, XS_REST = XS_CHUNKS % NT;
+    constexpr int XS_PER_T = XS_FULL + 1;
     constexpr int XS_ELEMS = CV_XS_ROWS * CV_LDP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* Xs = (bf16*)smem_raw;                       // [2][XS_ROWS][LDP]
@@ -102,25 +102,22 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     u32x4 xr[2][XS_PER_T];   // activations on their way to LDS
     u32x4 wr[2][3];          // weight fragments of the three taps of a stage
 
-#define CV_LOAD_X(SET, S)                                                                         \
-    {                                                                                             \
+#define CV_LOAD_X1(SET, S, I)                                                                     \
+    if ((I) < XS_FULL || tid < XS_REST) {                                                         \
         const int kh_ = (S) / c_chunks, c0_ = ((S) % c_chunks) * CV_BK;                           \
         const bf16* src_ = a.X + ((long long)m0 - 1 + (long long)(kh_ - 1) * a.Wp) * a.cin + c0_; \
-        _Pragma("unroll") for (int i = 0; i < XS_PER_T; ++i) {                                    \
-            int q = tid + i * NT;                                                                 \
-            q = q < XS_CHUNKS ? q : q - XS_CHUNKS;                                                \
-            xr[SET][i] = *(const u32x4*)(src_ + (long long)(q >> 3) * a.cin + (q & 7) * 8);       \
-        }                                                                                         \
+        const int q = tid + (I) * NT;                                                             \
+        xr[SET][I] = *(const u32x4*)(src_ + (long long)(q >> 3) * a.cin + (q & 7) * 8);           \
     }
+#define CV_LOAD_X(SET, S) CV_LOAD_X1(SET, S, 0) CV_LOAD_X1(SET, S, 1) CV_LOAD_X1(SET, S, 2)
 #define CV_LOAD_W(SET, S, KW)                                                                     \
     {                                                                                             \
         const int kh_ = (S) / c_chunks, kc_ = ((S) % c_chunks) * (CV_BK / 16);                    \
         wr[SET][KW] = *(const u32x4*)(wbase + ((size_t)(kh_ * 3 + (KW)) * kfr + kc_) * 512);      \
     }
 #define CV_STORE1(SET, BUF, I)                                                                    \
-    {                                                                                             \
-        int q = tid + (I) * NT;                                                                   \
-        q = q < XS_CHUNKS ? q : q - XS_CHUNKS;                                                    \
+    if ((I) < XS_FULL || tid < XS_REST) {                                                         \
+        const int q = tid + (I) * NT;                                                             \
         *(u32x4*)(Xs + (BUF) * XS_ELEMS + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[SET][I];          \
     }
 #define CV_READ1(DST, J, BUF, KW)                                                                 \
@@ -143,11 +140,10 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     {                                                                                             \
         const int s2_ = min((S) + 2, last);                                                       \
         CV_READ1(xa, 0, BUF, 0) CV_READ1(xa, 1, BUF, 0) CV_READ1(xa, 2, BUF, 0) CV_READ1(xa, 3, BUF, 0) \
-        CV_LOAD_X(SET, s2_)                                                                       \
-        CV_READ1(xb, 0, BUF, 1) CV_READ1(xb, 1, BUF, 1) CV_F                                      \
-        CV_MMA1(xa, 0, SET, 0) CV_F CV_READ1(xb, 2, BUF, 1) CV_F                                  \
-        CV_MMA1(xa, 1, SET, 0) CV_F CV_READ1(xb, 3, BUF, 1) CV_F                                  \
-        CV_MMA1(xa, 2, SET, 0) CV_F                                                               \
+        CV_READ1(xb, 0, BUF, 1) CV_F                                                              \
+        CV_MMA1(xa, 0, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 0) CV_READ1(xb, 1, BUF, 1) CV_F          \
+        CV_MMA1(xa, 1, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 1) CV_READ1(xb, 2, BUF, 1) CV_F          \
+        CV_MMA1(xa, 2, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 2) CV_READ1(xb, 3, BUF, 1) CV_F          \
         CV_MMA1(xa, 3, SET, 0) CV_F CV_LOAD_W(SET, s2_, 0) CV_F                                   \
         CV_MMA1(xb, 0, SET, 1) CV_F CV_READ1(xa, 0, BUF, 2) CV_F                                  \
         CV_MMA1(xb, 1, SET, 1) CV_F CV_READ1(xa, 1, BUF, 2) CV_F                                  \
@@ -173,22 +169,17 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         __syncthreads();
     }
     // Two stages per trip, so that register sets and LDS buffers are compile-time choices; an
-    // odd stage count peels its first stage.  (One loop with an exit in the middle would do, but
-    // the accumulators then live across two different exits and get copied around every stage.)
-    if (n_stages & 1) {
-        CV_STAGE(0, 0, 0)
-        for (int s = 1; s < n_stages; s += 2) {
-            CV_STAGE(s, 1, 1)
-            CV_STAGE(s + 1, 0, 0)
-        }
-    } else {
-        for (int s = 0; s < n_stages; s += 2) {
-            CV_STAGE(s, 0, 0)
-            CV_STAGE(s + 1, 1, 1)
-        }
+    // odd stage count runs its last stage after the loop.  (One loop with an exit in the middle
+    // would do, but the accumulators then live across two different exits and get copied around
+    // every stage.)
+    for (int s = 0; s + 1 < n_stages; s += 2) {
+        CV_STAGE(s, 0, 0)
+        CV_STAGE(s + 1, 1, 1)
     }
+    if (n_stages & 1) CV_STAGE(last, 0, 0)
 #undef CV_STAGE
 #undef CV_LOAD_X
+#undef CV_LOAD_X1
 #undef CV_LOAD_W
 #undef CV_STORE1
 #undef CV_READ1
