@@ -35,8 +35,9 @@ struct UpdateArgs {
     int do_step;     // 0: only refresh the bfloat16 copies
     // role (2)
     const float* part3; int blocks3; size_t slot3; int C;
-    // block ranges
-    int nb_main, nb_l3, nb_finish;
+    // block ranges; vec: role (1) handles four parameters per thread over [0, W3) and nb_tail
+    // blocks handle [W3, total) one by one unless role (2) does
+    int nb_main, nb_tail, nb_l3, nb_finish, vec;
 };
 
 struct FinishArgs {
@@ -72,6 +73,46 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
                 a.wq2t[wfrag_index(i, 8 - tap, o, a.c2)] = q;
             } else a.wq2[r] = q;
         } else if (j >= a.po.W3 && j < a.po.b3) a.wq3[j - a.po.W3] = q;
+    }
+}
+
+// Four consecutive parameters (all block boundaries below W3 are multiples of four here, so
+// the four lie in the same block).
+__device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32x4 g)
+{
+    f32x4 w = *(const f32x4*)(a.theta + j);
+    if (a.do_step) {
+        if (a.mu != 0.f) {
+            const f32x4 vo = *(const f32x4*)(a.vel + j);
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(a.mu, vo[e], g[e]);
+            *(f32x4*)(a.vel + j) = v;
+            g = v;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = __builtin_fmaf(-a.lr, g[e], w[e]);
+        *(f32x4*)(a.theta + j) = w;
+    }
+    if (a.wq1) {
+        bf16x4 q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q[e] = (bf16)w[e];
+        if (j < a.po.b1) {
+            const size_t r = j - a.po.W1;
+            if (a.frag) {
+                const int i = (int)(r % a.c_in), tap = (int)((r / a.c_in) % 9), o = (int)(r / ((size_t)a.c_in * 9));
+                *(bf16x4*)(a.wq1 + wfrag_index(o, tap, i, a.c_in)) = q;
+            } else *(bf16x4*)(a.wq1 + r) = q;
+        } else if (j >= a.po.W2 && j < a.po.b2) {
+            const size_t r = j - a.po.W2;
+            if (a.frag) {
+                const int i = (int)(r % a.c1), tap = (int)((r / a.c1) % 9), o = (int)(r / ((size_t)a.c1 * 9));
+                *(bf16x4*)(a.wq2 + wfrag_index(o, tap, i, a.c1)) = q;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a.wq2t[wfrag_index(i + e, 8 - tap, o, a.c2)] = q[e];
+            } else *(bf16x4*)(a.wq2 + r) = q;
+        }
     }
 }
 
@@ -132,7 +173,30 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
 {
     const int b = blockIdx.x;
     if (b < a.nb_main) {
-        // role (1); W3/b3 are left to role (2) when it is active
+        // role (1), four parameters per thread over [0, W3): the partial gradients are added in
+        // ascending order of the split, four loads in flight at a time
+        if (a.vec) {
+            const size_t j = ((size_t)b * 256 + threadIdx.x) * 4;
+            if (j >= a.po.W3) return;
+            f32x4 g = {0.f, 0.f, 0.f, 0.f};
+            if (a.do_step) {
+                const int splits = j < a.po.W2 ? a.splits1 : a.splits2;
+                const float* gp = a.grad + j;
+                g = *(const f32x4*)gp;
+                int s = 1;
+                for (; s + 3 < splits; s += 4) {
+                    const f32x4 v0 = *(const f32x4*)(gp + (size_t)s * a.stride);
+                    const f32x4 v1 = *(const f32x4*)(gp + (size_t)(s + 1) * a.stride);
+                    const f32x4 v2 = *(const f32x4*)(gp + (size_t)(s + 2) * a.stride);
+                    const f32x4 v3 = *(const f32x4*)(gp + (size_t)(s + 3) * a.stride);
+                    g = (((g + v0) + v1) + v2) + v3;
+                }
+                for (; s < splits; ++s) g += *(const f32x4*)(gp + (size_t)s * a.stride);
+            }
+            apply_update4(a, j, g);
+            return;
+        }
+        // role (1), one parameter per thread; W3/b3 are left to role (2) when it is active
         const size_t j = (size_t)b * 256 + threadIdx.x;
         const size_t limit = a.nb_l3 ? a.po.W3 : a.po.total;
         if (j >= limit) return;
@@ -143,10 +207,15 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
             for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
         }
         apply_update(a, j, g);
-    } else if (b < a.nb_main + a.nb_l3) {
+    } else if (b < a.nb_main + a.nb_tail) {
+        // [W3, total) one by one (only when role (2) is not active)
+        const size_t j = a.po.W3 + (size_t)(b - a.nb_main) * 256 + threadIdx.x;
+        if (j >= a.po.total) return;
+        apply_update(a, j, a.do_step ? a.grad[j] : 0.f);
+    } else if (b < a.nb_main + a.nb_tail + a.nb_l3) {
         // role (2): slot layout [32 classes][c2] weights, then [32] biases
         const int lane = threadIdx.x & 63;
-        const int k = (b - a.nb_main) * 4 + (threadIdx.x >> 6);
+        const int k = (b - a.nb_main - a.nb_tail) * 4 + (threadIdx.x >> 6);
         const int n_w = a.C * a.c2;
         if (k >= n_w + a.C) return;
         float acc = 0.f;
@@ -158,7 +227,7 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
         }
         if (lane == 0) apply_update(a, a.po.W3 + k, acc);
     } else {
-        finish_block(f, b - a.nb_main - a.nb_l3);
+        finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3);
     }
 }
 
@@ -186,7 +255,7 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step,
     a.theta = (float*)(ws + p.theta);
     a.vel = (float*)(ws + p.vel);
     a.grad = (const float*)(ws + p.grad);
-    a.stride = p.po.total;
+    a.stride = p.grad_stride;
     a.splits1 = p.mfma ? p.splits1 : 1;
     a.splits2 = p.mfma ? p.splits2 : 1;
     a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
@@ -200,11 +269,20 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step,
     a.blocks3 = p.blocks3; a.slot3 = conv3_bwd_slot_floats(p.g); a.C = p.g.C;
     const bool params = do_step || p.bf16;
     const bool l3 = params && p.mfma && do_step;
-    a.nb_main = params ? cdiv(l3 ? p.po.W3 : p.po.total, 256) : 0;
+    // four parameters per thread when every block below W3 starts at a multiple of four and the
+    // split copies keep 16-byte alignment
+    a.vec = (p.po.b1 % 4 == 0 && p.po.W2 % 4 == 0 && p.po.b2 % 4 == 0 && p.po.W3 % 4 == 0) ? 1 : 0;
+    if (a.vec) {
+        a.nb_main = params ? cdiv(p.po.W3 / 4, 256) : 0;
+        a.nb_tail = (params && !l3) ? cdiv(p.po.total - p.po.W3, 256) : 0;
+    } else {
+        a.nb_main = params ? cdiv(l3 ? p.po.W3 : p.po.total, 256) : 0;
+        a.nb_tail = 0;
+    }
     a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 4) : 0;
     a.nb_finish = finish ? p.g.n + 1 : 0;
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
-    const int blocks = a.nb_main + a.nb_l3 + a.nb_finish;
+    const int blocks = a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
     if (blocks == 0) return;
     const char* name = do_step ? (finish ? "sgd_update+finish_pass" : "sgd_update") : (params ? "weights_to_bf16" : "finish_pass");
     ST_LAUNCH(c, name, k_step_end, dim3(blocks), dim3(256), 0, a, f);

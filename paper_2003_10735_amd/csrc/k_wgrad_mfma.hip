@@ -219,7 +219,7 @@ void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, con
 {
     WgradArgs a;
     a.dYT = dYT; a.XT = XT; a.dW = dW; a.db = db;
-    a.split_stride = p.po.total;
+    a.split_stride = p.grad_stride;
     a.cin = cin; a.cout = cout; a.PPT = p.PPT; a.guard = p.guard; a.Wp = p.g.Wp;
     a.n_units = cdiv(p.g.padded_positions(), 16);
     a.units_per_wave = cdiv(a.n_units, splits * 4);

@@ -147,7 +147,8 @@ Plan make_plan(const st_head_desc& d)
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.theta = take(off, p.po.total * 4);
     p.vel = take(off, p.po.total * 4);
-    p.grad = take(off, p.po.total * 4 * p.grad_copies);
+    p.grad_stride = (p.po.total + 3) / 4 * 4;
+    p.grad = take(off, p.grad_stride * 4 * p.grad_copies);
     p.grad3 = take(off, (size_t)std::max(p.blocks3, 1) * conv3_bwd_slot_floats(g) * 4);
     p.best = take(off, p.po.total * 4);
     if (p.bf16) {

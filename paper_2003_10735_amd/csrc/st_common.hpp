@@ -99,6 +99,7 @@ struct Plan {
     int splits1, splits2;   // position splits of the layer-1 / layer-2 weight-gradient kernels
     int blocks3;            // per-block partial slots of the layer-3 backward kernel
     int grad_copies;        // max(splits1, splits2): partial gradient copies the update sums
+    size_t grad_stride;     // floats between two copies (total rounded up to 16 bytes)
     int guard;          // guard rows before and after every position-major activation buffer;
                         // also the number of guard columns in front of a channel-major row
     int PPT;            // row pitch (elements) of the channel-major copies
