@@ -50,23 +50,6 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// number of valid labels (constant over the steps of one call)
-__global__ void __launch_bounds__(256)
-k_count_valid(const int32_t* __restrict__ labels, long long P, int C, int ignore, unsigned long long* out)
-{
-    __shared__ unsigned int part[4];
-    unsigned int cnt = 0;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < P; i += (long long)gridDim.x * 256) {
-        const int y = labels[i];
-        cnt += (y != ignore && y >= 0 && y < C) ? 1u : 0u;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = cnt;
-    __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(out, (unsigned long long)(part[0] + part[1] + part[2] + part[3]));
-}
-
 // weight with which frame index X (0 .. 8*len-1) contributes to cell `cell` of a line of `len`
 // cells: the tent (1, 3, .. 15, 15, .. 3, 1)/16 around the cell, plus, for the first and last
 // cell, the weight that edge replication folds back onto them
@@ -89,10 +72,12 @@ __device__ __forceinline__ float tap_weight(int X, int cell, int len)
 // not depend on the order of additions.
 template <int CP>
 __global__ void __launch_bounds__(256)
-k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, Geo g)
+k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, unsigned long long* __restrict__ n_valid,
+                Geo g)
 {
     constexpr int NCOL = LOSS_TX * 8 + 8;
     __shared__ float colsum[CP][NCOL + 1];
+    __shared__ unsigned int cnt_part[4];
     const int tid = threadIdx.x;
     const int tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
     const int tx = blockIdx.x % tiles_x, cy = (blockIdx.x / tiles_x) % g.h, img = blockIdx.x / (tiles_x * g.h);
@@ -101,16 +86,34 @@ k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, Geo g
     for (int i = tid; i < CP * (NCOL + 1); i += 256) (&colsum[0][0])[i] = 0.f;
     __syncthreads();
     const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
-    const int Y0 = max(8 * cy - 4, 0), Y1 = min(8 * cy + 12, g.H);
+    const int Yt = 8 * cy - 4;                             // frame row of tent position 0
+    unsigned int cnt = 0;                                  // valid labels of this block's own 8 x 256 pixels
     for (int col = tid; col < NCOL; col += 256) {
         const int X = X0 + col;
-        if (X < 0 || X >= g.W) continue;
-        for (int Y = Y0; Y < Y1; ++Y) {
-            const int y = lab[(size_t)Y * g.W + X];
-            if (y != g.ignore_index && y >= 0 && y < g.C) colsum[y][col] += tap_weight(Y, cy, g.h);
+        const bool xin = X >= 0 && X < g.W;
+        const int Xc = min(max(X, 0), g.W - 1);
+        // the 16 rows under the tent: all loads first (clamped, so none depends on a branch)
+        int ys[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ys[r] = lab[(size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc];
+        const bool own_col = col >= 4 && col < NCOL - 4;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int Y = Yt + r, y = ys[r];
+            if (xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C) {
+                colsum[y][col] += tap_weight(Y, cy, g.h);
+                if (own_col && r >= 4 && r < 12) ++cnt;
+            }
         }
     }
+    if (n_valid) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off, 64);
+        if ((tid & 63) == 0) cnt_part[tid >> 6] = cnt;
+    }
     __syncthreads();
+    if (n_valid && tid == 0)
+        atomicAdd(n_valid, (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
     for (int i = tid; i < g.C * LOSS_TX; i += 256) {
         const int lc = i % LOSS_TX, c = i / LOSS_TX;
         const int cx = tx * LOSS_TX + lc;
@@ -353,14 +356,6 @@ size_t loss_slot_floats(const Geo& g)
 
 int loss_blocks(const Geo& g) { return g.n * loss_tiling(g).tiles(); }
 
-void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long* out)
-{
-    const long long P = g.pixels();
-    int blocks = cdiv(P, 256 * 8);
-    if (blocks > 1024) blocks = 1024;
-    ST_LAUNCH(c, "count_valid", k_count_valid, dim3(blocks), dim3(256), 0, labels, P, g.C, g.ignore_index, out);
-}
-
 template <int CP>
 static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
@@ -394,11 +389,12 @@ static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* lab
     default: c.status = ST_ERR_SHAPE; break;                                                  \
     }
 
-// T = U^T (one-hot valid labels); once per call
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T)
+// T = U^T (one-hot valid labels); once per call.  With n_valid (a cleared counter) the kernel also
+// counts the valid labels: every pixel belongs to the 8 x 256 pixels of exactly one block.
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsigned long long* n_valid)
 {
     const dim3 grid(g.n * g.h * ((g.w + LOSS_TX - 1) / LOSS_TX));
-#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, T, g)
+#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, T, n_valid, g)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
 }

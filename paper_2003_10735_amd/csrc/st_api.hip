@@ -298,8 +298,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     permute_params(c, p, head_params, theta, 0);
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
     update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
-    count_valid(c, g, teacher_labels, n_valid);
-    label_adjoint(c, g, teacher_labels, (float*)(ws + p.tadj));
+    label_adjoint(c, g, teacher_labels, (float*)(ws + p.tadj), n_valid);   // also counts the valid labels
 
     double best_metric = -1.0;
     std::vector<double> frame_metric;

@@ -33,8 +33,7 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
 // k_loss.hip
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
-void count_valid(Ctx& c, const Geo& g, const int32_t* labels, unsigned long long* out);
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T);
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsigned long long* n_valid);
 void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble);
