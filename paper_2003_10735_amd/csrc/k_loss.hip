@@ -18,8 +18,8 @@
 // so the per-step kernel needs no per-class label test at all: per pixel and class it does one
 // fma (interpolate), max/compare (prediction), fma + exp, add, and two fmas (U^T along y).
 //
-// Work split: one 256-thread block per tile of LOSS_TY x LOSS_TX groups of 8 x 8 pixels, one
-// thread per pixel column.  A tile touches (LOSS_TY + 2) x (LOSS_TX + 2) low-resolution cells;
+// Work split: one 512-thread block per tile of 1 x LOSS_TX groups of 8 x 8 pixels, two threads
+// per pixel column (four pixels each).  A tile touches 3 x (LOSS_TX + 2) low-resolution cells;
 // its share of U^T P for those cells goes to a slot of its own, and the consumer adds the (at
 // most four) slots that meet in a cell in a fixed order.  No floating-point atomics anywhere:
 // results do not change from run to run.
@@ -128,37 +128,59 @@ k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, unsig
     }
 }
 
+constexpr int LOSS_THREADS = 512;
+
 template <int CP, bool GRAD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(LOSS_THREADS)
 k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
        unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
 {
-    constexpr int CW = LOSS_CW, CH = LOSS_CH, CWP = CW + 1;
+    static_assert(LOSS_TY == 1, "one row group per tile: the two halves of a block split its 8 pixel rows");
+    constexpr int CW = LOSS_CW, CH = LOSS_CH, CWP = CW + 1, NT = LOSS_THREADS;
     __shared__ float zt[CP][CH][CWP];                 // logits of the touched cells
-    // per row group and column group: what they hand to their 3 x 3 cells (left, centre, right,
-    // unused); written once, never read-modify-written
-    __shared__ __attribute__((aligned(16))) float contrib[GRAD ? LOSS_TY : 1][GRAD ? CP : 1][3][LOSS_TX][4];
+    // per half, class, cell row (upper / lower of the half) and column group: what the group hands
+    // to its (left, centre, right, unused) cells; written once, never read-modify-written
+    __shared__ __attribute__((aligned(16))) float contrib[GRAD ? 2 : 1][GRAD ? CP : 1][2][LOSS_TX][4];
     __shared__ unsigned int conf_l[32 * 32];          // label x prediction counts of this tile
-    __shared__ float wsum[4];
+    __shared__ float wsum[NT / 64];
 
     const int tid = threadIdx.x;
     const int tile = blockIdx.x % lt.tiles(), img = blockIdx.x / lt.tiles();
-    const int tile_x = tile % lt.tiles_x, tile_y = tile / lt.tiles_x;
+    const int tile_x = tile % lt.tiles_x, qy = tile / lt.tiles_x;   // qy: row group = cell row
     const int C = g.C, hw = g.h * g.w;
-    const int cx0 = tile_x * LOSS_TX - 1, cy0 = tile_y * LOSS_TY - 1;  // cell of local (0, 0)
+    const int cx0 = tile_x * LOSS_TX - 1, cy0 = qy - 1;  // cell of local (0, 0)
 
     // ---- stage the touched cells (edge replication = clamped read); padded classes get a
-    //      large negative logit: they never win, their softmax term is exactly 0
-    for (int i = tid; i < CP * CH * CW; i += 256) {
+    //      large negative logit: they never win, their softmax term is exactly 0.
+    //      All global loads of the prologue are issued before anything waits for one of them.
+    constexpr int NZ = (CP * CH * CW + NT - 1) / NT;
+    float zv[NZ];
+#pragma unroll
+    for (int k = 0; k < NZ; ++k) {
+        const int i = min(tid + k * NT, CP * CH * CW - 1);
         const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
         const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
-        zt[c][r][lc] = c < C ? z[((size_t)img * C + c) * hw + cy * g.w + cx] : -1e30f;
+        zv[k] = z[((size_t)img * C + min(c, C - 1)) * hw + cy * g.w + cx];
     }
-    for (int i = tid; i < C * C; i += 256) conf_l[i] = 0;
-    __syncthreads();
+    // T over the cells this tile owns, for the  - <T, z>  part of the loss (see the header)
+    constexpr int NTT = (32 * LOSS_TX + NT - 1) / NT;
+    float tv[NTT];
+    const bool want_tz = T && loss_part;
+#pragma unroll
+    for (int k = 0; k < NTT; ++k) {
+        const int i = tid + k * NT;
+        const int lc = i % LOSS_TX, c = i / LOSS_TX;
+        const int cx = tile_x * LOSS_TX + lc;
+        tv[k] = (want_tz && c < C && cx < g.w) ? T[((size_t)img * C + c) * hw + qy * g.w + cx] : 0.f;
+    }
+    for (int i = tid; i < C * C; i += NT) conf_l[i] = 0;
 
-    const int j = tid & 7, tq = tid >> 3;
+    // Two threads per pixel column: `half` 0 takes the upper four pixels of the 8 (they
+    // interpolate between cell rows qy-1 and qy), half 1 the lower four (rows qy and qy+1).
+    // The per-thread instruction stream is the critical path of this kernel, so it is kept short.
+    const int half = tid >> 8, t = tid & 255;
+    const int j = t & 7, tq = t >> 3;
     const int X = (tile_x * LOSS_TX + tq) * 8 + j;
     const bool col_ok = X < g.W;
     const float fx = (j < 4 ? 2 * j + 9 : 2 * j - 7) * 0.0625f;
@@ -172,144 +194,143 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const fl
         const int q = tile_x * LOSS_TX + tq;
         if ((q == 0 && j < 4) || (q == g.w - 1 && j >= 4)) { w_mid += w_side; w_side = 0.f; }
     }
-
-    float loss_acc = 0.f;
     const int32_t* lab_img = labels ? labels + (size_t)img * g.H * g.W : nullptr;
     uint8_t* pred_img = pred ? pred + (size_t)img * g.H * g.W : nullptr;
+    const int Yb = qy * 8 + half * 4;    // first of this thread's four pixel rows
+    // labels of this thread's 4 pixels, fetched before the barrier
+    int lab4[4];
+    if (lab_img) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < NZ; ++k) {
+        const int i = tid + k * NT;
+        const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
+        if (i < CP * CH * CW) zt[c][r][lc] = c < C ? zv[k] : -1e30f;
+    }
+    __syncthreads();
 
-    // ---- minus <T, z> over the cells this tile owns (part of the loss; see the header)
-    if (T && loss_part) {
-        for (int i = tid; i < C * LOSS_TY * LOSS_TX; i += 256) {
-            const int lc = i % LOSS_TX, r = (i / LOSS_TX) % LOSS_TY, c = i / (LOSS_TX * LOSS_TY);
-            const int cx = tile_x * LOSS_TX + lc, cy = tile_y * LOSS_TY + r;
-            if (cx < g.w && cy < g.h)
-                loss_acc -= T[((size_t)img * C + c) * hw + cy * g.w + cx] * zt[c][r + 1][lc + 1];
-        }
+    float loss_acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < NTT; ++k) {
+        const int i = tid + k * NT;
+        const int lc = i % LOSS_TX, c = min(i / LOSS_TX, CP - 1);
+        loss_acc -= tv[k] * zt[c][1][lc + 1];     // tv is 0 where the cell or class does not exist
     }
 
-#pragma unroll 1
-    for (int gy = 0; gy < LOSS_TY; ++gy) {
-        const int qy = tile_y * LOSS_TY + gy;   // row group
-        if (qy >= g.h) break;                   // uniform over the block
-        // labels of this column's 8 pixels, fetched up front
-        int lab8[8];
+    // x-interpolated logits on this half's upper cell row and their difference to the lower one
+    // (the y interpolation is fma(fy, difference, upper row): same roundings as lerp1)
+    float Hu[CP], D[CP];
+#pragma unroll
+    for (int c = 0; c < CP; ++c) {
+        Hu[c] = lerp1(zt[c][half][cl], zt[c][half][cl + 1], fx);
+        const float Hl = lerp1(zt[c][half + 1][cl], zt[c][half + 1][cl + 1], fx);
+        D[c] = __fsub_rn(Hl, Hu[c]);
+    }
+    float Vu[GRAD ? CP : 1], Vl[GRAD ? CP : 1];    // U^T along y: upper / lower cell row of the half
+    if (GRAD) {
+#pragma unroll
+        for (int c = 0; c < CP; ++c) { Vu[c] = 0.f; Vl[c] = 0.f; }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        // weight of the lower cell row: (9, 11, 13, 15) / 16 in the upper half, (1, 3, 5, 7) / 16 below
+        const float fy = half ? (2 * i + 1) * 0.0625f : (2 * i + 9) * 0.0625f;
+        const int Y = Yb + i;
+        float Z[CP];
+#pragma unroll
+        for (int c = 0; c < CP; ++c) Z[c] = __builtin_fmaf(fy, D[c], Hu[c]);
+        // prediction: the largest logit, lowest index among equals
+        float m = Z[0];
+#pragma unroll
+        for (int c = 1; c < CP; ++c) m = fmaxf(m, Z[c]);
+        int best = CP - 1;
+#pragma unroll
+        for (int c = CP - 2; c >= 0; --c) best = Z[c] == m ? c : best;
+        if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
         if (lab_img) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) lab8[i] = col_ok ? lab_img[(size_t)(qy * 8 + i) * g.W + X] : -1;
-        }
-        // x-interpolated logits on cell rows qy-1, qy, qy+1 and their differences (the y
-        // interpolation is fma(fy, difference, upper row): same roundings as lerp1)
-        float Hm[CP], H0[CP], D0[CP], D1[CP];
-#pragma unroll
-        for (int c = 0; c < CP; ++c) {
-            Hm[c] = lerp1(zt[c][gy][cl], zt[c][gy][cl + 1], fx);
-            H0[c] = lerp1(zt[c][gy + 1][cl], zt[c][gy + 1][cl + 1], fx);
-            const float Hp = lerp1(zt[c][gy + 2][cl], zt[c][gy + 2][cl + 1], fx);
-            D0[c] = __fsub_rn(H0[c], Hm[c]);
-            D1[c] = __fsub_rn(Hp, H0[c]);
-        }
-        float Vm[GRAD ? CP : 1], V0[GRAD ? CP : 1], Vp[GRAD ? CP : 1];
-        if (GRAD) {
-#pragma unroll
-            for (int c = 0; c < CP; ++c) { Vm[c] = 0.f; V0[c] = 0.f; Vp[c] = 0.f; }
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float fy = (i < 4 ? 2 * i + 9 : 2 * i - 7) * 0.0625f;
-            const int Y = qy * 8 + i;
-            float Z[CP];
-#pragma unroll
-            for (int c = 0; c < CP; ++c) Z[c] = i < 4 ? __builtin_fmaf(fy, D0[c], Hm[c]) : __builtin_fmaf(fy, D1[c], H0[c]);
-            // prediction: the largest logit, lowest index among equals
-            float m = Z[0];
-#pragma unroll
-            for (int c = 1; c < CP; ++c) m = fmaxf(m, Z[c]);
-            int best = CP - 1;
-#pragma unroll
-            for (int c = CP - 2; c >= 0; --c) best = Z[c] == m ? c : best;
-            if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
-            if (lab_img) {
-                const int y = lab8[i];
-                const bool valid = y != g.ignore_index && y >= 0 && y < C;   // y = -1 off the frame
-                const float mb = -m * 1.44269504088896341f;
-                float s = 0.f;
-#pragma unroll
-                for (int c = 0; c < CP; ++c) {
-                    Z[c] = __builtin_amdgcn_exp2f(__builtin_fmaf(Z[c], 1.44269504088896341f, mb));
-                    s += Z[c];
-                }
-                if (valid) {
-                    loss_acc += __builtin_fmaf(__builtin_amdgcn_logf(s), 0.693147180559945309f, m);
-                    atomicAdd(&conf_l[y * C + best], 1u);
-                }
-                if (GRAD) {
-                    const float rs = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
-                    const float wa = (1.f - fy) * rs, wb = fy * rs;
-#pragma unroll
-                    for (int c = 0; c < CP; ++c) {
-                        if (i < 4) { Vm[c] = __builtin_fmaf(wa, Z[c], Vm[c]); V0[c] = __builtin_fmaf(wb, Z[c], V0[c]); }
-                        else       { V0[c] = __builtin_fmaf(wa, Z[c], V0[c]); Vp[c] = __builtin_fmaf(wb, Z[c], Vp[c]); }
-                    }
-                }
-            }
-        }
-        if (GRAD) {
-            // same for the first / last row group: the cell row outside the grid is the border row
-            if (qy == 0) {
-#pragma unroll
-                for (int c = 0; c < CP; ++c) { V0[c] += Vm[c]; Vm[c] = 0.f; }
-            }
-            if (qy == g.h - 1) {
-#pragma unroll
-                for (int c = 0; c < CP; ++c) { V0[c] += Vp[c]; Vp[c] = 0.f; }
-            }
-            // adjoint of the x interpolation, reduced over the group's 8 columns: columns 0-3 feed
-            // the left and the centre cell, columns 4-7 the centre and the right cell
+            const int y = lab4[i];
+            const bool valid = y != g.ignore_index && y >= 0 && y < C;   // y = -1 off the frame
+            const float mb = -m * 1.44269504088896341f;
+            float sum = 0.f;
 #pragma unroll
             for (int c = 0; c < CP; ++c) {
-                float side[3], mid[3];
+                Z[c] = __builtin_amdgcn_exp2f(__builtin_fmaf(Z[c], 1.44269504088896341f, mb));
+                sum += Z[c];
+            }
+            if (valid) {
+                loss_acc += __builtin_fmaf(__builtin_amdgcn_logf(sum), 0.693147180559945309f, m);
+                atomicAdd(&conf_l[y * C + best], 1u);
+            }
+            if (GRAD) {
+                const float rs = valid ? __builtin_amdgcn_rcpf(sum) : 0.f;
+                const float wa = (1.f - fy) * rs, wb = fy * rs;
 #pragma unroll
-                for (int r = 0; r < 3; ++r) {
-                    const float v = r == 0 ? Vm[c] : (r == 1 ? V0[c] : Vp[c]);
-                    side[r] = quad_sum(v * w_side);   // lanes 0-3: left cell, lanes 4-7: right cell
-                    mid[r] = group8_sum(v * w_mid);
-                }
-                // lane 0 of the group writes (left, centre), lane 4 writes (right, unused)
-                if ((j & 3) == 0) {
-#pragma unroll
-                    for (int r = 0; r < 3; ++r)
-                        *(float2*)&contrib[gy][c][r][tq][j >> 1] = make_float2(side[r], j == 0 ? mid[r] : 0.f);
+                for (int c = 0; c < CP; ++c) {
+                    Vu[c] = __builtin_fmaf(wa, Z[c], Vu[c]);
+                    Vl[c] = __builtin_fmaf(wb, Z[c], Vl[c]);
                 }
             }
         }
     }
+    if (GRAD) {
+        // edge replication for the first / last row group: the cell row outside the grid is the
+        // border row itself
+        if (qy == 0 && half == 0) {
+#pragma unroll
+            for (int c = 0; c < CP; ++c) { Vl[c] += Vu[c]; Vu[c] = 0.f; }
+        }
+        if (qy == g.h - 1 && half == 1) {
+#pragma unroll
+            for (int c = 0; c < CP; ++c) { Vu[c] += Vl[c]; Vl[c] = 0.f; }
+        }
+        // adjoint of the x interpolation, reduced over the group's 8 columns: columns 0-3 feed
+        // the left and the centre cell, columns 4-7 the centre and the right cell
+#pragma unroll
+        for (int c = 0; c < CP; ++c) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const float v = r == 0 ? Vu[c] : Vl[c];
+                const float side = quad_sum(v * w_side);   // lanes 0-3: left cell, lanes 4-7: right cell
+                const float mid = group8_sum(v * w_mid);
+                // lane 0 of the group writes (left, centre), lane 4 writes (right, unused)
+                if ((j & 3) == 0)
+                    *(float2*)&contrib[half][c][r][tq][j >> 1] = make_float2(side, j == 0 ? mid : 0.f);
+            }
+        }
+    }
 
-    // ---- loss of this tile: wave sums, then the four waves in order
+    // ---- loss of this tile: wave sums, then the waves in order
     loss_acc = wave_sum(loss_acc);
     if ((tid & 63) == 0) wsum[tid >> 6] = loss_acc;
     __syncthreads();
-    if (tid == 0 && loss_part) loss_part[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    if (tid == 0 && loss_part) {
+        float acc = wsum[0];
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) acc += wsum[w];
+        loss_part[blockIdx.x] = acc;
+    }
     if (conf && lab_img)
-        for (int i = tid; i < C * C; i += 256)
+        for (int i = tid; i < C * C; i += NT)
             if (conf_l[i]) atomicAdd(&conf[(size_t)img * C * C + i], (unsigned long long)conf_l[i]);
 
     if (GRAD) {
-        // rows of `contrib` a short last tile never wrote must read as zero
-        const int rows_done = min(LOSS_TY, g.h - tile_y * LOSS_TY);   // row groups processed
         float* slot = slots + (size_t)blockIdx.x * CP * CH * CW;
         // cell totals: column group lc gives its left part, lc-1 its centre part, lc-2 its right
-        // part; cell row r gets row r - gy of row group gy (gy = 0 first).  Cells outside the grid
-        // received nothing (their weight went to the border cells above).
-        __syncthreads();
-        for (int i = tid; i < CP * CH * CW; i += 256) {
+        // part; cell row 0 comes from the upper half, row 2 from the lower half, row 1 from both
+        // (upper half first).  Cells outside the grid received nothing (their weight went to the
+        // border cells above).
+        for (int i = tid; i < CP * CH * CW; i += NT) {
             const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
             float v = 0.f;
-            for (int gy = 0; gy < rows_done; ++gy) {
-                const int rr = r - gy;
-                if (rr < 0 || rr > 2) continue;
-                if (lc < LOSS_TX) v += contrib[gy][c][rr][lc][0];
-                if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[gy][c][rr][lc - 1][1];
-                if (lc >= 2) v += contrib[gy][c][rr][lc - 2][2];
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int rr = r - hf;
+                if (rr < 0 || rr > 1) continue;
+                if (lc < LOSS_TX) v += contrib[hf][c][rr][lc][0];
+                if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[hf][c][rr][lc - 1][1];
+                if (lc >= 2) v += contrib[hf][c][rr][lc - 2][2];
             }
             slot[i] = v;
         }
@@ -364,14 +385,14 @@ static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* lab
     const LossTiling lt = loss_tiling(g);
     const int blocks = g.n * lt.tiles();
     if (grad) {
-        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(256), 0, z, labels, T, pred,
+        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, z, labels, T, pred,
                   slots, loss_part, conf, g, lt);
         // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
         if (assemble)
             ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
                       dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
-        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(256), 0, z, labels, T, pred, slots,
+        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, z, labels, T, pred, slots,
                   loss_part, conf, g, lt);
     }
 }
