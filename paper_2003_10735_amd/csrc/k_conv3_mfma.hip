@@ -64,16 +64,21 @@ void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const f
 }
 
 // ------------------------------------------------------------------ backward
-// One block = 128 consecutive padded positions (g is zero on the border).  The block first forms
-// g = d loss / d z for its cells from what the loss kernel left behind -- the per-tile slots of
-// U^T softmax (added in a fixed order: tile rows first), minus U^T of the one-hot labels, over
+// One block = C3B_BP consecutive padded positions (g is zero on the border).  The block first
+// forms g = d loss / d z for its cells from what the loss kernel left behind -- the per-tile slots
+// of U^T softmax (added in a fixed order: tile rows first), minus U^T of the one-hot labels, over
 // N_valid -- rounds it to bfloat16 and stages it in LDS in both orientations, with W3 transposed.
 // Then
-//   wavefront w computes da2 for positions 32w .. 32w+31 and all channels  (K = classes),
-//   wavefront w computes dW3 for channel tiles w, w+4, ..  over all 128 positions (K = positions),
+//   wavefront w computes da2 for positions 32 (w % 2) .. +31 and half of the channel tiles
+//   (K = classes),
+//   wavefront w computes dW3 for channel tiles w, w+4, ..  over all positions (K = positions),
 // so no sum crosses wavefronts.  Partial dW3 / db3 go to one slot per block; the optimiser
 // kernel adds the slots in order.  All global loads a wavefront needs later (ReLU mask, a2
 // fragments) are issued before the first barrier, so their latency overlaps the staging.
+// The work per position is small and every phase is a chain of dependent memory round trips, so
+// the block is kept small: the grid then covers the whole chip and each chain is short.
+constexpr int C3B_BP = 64;
+
 template <int C2>
 __global__ void __launch_bounds__(256)
 k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
@@ -82,41 +87,47 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
                  const bf16* __restrict__ W3q, bf16* __restrict__ da2, bf16* __restrict__ da2T,
                  float* __restrict__ part, Geo g, int PPT, int guard)
 {
+    constexpr int BP = C3B_BP;
     constexpr int OT = C2 / 32;            // channel tiles
+    constexpr int OH = OT / 2;             // da2 channel tiles per wavefront
     constexpr int DW = (OT + 3) / 4;       // dW3 channel tiles per wavefront
-    constexpr int GP = 128 + 8;            // pitch of g_cp rows (positions)
+    constexpr int KS = BP / 16;            // K steps of the dW3 product
+    constexpr int GP = BP + 8;             // pitch of g_cp rows (positions)
     constexpr int GC = 32 + 8;             // pitch of g_pc / w3t rows (classes)
     constexpr int OLD = C2 + 8;            // pitch of the output tile
+    static_assert(OT % 2 == 0, "two wavefronts share the channel tiles of a position half");
     __shared__ __attribute__((aligned(16))) bf16 g_cp[32 * GP];     // [class][position]
-    __shared__ __attribute__((aligned(16))) bf16 g_pc[128 * GC];    // [position][class]
+    __shared__ __attribute__((aligned(16))) bf16 g_pc[BP * GC];     // [position][class]
     __shared__ __attribute__((aligned(16))) bf16 w3t[C2 * GC];      // [channel][class]
-    __shared__ __attribute__((aligned(16))) bf16 Os[128 * OLD];     // da2 tile [position][channel]
+    __shared__ __attribute__((aligned(16))) bf16 Os[BP * OLD];      // da2 tile [position][channel]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int PP = g.padded_positions(), frame = g.Hp * g.Wp, hw = g.h * g.w;
-    const int m0 = blockIdx.x * 128;
+    const int m0 = blockIdx.x * BP;
 
     // ---- early loads: ReLU mask of this lane's position, a2 fragments of this wavefront's tiles
-    const int pm = wave * 32 + l32;                // position (inside the block) for the da2 part
+    const int pm = (wave & 1) * 32 + l32;          // position (inside the block) for the da2 part
+    const int t0 = (wave >> 1) * OH;               // first channel tile of the da2 part
     const size_t mrow = (size_t)min(m0 + pm, PP - 1) * C2;
-    bf16x4 mk[OT][4];
+    bf16x4 mk[OH][4];
 #pragma unroll
-    for (int t = 0; t < OT; ++t)
+    for (int t = 0; t < OH; ++t)
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(a2 + mrow + t * 32 + rg * 8 + lhi * 4);
-    bf16x8 xf[DW][8];
+        for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(a2 + mrow + (t0 + t) * 32 + rg * 8 + lhi * 4);
+    bf16x8 xf[DW][KS];
 #pragma unroll
     for (int d = 0; d < DW; ++d) {
         const int t = min(wave + 4 * d, OT - 1);
         const bf16* xrow = a2T + xt_index(t * 32 + l32, guard + m0 + lhi * 8, PPT / 8);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) xf[d][ks] = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups per step
+        for (int ks = 0; ks < KS; ++ks) xf[d][ks] = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups per step
     }
 
     // ---- stage g (both orientations) and W3^T
     {
-        const int p = tid & 127, chalf = tid >> 7;     // this thread: one position, every other class
+        const int p = tid & (BP - 1), cq = tid / BP;     // this thread: one position, every fourth class
+        constexpr int NQ = 256 / BP;
         const int mp = m0 + p;
         const int img = min(mp / frame, g.n - 1), rr = mp - img * frame, y = rr / g.Wp, x = rr - y * g.Wp;
         const bool inside = mp < PP && y >= 1 && y <= g.h && x >= 1 && x <= g.w;
@@ -142,17 +153,18 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
         const int cstride = LOSS_CH * LOSS_CW;
         const size_t tbase = (size_t)img * g.C * hw + cy * g.w + cx;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int c = min(chalf + 2 * k, g.C - 1);     // classes beyond C re-read the last one, unused
+        for (int k = 0; k < 32 / NQ; ++k) {
+            const int cc = cq + NQ * k;
+            const int c = min(cc, g.C - 1);     // classes beyond C re-read the last one, unused
             float v = 0.f;
 #pragma unroll
             for (int a = 0; a < 3; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) v = __builtin_fmaf(wgt[a][b], slots[(size_t)off[a][b] + (size_t)c * cstride], v);
             v = (v - T[tbase + (size_t)c * hw]) * inv_n;
-            const bf16 q = (chalf + 2 * k < g.C) ? (bf16)v : (bf16)0.f;
-            g_cp[(chalf + 2 * k) * GP + p] = q;
-            g_pc[p * GC + chalf + 2 * k] = q;
+            const bf16 q = (cc < g.C) ? (bf16)v : (bf16)0.f;
+            g_cp[cc * GP + p] = q;
+            g_pc[p * GC + cc] = q;
         }
     }
     for (int i = tid; i < C2 * 32; i += 256) {
@@ -163,33 +175,33 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
 
     // ---- da2: D[o][pos] = sum_c W3T[o][c] * g[c][pos], two K steps cover 32 classes
     {
-        f32x16 acc[OT];
+        f32x16 acc[OH];
 #pragma unroll
-        for (int t = 0; t < OT; ++t)
+        for (int t = 0; t < OH; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const bf16x8 gf = *(const bf16x8*)(g_pc + pm * GC + ks * 16 + lhi * 8);
 #pragma unroll
-            for (int t = 0; t < OT; ++t) {
-                const bf16x8 wf = *(const bf16x8*)(w3t + (t * 32 + l32) * GC + ks * 16 + lhi * 8);
+            for (int t = 0; t < OH; ++t) {
+                const bf16x8 wf = *(const bf16x8*)(w3t + ((t0 + t) * 32 + l32) * GC + ks * 16 + lhi * 8);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, gf, acc[t], 0, 0, 0);
             }
         }
         // (a2 is zero on the border, and g is zero there too: border rows of da2 come out zero)
 #pragma unroll
-        for (int t = 0; t < OT; ++t)
+        for (int t = 0; t < OH; ++t)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 bf16x4 ov;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ov[e] = (bf16)((float)mk[t][rg][e] > 0.f ? acc[t][rg * 4 + e] : 0.f);
-                *(bf16x4*)(Os + pm * OLD + t * 32 + rg * 8 + lhi * 4) = ov;
+                *(bf16x4*)(Os + pm * OLD + (t0 + t) * 32 + rg * 8 + lhi * 4) = ov;
             }
     }
 
-    // ---- dW3: D[c][o] = sum_pos g[c][pos] * a2[pos][o] over this block's 128 positions
+    // ---- dW3: D[c][o] = sum_pos g[c][pos] * a2[pos][o] over this block's positions
     float* slot = part + (size_t)blockIdx.x * (32 * C2 + 32);
 #pragma unroll
     for (int d = 0; d < DW; ++d) {
@@ -199,7 +211,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
                 const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf[d][ks], acc, 0, 0, 0);
             }
@@ -212,18 +224,18 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     }
     if (tid < 32) {
         float s = 0.f;
-        for (int p = 0; p < 128; ++p) s += (float)g_cp[tid * GP + p];
+        for (int p = 0; p < BP; ++p) s += (float)g_cp[tid * GP + p];
         slot[32 * C2 + tid] = s;
     }
     __syncthreads();
 
     // ---- write the da2 tile: position-major rows and channel-major 8-position groups
-    for (int q = tid; q < 128 * (C2 / 8); q += 256) {
+    for (int q = tid; q < BP * (C2 / 8); q += 256) {
         const int p = q / (C2 / 8), part8 = q % (C2 / 8);
         if (m0 + p < PP)
             *(uint4*)(da2 + (size_t)(m0 + p) * C2 + part8 * 8) = *(const uint4*)(Os + p * OLD + part8 * 8);
     }
-    for (int q = tid; q < 16 * C2; q += 256) {
+    for (int q = tid; q < (BP / 8) * C2; q += 256) {
         const int o = q % C2, pg = q / C2;
         bf16x8 ov;
 #pragma unroll
@@ -232,7 +244,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     }
 }
 
-int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions(), 128); }
+int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions(), C3B_BP); }
 size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
