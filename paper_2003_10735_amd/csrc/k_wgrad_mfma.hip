@@ -21,6 +21,8 @@
 // are added by the optimiser kernel, also in a fixed order: no floating-point atomics.  The
 // bias gradient (row sums of dY) comes from one extra MFMA against a fragment of ones in the
 // blocks of the first input-channel tile.
+#include <algorithm>
+
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
 
@@ -40,11 +42,17 @@ struct WgradArgs {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// TAG only gives layer 1 and layer 2 a kernel symbol each, so that profiles list them separately.
-template <int TAG>
-__global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
+// One launch serves both 3x3 layers: blocks [0, blocks1) work on the first argument set, the rest
+// on the second.  Every block pays the same fixed cost (pipeline fill, the reduction through LDS,
+// the partial-result store) whatever its share of positions, so one grid that covers the chip
+// once, with the position splits of the two layers balanced against each other, is much cheaper
+// than two grids that each cover it once.
+__global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a2, int blocks1)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const bool second = (int)blockIdx.x >= blocks1;
+    const WgradArgs& a = second ? a2 : a1;
+    const int bid = second ? blockIdx.x - blocks1 : blockIdx.x;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -52,8 +60,8 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
     // of work items in split-major order, so that one XCD's L2 only ever sees about 1/8 of the
     // positions (all channels) instead of every position of a few channels
     const int tiles = a.o_tiles * a.i_tiles;
-    const int item = (blockIdx.x % 8) * a.items_per_xcd + blockIdx.x / 8;
-    if ((int)(blockIdx.x / 8) >= a.items_per_xcd || item >= tiles * a.splits) return;
+    const int item = (bid % 8) * a.items_per_xcd + bid / 8;     // blocks1 is a multiple of 8
+    if (bid / 8 >= a.items_per_xcd || item >= tiles * a.splits) return;
     const int split = item / tiles, tile = item % tiles;
     const int ot = tile / a.i_tiles, it = tile % a.i_tiles;
     const int o0 = ot * 32, i0 = it * 32;
@@ -204,18 +212,32 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a)
 
 bool wgrad3x3_mfma_supported(int cin, int cout) { return cin % 32 == 0 && cout % 32 == 0; }
 
-int wgrad_splits_for(const Geo& g, int cin, int cout)
+// Position splits of the two layers for the shared launch: tiles1 * s1 + tiles2 * s2 blocks should
+// cover the compute units once, and the longest per-wavefront share (the launch's critical
+// path) should be as short as possible; among equals, fewer partial copies.
+void wgrad_splits_for(const Geo& g, int* s1_out, int* s2_out)
 {
-    const int tiles = (cout / 32) * (cin / 32);
-    int s = cdiv(256, tiles);
+    const int n_cu = 256;
+    const int tiles1 = (g.c1 / 32) * (g.c_in / 32), tiles2 = (g.c2 / 32) * (g.c1 / 32);
     const int n_units = cdiv(g.padded_positions(), 16);
-    // keep at least 8 units (128 positions) per wavefront
-    while (s > 1 && cdiv(n_units, s * 4) < 8) --s;
-    return s < 1 ? 1 : (s > 16 ? 16 : s);
+    int best1 = 1, best2 = 1;
+    long best_cost = -1;
+    for (int s1 = 1; s1 <= 16; ++s1) {
+        int s2 = (n_cu - tiles1 * s1) / tiles2;
+        if (s2 < 1) s2 = 1;
+        if (s2 > 16) s2 = 16;
+        // keep at least 8 units (128 positions) per wavefront
+        if (s1 > 1 && cdiv(n_units, s1 * 4) < 8) break;
+        while (s2 > 1 && cdiv(n_units, s2 * 4) < 8) --s2;
+        const int rounds = cdiv(tiles1 * s1 + tiles2 * s2, n_cu);
+        const long cost = (long)rounds * std::max(cdiv(n_units, s1 * 4), cdiv(n_units, s2 * 4)) * 64 + s1 + s2;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best1 = s1; best2 = s2; }
+    }
+    *s1_out = best1; *s2_out = best2;
 }
 
-void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, const bf16* XT, float* dW,
-                   float* db, int cin, int cout, int splits, int layer)
+static WgradArgs wgrad_args(const Plan& p, const bf16* dYT, const bf16* XT, float* dW, float* db, int cin,
+                            int cout, int splits)
 {
     WgradArgs a;
     a.dYT = dYT; a.XT = XT; a.dW = dW; a.db = db;
@@ -224,15 +246,22 @@ void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, con
     a.n_units = cdiv(p.g.padded_positions(), 16);
     a.units_per_wave = cdiv(a.n_units, splits * 4);
     a.o_tiles = cout / 32; a.i_tiles = cin / 32;
-    const size_t smem = (size_t)(4 * 9 * 32 * 32 + 4 * 32) * sizeof(float);
     a.splits = splits;
     a.items_per_xcd = cdiv(a.o_tiles * a.i_tiles * splits, 8);
-    auto go = [&](auto kernel) {
-        ensure_dynamic_lds((const void*)kernel, smem);
-        ST_LAUNCH(c, name, kernel, dim3(a.items_per_xcd * 8), dim3(256), smem, a);
-    };
-    if (layer == 1) go(k_wgrad3x3_mfma<1>);
-    else go(k_wgrad3x3_mfma<2>);
+    return a;
+}
+
+// weight and bias gradients of layer 1 (dY = da1, X = features) and layer 2 (dY = da2, X = a1)
+void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, const bf16* da2T,
+                   const bf16* a1T, float* grad)
+{
+    const Geo& g = p.g;
+    const WgradArgs a1 = wgrad_args(p, da1T, featT, grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1);
+    const WgradArgs a2 = wgrad_args(p, da2T, a1T, grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2);
+    const int blocks1 = a1.items_per_xcd * 8, blocks2 = a2.items_per_xcd * 8;
+    const size_t smem = (size_t)(4 * 9 * 32 * 32 + 4 * 32) * sizeof(float);
+    ensure_dynamic_lds((const void*)k_wgrad3x3_mfma, smem);
+    ST_LAUNCH(c, "conv12_wgrad_mfma", k_wgrad3x3_mfma, dim3(blocks1 + blocks2), dim3(256), smem, a1, a2, blocks1);
 }
 
 }  // namespace st

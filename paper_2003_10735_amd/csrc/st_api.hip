@@ -110,8 +110,8 @@ Plan make_plan(const st_head_desc& d)
     p.mfma = p.bf16 && conv3x3_mfma_supported(g.c_in, g.c1) && conv3x3_mfma_supported(g.c1, g.c2) &&
              wgrad3x3_mfma_supported(g.c_in, g.c1) && wgrad3x3_mfma_supported(g.c1, g.c2) &&
              conv3_mfma_supported(g.c2, g.C);
-    p.splits1 = p.mfma ? wgrad_splits_for(g, g.c_in, g.c1) : 1;
-    p.splits2 = p.mfma ? wgrad_splits_for(g, g.c1, g.c2) : 1;
+    p.splits1 = p.splits2 = 1;
+    if (p.mfma) wgrad_splits_for(g, &p.splits1, &p.splits2);
     p.blocks3 = p.mfma ? conv3_bwd_blocks(g) : 0;
     p.grad_copies = std::max(p.splits1, p.splits2);
     // guard: a 3x3 tap reaches Wp + 1 rows back/ahead of a tile that may overrun the grid by
@@ -199,12 +199,10 @@ static void backward(Ctx& c, const Plan& p, char* ws)
     conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
                    (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
                    (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
-    wgrad3x3_mfma(c, "conv2_wgrad_mfma", p, (const bf16*)(ws + p.da2T), (const bf16*)(ws + p.a1T),
-                  grad + p.po.W2, grad + p.po.b2, g.c1, g.c2, p.splits2, 2);
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
                  (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
-    wgrad3x3_mfma(c, "conv1_wgrad_mfma", p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT),
-                  grad + p.po.W1, grad + p.po.b1, g.c_in, g.c1, p.splits1, 1);
+    wgrad3x3_mfma(c, p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT), (const bf16*)(ws + p.da2T),
+                  (const bf16*)(ws + p.a1T), grad);
 }
 
 }  // namespace st

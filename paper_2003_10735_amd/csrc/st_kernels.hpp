@@ -19,9 +19,9 @@ bool conv3x3_mfma_supported(int cin, int cout);
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
                   const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer);
 bool wgrad3x3_mfma_supported(int cin, int cout);
-int wgrad_splits_for(const Geo& g, int cin, int cout);
-void wgrad3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* dYT, const bf16* XT, float* dW,
-                   float* db, int cin, int cout, int splits, int layer);
+void wgrad_splits_for(const Geo& g, int* splits1, int* splits2);
+void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, const bf16* da2T,
+                   const bf16* a1T, float* grad);
 bool conv3_mfma_supported(int c2, int C);
 void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z);
 int conv3_bwd_blocks(const Geo& g);
