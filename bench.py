@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="720p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (outside the timed "
+                         "region): the known-size reference that scales hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; sharding is by video stream (one head per "
@@ -115,6 +118,13 @@ def main():
     for _ in range(args.warmup):
         one_call()
     torch.cuda.synchronize()
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # which kernel dominates: one untimed call with an event pair around every launch
     st.st_profile_reset()

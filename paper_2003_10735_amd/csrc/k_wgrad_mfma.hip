@@ -63,7 +63,9 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     const int item = (bid % 8) * a.items_per_xcd + bid / 8;     // blocks1 is a multiple of 8
     if (bid / 8 >= a.items_per_xcd || item >= tiles * a.splits) return;
     const int split = item / tiles, tile = item % tiles;
-    const int ot = tile / a.i_tiles, it = tile % a.i_tiles;
+    // output-channel tile fastest: the blocks that stream the same X rows (same split, same
+    // input-channel tile) are neighbours in the order, run on one XCD and share them in its L2
+    const int ot = tile % a.o_tiles, it = tile / a.o_tiles;
     const int o0 = ot * 32, i0 = it * 32;
 
     // acc[0..8]: the nine taps; acc[9]: row sums of dY (bias gradient), only in blocks with it == 0
@@ -105,23 +107,30 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     // enters on the left is the last one of the previous 8-position group, the one on the right
     // the first of the next group: both sit in the *other half* of the wavefront (lane ^ 32), in
     // this unit's registers or in a neighbouring unit's, so they are fetched with a cross-lane
-    // permute instead of being loaded again.  The permutes for unit u + 1 are issued while the
-    // MFMAs of unit u run (WG_NEIGHBOURS one unit ahead of WG_COMPUTE).
+    // permute instead of being loaded again.  The permutes for unit u + 1 are issued before the
+    // MFMAs of unit u and their results are picked up after them (there is one wavefront per
+    // SIMD, so a wait for the permute with no MFMA in flight would idle the matrix core).
     //   up3[kh]: dword 3 of lane^32 in the unit being prepared; dn0[kh]: dword 0 of lane^32 in the
     //   unit after it.  For a lane of the lower half (lhi = 0) the left neighbour is the upper
     //   half of the *previous* unit (carry_prev) and the right one the upper half of this unit
     //   (carry_next, fetched when the previous unit was prepared).
     unsigned int prev_cur[3], next_cur[3];      // neighbours of the unit about to be computed
     unsigned int carry_prev[3], carry_next[3];
-#define WG_NEIGHBOURS(SLOT, NEXT, OUTP, OUTN)                                                   \
+    unsigned int up3_[3], dn0_[3];                // permute results in flight
+#define WG_NEIGHBOURS_ISSUE(SLOT, NEXT)                                                          \
     {                                                                                           \
         _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
-            const unsigned int up3_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[SLOT][kh][3]); \
-            const unsigned int dn0_ = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]); \
-            OUTP[kh] = lhi ? up3_ : carry_prev[kh];                                             \
-            OUTN[kh] = lhi ? dn0_ : carry_next[kh];                                             \
-            carry_prev[kh] = up3_;                                                              \
-            carry_next[kh] = dn0_;                                                              \
+            up3_[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[SLOT][kh][3]);                \
+            dn0_[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]);                \
+        }                                                                                       \
+    }
+#define WG_NEIGHBOURS_FINISH(OUTP, OUTN)                                                        \
+    {                                                                                           \
+        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
+            OUTP[kh] = lhi ? up3_[kh] : carry_prev[kh];                                         \
+            OUTN[kh] = lhi ? dn0_[kh] : carry_next[kh];                                         \
+            carry_prev[kh] = up3_[kh];                                                          \
+            carry_next[kh] = dn0_[kh];                                                          \
         }                                                                                       \
     }
 #define WG_COMPUTE(SLOT)                                                                        \
@@ -156,24 +165,27 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
             carry_prev[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[DEPTH - 1][kh][3]);
             carry_next[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[0][kh][0]);
         }
-        WG_NEIGHBOURS(0, 1, prev_cur, next_cur)
+        WG_NEIGHBOURS_ISSUE(0, 1)
+        WG_NEIGHBOURS_FINISH(prev_cur, next_cur)
         for (int u = unit0; u < unit1; u += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 WG_LOAD((d + DEPTH - 1) % DEPTH, min(u + d + DEPTH - 1, unit1))
                 if (u + d < unit1) {
-                    unsigned int prev_nxt[3], next_nxt[3];
-                    // neighbours of unit u + d + 1 (its right neighbours come from unit u + d + 2)
-                    if (u + d + 1 < unit1) WG_NEIGHBOURS((d + 1) % DEPTH, (d + 2) % DEPTH, prev_nxt, next_nxt)
+                    // neighbours of unit u + d + 1 (its right neighbours come from unit u + d + 2;
+                    // past the end of the range the slots hold clamped re-loads, finite and unused)
+                    WG_NEIGHBOURS_ISSUE((d + 1) % DEPTH, (d + 2) % DEPTH)
+                    __builtin_amdgcn_sched_barrier(0);
                     WG_COMPUTE(d)
-#pragma unroll
-                    for (int kh = 0; kh < 3; ++kh) { prev_cur[kh] = prev_nxt[kh]; next_cur[kh] = next_nxt[kh]; }
+                    __builtin_amdgcn_sched_barrier(0);
+                    WG_NEIGHBOURS_FINISH(prev_cur, next_cur)
                 }
             }
         }
     }
 #undef WG_LOAD
-#undef WG_NEIGHBOURS
+#undef WG_NEIGHBOURS_ISSUE
+#undef WG_NEIGHBOURS_FINISH
 #undef WG_COMPUTE
 
     // ---- every wavefront leaves its block in LDS as [tap][o][i]; then all 256 threads add the
