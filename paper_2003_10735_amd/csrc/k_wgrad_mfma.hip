@@ -11,9 +11,9 @@
 // 16 positions it loads one dY fragment and, per kernel row kh, one 16-byte window of X (the
 // row pitch of the padded grid is a multiple of 8, so all of them are aligned fragments of the
 // blocked channel-major layout and every wavefront load is one contiguous kilobyte); the kw = 0
-// and kw = 2 operands are the same window shifted by one element, built in registers
-// (v_alignbyte + a cross-lane permute for the element that enters) instead of being loaded
-// again.  9 MFMAs per 4 loads.  A bigger block would need fewer loads per MFMA but leaves too few blocks to fill the
+// and kw = 2 products use the dY fragment shifted by one position, built in registers
+// (v_alignbyte + a cross-lane permute for the element that enters) instead of loading shifted
+// windows.  9 MFMAs per 4 loads.  A bigger block would need fewer loads per MFMA but leaves too few blocks to fill the
 // chip without multiplying the partial copies.
 //
 // The four wavefronts of a block own the same output block and a quarter each of the block's
@@ -103,52 +103,55 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
         _Pragma("unroll") for (int kh = 0; kh < 3; ++kh)                                        \
             rx[SLOT][kh] = *(const u32x4*)(xb + g_ + (ptrdiff_t)(kh - 1) * row_groups * 256);   \
     }
-    // The kw = 0 / kw = 2 operands are the kw = 1 window moved by one position.  The element that
-    // enters on the left is the last one of the previous 8-position group, the one on the right
-    // the first of the next group: both sit in the *other half* of the wavefront (lane ^ 32), in
-    // this unit's registers or in a neighbouring unit's, so they are fetched with a cross-lane
-    // permute instead of being loaded again.  The permutes for unit u + 1 are issued before the
-    // MFMAs of unit u and their results are picked up after them (there is one wavefront per
-    // SIMD, so a wait for the permute with no MFMA in flight would idle the matrix core).
-    //   up3[kh]: dword 3 of lane^32 in the unit being prepared; dn0[kh]: dword 0 of lane^32 in the
-    //   unit after it.  For a lane of the lower half (lhi = 0) the left neighbour is the upper
-    //   half of the *previous* unit (carry_prev) and the right one the upper half of this unit
-    //   (carry_next, fetched when the previous unit was prepared).
-    unsigned int prev_cur[3], next_cur[3];      // neighbours of the unit about to be computed
-    unsigned int carry_prev[3], carry_next[3];
-    unsigned int up3_[3], dn0_[3];                // permute results in flight
+    // The three taps of a kernel row differ by one position.  Moving the reduction index instead
+    // of the window,
+    //     dW[o][kh][kw][i] = sum_p dY[o][p - (kw - 1)] * X[i][p + (kh - 1) * Wp],
+    // the kw = 0 / kw = 2 products use the same X fragment as kw = 1 and a dY fragment moved by
+    // one position, which is built once per unit (not once per kernel row) in registers:
+    // v_alignbyte over the lane's four dwords plus the one element that enters from the
+    // neighbouring 8-position group.  That element sits in the *other half* of the wavefront
+    // (lane ^ 32), in this unit's registers or in a neighbouring unit's, and is fetched with a
+    // cross-lane permute.  The permutes for unit u + 1 are issued before the MFMAs of unit u and
+    // their results are picked up after them (there is one wavefront per SIMD, so a wait for
+    // the permute with no MFMA in flight would idle the matrix core).
+    //   up3_: dword 3 of lane^32 in the unit being prepared; dn0_: dword 0 of lane^32 in the unit
+    //   after it.  For a lane of the lower half (lhi = 0) the element before its group is in the
+    //   upper half of the *previous* unit (carry_prev) and the one after its group in the upper
+    //   half of this unit (carry_next, fetched when the previous unit was prepared).
+    // (dY is zero on the border of the padded grid and in the guard columns, so the terms the
+    //  shift moves across the ends of the position range are zero.)
+    unsigned int prev_cur, next_cur;      // neighbours of the unit about to be computed
+    unsigned int carry_prev, carry_next;
+    unsigned int up3_, dn0_;              // permute results in flight
 #define WG_NEIGHBOURS_ISSUE(SLOT, NEXT)                                                          \
     {                                                                                           \
-        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
-            up3_[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[SLOT][kh][3]);                \
-            dn0_[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[NEXT][kh][0]);                \
-        }                                                                                       \
+        up3_ = __builtin_amdgcn_ds_bpermute(swap_addr, ry[SLOT][3]);                            \
+        dn0_ = __builtin_amdgcn_ds_bpermute(swap_addr, ry[NEXT][0]);                            \
     }
-#define WG_NEIGHBOURS_FINISH(OUTP, OUTN)                                                        \
+#define WG_NEIGHBOURS_FINISH()                                                                  \
     {                                                                                           \
-        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
-            OUTP[kh] = lhi ? up3_[kh] : carry_prev[kh];                                         \
-            OUTN[kh] = lhi ? dn0_[kh] : carry_next[kh];                                         \
-            carry_prev[kh] = up3_[kh];                                                          \
-            carry_next[kh] = dn0_[kh];                                                          \
-        }                                                                                       \
+        prev_cur = lhi ? up3_ : carry_prev;                                                     \
+        next_cur = lhi ? dn0_ : carry_next;                                                     \
+        carry_prev = up3_;                                                                      \
+        carry_next = dn0_;                                                                      \
     }
 #define WG_COMPUTE(SLOT)                                                                        \
     {                                                                                           \
-        const bf16x8 y0 = as_bf16x8(ry[SLOT]);                                                  \
+        const u32x4 w_ = ry[SLOT];                                                              \
+        u32x4 ym_, yp_;    /* dY at p - 1 and at p + 1 */                                       \
+        ym_[0] = __builtin_amdgcn_alignbyte(w_[0], prev_cur, 2);                                \
+        ym_[1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                                   \
+        ym_[2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                                   \
+        ym_[3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                                   \
+        yp_[0] = ym_[1]; yp_[1] = ym_[2]; yp_[2] = ym_[3];                                      \
+        yp_[3] = __builtin_amdgcn_alignbyte(next_cur, w_[3], 2);                                \
+        const bf16x8 y0 = as_bf16x8(w_), ym = as_bf16x8(ym_), yp = as_bf16x8(yp_);              \
         if (want_bias) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, ones, acc[9], 0, 0, 0); \
         _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
-            const u32x4 w_ = rx[SLOT][kh];                                                      \
-            u32x4 lft, rgt;                                                                     \
-            lft[0] = __builtin_amdgcn_alignbyte(w_[0], prev_cur[kh], 2);                        \
-            lft[1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                               \
-            lft[2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                               \
-            lft[3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                               \
-            rgt[0] = lft[1]; rgt[1] = lft[2]; rgt[2] = lft[3];                                  \
-            rgt[3] = __builtin_amdgcn_alignbyte(next_cur[kh], w_[3], 2);                        \
-            acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(lft), acc[kh * 3 + 0], 0, 0, 0); \
-            acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(w_), acc[kh * 3 + 1], 0, 0, 0);  \
-            acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, as_bf16x8(rgt), acc[kh * 3 + 2], 0, 0, 0); \
+            const bf16x8 x_ = as_bf16x8(rx[SLOT][kh]);                                          \
+            acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yp, x_, acc[kh * 3 + 0], 0, 0, 0); \
+            acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, x_, acc[kh * 3 + 1], 0, 0, 0); \
+            acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ym, x_, acc[kh * 3 + 2], 0, 0, 0); \
         }                                                                                       \
     }
 
@@ -160,13 +163,10 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
         WG_LOAD(DEPTH - 1, unit0 - 1)
 #pragma unroll
         for (int d = 0; d < DEPTH - 1; ++d) WG_LOAD(d, min(unit0 + d, unit1))
-#pragma unroll
-        for (int kh = 0; kh < 3; ++kh) {
-            carry_prev[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[DEPTH - 1][kh][3]);
-            carry_next[kh] = __builtin_amdgcn_ds_bpermute(swap_addr, rx[0][kh][0]);
-        }
+        carry_prev = __builtin_amdgcn_ds_bpermute(swap_addr, ry[DEPTH - 1][3]);
+        carry_next = __builtin_amdgcn_ds_bpermute(swap_addr, ry[0][0]);
         WG_NEIGHBOURS_ISSUE(0, 1)
-        WG_NEIGHBOURS_FINISH(prev_cur, next_cur)
+        WG_NEIGHBOURS_FINISH()
         for (int u = unit0; u < unit1; u += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
@@ -178,7 +178,7 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
                     __builtin_amdgcn_sched_barrier(0);
                     WG_COMPUTE(d)
                     __builtin_amdgcn_sched_barrier(0);
-                    WG_NEIGHBOURS_FINISH(prev_cur, next_cur)
+                    WG_NEIGHBOURS_FINISH()
                 }
             }
         }
