@@ -19,8 +19,8 @@
 // The four wavefronts of a block own the same output block and a quarter each of the block's
 // position range; they are added through LDS in a fixed order, and the grid's position splits
 // are added by the optimiser kernel, also in a fixed order: no floating-point atomics.  The
-// bias gradient (row sums of dY) comes from one extra MFMA against a fragment of ones in the
-// blocks of the first input-channel tile.
+// bias gradient (sums of dY over the positions) comes from one extra MFMA against a fragment of
+// ones in the blocks of the first input-channel tile.
 #include <algorithm>
 
 #include "st_kernels.hpp"
@@ -111,109 +111,152 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     // v_alignbyte over the lane's four dwords plus the one element that enters from the
     // neighbouring 8-position group.  That element sits in the *other half* of the wavefront
     // (lane ^ 32), in this unit's registers or in a neighbouring unit's, and is fetched with a
-    // cross-lane permute.  The permutes for unit u + 1 are issued before the MFMAs of unit u and
-    // their results are picked up after them (there is one wavefront per SIMD, so a wait for
-    // the permute with no MFMA in flight would idle the matrix core).
+    // cross-lane permute, issued a unit before its result is picked up.
     //   up3_: dword 3 of lane^32 in the unit being prepared; dn0_: dword 0 of lane^32 in the unit
     //   after it.  For a lane of the lower half (lhi = 0) the element before its group is in the
     //   upper half of the *previous* unit (carry_prev) and the one after its group in the upper
     //   half of this unit (carry_next, fetched when the previous unit was prepared).
     // (dY is zero on the border of the padded grid and in the guard columns, so the terms the
     //  shift moves across the ends of the position range are zero.)
-    unsigned int prev_cur, next_cur;      // neighbours of the unit about to be computed
     unsigned int carry_prev, carry_next;
     unsigned int up3_, dn0_;              // permute results in flight
-#define WG_NEIGHBOURS_ISSUE(SLOT, NEXT)                                                          \
+    u32x4 ymb[2], ypb[2];                 // dY at p - 1 / p + 1 of the unit in work and of the next one
+#define WG_NEIGHBOURS_ISSUE(SLOT, NEXT)                                                         \
     {                                                                                           \
         up3_ = __builtin_amdgcn_ds_bpermute(swap_addr, ry[SLOT][3]);                            \
         dn0_ = __builtin_amdgcn_ds_bpermute(swap_addr, ry[NEXT][0]);                            \
     }
-#define WG_NEIGHBOURS_FINISH()                                                                  \
+    // picks up the permutes issued for the unit in SLOT and builds its shifted fragments in BUF
+#define WG_SHIFTED(SLOT, BUF)                                                                   \
     {                                                                                           \
-        prev_cur = lhi ? up3_ : carry_prev;                                                     \
-        next_cur = lhi ? dn0_ : carry_next;                                                     \
+        const unsigned int prev_ = lhi ? up3_ : carry_prev;                                     \
+        const unsigned int next_ = lhi ? dn0_ : carry_next;                                     \
         carry_prev = up3_;                                                                      \
         carry_next = dn0_;                                                                      \
-    }
-#define WG_COMPUTE(SLOT)                                                                        \
-    {                                                                                           \
         const u32x4 w_ = ry[SLOT];                                                              \
-        u32x4 ym_, yp_;    /* dY at p - 1 and at p + 1 */                                       \
-        ym_[0] = __builtin_amdgcn_alignbyte(w_[0], prev_cur, 2);                                \
-        ym_[1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                                   \
-        ym_[2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                                   \
-        ym_[3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                                   \
-        yp_[0] = ym_[1]; yp_[1] = ym_[2]; yp_[2] = ym_[3];                                      \
-        yp_[3] = __builtin_amdgcn_alignbyte(next_cur, w_[3], 2);                                \
-        const bf16x8 y0 = as_bf16x8(w_), ym = as_bf16x8(ym_), yp = as_bf16x8(yp_);              \
-        if (want_bias) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, ones, acc[9], 0, 0, 0); \
-        _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                      \
-            const bf16x8 x_ = as_bf16x8(rx[SLOT][kh]);                                          \
-            acc[kh * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yp, x_, acc[kh * 3 + 0], 0, 0, 0); \
-            acc[kh * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y0, x_, acc[kh * 3 + 1], 0, 0, 0); \
-            acc[kh * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ym, x_, acc[kh * 3 + 2], 0, 0, 0); \
+        ymb[BUF][0] = __builtin_amdgcn_alignbyte(w_[0], prev_, 2);                              \
+        ymb[BUF][1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                              \
+        ymb[BUF][2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                              \
+        ymb[BUF][3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                              \
+        ypb[BUF][0] = ymb[BUF][1]; ypb[BUF][1] = ymb[BUF][2]; ypb[BUF][2] = ymb[BUF][3];        \
+        ypb[BUF][3] = __builtin_amdgcn_alignbyte(next_, w_[3], 2);                              \
+    }
+#define WG_MMA(T, Y, KH, SLOT)                                                                  \
+    acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(rx[SLOT][KH]), as_bf16x8(Y), acc[T], 0, 0, 0);
+#define WG_F __builtin_amdgcn_sched_barrier(0);
+    // One unit in slot D of the ring.  There is one wavefront per SIMD, so whatever this wavefront
+    // issues between two MFMAs is all that can overlap them: the loads of unit + DEPTH - 1, the
+    // pick-up of the permutes and the shifted fragments of unit + 1, and the permutes of unit + 2
+    // are spread over the gaps between this unit's MFMAs, in a pinned order.
+#define WG_UNIT(D, U, BIAS)                                                                     \
+    {                                                                                           \
+        const int L_ = ((D) + DEPTH - 1) % DEPTH, N1_ = ((D) + 1) % DEPTH;                      \
+        const int N2_ = ((D) + 2) % DEPTH, N3_ = ((D) + 3) % DEPTH, B_ = (D) & 1;               \
+        const ptrdiff_t g_ = (ptrdiff_t)min((U) + DEPTH - 1, unit1) * 2 * 256;                  \
+        if (BIAS) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, as_bf16x8(ry[D]), acc[9], 0, 0, 0); \
+        WG_MMA(0, ypb[B_], 0, D) WG_F                                                           \
+        ry[L_] = *(const u32x4*)(ya + g_); WG_F                                                 \
+        WG_MMA(1, ry[D], 0, D) WG_F                                                             \
+        rx[L_][0] = *(const u32x4*)(xb + g_ - (ptrdiff_t)row_groups * 256); WG_F                \
+        WG_MMA(2, ymb[B_], 0, D) WG_F                                                           \
+        rx[L_][1] = *(const u32x4*)(xb + g_); WG_F                                              \
+        WG_MMA(3, ypb[B_], 1, D) WG_F                                                           \
+        rx[L_][2] = *(const u32x4*)(xb + g_ + (ptrdiff_t)row_groups * 256); WG_F                \
+        WG_MMA(4, ry[D], 1, D) WG_F                                                             \
+        WG_SHIFTED(N1_, 1 - B_) WG_F                                                            \
+        WG_MMA(5, ymb[B_], 1, D) WG_F                                                           \
+        WG_NEIGHBOURS_ISSUE(N2_, N3_) WG_F                                                      \
+        WG_MMA(6, ypb[B_], 2, D)                                                                \
+        WG_MMA(7, ry[D], 2, D)                                                                  \
+        WG_MMA(8, ymb[B_], 2, D) WG_F                                                           \
+    }
+    // the same unit when it may lie beyond the end of the range (last, partial trip of the loop):
+    // the bookkeeping runs as above, the MFMAs only for units inside the range
+#define WG_UNIT_TAIL(D, U, BIAS)                                                                \
+    {                                                                                           \
+        const int L_ = ((D) + DEPTH - 1) % DEPTH, N1_ = ((D) + 1) % DEPTH;                      \
+        const int N2_ = ((D) + 2) % DEPTH, N3_ = ((D) + 3) % DEPTH, B_ = (D) & 1;               \
+        if ((U) < unit1) {                                                                      \
+            if (BIAS) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, as_bf16x8(ry[D]), acc[9], 0, 0, 0); \
+            _Pragma("unroll") for (int kh = 0; kh < 3; ++kh) {                                  \
+                WG_MMA(kh * 3 + 0, ypb[B_], kh, D)                                              \
+                WG_MMA(kh * 3 + 1, ry[D], kh, D)                                                \
+                WG_MMA(kh * 3 + 2, ymb[B_], kh, D)                                              \
+            }                                                                                   \
+        }                                                                                       \
+        WG_F                                                                                    \
+        WG_LOAD(L_, min((U) + DEPTH - 1, unit1))                                                \
+        WG_SHIFTED(N1_, 1 - B_)                                                                 \
+        WG_NEIGHBOURS_ISSUE(N2_, N3_) WG_F                                                      \
+    }
+#define WG_LOOPS(BIAS)                                                                          \
+    {                                                                                           \
+        int u = unit0;                                                                          \
+        for (; u + DEPTH <= unit1; u += DEPTH) {                                                \
+            _Pragma("unroll") for (int d = 0; d < DEPTH; ++d) WG_UNIT(d, u + d, BIAS)           \
+        }                                                                                       \
+        if (u < unit1) {                                                                        \
+            _Pragma("unroll") for (int d = 0; d < DEPTH; ++d) WG_UNIT_TAIL(d, u + d, BIAS)      \
         }                                                                                       \
     }
 
+    static_assert(DEPTH % 2 == 0 && DEPTH >= 4, "two fragment buffers alternate; permutes look three units ahead");
     if (unit0 < unit1) {
         // unit0 - 1 (guard columns make it readable) supplies the first left neighbours and
         // unit1 (tail guard) the last right neighbours
         // (all loads are unconditional, with the unit index clamped to unit1: a load under a
-        //  branch would force the compiler to wait for every outstanding load at the join)
+        //  branch would force the compiler to wait for every outstanding load at the join;
+        //  past the end of the range the slots hold clamped re-loads, finite and unused)
         WG_LOAD(DEPTH - 1, unit0 - 1)
 #pragma unroll
         for (int d = 0; d < DEPTH - 1; ++d) WG_LOAD(d, min(unit0 + d, unit1))
         carry_prev = __builtin_amdgcn_ds_bpermute(swap_addr, ry[DEPTH - 1][3]);
         carry_next = __builtin_amdgcn_ds_bpermute(swap_addr, ry[0][0]);
         WG_NEIGHBOURS_ISSUE(0, 1)
-        WG_NEIGHBOURS_FINISH()
-        for (int u = unit0; u < unit1; u += DEPTH) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-                WG_LOAD((d + DEPTH - 1) % DEPTH, min(u + d + DEPTH - 1, unit1))
-                if (u + d < unit1) {
-                    // neighbours of unit u + d + 1 (its right neighbours come from unit u + d + 2;
-                    // past the end of the range the slots hold clamped re-loads, finite and unused)
-                    WG_NEIGHBOURS_ISSUE((d + 1) % DEPTH, (d + 2) % DEPTH)
-                    __builtin_amdgcn_sched_barrier(0);
-                    WG_COMPUTE(d)
-                    __builtin_amdgcn_sched_barrier(0);
-                    WG_NEIGHBOURS_FINISH()
-                }
-            }
-        }
+        WG_SHIFTED(0, 0)
+        WG_NEIGHBOURS_ISSUE(1, 2)
+        if (want_bias) WG_LOOPS(true) else WG_LOOPS(false)
     }
 #undef WG_LOAD
 #undef WG_NEIGHBOURS_ISSUE
-#undef WG_NEIGHBOURS_FINISH
-#undef WG_COMPUTE
+#undef WG_SHIFTED
+#undef WG_MMA
+#undef WG_F
+#undef WG_UNIT
+#undef WG_UNIT_TAIL
+#undef WG_LOOPS
 
     // ---- every wavefront leaves its block in LDS as [tap][o][i]; then all 256 threads add the
-    //      four copies in the order ((w0 + w1) + w2) + w3 and write the result with 16-byte stores
+    //      four copies in the order ((w0 + w1) + w2) + w3 and write the result with 16-byte stores.
+    //      The X fragment is the MFMA's A operand, so a lane holds four consecutive input channels
+    //      i of one output channel o per register group: one 16-byte LDS write.  Rows are 128
+    //      bytes; the 16-byte chunk c of row o is stored at chunk c ^ ((o >> 1) & 7), which spreads
+    //      the 16 lanes of a write (and of a read) over all banks.
     float* red = (float*)smem_raw;                 // [4][9 * 32 rows][32]
-    float* redb = red + 4 * 9 * 32 * 32;           // [4][32] row sums of dY
+    float* redb = red + 4 * 9 * 32 * 32;           // [4][32] sums of dY over the positions
+    {
+        const int sw = (l32 >> 1) & 7;
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+        for (int t = 0; t < 9; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int ol = (r >> 2) * 8 + lhi * 4 + (r & 3);
-            red[((wave * 9 + t) * 32 + ol) * 32 + l32] = acc[t][r];
-        }
-    if (want_bias && l32 == 0) {
-        // every column of acc[9] holds the row sums; column 0 lives in lanes 0 and 32
-#pragma unroll
-        for (int r = 0; r < 16; ++r) redb[wave * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3)] = acc[9][r];
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 v = {acc[t][gq * 4], acc[t][gq * 4 + 1], acc[t][gq * 4 + 2], acc[t][gq * 4 + 3]};
+                *(f32x4*)(red + ((wave * 9 + t) * 32 + l32) * 32 + (((gq * 2 + lhi) ^ sw) << 2)) = v;
+            }
     }
+    // every row of acc[9] holds the sums over the positions: row 0 lives in lanes 0 .. 31
+    if (want_bias && lhi == 0) redb[wave * 32 + l32] = acc[9][0];
     __syncthreads();
     float* dW = a.dW + (size_t)split * a.split_stride;
     for (int q = tid; q < 9 * 32 * 8; q += 256) {
         const int row = q >> 3, part = q & 7;
-        const f32x4 v0 = *(const f32x4*)(red + ((0 * 9 * 32 + row) * 32 + part * 4));
-        const f32x4 v1 = *(const f32x4*)(red + ((1 * 9 * 32 + row) * 32 + part * 4));
-        const f32x4 v2 = *(const f32x4*)(red + ((2 * 9 * 32 + row) * 32 + part * 4));
-        const f32x4 v3 = *(const f32x4*)(red + ((3 * 9 * 32 + row) * 32 + part * 4));
-        const f32x4 sum = ((v0 + v1) + v2) + v3;
         const int t = row >> 5, ol = row & 31;
+        const int chunk = (part ^ ((ol >> 1) & 7)) << 2;
+        const f32x4 v0 = *(const f32x4*)(red + ((0 * 9 * 32 + row) * 32 + chunk));
+        const f32x4 v1 = *(const f32x4*)(red + ((1 * 9 * 32 + row) * 32 + chunk));
+        const f32x4 v2 = *(const f32x4*)(red + ((2 * 9 * 32 + row) * 32 + chunk));
+        const f32x4 v3 = *(const f32x4*)(red + ((3 * 9 * 32 + row) * 32 + chunk));
+        const f32x4 sum = ((v0 + v1) + v2) + v3;
         *(f32x4*)(dW + ((size_t)(o0 + ol) * 9 + t) * a.cin + i0 + part * 4) = sum;
     }
     if (want_bias && tid < 32) {
