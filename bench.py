@@ -26,6 +26,33 @@ PEAK_TFLOPS_BF16 = 2500.0   # MI355X dense bf16 MFMA
 PEAK_TFLOPS_F32 = 157.3     # MI355X fp32 vector / matrix
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the passes and their
+# copy-kernel scale factors are recorded under profiles/).  A figure holds only for the kernel
+# source it was measured on: (source file, sha256 of that file at measurement, fetched MiB, written MiB)
+MEASURED_TRAFFIC = {
+    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "029d9c26feb57bb1ec266e090c5726f6273aec404fa65a37516a12d7b338fc1e", 31.53, 9.43),
+    "conv1_fwd_mfma": ("k_conv_mfma.hip", "2043fe0260c23b9aff56b2ed38514fc7c9a81d0640ab3bd3a5d52cb33f2d31eb", 13.75, 7.55),
+    "upsample_ce_grad": ("k_loss.hip", "8b75b924aa483d9b9ceb99376b56fc188e34da54a9a2c068cc2c9c90dede6f04", 12.26, 3.68),
+}
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel`, or None when there is no measurement for the kernel
+    source as it stands."""
+    import hashlib
+    entry = MEASURED_TRAFFIC.get(kernel)
+    if entry is None:
+        return None
+    src, digest, fetch_mib, write_mib = entry
+    path = os.path.join(ROOT, "paper_2003_10735_amd", "csrc", src)
+    try:
+        with open(path, "rb") as fh:
+            if hashlib.sha256(fh.read()).hexdigest() != digest:
+                return None
+    except OSError:
+        return None
+    return round((fetch_mib + write_mib) * 1048576.0)
+
 
 def kernel_work(wl):
     """Algorithmic work per launch of each kernel family: name prefix -> (bound, amount, unit).
@@ -171,7 +198,7 @@ def main():
         else:
             peak, achieved, unit = PEAK_HBM_GBS, amount / avg_s / 1e9, "GB/s"
         return {"bound": bound, "kernel": name, "achieved": round(achieved, 3), "peak": peak,
-                "unit": unit, "frac": round(achieved / peak, 5), "traffic": None,
+                "unit": unit, "frac": round(achieved / peak, 5), "traffic": measured_traffic(name),
                 "avg_launch_us": round(avg_s * 1e6, 2), "launches": launches,
                 "work_per_launch": amount}
 

@@ -63,8 +63,10 @@ enum { ST_COMPUTE_F32 = 0, ST_COMPUTE_BF16 = 1 }; /* st_head_desc.compute */
  * compute = ST_COMPUTE_BF16: convolution operands (features, weights, activations and the
  *   back-propagated gradients) are rounded to bfloat16, products accumulate in float32 on the
  *   matrix cores; master weights, optimiser arithmetic, logits, loss and weight gradients stay
- *   float32.  Requires c_in, c1, c2 to be multiples of 32 and n_classes <= 32.
- * Limits: upscale == 8; 2 <= n_classes <= 64; labels outside [0, n_classes) are skipped like
+ *   float32.  Shapes with c_in a multiple of 64, c1 and c2 multiples of 32 and c2 one of
+ *   64, 128, 256 run on the matrix-core kernels; every other shape runs on plain tiled kernels
+ *   with the same rounding points (same results up to the order of float32 additions).
+ * Limits: upscale == 8; 2 <= n_classes <= 32; labels outside [0, n_classes) are skipped like
  * ignore_index (they count neither in the loss nor in the metric). */
 typedef struct st_head_desc {
     int32_t n, c_in, h, w;     /* feature map [n, c_in, h, w]                         */
