@@ -70,7 +70,7 @@ def kernel_work(wl):
     conv3 = 2.0 * M * C * wl.c2
     return {
         "conv1_fwd": ("mfma", conv1), "conv12_wgrad": ("mfma", conv1 + conv2),
-        "conv2_fwd": ("mfma", conv2), "conv2_dgrad": ("mfma", conv2),
+        "conv2_fwd": ("mfma", conv2 + conv3), "conv2_dgrad": ("mfma", conv2),
         "conv3_fwd": ("mfma", conv3), "conv3_wgrad": ("mfma", conv3), "conv3_dgrad": ("mfma", conv3),
         "conv3_bwd": ("mfma", 2 * conv3),
         "upsample_ce_grad": ("alu", 19.0 * C * P),

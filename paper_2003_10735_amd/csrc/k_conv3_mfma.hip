@@ -11,57 +11,7 @@
 
 namespace st {
 
-// ------------------------------------------------------------------ forward
-// One wavefront = 32 consecutive (unpadded) positions; the weights are the A operand (rows =
-// classes), the activations the B operand, so register r of a lane is one class of one position
-// and each store instruction writes 32 consecutive positions of one class plane.
-template <int KSTEPS>   // c2 / 16
-__global__ void __launch_bounds__(256)
-k_logits_mfma(const bf16* __restrict__ a2, const bf16* __restrict__ W3q, const float* __restrict__ b3,
-              float* __restrict__ z, Geo g)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l32 = lane & 31, lhi = lane >> 5;
-    const int hw = g.h * g.w, total = g.n * hw;
-    const int q = (blockIdx.x * 4 + wave) * 32 + l32;
-    const int qc = min(q, total - 1);
-    const int img = qc / hw, rr = qc - img * hw, y = rr / g.w, x = rr - y * g.w;
-    const size_t mp = ((size_t)img * g.Hp + y + 1) * g.Wp + x + 1;
-    const bf16* arow = a2 + mp * g.c2 + lhi * 8;
-    const bf16* wrow = W3q + (size_t)min(l32, g.C - 1) * g.c2 + lhi * 8;
-    f32x16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    const bf16x8 zero = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        bf16x8 wf = *(const bf16x8*)(wrow + ks * 16);
-        if (l32 >= g.C) wf = zero;
-        const bf16x8 xf = *(const bf16x8*)(arow + ks * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc, 0, 0, 0);
-    }
-    if (q < total) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
-            if (c < g.C) z[((size_t)img * g.C + c) * hw + rr] = acc[r] + b3[c];
-        }
-    }
-}
-
 bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 == 256) && C <= 32; }
-
-void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z)
-{
-    const Geo& g = p.g;
-    const dim3 grid(cdiv(g.positions(), 128));
-    switch (g.c2) {
-    case 64: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<4>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
-    case 128: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<8>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
-    case 256: ST_LAUNCH(c, "conv3_fwd_mfma", (k_logits_mfma<16>), grid, dim3(256), 0, a2, W3q, b3, z, g); break;
-    default: c.status = ST_ERR_SHAPE;
-    }
-}
 
 // ------------------------------------------------------------------ backward
 // One block = C3B_BP consecutive padded positions (g is zero on the border).  The block first

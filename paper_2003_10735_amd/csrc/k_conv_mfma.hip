@@ -30,7 +30,9 @@
 // A lane owns 4 consecutive output channels of one position per register group, which packs
 // into one 8-byte LDS write in the epilogue.  The epilogue stages the tile in LDS and writes it
 // twice with 16-byte stores: position-major (input of the next convolution) and channel-major
-// (operand of the weight-gradient kernel).
+// (operand of the weight-gradient kernel).  For the layer that feeds the 1x1 classifier the
+// staged tile is also multiplied with the classifier's weights (16 more MFMAs per block), which
+// saves the classifier a launch and a pass over the activations.
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
 
@@ -55,6 +57,12 @@ struct ConvArgs {
     const bf16* mask;   // EPI 1: activation whose sign gates the gradient, [PP][cout]
     bf16* Y;            // [PP][cout] or nullptr
     bf16* YT;           // channel-major copy, blocked layout of xt_index(), or nullptr
+    // EPI 2: the 1x1 classifier rides along.  Every block adds its 64 channels' share of the
+    // logits of its 128 positions: zpart[n-tile][padded position][32 classes] float32; the
+    // consumer adds the n_tiles shares and the bias.
+    const bf16* W3q;    // [n_cls][cout] bfloat16
+    float* zpart;
+    int n_cls;
     int PP, Hp, Wp, h, w, cin, cout, PPT, guard;
     int m_tiles, n_tiles, tiles_per_xcd;
 };
@@ -220,6 +228,18 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         mine = sum;
     }
 
+    // classifier fragments (A operand: rows = classes, k = 16 channels of this tile), fetched
+    // now so that they arrive while the tile is being staged
+    u32x4 w3f[4];
+    if (EPI == 2) {
+        const bf16* w3row = a.W3q + (size_t)min(l32, a.n_cls - 1) * a.cout + n0 + lhi * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const u32x4 v = *(const u32x4*)(w3row + ks * 16);
+            w3f[ks] = l32 < a.n_cls ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+
     // ---- epilogue: bias + ReLU (forward) or ReLU mask (data-gradient), zero outside the grid,
     //      round to bfloat16, stage the tile in LDS as [position][channel]
     bf16* Os = (bf16*)(smem_raw + CV_RED_BYTES);     // [CV_BM][CV_OLD], behind the partial sums
@@ -236,7 +256,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
             float v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = mine[rg * 4 + e];
-            if (EPI == 0) {
+            if (EPI != 1) {
                 const float4 b = *(const float4*)(a.bias + cg);
                 v[0] = fmaxf(v[0] + b.x, 0.f); v[1] = fmaxf(v[1] + b.y, 0.f);
                 v[2] = fmaxf(v[2] + b.z, 0.f); v[3] = fmaxf(v[3] + b.w, 0.f);
@@ -253,6 +273,24 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         }
     }
     __syncthreads();
+    if (EPI == 2 && wave < 4) {
+        // D[class][position] for positions 32 wave .. +31 over the tile's 64 channels
+        f32x16 zacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zacc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 xf = *(const bf16x8*)(Os + (wave * 32 + l32) * CV_OLD + ks * 16 + lhi * 8);
+            zacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w3f[ks]), xf, zacc, 0, 0, 0);
+        }
+        const int mp = m0 + wave * 32 + l32;
+        if (mp < a.PP) {
+            float* zrow = a.zpart + ((size_t)nt * a.PP + mp) * 32 + lhi * 4;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+                *(f32x4*)(zrow + gq * 8) = f32x4{zacc[gq * 4], zacc[gq * 4 + 1], zacc[gq * 4 + 2], zacc[gq * 4 + 3]};
+        }
+    }
     const int n_valid = min(CV_BN, a.cout - n0);
     if (a.Y) {
         // position-major: 16 bytes = 8 channels of one position
@@ -278,12 +316,15 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 
 bool conv3x3_mfma_supported(int cin, int cout) { return cin % CV_BK == 0 && cout % 32 == 0 && cout >= 32; }
 
-// epi 0: Y = relu(conv + bias); epi 1: Y = conv * [mask > 0]
+// epi 0: Y = relu(conv + bias); epi 1: Y = conv * [mask > 0]; with W3q / zpart (epi 0, cout a
+// multiple of 64) the block also leaves its share of the classifier's logits
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
-                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer)
+                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer, const bf16* W3q,
+                  float* zpart)
 {
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
+    a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C;
     a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.h = p.g.h; a.w = p.g.w;
     a.cin = cin; a.cout = cout;
     a.PPT = p.PPT; a.guard = p.guard;
@@ -299,6 +340,7 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
         ST_LAUNCH(c, name, kernel, grid, dim3(512), smem, a);
     };
     if (epi == 1) go(k_conv3x3_mfma<1, 3>);
+    else if (zpart) go(k_conv3x3_mfma<2, 2>);
     else if (layer == 1) go(k_conv3x3_mfma<0, 1>);
     else go(k_conv3x3_mfma<0, 2>);
 }

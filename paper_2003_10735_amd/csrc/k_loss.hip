@@ -24,6 +24,7 @@
 // most four) slots that meet in a cell in a fixed order.  No floating-point atomics anywhere:
 // results do not change from run to run.
 #include "st_kernels.hpp"
+#include "st_mfma.hpp"
 
 namespace st {
 
@@ -132,7 +133,7 @@ constexpr int LOSS_THREADS = 512;
 
 template <int CP, bool GRAD>
 __global__ void __launch_bounds__(LOSS_THREADS)
-k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const float* __restrict__ T,
+k_loss(ZSrc zs, const int32_t* __restrict__ labels, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
        unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
 {
@@ -155,13 +156,40 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const fl
     //      large negative logit: they never win, their softmax term is exactly 0.
     //      All global loads of the prologue are issued before anything waits for one of them.
     constexpr int NZ = (CP * CH * CW + NT - 1) / NT;
+    constexpr int NZQ = (CH * CW * 8 + NT - 1) / NT;     // 16-byte chunks of the 32-class rows
     float zv[NZ];
+    f32x4 zq[NZQ], bq[NZQ];
+    if (zs.parts) {
+        const size_t PP = (size_t)g.padded_positions();
 #pragma unroll
-    for (int k = 0; k < NZ; ++k) {
-        const int i = min(tid + k * NT, CP * CH * CW - 1);
-        const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
-        const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
-        zv[k] = z[((size_t)img * C + min(c, C - 1)) * hw + cy * g.w + cx];
+        for (int k = 0; k < NZQ; ++k) {
+            const int i = min(tid + k * NT, CH * CW * 8 - 1);
+            const int cell = i >> 3, chunk = i & 7;
+            const int lc = cell % CW, r = cell / CW;
+            const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
+            const size_t mp = ((size_t)img * g.Hp + cy + 1) * g.Wp + cx + 1;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            // at most four shares (256 channels); absent ones re-read the last with weight 0, so
+            // that no load sits under a branch
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                const float wgt = part < zs.n_parts ? 1.f : 0.f;
+                const f32x4 v = *(const f32x4*)(zs.parts + ((size_t)min(part, zs.n_parts - 1) * PP + mp) * 32 + chunk * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(wgt, v[e], acc[e]);
+            }
+            zq[k] = acc;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bq[k][e] = zs.b3[min(chunk * 4 + e, C - 1)];
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < NZ; ++k) {
+            const int i = min(tid + k * NT, CP * CH * CW - 1);
+            const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
+            const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
+            zv[k] = zs.planar[((size_t)img * C + min(c, C - 1)) * hw + cy * g.w + cx];
+        }
     }
     // T over the cells this tile owns, for the  - <T, z>  part of the loss (see the header)
     constexpr int NTT = (32 * LOSS_TX + NT - 1) / NT;
@@ -203,13 +231,37 @@ k_loss(const float* __restrict__ z, const int32_t* __restrict__ labels, const fl
 #pragma unroll
         for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : -1;
     }
+    if (zs.parts) {
 #pragma unroll
-    for (int k = 0; k < NZ; ++k) {
-        const int i = tid + k * NT;
-        const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
-        if (i < CP * CH * CW) zt[c][r][lc] = c < C ? zv[k] : -1e30f;
+        for (int k = 0; k < NZQ; ++k) {
+            const int i = tid + k * NT;
+            const int cell = i >> 3, chunk = i & 7;
+            const int lc = cell % CW, r = cell / CW;
+            if (i < CH * CW * 8) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int c = chunk * 4 + e;
+                    if (c < CP) zt[c][r][lc] = c < C ? zq[k][e] + bq[k][e] : -1e30f;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < NZ; ++k) {
+            const int i = tid + k * NT;
+            const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
+            if (i < CP * CH * CW) zt[c][r][lc] = c < C ? zv[k] : -1e30f;
+        }
     }
     __syncthreads();
+    // the logits of this tile's own cells, as used below, for whoever wants the planar tensor
+    if (zs.parts && zs.z_out) {
+        for (int i = tid; i < C * LOSS_TX; i += NT) {
+            const int lc = i % LOSS_TX, c = i / LOSS_TX;
+            const int cx = tile_x * LOSS_TX + lc;
+            if (cx < g.w) zs.z_out[((size_t)img * C + c) * hw + qy * g.w + cx] = zt[c][1][lc + 1];
+        }
+    }
 
     float loss_acc = 0.f;
 #pragma unroll
@@ -378,21 +430,21 @@ size_t loss_slot_floats(const Geo& g)
 int loss_blocks(const Geo& g) { return g.n * loss_tiling(g).tiles(); }
 
 template <int CP>
-static void loss_launch(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T,
+static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
                         const unsigned long long* n_valid, bool grad, bool assemble)
 {
     const LossTiling lt = loss_tiling(g);
     const int blocks = g.n * lt.tiles();
     if (grad) {
-        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, z, labels, T, pred,
+        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, T, pred,
                   slots, loss_part, conf, g, lt);
         // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
         if (assemble)
             ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
                       dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
-        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, z, labels, T, pred, slots,
+        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, T, pred, slots,
                   loss_part, conf, g, lt);
     }
 }
@@ -420,11 +472,11 @@ void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsign
 #undef ST_CALL
 }
 
-void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble)
 {
-#define ST_CALL(CP) loss_launch<CP>(c, g, z, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
+#define ST_CALL(CP) loss_launch<CP>(c, g, zs, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
 }

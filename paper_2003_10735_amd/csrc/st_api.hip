@@ -144,6 +144,8 @@ Plan make_plan(const st_head_desc& d)
     p.z = take(off, (size_t)g.n * g.C * hw * 4);
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
     p.tadj = take(off, (size_t)g.n * g.C * hw * 4);
+    p.z_parts = p.mfma ? g.c2 / 64 : 0;
+    if (p.mfma) p.zpart = take(off, (size_t)p.z_parts * PP * 32 * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.theta = take(off, p.po.total * 4);
     p.vel = take(off, p.po.total * 4);
@@ -177,7 +179,10 @@ static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
     zero_bytes(c, ws + p.conf, (size_t)p.g.n * p.g.C * p.g.C * 8);
 }
 
-// one forward pass of the head: features (already packed) -> low-resolution logits z
+// one forward pass of the head: features (already packed) -> low-resolution logits.  The plain
+// path leaves the planar tensor z; the matrix-core path leaves per-channel-tile shares of the
+// logits (the classifier rides along with layer 2), which the loss kernel adds up -- and writes
+// to z on the way.
 static void forward(Ctx& c, const Plan& p, char* ws, float* z)
 {
     if (!p.mfma) { generic_forward(c, p, ws, z); return; }
@@ -185,9 +190,21 @@ static void forward(Ctx& c, const Plan& p, char* ws, float* z)
     const float* theta = (const float*)(ws + p.theta);
     conv3x3_mfma(c, "conv1_fwd_mfma", p, (const bf16*)(ws + p.feat), (const bf16*)(ws + p.wq1), theta + p.po.b1,
                  nullptr, (bf16*)(ws + p.a1), (bf16*)(ws + p.a1T), g.c_in, g.c1, 0, 1);
-    conv3x3_mfma(c, "conv2_fwd_mfma", p, (const bf16*)(ws + p.a1), (const bf16*)(ws + p.wq2), theta + p.po.b2,
-                 nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0, 2);
-    logits_mfma(c, p, (const bf16*)(ws + p.a2), (const bf16*)(ws + p.wq3), theta + p.po.b3, z);
+    conv3x3_mfma(c, "conv2_fwd_logits_mfma", p, (const bf16*)(ws + p.a1), (const bf16*)(ws + p.wq2),
+                 theta + p.po.b2, nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0, 2,
+                 (const bf16*)(ws + p.wq3), (float*)(ws + p.zpart));
+}
+
+static ZSrc z_source(const Plan& p, char* ws, float* z)
+{
+    ZSrc zs;
+    zs.planar = z; zs.parts = nullptr; zs.n_parts = 0; zs.b3 = nullptr; zs.z_out = nullptr;
+    if (p.mfma) {
+        zs.planar = nullptr;
+        zs.parts = (const float*)(ws + p.zpart); zs.n_parts = p.z_parts;
+        zs.b3 = (const float*)(ws + p.theta) + p.po.b3; zs.z_out = z;
+    }
+    return zs;
 }
 
 // partial backward: gradients of the head's parameters only; nothing flows into the features
@@ -251,8 +268,9 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     update_params(c, p, ws, 0.f, 0.f, false);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
-    if (pred)
-        loss_pass(c, p.g, z, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr, false, false);
+    if (pred || p.mfma)
+        loss_pass(c, p.g, z_source(p, ws, z), nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr,
+                  false, false);
     return c.status;
 }
 
@@ -305,7 +323,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
         forward(c, p, ws, z);
-        loss_pass(c, g, z, teacher_labels, (const float*)(ws + p.tadj),
+        loss_pass(c, g, z_source(p, ws, z), teacher_labels, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);

@@ -17,13 +17,13 @@ void generic_backward(Ctx& c, const Plan& p, char* ws);
 // k_conv_mfma.hip, k_wgrad_mfma.hip, k_conv3_mfma.hip -- matrix-core kernels of the bfloat16 path
 bool conv3x3_mfma_supported(int cin, int cout);
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
-                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer);
+                  const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer,
+                  const bf16* W3q = nullptr, float* zpart = nullptr);
 bool wgrad3x3_mfma_supported(int cin, int cout);
 void wgrad_splits_for(const Geo& g, int* splits1, int* splits2);
 void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, const bf16* da2T,
                    const bf16* a1T, float* grad);
 bool conv3_mfma_supported(int c2, int C);
-void logits_mfma(Ctx& c, const Plan& p, const bf16* a2, const bf16* W3q, const float* b3, float* z);
 int conv3_bwd_blocks(const Geo& g);
 size_t conv3_bwd_slot_floats(const Geo& g);
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
@@ -34,7 +34,15 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
 void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsigned long long* n_valid);
-void loss_pass(Ctx& c, const Geo& g, const float* z, const int32_t* labels, const float* T, uint8_t* pred,
+// Where the loss kernel finds the low-resolution logits: either the planar tensor [n, C, h, w], or
+// the shares the classifier-fused convolution left behind, [n_parts][padded position][32 classes],
+// to be added in ascending order together with the bias b3; in that case the kernel also writes
+// the sums to the planar tensor z_out (each tile its own cells), if given.
+struct ZSrc {
+    const float* planar;
+    const float* parts; int n_parts; const float* b3; float* z_out;
+};
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble);
 
