@@ -211,6 +211,35 @@ def make_learnable_features(wl: Workload, labels: np.ndarray, strength: float = 
     return f.astype(np.float32)
 
 
+def clip_frames(wl: Workload, learnable: bool = False, strength: float = 2.0):
+    """The frames of a temporal clip: labels are the Voronoi map moved `shift_px` pixels per frame,
+    features drift as f_t = f_{t-1} + drift * N(0,1) on a float32 master.  With `learnable` the
+    master of every frame additionally carries that frame's labels (see make_learnable_features),
+    so that a trained head scores well on the next frame; the measured clip uses plain noise.
+    Yields (features, labels) with features in the workload's dtype."""
+    n_frames = int(wl.extra["frames"])
+    drift, shift = float(wl.extra["drift"]), int(wl.extra["shift_px"])
+    rng0 = np.random.default_rng(wl.feat_seed)
+    noise = rng0.standard_normal((wl.n, wl.c_in, wl.h, wl.w), dtype=np.float32)
+    if not learnable and wl.clamp_features:
+        np.maximum(noise, 0.0, out=noise)
+    for t in range(n_frames):
+        labels = make_labels(wl, frame_shift=t * shift)
+        if t > 0:
+            noise = drift_features(noise, drift, wl.feat_seed + 1000 + t)
+        f = noise
+        if learnable:
+            rng = np.random.default_rng(7)
+            code = rng.standard_normal((wl.n_classes + 1, wl.c_in)).astype(np.float32)
+            s_ = wl.upscale
+            centre = labels[:, s_ // 2::s_, s_ // 2::s_][:, :wl.h, :wl.w]
+            centre = np.where((centre >= 0) & (centre < wl.n_classes), centre, wl.n_classes)
+            f = noise * np.float32(0.3) + np.float32(strength) * np.transpose(code[centre], (0, 3, 1, 2))
+            if wl.clamp_features:
+                f = np.maximum(f, 0.0)
+        yield (f32_to_bf16_bits(f) if wl.feat_dtype == "bf16" else f.astype(np.float32)), labels
+
+
 def small_variant(wl: Workload, **kw) -> Workload:
     """A copy of a workload with some fields replaced (ragged test sizes and the like)."""
     d = {k: getattr(wl, k) for k in wl.__dataclass_fields__}
