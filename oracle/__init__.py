@@ -174,6 +174,24 @@ def sgd(theta, grad, vel, lr, mu):
     return theta, vel
 
 
+class Optim(C.Structure):
+    """kind 0: gradient descent with optional momentum; kind 1: Adam (t0 = steps taken before)."""
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_double), ("mu", C.c_double), ("beta1", C.c_double),
+                ("beta2", C.c_double), ("eps", C.c_double), ("t0", C.c_int64)]
+
+
+def adam_optim(lr, beta1=0.9, beta2=0.999, eps=1e-8, t0=0) -> Optim:
+    return Optim(1, lr, 0.0, beta1, beta2, eps, t0)
+
+
+def adam(theta, grad, m, v, lr, beta1, beta2, eps, t):
+    """One Adam step number t (1-based) on copies; returns (theta, m, v)."""
+    theta, grad, m, v = _f64(theta).copy(), _f64(grad), _f64(m).copy(), _f64(v).copy()
+    lib().sto_adam(_d(theta), _d(grad), _d(m), _d(v), C.c_int64(theta.size), C.c_double(lr),
+                   C.c_double(beta1), C.c_double(beta2), C.c_double(eps), C.c_int64(t))
+    return theta, m, v
+
+
 # ------------------------------------------------------------------ the head
 def num_params(d: Desc) -> int:
     return int(lib().sto_num_params(C.byref(d)))
@@ -215,6 +233,25 @@ def partial_distill(d: Desc, features, labels, params, steps, lr, momentum=0.0, 
                               _d(vel), steps, C.c_double(lr), C.c_double(momentum), _d(losses),
                               _d(mious), _p(conf, C.c_int64), _p(pred, C.c_uint8))
     return dict(params=params, velocity=vel, losses=losses, mious=mious, conf=conf, pred=pred)
+
+
+def partial_distill_opt(d: Desc, features, labels, params, steps, optim: Optim, s1=None, s2=None):
+    """k fixed steps with an explicit optimiser description; s1 / s2 are its state arrays
+    (velocity, or Adam's m and v), zero when absent.  Returns the same dict as partial_distill
+    plus s1, s2."""
+    features = _f64(features)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    params = _f64(params).copy()
+    s1 = _f64(s1).copy() if s1 is not None else np.zeros_like(params)
+    s2 = _f64(s2).copy() if s2 is not None else np.zeros_like(params)
+    losses = np.empty(steps + 1)
+    mious = np.empty((steps + 1, d.n))
+    conf = np.empty((d.n, d.n_classes, d.n_classes), dtype=np.int64)
+    pred = np.empty((d.n, 8 * d.h, 8 * d.w), dtype=np.uint8)
+    lib().sto_partial_distill_opt(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params),
+                                  C.byref(optim), _d(s1), _d(s2), steps, _d(losses), _d(mious),
+                                  _p(conf, C.c_int64), _p(pred, C.c_uint8))
+    return dict(params=params, s1=s1, s2=s2, losses=losses, mious=mious, conf=conf, pred=pred)
 
 
 def train(d: Desc, features, labels, params, max_updates, lr, threshold, momentum=0.0,

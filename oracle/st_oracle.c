@@ -14,7 +14,8 @@
  *   metric     = mean IoU (Eq. 1) of prediction against the teacher's labels
  *   repeat:  loss = per-pixel cross-entropy (Section 5.2), gradients by the
  *            chain rule down to the first trainable layer and no further,
- *            one optimiser step, Forward, metric
+ *            one optimiser step (gradient descent, optionally with momentum,
+ *            or Adam as in Section 5.2), Forward, metric
  *
  * The head is conv3x3(+bias, ReLU), conv3x3(+bias, ReLU), conv1x1(+bias), then
  * an x8 bilinear up-sampling to the input resolution (Section 2.2: the output
@@ -393,6 +394,39 @@ void sto_sgd(double* theta, const double* grad, double* vel, int64_t n, double l
     }
 }
 
+/* Adam, the optimiser of the paper's experiments (Section 5.2: learning rate 0.01).  The
+ * paper gives no further constants; the caller passes them (the published defaults are
+ * beta1 = 0.9, beta2 = 0.999, eps = 1e-8).  Step t = 1, 2, .. of the published algorithm:
+ *   m <- beta1 m + (1 - beta1) g          v <- beta2 v + (1 - beta2) g^2
+ *   mhat = m / (1 - beta1^t)              vhat = v / (1 - beta2^t)
+ *   theta <- theta - lr mhat / (sqrt(vhat) + eps)                                        */
+void sto_adam(double* theta, const double* grad, double* m, double* v, int64_t n, double lr,
+              double beta1, double beta2, double eps, int64_t t)
+{
+    const double bc1 = 1.0 - pow(beta1, (double)t), bc2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        m[i] = beta1 * m[i] + (1.0 - beta1) * grad[i];
+        v[i] = beta2 * v[i] + (1.0 - beta2) * grad[i] * grad[i];
+        const double mhat = m[i] / bc1, vhat = v[i] / bc2;
+        theta[i] -= lr * mhat / (sqrt(vhat) + eps);
+    }
+}
+
+/* One optimiser description for the loops below.  kind 0: gradient descent with optional
+ * momentum (state s1 = velocity); kind 1: Adam (s1 = m, s2 = v, t0 = steps taken before). */
+typedef struct {
+    int32_t kind;
+    double lr, mu, beta1, beta2, eps;
+    int64_t t0;
+} sto_optim;
+
+static void optim_step(const sto_optim* o, double* theta, const double* grad, double* s1, double* s2,
+                       int64_t n, int64_t step_in_call)
+{
+    if (o->kind == 1) sto_adam(theta, grad, s1, s2, n, o->lr, o->beta1, o->beta2, o->eps, o->t0 + step_in_call);
+    else sto_sgd(theta, grad, o->mu != 0.0 ? s1 : NULL, n, o->lr, o->mu);
+}
+
 /* ------------------------------------------------------------------ the head and the loop */
 typedef struct {
     int32_t n, c_in, h, w;
@@ -555,9 +589,9 @@ double sto_loss_and_grad(const sto_desc* d, const double* features, const int32_
  * losses[i], mious[i*n + frame] describe the parameters before update i+1; entry k the final
  * ones (k steps = k+1 forwards).  params (and velocity when mu != 0) are updated in place.
  * conf_final [n,C,C] and pred_final [n,8h,8w] (both optional) belong to the final forward. */
-void sto_partial_distill(const sto_desc* d, const double* features, const int32_t* labels,
-                         double* params, double* velocity, int steps, double lr, double mu,
-                         double* losses, double* mious, int64_t* conf_final, uint8_t* pred_final)
+void sto_partial_distill_opt(const sto_desc* d, const double* features, const int32_t* labels,
+                             double* params, const sto_optim* opt, double* s1, double* s2, int steps,
+                             double* losses, double* mious, int64_t* conf_final, uint8_t* pred_final)
 {
     const size_t np = offsets(d).total;
     double* grad = dalloc(np);
@@ -567,9 +601,18 @@ void sto_partial_distill(const sto_desc* d, const double* features, const int32_
                                        last ? pred_final : NULL, last ? conf_final : NULL,
                                        mious + (size_t)it * d->n);
         if (last) break;
-        sto_sgd(params, grad, mu != 0.0 ? velocity : NULL, (int64_t)np, lr, mu);
+        optim_step(opt, params, grad, s1, s2, (int64_t)np, it + 1);
     }
     free(grad);
+}
+
+void sto_partial_distill(const sto_desc* d, const double* features, const int32_t* labels,
+                         double* params, double* velocity, int steps, double lr, double mu,
+                         double* losses, double* mious, int64_t* conf_final, uint8_t* pred_final)
+{
+    const sto_optim o = {0, lr, mu, 0.0, 0.0, 0.0, 0};
+    sto_partial_distill_opt(d, features, labels, params, &o, velocity, NULL, steps, losses, mious,
+                            conf_final, pred_final);
 }
 
 /* Student training exactly as Algorithm 1 states it: skip when the first metric already
@@ -578,9 +621,9 @@ void sto_partial_distill(const sto_desc* d, const double* features, const int32_
  * paper prints; 0: '>=').  The metric is the mean over frames of the per-frame mean IoU.
  * On return params holds best_student; returns the number of updates taken;
  * *best_metric receives the matching metric; metrics[0..updates] the trace. */
-int sto_train(const sto_desc* d, const double* features, const int32_t* labels,
-              double* params, double* velocity, int max_updates, double lr, double mu,
-              double threshold, int strict_break, double* best_metric, double* metrics)
+int sto_train_opt(const sto_desc* d, const double* features, const int32_t* labels,
+                  double* params, const sto_optim* opt, double* s1, double* s2, int max_updates,
+                  double threshold, int strict_break, double* best_metric, double* metrics)
 {
     const size_t np = offsets(d).total;
     double* grad = dalloc(np);
@@ -597,7 +640,7 @@ int sto_train(const sto_desc* d, const double* features, const int32_t* labels,
     memcpy(best, params, sizeof(double) * np);
     if (bm < threshold) {
         for (int i = 1; i <= max_updates; ++i) {
-            sto_sgd(params, grad, mu != 0.0 ? velocity : NULL, (int64_t)np, lr, mu);
+            optim_step(opt, params, grad, s1, s2, (int64_t)np, i);
             ++updates;
             sto_loss_and_grad(d, features, labels, params, grad, NULL, NULL, fm);
             metric = 0.0;
@@ -612,4 +655,13 @@ int sto_train(const sto_desc* d, const double* features, const int32_t* labels,
     *best_metric = bm;
     free(grad); free(best); free(fm);
     return updates;
+}
+
+int sto_train(const sto_desc* d, const double* features, const int32_t* labels,
+              double* params, double* velocity, int max_updates, double lr, double mu,
+              double threshold, int strict_break, double* best_metric, double* metrics)
+{
+    const sto_optim o = {0, lr, mu, 0.0, 0.0, 0.0, 0};
+    return sto_train_opt(d, features, labels, params, &o, velocity, NULL, max_updates, threshold,
+                         strict_break, best_metric, metrics);
 }

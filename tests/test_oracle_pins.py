@@ -12,6 +12,7 @@ import torch
 import torch.nn.functional as F
 
 import oracle as O
+import workloads as WL
 
 torch.set_num_threads(4)
 RNG = np.random.default_rng(12345)
@@ -293,3 +294,66 @@ def test_bf16_rounding_matches_library_and_ties_to_even():
     assert O.round_bf16(np.array([1.00390625]))[0] == 1.0
     # 1 + 3*2^-8 lies halfway between 1+2^-7 and 1+2^-6 -> 1 + 2^-6
     assert O.round_bf16(np.array([1.01171875]))[0] == 1.015625
+
+
+# ------------------------------------------------------------------ Adam (Section 5.2: the paper's optimiser)
+def test_adam_first_step_closed_form():
+    """From zero state the bias-corrected moments of step 1 are g and g^2, so the step is
+    -lr * g / (|g| + eps) whatever beta1, beta2 are."""
+    rng = np.random.default_rng(11)
+    theta, g = rng.standard_normal(257), rng.standard_normal(257) * 1e-3
+    g[::17] = 0.0
+    for b1, b2 in ((0.9, 0.999), (0.5, 0.8)):
+        t1, m, v = O.adam(theta, g, np.zeros(257), np.zeros(257), 0.01, b1, b2, 1e-8, 1)
+        np.testing.assert_allclose(t1, theta - 0.01 * g / (np.abs(g) + 1e-8), rtol=0, atol=1e-15)
+        np.testing.assert_allclose(m, (1 - b1) * g, rtol=1e-15, atol=0)
+        np.testing.assert_allclose(v, (1 - b2) * g * g, rtol=1e-15, atol=0)
+    assert np.all(t1[::17] == theta[::17])   # zero gradient: no move
+
+
+def test_adam_constant_gradient_walks_at_lr():
+    """With the same gradient every step, mhat = g and vhat = g^2 for every t: each step moves
+    every parameter by lr * g / (|g| + eps), i.e. by lr against the gradient's sign."""
+    g = np.array([2.0, -0.5, 1e-3, -7.0])
+    theta, m, v = np.zeros(4), np.zeros(4), np.zeros(4)
+    for t in range(1, 21):
+        theta, m, v = O.adam(theta, g, m, v, 0.01, 0.9, 0.999, 1e-8, t)
+    np.testing.assert_allclose(theta, -20 * 0.01 * g / (np.abs(g) + 1e-8), rtol=1e-12)
+
+
+def test_adam_matches_independent_library():
+    """Ten steps on a changing gradient against torch.optim.Adam (float64, CPU)."""
+    rng = np.random.default_rng(12)
+    x0 = rng.standard_normal(300)
+    grads = [rng.standard_normal(300) * (0.1 + i) for i in range(10)]
+    w = torch.tensor(x0.copy(), dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([w], lr=0.01, betas=(0.9, 0.999), eps=1e-8)
+    theta, m, v = x0.copy(), np.zeros(300), np.zeros(300)
+    for t, g in enumerate(grads, start=1):
+        w.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        theta, m, v = O.adam(theta, g, m, v, 0.01, 0.9, 0.999, 1e-8, t)
+        np.testing.assert_allclose(theta, w.detach().numpy(), rtol=0, atol=1e-13)
+
+
+def test_adam_loop_equals_manual_steps():
+    """The optimiser-generic loop with Adam is the manual sequence loss/gradient -> Adam step,
+    with the step counter continuing from t0."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=4, h=4, w=5, c1=4, c2=4, n_classes=3, n_sites=4)
+    d = O.desc_of(wl)
+    f = WL.features_as_f64(wl, WL.make_features(wl))
+    lab = WL.make_labels(wl)
+    p0 = WL.make_head_params(wl).astype(np.float64)
+    r = O.partial_distill_opt(d, f, lab, p0, 3, O.adam_optim(0.01, t0=5))
+    theta, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    for k in range(3):
+        loss, grad, _ = O.loss_and_grad(d, f, lab, theta)[:3]
+        assert loss == r["losses"][k]
+        theta, m, v = O.adam(theta, grad, m, v, 0.01, 0.9, 0.999, 1e-8, 5 + k + 1)
+    np.testing.assert_array_equal(theta, r["params"])
+    np.testing.assert_array_equal(m, r["s1"])
+    np.testing.assert_array_equal(v, r["s2"])
+    # and the descent-with-momentum description reproduces the dedicated entry point
+    a = O.partial_distill(d, f, lab, p0, 3, 0.01, momentum=0.9)
+    b = O.partial_distill_opt(d, f, lab, p0, 3, O.Optim(0, 0.01, 0.9, 0, 0, 0, 0))
+    np.testing.assert_array_equal(a["params"], b["params"])
