@@ -76,6 +76,7 @@ def kernel_work(wl):
         "upsample_ce_grad": ("alu", 19.0 * C * P),
         "upsample_ce": ("alu", 10.0 * C * P),
         "sgd_update": ("hbm", (22.0 if wl.momentum else 14.0) * wl.n_params),
+        "adam_update": ("hbm", 30.0 * wl.n_params),
         "pack_features": ("hbm", 2.0 * wl.n * wl.c_in * wl.h * wl.w * 2),
     }
 
@@ -97,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="720p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--optimizer", choices=("sgd", "adam"), default="sgd",
+                    help="sgd: the workload's optimiser (the headline configuration); adam: the "
+                         "paper's optimiser (Section 5.2) with beta 0.9 / 0.999, eps 1e-8, state reset per key frame")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (outside the timed "
                          "region): the known-size reference that scales hardware byte counters")
@@ -135,10 +139,19 @@ def main():
     ws = st.new_workspace(desc)
     stream = torch.cuda.current_stream()
 
+    use_adam = args.optimizer == "adam"
+    adam = dict(m=torch.zeros_like(p), v=torch.zeros_like(p), t0=0) if use_adam else None
+
     def one_call():
         p.copy_(p0)                      # the head is re-initialised for every key frame
         if vel is not None:
             vel.zero_()
+        if use_adam:
+            adam["m"].zero_()
+            adam["v"].zero_()
+            st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, adam=adam, losses=losses, mious=mious,
+                                  confusion=conf, workspace=ws, stream=stream)
+            return
         st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
                               losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream)
 
@@ -230,8 +243,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: features [{wl.n},{wl.c_in},{wl.h},{wl.w}] {wl.feat_dtype}, head "
                                f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, "
-                               f"{wl.steps} SGD steps per key frame (one bench step = one key frame)",
-                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum},
+                               f"{wl.steps} {'Adam' if args.optimizer == 'adam' else 'SGD'} steps per key frame (one bench step = one key frame)",
+                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer},
         "key_frames_per_s": round(args.steps / elapsed, 3),
         "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
         "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],

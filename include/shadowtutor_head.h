@@ -89,7 +89,20 @@ typedef struct st_distill_opts {
                              0: when metric >= threshold                                     */
     int32_t return_best;  /* with threshold > 0 -- 1: head_params receives best_student of
                              Algorithm 1 (strictly-better rule); 0: the last parameters      */
+    /* Optimiser (Algorithm 1, OptimStep).  ST_OPTIM_SGD: the descent above.  ST_OPTIM_ADAM: the
+     * optimiser of the paper's experiments (Section 5.2, learning rate 0.01); the paper gives
+     * no further constants, the published defaults are beta1 0.9, beta2 0.999, eps 1e-8.
+     * Step t = adam_t0 + 1, adam_t0 + 2, ..:
+     *   m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+     *   theta <- theta - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+     * momentum must be 0 with Adam. */
+    int32_t optimizer;    /* ST_OPTIM_SGD | ST_OPTIM_ADAM                                    */
+    float beta1, beta2, eps;
+    float* adam_m;        /* in/out, st_num_params floats each, same order as head_params;   */
+    float* adam_v;        /* required with ST_OPTIM_ADAM (zero them before the first step)   */
+    int32_t adam_t0;      /* optimiser steps already taken on this state (>= 0)              */
 } st_distill_opts;
+enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 
 /* Outputs of st_partial_distill.  The struct lives in HOST memory; the arrays are DEVICE
  * pointers and each may be NULL.  Entry i of losses / mious describes the parameters before

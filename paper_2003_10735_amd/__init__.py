@@ -20,6 +20,7 @@ ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_D
 ST_F32, ST_BF16 = 0, 1
 ST_NCHW = 0
 ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
+ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 
 EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
            "st_miou", "st_strerror", "st_last_hip_error", "st_version",
@@ -33,7 +34,9 @@ class StHeadDesc(C.Structure):
 
 class StDistillOpts(C.Structure):
     _fields_ = [("momentum", C.c_float), ("velocity", C.c_void_p), ("threshold", C.c_double),
-                ("strict_break", C.c_int32), ("return_best", C.c_int32)]
+                ("strict_break", C.c_int32), ("return_best", C.c_int32),
+                ("optimizer", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t0", C.c_int32)]
 
 
 class StDistillResult(C.Structure):
@@ -181,14 +184,22 @@ def st_head_forward(desc: HeadDesc, features, head_params, logits_lowres=None, p
 def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, steps: int, lr: float,
                        momentum: float = 0.0, velocity=None, threshold: float = 0.0,
                        strict_break: bool = True, return_best: bool = False, losses=None,
-                       mious=None, confusion=None, pred=None, workspace=None, stream=None):
-    """Runs the library's st_partial_distill; head_params (and velocity) are updated in place.
+                       mious=None, confusion=None, pred=None, workspace=None, stream=None,
+                       adam=None):
+    """Runs the library's st_partial_distill; head_params (and the optimiser state) are updated
+    in place.  `adam` = dict(m=, v=, t0=0, beta1=0.9, beta2=0.999, eps=1e-8) selects Adam.
     Returns (steps_taken, best_metric or None)."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
-    use_opts = momentum != 0.0 or threshold > 0.0 or velocity is not None
+    use_opts = momentum != 0.0 or threshold > 0.0 or velocity is not None or adam is not None
     opts = StDistillOpts(momentum, _ptr(velocity), threshold, 1 if strict_break else 0,
-                         1 if return_best else 0)
+                         1 if return_best else 0, ST_OPTIM_SGD, 0.0, 0.0, 0.0, None, None, 0)
+    if adam is not None:
+        opts.optimizer = ST_OPTIM_ADAM
+        opts.beta1, opts.beta2 = adam.get("beta1", 0.9), adam.get("beta2", 0.999)
+        opts.eps = adam.get("eps", 1e-8)
+        opts.adam_m, opts.adam_v = _ptr(adam["m"]), _ptr(adam["v"])
+        opts.adam_t0 = int(adam.get("t0", 0))
     res = StDistillResult(_ptr(losses), _ptr(mious), _ptr(confusion), _ptr(pred), 0, 0.0)
     st = lib().st_partial_distill(C.byref(d), _ptr(features), _ptr(teacher_labels), _ptr(head_params),
                                   steps, lr, C.byref(opts) if use_opts else None, C.byref(res),

@@ -11,7 +11,7 @@ namespace st {
 // One kernel closes a training step; its blocks play three roles (block index ranges):
 //
 //  (1) optimiser step over the flat parameter buffer: theta <- theta - lr * v, v <- mu * v + g
-//      (mu == 0: v is not touched).  g is the sum, in ascending order, of the partial gradients
+//      (mu == 0: v is not touched), or an Adam step (Section 5.2 of the paper; AdamStep).  g is the sum, in ascending order, of the partial gradients
 //      the backward kernels left behind: `splits1` copies for W1/b1 and `splits2` for W2/b2
 //      (position splits of the weight-gradient kernels, `stride` floats apart).
 //  (2) the same for W3/b3 when the classifier's backward kernel left one slot per block: one
@@ -27,11 +27,12 @@ namespace st {
 // wq3 has theta's order.  So do wq1 and wq2 for the plain tiled kernels (frag == 0); the
 // matrix-core convolutions read wq1, wq2 and wq2t in fragment order (wfrag_index).
 struct UpdateArgs {
-    float* theta; float* vel; const float* grad; size_t stride; int splits1, splits2;
+    float* theta; float* vel; float* vel2; const float* grad; size_t stride; int splits1, splits2;
     bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
     ParamOffsets po; int c_in, c1, c2;
     int frag;        // wq1 / wq2 / wq2t in fragment order
     float lr, mu;
+    int adam; AdamStep ad;   // adam != 0: vel = first moment m, vel2 = second moment v
     int do_step;     // 0: only refresh the bfloat16 copies
     // role (2)
     const float* part3; int blocks3; size_t slot3; int C;
@@ -49,12 +50,20 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
 {
     float w = a.theta[j];
     if (a.do_step) {
-        if (a.mu != 0.f) {
-            const float v = __builtin_fmaf(a.mu, a.vel[j], g);
-            a.vel[j] = v;
-            g = v;
+        if (a.adam) {
+            const float m = __builtin_fmaf(a.ad.beta1, a.vel[j], a.ad.one_minus_beta1 * g);
+            const float v = __builtin_fmaf(a.ad.beta2, a.vel2[j], a.ad.one_minus_beta2 * (g * g));
+            a.vel[j] = m;
+            a.vel2[j] = v;
+            w = w - a.ad.step_scale * m / (__fsqrt_rn(v) * a.ad.inv_sqrt_bc2 + a.ad.eps);
+        } else {
+            if (a.mu != 0.f) {
+                const float v = __builtin_fmaf(a.mu, a.vel[j], g);
+                a.vel[j] = v;
+                g = v;
+            }
+            w = __builtin_fmaf(-a.lr, g, w);
         }
-        w = __builtin_fmaf(-a.lr, g, w);
         a.theta[j] = w;
     }
     if (a.wq1) {
@@ -82,16 +91,29 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
 {
     f32x4 w = *(const f32x4*)(a.theta + j);
     if (a.do_step) {
-        if (a.mu != 0.f) {
-            const f32x4 vo = *(const f32x4*)(a.vel + j);
-            f32x4 v;
+        if (a.adam) {
+            const f32x4 mo = *(const f32x4*)(a.vel + j), vo = *(const f32x4*)(a.vel2 + j);
+            f32x4 m, v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(a.mu, vo[e], g[e]);
-            *(f32x4*)(a.vel + j) = v;
-            g = v;
+            for (int e = 0; e < 4; ++e) {
+                m[e] = __builtin_fmaf(a.ad.beta1, mo[e], a.ad.one_minus_beta1 * g[e]);
+                v[e] = __builtin_fmaf(a.ad.beta2, vo[e], a.ad.one_minus_beta2 * (g[e] * g[e]));
+                w[e] = w[e] - a.ad.step_scale * m[e] / (__fsqrt_rn(v[e]) * a.ad.inv_sqrt_bc2 + a.ad.eps);
+            }
+            *(f32x4*)(a.vel + j) = m;
+            *(f32x4*)(a.vel2 + j) = v;
+        } else {
+            if (a.mu != 0.f) {
+                const f32x4 vo = *(const f32x4*)(a.vel + j);
+                f32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(a.mu, vo[e], g[e]);
+                *(f32x4*)(a.vel + j) = v;
+                g = v;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = __builtin_fmaf(-a.lr, g[e], w[e]);
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = __builtin_fmaf(-a.lr, g[e], w[e]);
         *(f32x4*)(a.theta + j) = w;
     }
     if (a.wq1) {
@@ -248,12 +270,15 @@ static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* 
 
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
 // finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
-void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step, bool finish, float* loss_out,
+void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
               double* miou_out, long long* conf_out)
 {
     UpdateArgs a;
     a.theta = (float*)(ws + p.theta);
     a.vel = (float*)(ws + p.vel);
+    a.vel2 = (float*)(ws + p.vel2);
+    a.adam = adam ? 1 : 0;
+    if (adam) a.ad = *adam; else memset(&a.ad, 0, sizeof(a.ad));
     a.grad = (const float*)(ws + p.grad);
     a.stride = p.grad_stride;
     a.splits1 = p.mfma ? p.splits1 : 1;
@@ -284,13 +309,13 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step,
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
     const int blocks = a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
     if (blocks == 0) return;
-    const char* name = do_step ? (finish ? "sgd_update+finish_pass" : "sgd_update") : (params ? "weights_to_bf16" : "finish_pass");
+    const char* name = do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
     ST_LAUNCH(c, name, k_step_end, dim3(blocks), dim3(256), 0, a, f);
 }
 
 void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step)
 {
-    step_end(c, p, ws, lr, mu, do_step, false, nullptr, nullptr, nullptr);
+    step_end(c, p, ws, lr, mu, nullptr, do_step, false, nullptr, nullptr, nullptr);
 }
 
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)

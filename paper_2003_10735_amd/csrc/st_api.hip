@@ -149,6 +149,7 @@ Plan make_plan(const st_head_desc& d)
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.theta = take(off, p.po.total * 4);
     p.vel = take(off, p.po.total * 4);
+    p.vel2 = take(off, p.po.total * 4);
     p.grad_stride = (p.po.total + 3) / 4 * 4;
     p.grad = take(off, p.grad_stride * 4 * p.grad_copies);
     p.grad3 = take(off, (size_t)std::max(p.blocks3, 1) * conv3_bwd_slot_floats(g) * 4);
@@ -286,8 +287,24 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     double threshold = 0.0;
     float* velocity = nullptr;
     bool strict = true, return_best = false;
+    bool use_adam = false;
+    float *adam_m = nullptr, *adam_v = nullptr;
+    double beta1 = 0.0, beta2 = 0.0;
+    float adam_eps = 0.f;
+    long long adam_t0 = 0;
     if (opts) {
         if (!isfinite(opts->momentum) || opts->momentum < 0.f || isnan(opts->threshold)) return ST_ERR_ARG;
+        if (opts->optimizer != ST_OPTIM_SGD && opts->optimizer != ST_OPTIM_ADAM) return ST_ERR_ARG;
+        if (opts->optimizer == ST_OPTIM_ADAM) {
+            if (opts->momentum != 0.f) return ST_ERR_ARG;
+            if (!(opts->beta1 >= 0.f && opts->beta1 < 1.f) || !(opts->beta2 >= 0.f && opts->beta2 < 1.f) ||
+                !(opts->eps > 0.f) || !isfinite(opts->eps) || opts->adam_t0 < 0)
+                return ST_ERR_ARG;
+            if (!opts->adam_m || !opts->adam_v) return ST_ERR_NULL;
+            use_adam = true;
+            adam_m = opts->adam_m; adam_v = opts->adam_v;
+            beta1 = opts->beta1; beta2 = opts->beta2; adam_eps = opts->eps; adam_t0 = opts->adam_t0;
+        }
         mu = opts->momentum;
         velocity = opts->velocity;
         if (mu != 0.f && !velocity) return ST_ERR_NULL;
@@ -313,6 +330,10 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     pack_features(c, p, features, desc->feat_dtype, ws);
     permute_params(c, p, head_params, theta, 0);
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
+    if (use_adam) {
+        permute_params(c, p, adam_m, (float*)(ws + p.vel), 0);
+        permute_params(c, p, adam_v, (float*)(ws + p.vel2), 0);
+    }
     update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
     label_adjoint(c, g, teacher_labels, (float*)(ws + p.tadj), n_valid);   // also counts the valid labels
 
@@ -364,13 +385,27 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         }
         if (stop) break;
         backward(c, p, ws);
-        step_end(c, p, ws, lr, mu, true, !finish_now, loss_out, miou_out, conf_out);
+        AdamStep ad;
+        if (use_adam) {
+            // bias corrections of step t in double precision, handed to the kernel as two factors
+            const double t = (double)(adam_t0 + it + 1);
+            ad.beta1 = (float)beta1; ad.beta2 = (float)beta2;
+            ad.one_minus_beta1 = (float)(1.0 - beta1); ad.one_minus_beta2 = (float)(1.0 - beta2);
+            ad.eps = adam_eps;
+            ad.step_scale = (float)((double)lr / (1.0 - pow(beta1, t)));
+            ad.inv_sqrt_bc2 = (float)(1.0 / sqrt(1.0 - pow(beta2, t)));
+        }
+        step_end(c, p, ws, lr, mu, use_adam ? &ad : nullptr, true, !finish_now, loss_out, miou_out, conf_out);
         ++taken;
     }
     if (early_exit && return_best && have_best)
         ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
     permute_params(c, p, theta, head_params, 1);
     if (mu != 0.f) permute_params(c, p, (const float*)(ws + p.vel), velocity, 1);
+    if (use_adam) {
+        permute_params(c, p, (const float*)(ws + p.vel), adam_m, 1);
+        permute_params(c, p, (const float*)(ws + p.vel2), adam_v, 1);
+    }
     if (early_exit) ST_HIP(c, hipStreamSynchronize(c.stream));
     if (out) {
         out->steps_taken = taken;

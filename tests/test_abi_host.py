@@ -74,6 +74,18 @@ def test_null_and_argument_errors():
     assert pd(C.byref(cd), dummy, dummy, dummy, 1, 0.1, C.byref(opts), None, dummy, None) == st.ST_ERR_NULL
     opts = st.StDistillOpts(float("nan"), dummy, 0.0, 1, 0)
     assert pd(C.byref(cd), dummy, dummy, dummy, 1, 0.1, C.byref(opts), None, dummy, None) == st.ST_ERR_ARG
+    # Adam: state arrays required, no momentum, constants in range
+    def adam_opts(**kw):
+        o = st.StDistillOpts(0.0, None, 0.0, 1, 0, st.ST_OPTIM_ADAM, 0.9, 0.999, 1e-8, dummy, dummy, 0)
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return o
+    for kw, status in (({"adam_m": None}, st.ST_ERR_NULL), ({"adam_v": None}, st.ST_ERR_NULL),
+                       ({"momentum": 0.5, "velocity": dummy}, st.ST_ERR_ARG), ({"beta1": 1.0}, st.ST_ERR_ARG),
+                       ({"beta2": -0.1}, st.ST_ERR_ARG), ({"eps": 0.0}, st.ST_ERR_ARG),
+                       ({"adam_t0": -1}, st.ST_ERR_ARG), ({"optimizer": 2}, st.ST_ERR_ARG)):
+        o = adam_opts(**kw)
+        assert pd(C.byref(cd), dummy, dummy, dummy, 1, 0.1, C.byref(o), None, dummy, None) == status, kw
     assert L.st_miou(None, dummy, 10, 3, -1, dummy, dummy, None) == st.ST_ERR_NULL
     assert L.st_miou(dummy, dummy, -1, 3, -1, dummy, dummy, None) == st.ST_ERR_SHAPE
     assert L.st_miou(None, None, 0, 3, -1, None, dummy, None) == st.ST_ERR_NULL

@@ -43,3 +43,12 @@ def test_1080p_ignore_and_momentum():
 
 def test_batch4_shared_head():
     compare_bf16(WL.WORKLOADS["batch4"], steps=1)
+
+
+def test_720p_adam_two_steps():
+    """The paper's optimiser (Section 5.2) at the benchmark's shape; see check_adam for why the
+    weights are compared where the first gradient is not tiny."""
+    from test_gpu_parity import check_adam
+    wl = WL.WORKLOADS["720p"]
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    check_adam(wl, f, lab, p, 2, True, 2e-3, 2e-2)

@@ -207,3 +207,59 @@ def test_matrix_core_path_small_shapes(case):
     again = run_gpu(wl, f, lab, p)
     for k in ("params", "losses", "mious", "conf", "pred"):
         np.testing.assert_array_equal(gpu[k], again[k])
+
+
+# ------------------------------------------------------------------ Adam (the paper's optimiser, Section 5.2)
+def run_gpu_adam(wl, feats, labels, params, steps, t0=0, m=None, v=None):
+    import torch
+    import paper_2003_10735_amd as st
+    from gpu_util import to_dev_features
+    desc = st.HeadDesc.of(wl)
+    p = torch.from_numpy(params.astype(np.float32)).cuda()
+    mt = torch.from_numpy((m if m is not None else np.zeros_like(params)).astype(np.float32)).cuda()
+    vt = torch.from_numpy((v if v is not None else np.zeros_like(params)).astype(np.float32)).cuda()
+    losses = torch.full((steps + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    taken, _ = st.st_partial_distill(desc, to_dev_features(wl, feats), torch.from_numpy(labels).cuda(), p, steps,
+                                     wl.lr, losses=losses, adam=dict(m=mt, v=vt, t0=t0))
+    torch.cuda.synchronize()
+    assert taken == steps
+    return dict(params=p.cpu().numpy(), m=mt.cpu().numpy(), v=vt.cpu().numpy(), losses=losses.cpu().numpy())
+
+
+def check_adam(wl, feats, labels, params, steps, bf16_operands, loss_tol, tol):
+    """Adam's update m / (sqrt(v) + eps) is (nearly) the sign of the gradient where the
+    gradient is tiny, so two correct implementations whose gradients differ in the last bits
+    may move such a parameter in opposite directions.  Elementwise parity of the weights is
+    therefore required only where the oracle's own first gradient is not tiny; the losses, the
+    second moments (continuous in g) and the share of excused elements are checked as well."""
+    d = O.desc_of(wl, bf16_operands)
+    f64 = WL.features_as_f64(wl, feats)
+    o = O.partial_distill_opt(d, f64, labels, params.astype(np.float64), steps, O.adam_optim(wl.lr))
+    g = run_gpu_adam(wl, feats, labels, params, steps)
+    np.testing.assert_allclose(g["losses"], o["losses"], rtol=loss_tol, atol=loss_tol)
+    _, g0, _, _, _ = O.loss_and_grad(d, f64, labels, params.astype(np.float64))
+    solid = np.abs(g0) > 1e-3 * np.abs(g0).max()
+    assert solid.mean() > 0.5
+    scale = np.abs(o["params"]).max()
+    assert np.max(np.abs(g["params"] - o["params"])[solid]) <= tol * scale
+    # everywhere: never further apart than the walk of `steps` full-size steps in opposite directions
+    assert np.max(np.abs(g["params"] - o["params"])) <= 2.0 * steps * wl.lr * 1.01
+    assert rel_err(g["v"], o["s2"]) <= max(tol, 1e-3)
+    return g, o
+
+
+def test_adam_tiny_f32():
+    wl = WL.WORKLOADS["tiny"]
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    g, o = check_adam(wl, f, lab, p, 4, None, 1e-4, 1e-3)
+    # the step counter continues: two calls of two steps equal one call of four
+    a = run_gpu_adam(wl, f, lab, p, 2)
+    b = run_gpu_adam(wl, f, lab, a["params"], 2, t0=2, m=a["m"], v=a["v"])
+    np.testing.assert_array_equal(b["params"], g["params"])
+    np.testing.assert_array_equal(b["v"], g["v"])
+
+
+def test_adam_matrix_core_path():
+    wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3, lr=0.01)
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    check_adam(wl, f, lab, p, 3, True, 2e-3, 2e-2)
