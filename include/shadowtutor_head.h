@@ -155,6 +155,41 @@ int st_partial_distill(const st_head_desc* desc, const void* features,
 int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_t n_classes,
             int32_t ignore_index, int64_t* confusion, double* miou, void* stream);
 
+/* ---- scheduling arithmetic around the training step (host only, no GPU work) ------------- */
+
+/* Key-frame striding, Algorithm 2: the ratio of the next stride to the current one is linear in
+ * the metric through (0, 0) and (THRESHOLD, 1) below the threshold, and through (THRESHOLD, 1)
+ * and (1, 2) from it on; the new stride is clamped to [min_stride, max_stride].
+ * Returns NaN unless 0 < threshold < 1, min_stride <= max_stride and the inputs are numbers. */
+double st_next_stride(double stride, double metric, double threshold, double min_stride, double max_stride);
+
+/* Quantities of Section 4.4 (Table 1's notation).  Times in seconds; s_net in any unit of data
+ * (the traffic bounds come out in that unit per second). */
+typedef struct st_schedule_params {
+    double t_si;        /* latency of student inference                          */
+    double t_sd;        /* latency of one distillation step                      */
+    double t_ti;        /* latency of teacher inference                          */
+    double t_net;       /* network latency associated with one key frame         */
+    double s_net;       /* networked data size associated with one key frame     */
+    double min_stride, max_stride, max_updates;
+} st_schedule_params;
+
+typedef struct st_schedule_bounds_out {
+    double t_c_lower, t_c_upper;                /* Eq. 2  */
+    double traffic_lower, traffic_upper;        /* Eqs. 8, 12 */
+    double throughput_lower, throughput_upper;  /* Eqs. 13, 14 (frames per second) */
+} st_schedule_bounds_out;
+
+/* Fills *out from *p.  ST_ERR_NULL / ST_ERR_ARG (negative or non-finite entries, min_stride <= 0,
+ * max_stride < min_stride, t_si <= 0). */
+int st_schedule_bounds(const st_schedule_params* p, st_schedule_bounds_out* out);
+
+/* Eq. 3: total time to process n_frames with n_key_frames key frames, n_distill_steps
+ * distillation steps and t_c seconds for the min_stride frames after each key frame.
+ * (Eq. 4 is n_key_frames * s_net over it, Eq. 9 n_frames over it.)  NaN if p is NULL. */
+double st_schedule_total_time(const st_schedule_params* p, double n_frames, double n_distill_steps,
+                              double n_key_frames, double t_c);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* st_strerror(int status);
 

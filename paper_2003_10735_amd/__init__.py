@@ -24,7 +24,8 @@ ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 
 EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
            "st_miou", "st_strerror", "st_last_hip_error", "st_version",
-           "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read"]
+           "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read",
+           "st_next_stride", "st_schedule_bounds", "st_schedule_total_time"]
 
 
 class StHeadDesc(C.Structure):
@@ -37,6 +38,16 @@ class StDistillOpts(C.Structure):
                 ("strict_break", C.c_int32), ("return_best", C.c_int32),
                 ("optimizer", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t0", C.c_int32)]
+
+
+class StScheduleParams(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("t_si", "t_sd", "t_ti", "t_net", "s_net", "min_stride",
+                                          "max_stride", "max_updates")]
+
+
+class StScheduleBounds(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("t_c_lower", "t_c_upper", "traffic_lower", "traffic_upper",
+                                          "throughput_lower", "throughput_upper")]
 
 
 class StDistillResult(C.Structure):
@@ -93,6 +104,12 @@ def lib():
         L.st_version.restype = C.c_char_p
         L.st_get_workspace_layout.restype = C.c_int
         L.st_get_workspace_layout.argtypes = [C.POINTER(StHeadDesc), C.POINTER(StWorkspaceLayout)]
+        L.st_next_stride.restype = C.c_double
+        L.st_next_stride.argtypes = [C.c_double] * 5
+        L.st_schedule_bounds.restype = C.c_int
+        L.st_schedule_bounds.argtypes = [C.POINTER(StScheduleParams), C.POINTER(StScheduleBounds)]
+        L.st_schedule_total_time.restype = C.c_double
+        L.st_schedule_total_time.argtypes = [C.POINTER(StScheduleParams)] + [C.c_double] * 4
         L.st_profile_enable.argtypes = [C.c_int]
         L.st_profile_filter.argtypes = [C.c_char_p]
         L.st_profile_read.restype = C.c_int
@@ -239,6 +256,23 @@ def st_profile_read(max_stats: int = 64) -> dict:
     if n < 0:
         raise StError(n, "st_profile_read")
     return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms)) for i in range(n)}
+
+
+def st_next_stride(stride, metric, threshold, min_stride, max_stride) -> float:
+    return float(lib().st_next_stride(stride, metric, threshold, min_stride, max_stride))
+
+
+def st_schedule_bounds(**params) -> dict:
+    """Keyword arguments: the fields of st_schedule_params.  Returns the six bounds."""
+    p = StScheduleParams(**{k: float(v) for k, v in params.items()})
+    out = StScheduleBounds()
+    _check(lib().st_schedule_bounds(C.byref(p), C.byref(out)), "st_schedule_bounds")
+    return {k: getattr(out, k) for k, _ in StScheduleBounds._fields_}
+
+
+def st_schedule_total_time(n_frames, n_distill_steps, n_key_frames, t_c, **params) -> float:
+    p = StScheduleParams(**{k: float(v) for k, v in params.items()})
+    return float(lib().st_schedule_total_time(C.byref(p), n_frames, n_distill_steps, n_key_frames, t_c))
 
 
 def st_version() -> str:

@@ -83,3 +83,59 @@ def test_clip_720p_three_frames_bf16():
     assert o["key_frames"][0], "an untrained head starts below the threshold"
     agreed = compare(wl, g, o, thr, 1e-2)
     assert agreed >= 1
+
+
+def oracle_clip_strided(wl, frames, params, threshold, min_stride, max_stride, delay):
+    """Algorithms 3 and 4 in one loop, every computation by the oracle."""
+    from oracle import schedule as S
+    d = O.desc_of(wl)
+    client = params.astype(np.float64).copy()
+    server = client.copy()
+    stride, step, updated, pending = float(min_stride), float(min_stride), True, None
+    scores, key, updates, strides = [], [], [], []
+    for f, lab in frames:
+        f64 = WL.features_as_f64(wl, f)
+        is_key = step >= stride
+        if is_key:
+            r = O.train(d, f64, lab, server, wl.steps, wl.lr, threshold, strict_break=True)
+            server, pending = r["params"], r["best_metric"]
+            step, updated = 0.0, False
+            updates.append(r["updates"])
+        else:
+            updates.append(0)
+        key.append(is_key)
+        _, pred = O.head_forward(d, f64, client)
+        scores.append(float(np.mean([O.miou(O.confusion(pred[i], lab[i], wl.n_classes, wl.ignore_index))[0]
+                                     for i in range(wl.n)])))
+        step += 1.0
+        if not updated and step >= delay:
+            client = server.copy()
+            stride = S.next_stride(stride, pending, threshold, min_stride, max_stride)
+            updated = True
+        strides.append(stride)
+    return dict(scores=scores, key_frames=key, updates=updates, strides=strides)
+
+
+@pytest.mark.parametrize("delay", [1, 2])
+def test_strided_clip_with_delayed_updates(delay):
+    import torch
+    import paper_2003_10735_amd as st
+    from paper_2003_10735_amd.clip import run_clip_strided
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], name="clip-strided", c_in=8, h=8, w=10, c1=8, c2=8, n_classes=3,
+                          n_sites=5, label_seed=5, steps=8, lr=0.05,
+                          extra={"frames": 12, "drift": 0.05, "shift_px": 2, "threshold": 0.7})
+    thr, mn, mx = 0.7, 2.0, 6.0
+    frames = list(WL.clip_frames(wl, learnable=True))
+    p = WL.make_head_params(wl)
+    o = oracle_clip_strided(wl, frames, p, thr, mn, mx, delay)
+    pt = torch.from_numpy(p.astype(np.float32)).cuda()
+    dev = ((to_dev_features(wl, f), torch.from_numpy(lab).cuda()) for f, lab in frames)
+    g = run_clip_strided(st.HeadDesc.of(wl), dev, pt, threshold=thr, max_updates=wl.steps, lr=wl.lr,
+                         min_stride=mn, max_stride=mx, delay=delay)
+    assert o["key_frames"][0] and sum(o["key_frames"]) >= 3 and not all(o["key_frames"])
+    assert g["key_frames"] == o["key_frames"], (g["strides"], o["strides"])
+    assert g["updates"] == o["updates"]
+    np.testing.assert_allclose(g["strides"], o["strides"], atol=2e-2)
+    np.testing.assert_allclose(g["scores"], o["scores"], atol=5e-3)
+    # the key frame itself is still predicted by the old head: its score is the untrained one
+    assert g["scores"][0] < 0.3
