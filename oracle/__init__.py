@@ -19,7 +19,8 @@ _LIB = None
 class Desc(C.Structure):
     _fields_ = [("n", C.c_int32), ("c_in", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
                 ("c1", C.c_int32), ("c2", C.c_int32), ("n_classes", C.c_int32),
-                ("ignore_index", C.c_int32), ("bf16_operands", C.c_int32)]
+                ("ignore_index", C.c_int32), ("bf16_operands", C.c_int32),
+                ("pixel_weights", C.c_void_p)]
 
 
 def lib():
@@ -30,6 +31,7 @@ def lib():
             _build.build(force=True)
         _LIB = C.CDLL(path)
         _LIB.sto_softmax_ce.restype = C.c_double
+        _LIB.sto_softmax_ce_w.restype = C.c_double
         _LIB.sto_loss_and_grad.restype = C.c_double
         _LIB.sto_num_params.restype = C.c_int64
         _LIB.sto_miou.restype = C.c_int
@@ -55,7 +57,18 @@ def _f64(a):
 
 
 def desc(n, c_in, h, w, c1, c2, n_classes, ignore_index=-1, bf16_operands=False) -> Desc:
-    return Desc(n, c_in, h, w, c1, c2, n_classes, ignore_index, 1 if bf16_operands else 0)
+    return Desc(n, c_in, h, w, c1, c2, n_classes, ignore_index, 1 if bf16_operands else 0, None)
+
+
+def with_pixel_weights(d: Desc, weights) -> Desc:
+    """A copy of the descriptor whose loss scales pixel p by weights[p] (uint8 [n,8h,8w]).  The
+    returned descriptor keeps the array alive."""
+    w = np.ascontiguousarray(weights, dtype=np.uint8)
+    assert w.shape == (d.n, 8 * d.h, 8 * d.w)
+    out = Desc(d.n, d.c_in, d.h, d.w, d.c1, d.c2, d.n_classes, d.ignore_index, d.bf16_operands,
+               w.ctypes.data_as(C.c_void_p))
+    out._keep = w
+    return out
 
 
 def desc_of(wl, bf16_operands: bool | None = None) -> Desc:
@@ -139,14 +152,16 @@ def predict_from_logits(z_f32):
     return argmax_f32(upsample8_f32(z_f32))
 
 
-def softmax_ce(Z, labels, ignore_index=-1, want_grad=True):
+def softmax_ce(Z, labels, ignore_index=-1, want_grad=True, weights=None):
+    """Returns (loss, gradient, sum of the weights of the valid pixels)."""
     Z = _f64(Z)
     n, c, H, W = Z.shape
     labels = np.ascontiguousarray(labels, dtype=np.int32)
     G = np.empty_like(Z) if want_grad else None
     nv = C.c_int64(0)
-    loss = lib().sto_softmax_ce(_d(Z), _p(labels, C.c_int32), _d(G), n, c, C.c_int64(H * W),
-                                ignore_index, C.byref(nv))
+    wts = np.ascontiguousarray(weights, dtype=np.uint8) if weights is not None else None
+    loss = lib().sto_softmax_ce_w(_d(Z), _p(labels, C.c_int32), _p(wts, C.c_uint8), _d(G), n, c,
+                                  C.c_int64(H * W), ignore_index, C.byref(nv))
     return float(loss), G, int(nv.value)
 
 

@@ -304,17 +304,22 @@ static int label_valid(int32_t y, int C, int ignore_index)
     return y != ignore_index && y >= 0 && y < C;
 }
 
-/* Mean per-pixel cross-entropy of softmax(Z[:,p]) against the hard label y_p over the valid
- * pixels of all n frames (ComputeLoss of Algorithm 1; Section 5.2 without the x5 weighting),
- * and, when G != NULL, its derivative G[n,c,p] = (softmax_c - [c == y_p]) / N_valid (zero on
- * ignored pixels).  Returns the loss; *n_valid_out receives N_valid.  N_valid == 0 gives 0. */
-double sto_softmax_ce(const double* Z, const int32_t* labels, double* G,
-                      int n, int C, int64_t P, int ignore_index, int64_t* n_valid_out)
+/* Per-pixel cross-entropy of softmax(Z[:,p]) against the hard label y_p over the valid pixels
+ * of all n frames (ComputeLoss of Algorithm 1), each pixel scaled by an integer weight w_p
+ * (Section 5.2: the loss of pixels near and within non-background objects is scaled by 5; which
+ * pixels those are is the caller's business, it passes the map; weights == NULL means 1
+ * everywhere).  The loss is the weighted mean  sum_p w_p CE_p / sum_p w_p  over the valid
+ * pixels, and, when G != NULL, G[n,c,p] = w_p (softmax_c - [c == y_p]) / sum w is its
+ * derivative (zero on ignored pixels).  Returns the loss; *w_sum_out receives sum w (the
+ * number of valid pixels when unweighted).  sum w == 0 gives 0. */
+double sto_softmax_ce_w(const double* Z, const int32_t* labels, const uint8_t* weights, double* G,
+                        int n, int C, int64_t P, int ignore_index, int64_t* w_sum_out)
 {
-    int64_t n_valid = 0;
-    for (int64_t q = 0; q < (int64_t)n * P; ++q) n_valid += label_valid(labels[q], C, ignore_index);
-    if (n_valid_out) *n_valid_out = n_valid;
-    const double inv = n_valid > 0 ? 1.0 / (double)n_valid : 0.0;
+    int64_t w_sum = 0;
+    for (int64_t q = 0; q < (int64_t)n * P; ++q)
+        if (label_valid(labels[q], C, ignore_index)) w_sum += weights ? weights[q] : 1;
+    if (w_sum_out) *w_sum_out = w_sum;
+    const double inv = w_sum > 0 ? 1.0 / (double)w_sum : 0.0;
 
     /* one partial sum per row-sized chunk, then a serial sum: independent of thread count */
     const int64_t chunk = 1024;
@@ -335,15 +340,16 @@ double sto_softmax_ce(const double* Z, const int32_t* labels, double* G,
                 if (gb) for (int c = 0; c < C; ++c) gb[(size_t)c * P] = 0.0;
                 continue;
             }
+            const double wp = weights ? (double)weights[q] : 1.0;
             double m = zb[0];
             for (int c = 1; c < C; ++c) if (zb[(size_t)c * P] > m) m = zb[(size_t)c * P];
             double s = 0.0;
             for (int c = 0; c < C; ++c) s += exp(zb[(size_t)c * P] - m);
             const double lse = m + log(s);
-            acc += lse - zb[(size_t)y * P];
+            acc += wp * (lse - zb[(size_t)y * P]);
             if (gb)
                 for (int c = 0; c < C; ++c)
-                    gb[(size_t)c * P] = (exp(zb[(size_t)c * P] - lse) - (c == y ? 1.0 : 0.0)) * inv;
+                    gb[(size_t)c * P] = wp * (exp(zb[(size_t)c * P] - lse) - (c == y ? 1.0 : 0.0)) * inv;
         }
         part[ch] = acc;
     }
@@ -351,6 +357,13 @@ double sto_softmax_ce(const double* Z, const int32_t* labels, double* G,
     for (int64_t ch = 0; ch < n_chunks; ++ch) loss += part[ch];
     free(part);
     return loss * inv;
+}
+
+/* the unweighted mean (every weight 1) */
+double sto_softmax_ce(const double* Z, const int32_t* labels, double* G,
+                      int n, int C, int64_t P, int ignore_index, int64_t* n_valid_out)
+{
+    return sto_softmax_ce_w(Z, labels, NULL, G, n, C, P, ignore_index, n_valid_out);
 }
 
 /* conf[y, pred] += 1 over valid pixels (row = label, column = prediction). */
@@ -433,6 +446,7 @@ typedef struct {
     int32_t c1, c2, n_classes;
     int32_t ignore_index;  /* -1: none */
     int32_t bf16_operands; /* 1: round every convolution operand to bfloat16 first */
+    const uint8_t* pixel_weights; /* [n, 8h, 8w] loss weight of every pixel, or NULL: all 1 */
 } sto_desc;
 
 typedef struct {
@@ -556,7 +570,7 @@ double sto_loss_and_grad(const sto_desc* d, const double* features, const int32_
     double* Z = dalloc(nZ);
     double* G = grad ? dalloc(nZ) : NULL;
     sto_upsample8(s.z, Z, d->n * C, d->h, d->w);
-    const double loss = sto_softmax_ce(Z, labels, G, d->n, C, P, d->ignore_index, NULL);
+    const double loss = sto_softmax_ce_w(Z, labels, d->pixel_weights, G, d->n, C, P, d->ignore_index, NULL);
     free(Z);
 
     if (grad) {

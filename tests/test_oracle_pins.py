@@ -357,3 +357,79 @@ def test_adam_loop_equals_manual_steps():
     a = O.partial_distill(d, f, lab, p0, 3, 0.01, momentum=0.9)
     b = O.partial_distill_opt(d, f, lab, p0, 3, O.Optim(0, 0.01, 0.9, 0, 0, 0, 0))
     np.testing.assert_array_equal(a["params"], b["params"])
+
+
+# ------------------------------------------------------------------ weighted cross-entropy (Section 5.2)
+def test_weighted_ce_matches_independent_library():
+    """sum_p w_p CE_p / sum_p w_p and its gradient against CPU PyTorch (per-pixel losses from
+    F.cross_entropy, weighting and autograd by torch), with ignored pixels."""
+    rng = np.random.default_rng(21)
+    n, Cn, H, W = 2, 5, 8, 16
+    Z = rng.standard_normal((n, Cn, H, W)) * 3
+    lab = rng.integers(0, Cn, size=(n, H, W)).astype(np.int32)
+    lab[rng.random(lab.shape) < 0.1] = 255
+    wts = rng.choice([1, 5], size=(n, H, W)).astype(np.uint8)
+    loss, G, wsum = O.softmax_ce(Z, lab, ignore_index=255, weights=wts)
+    zt = torch.tensor(Z, dtype=torch.float64, requires_grad=True)
+    lt = torch.tensor(np.where(lab == 255, -100, lab).astype(np.int64))
+    per = F.cross_entropy(zt, lt, ignore_index=-100, reduction="none")
+    wt = torch.tensor(wts.astype(np.float64)) * (lt != -100)
+    ref = (per * wt).sum() / wt.sum()
+    ref.backward()
+    assert wsum == int(wt.sum().item())
+    assert abs(loss - ref.item()) < 1e-12
+    np.testing.assert_allclose(G, zt.grad.numpy(), rtol=0, atol=1e-14)
+
+
+def test_weighted_ce_special_cases():
+    rng = np.random.default_rng(22)
+    Z = rng.standard_normal((1, 4, 8, 8))
+    lab = rng.integers(0, 4, size=(1, 8, 8)).astype(np.int32)
+    base, G0, n0 = O.softmax_ce(Z, lab)
+    # all weights 1: the unweighted mean; a constant weight changes nothing either
+    l1, G1, s1 = O.softmax_ce(Z, lab, weights=np.ones((1, 8, 8), np.uint8))
+    l5, G5, s5 = O.softmax_ce(Z, lab, weights=np.full((1, 8, 8), 5, np.uint8))
+    assert l1 == base and s1 == n0 and s5 == 5 * n0
+    np.testing.assert_array_equal(G1, G0)
+    np.testing.assert_allclose(G5, G0, rtol=1e-15, atol=1e-18)
+    assert abs(l5 - base) < 1e-15
+    # weight 0 removes a pixel exactly like the ignore label does
+    w0 = np.ones((1, 8, 8), np.uint8); w0[0, 3, 4] = 0
+    lab_ign = lab.copy(); lab_ign[0, 3, 4] = 255
+    la, Ga, _ = O.softmax_ce(Z, lab, weights=w0)
+    lb, Gb, _ = O.softmax_ce(Z, lab_ign, ignore_index=255)
+    assert abs(la - lb) < 1e-15
+    np.testing.assert_allclose(Ga, Gb, rtol=0, atol=1e-17)
+    # uniform logits: every pixel's loss is ln C, so is any weighted mean of them
+    lu, _, _ = O.softmax_ce(np.zeros((1, 4, 8, 8)), lab, weights=rng.choice([1, 5], size=(1, 8, 8)).astype(np.uint8))
+    assert abs(lu - math.log(4)) < 1e-12
+
+
+def test_weighted_loss_gradient_by_finite_differences():
+    """The whole head's loss with pixel weights: analytic parameter gradient against central
+    differences (the weights enter the backward pass through d loss / d logits only)."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=3, h=3, w=4, c1=4, c2=3, n_classes=3, n_sites=4)
+    lab = WL.make_labels(wl)
+    wts = WL.object_weight_map(lab, radius=2)
+    assert set(np.unique(wts)) <= {1, 5} and (wts == 5).any()
+    d = O.with_pixel_weights(O.desc_of(wl), wts)
+    f = WL.features_as_f64(wl, WL.make_features(wl))
+    p = WL.make_head_params(wl).astype(np.float64)
+    p += np.random.default_rng(5).standard_normal(p.size) * 0.05      # biases away from zero
+    loss, grad, _, _, _ = O.loss_and_grad(d, f, lab, p)
+    loss_plain, _, _, _, _ = O.loss_and_grad(O.desc_of(wl), f, lab, p)
+    assert loss != loss_plain
+    rng = np.random.default_rng(6)
+    for j in rng.choice(p.size, size=40, replace=False):
+        e = np.zeros_like(p); e[j] = 1e-6
+        lp = O.loss_and_grad(d, f, lab, p + e, want_grad=False)[0]
+        lm = O.loss_and_grad(d, f, lab, p - e, want_grad=False)[0]
+        assert abs((lp - lm) / 2e-6 - grad[j]) < 1e-7 + 1e-5 * abs(grad[j]), j
+
+
+def test_object_weight_map_is_a_square_dilation():
+    lab = np.zeros((1, 9, 9), np.int32)
+    lab[0, 4, 4] = 3
+    w = WL.object_weight_map(lab, radius=2)
+    ref = np.ones((9, 9), np.uint8); ref[2:7, 2:7] = 5
+    np.testing.assert_array_equal(w[0], ref)

@@ -167,6 +167,20 @@ def make_labels(wl: Workload, frame_shift: int = 0) -> np.ndarray:
     return lab
 
 
+def object_weight_map(labels: np.ndarray, radius: int = 4, factor: int = 5, background: int = 0) -> np.ndarray:
+    """Per-pixel loss weights [n, H, W] uint8: `factor` on every pixel within `radius` pixels
+    (Chebyshev distance) of a pixel whose label is a non-background class, 1 elsewhere.  The
+    radius of "near" is not given in the paper: it is an input-recipe choice here."""
+    obj = (labels != background) & (labels >= 0) & (labels < 255)
+    near = obj.copy()
+    for _ in range(radius):       # one-pixel square dilation, `radius` times
+        g = near.copy()
+        g[:, 1:, :] |= near[:, :-1, :]; g[:, :-1, :] |= near[:, 1:, :]
+        near = g.copy()
+        near[:, :, 1:] |= g[:, :, :-1]; near[:, :, :-1] |= g[:, :, 1:]
+    return np.where(near, factor, 1).astype(np.uint8)
+
+
 # --------------------------------------------------------------------------- head init
 def param_slices(wl: Workload) -> dict:
     """Offsets of W1 (OIHW), b1, W2, b2, W3, b3 inside the flat parameter vector."""
