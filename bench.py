@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="720p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--weighted-loss", action="store_true",
+                    help="scale the loss of pixels within 4 px of a non-background (class 0) label by 5 "
+                         "(Section 5.2 of the paper); default: unweighted, the headline configuration")
     ap.add_argument("--optimizer", choices=("sgd", "adam"), default="sgd",
                     help="sgd: the workload's optimiser (the headline configuration); adam: the "
                          "paper's optimiser (Section 5.2) with beta 0.9 / 0.999, eps 1e-8, state reset per key frame")
@@ -140,6 +143,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     use_adam = args.optimizer == "adam"
+    pw = torch.from_numpy(WL.object_weight_map(labels, radius=4)).cuda() if args.weighted_loss else None
     adam = dict(m=torch.zeros_like(p), v=torch.zeros_like(p), t0=0) if use_adam else None
 
     def one_call():
@@ -150,10 +154,11 @@ def main():
             adam["m"].zero_()
             adam["v"].zero_()
             st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, adam=adam, losses=losses, mious=mious,
-                                  confusion=conf, workspace=ws, stream=stream)
+                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw)
             return
         st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
-                              losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream)
+                              losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream,
+                              pixel_weights=pw)
 
     for _ in range(args.warmup):
         one_call()
@@ -244,7 +249,7 @@ def main():
         "config": {"workload": f"{wl.name}: features [{wl.n},{wl.c_in},{wl.h},{wl.w}] {wl.feat_dtype}, head "
                                f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, "
                                f"{wl.steps} {'Adam' if args.optimizer == 'adam' else 'SGD'} steps per key frame (one bench step = one key frame)",
-                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer},
+                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss)},
         "key_frames_per_s": round(args.steps / elapsed, 3),
         "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
         "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],

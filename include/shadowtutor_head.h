@@ -101,6 +101,12 @@ typedef struct st_distill_opts {
     float* adam_m;        /* in/out, st_num_params floats each, same order as head_params;   */
     float* adam_v;        /* required with ST_OPTIM_ADAM (zero them before the first step)   */
     int32_t adam_t0;      /* optimiser steps already taken on this state (>= 0)              */
+    /* Loss weighting (Section 5.2: the cross-entropy of pixels near and within non-background
+     * objects is scaled by 5).  DEVICE pointer to one uint8 weight per pixel, [n, 8h, 8w], or NULL
+     * for weight 1 everywhere.  Which pixels count as "near" is the caller's decision.  The loss
+     * is the weighted mean  sum w_p CE_p / sum w_p  over the valid pixels; the metric ignores
+     * the weights. */
+    const uint8_t* pixel_weights;
 } st_distill_opts;
 enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 

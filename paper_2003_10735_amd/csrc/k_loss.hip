@@ -69,12 +69,12 @@ __device__ __forceinline__ float tap_weight(int X, int cell, int len)
 // cells (256 + 2 x 4 columns) adds its 16 rows' y-weights into a per-column table in LDS
 // (the class index is data, so the table cannot live in registers); then one thread per
 // (class, cell) applies the x-weights of the 16 columns under the cell.  All terms are
-// multiples of 1/256 and the sums stay below 2^8, so the result is exact in float32 and does
-// not depend on the order of additions.
+// multiples of 1/256 and the sums stay below 2^8 -- below 2^16 with 8-bit pixel weights -- so the
+// result is exact in float32 and does not depend on the order of additions.
 template <int CP>
 __global__ void __launch_bounds__(256)
-k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, unsigned long long* __restrict__ n_valid,
-                Geo g)
+k_label_adjoint(const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, float* __restrict__ T,
+                unsigned long long* __restrict__ n_valid, Geo g)
 {
     constexpr int NCOL = LOSS_TX * 8 + 8;
     __shared__ float colsum[CP][NCOL + 1];
@@ -84,26 +84,32 @@ k_label_adjoint(const int32_t* __restrict__ labels, float* __restrict__ T, unsig
     const int tx = blockIdx.x % tiles_x, cy = (blockIdx.x / tiles_x) % g.h, img = blockIdx.x / (tiles_x * g.h);
     const int hw = g.h * g.w;
     const int32_t* lab = labels + (size_t)img * g.H * g.W;
+    const uint8_t* wm = wmap ? wmap + (size_t)img * g.H * g.W : nullptr;
     for (int i = tid; i < CP * (NCOL + 1); i += 256) (&colsum[0][0])[i] = 0.f;
     __syncthreads();
     const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
     const int Yt = 8 * cy - 4;                             // frame row of tent position 0
-    unsigned int cnt = 0;                                  // valid labels of this block's own 8 x 256 pixels
+    unsigned int cnt = 0;     // valid labels (their weights) of this block's own 8 x 256 pixels
     for (int col = tid; col < NCOL; col += 256) {
         const int X = X0 + col;
         const bool xin = X >= 0 && X < g.W;
         const int Xc = min(max(X, 0), g.W - 1);
         // the 16 rows under the tent: all loads first (clamped, so none depends on a branch)
         int ys[16];
+        unsigned int ws[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) ys[r] = lab[(size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc];
+        for (int r = 0; r < 16; ++r) {
+            const size_t at = (size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc;
+            ys[r] = lab[at];
+            ws[r] = wm ? wm[at] : 1u;
+        }
         const bool own_col = col >= 4 && col < NCOL - 4;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int Y = Yt + r, y = ys[r];
             if (xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C) {
-                colsum[y][col] += tap_weight(Y, cy, g.h);
-                if (own_col && r >= 4 && r < 12) ++cnt;
+                colsum[y][col] += (float)ws[r] * tap_weight(Y, cy, g.h);
+                if (own_col && r >= 4 && r < 12) cnt += ws[r];
             }
         }
     }
@@ -133,7 +139,7 @@ constexpr int LOSS_THREADS = 512;
 
 template <int CP, bool GRAD>
 __global__ void __launch_bounds__(LOSS_THREADS)
-k_loss(ZSrc zs, const int32_t* __restrict__ labels, const float* __restrict__ T,
+k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
        unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
 {
@@ -227,9 +233,15 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const float* __restrict__ T,
     const int Yb = qy * 8 + half * 4;    // first of this thread's four pixel rows
     // labels of this thread's 4 pixels, fetched before the barrier
     int lab4[4];
+    float w4[4] = {1.f, 1.f, 1.f, 1.f};      // loss weight of each pixel
     if (lab_img) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : -1;
+        if (wmap) {
+            const uint8_t* wm = wmap + (size_t)img * g.H * g.W;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w4[i] = col_ok ? (float)wm[(size_t)(Yb + i) * g.W + X] : 0.f;
+        }
     }
     if (zs.parts) {
 #pragma unroll
@@ -312,11 +324,11 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const float* __restrict__ T,
                 sum += Z[c];
             }
             if (valid) {
-                loss_acc += __builtin_fmaf(__builtin_amdgcn_logf(sum), 0.693147180559945309f, m);
+                loss_acc += w4[i] * __builtin_fmaf(__builtin_amdgcn_logf(sum), 0.693147180559945309f, m);
                 atomicAdd(&conf_l[y * C + best], 1u);
             }
             if (GRAD) {
-                const float rs = valid ? __builtin_amdgcn_rcpf(sum) : 0.f;
+                const float rs = valid ? w4[i] * __builtin_amdgcn_rcpf(sum) : 0.f;
                 const float wa = (1.f - fy) * rs, wb = fy * rs;
 #pragma unroll
                 for (int c = 0; c < CP; ++c) {
@@ -430,21 +442,22 @@ size_t loss_slot_floats(const Geo& g)
 int loss_blocks(const Geo& g) { return g.n * loss_tiling(g).tiles(); }
 
 template <int CP>
-static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T,
+static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* wmap,
+                        const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
                         const unsigned long long* n_valid, bool grad, bool assemble)
 {
     const LossTiling lt = loss_tiling(g);
     const int blocks = g.n * lt.tiles();
     if (grad) {
-        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, T, pred,
+        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred,
                   slots, loss_part, conf, g, lt);
         // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
         if (assemble)
             ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
                       dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
-        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, T, pred, slots,
+        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred, slots,
                   loss_part, conf, g, lt);
     }
 }
@@ -464,19 +477,21 @@ static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* lab
 
 // T = U^T (one-hot valid labels); once per call.  With n_valid (a cleared counter) the kernel also
 // counts the valid labels: every pixel belongs to the 8 x 256 pixels of exactly one block.
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsigned long long* n_valid)
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, const uint8_t* wmap, float* T,
+                   unsigned long long* n_valid)
 {
     const dim3 grid(g.n * g.h * ((g.w + LOSS_TX - 1) / LOSS_TX));
-#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, T, n_valid, g)
+#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, wmap, T, n_valid, g)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
 }
 
-void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T, uint8_t* pred,
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* wmap, const float* T,
+               uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble)
 {
-#define ST_CALL(CP) loss_launch<CP>(c, g, zs, labels, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
+#define ST_CALL(CP) loss_launch<CP>(c, g, zs, labels, wmap, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
 }

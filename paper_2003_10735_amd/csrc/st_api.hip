@@ -270,7 +270,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred || p.mfma)
-        loss_pass(c, p.g, z_source(p, ws, z), nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr,
+        loss_pass(c, p.g, z_source(p, ws, z), nullptr, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr,
                   false, false);
     return c.status;
 }
@@ -292,6 +292,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     double beta1 = 0.0, beta2 = 0.0;
     float adam_eps = 0.f;
     long long adam_t0 = 0;
+    const uint8_t* pixel_weights = opts ? opts->pixel_weights : nullptr;
     if (opts) {
         if (!isfinite(opts->momentum) || opts->momentum < 0.f || isnan(opts->threshold)) return ST_ERR_ARG;
         if (opts->optimizer != ST_OPTIM_SGD && opts->optimizer != ST_OPTIM_ADAM) return ST_ERR_ARG;
@@ -335,7 +336,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         permute_params(c, p, adam_v, (float*)(ws + p.vel2), 0);
     }
     update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
-    label_adjoint(c, g, teacher_labels, (float*)(ws + p.tadj), n_valid);   // also counts the valid labels
+    label_adjoint(c, g, teacher_labels, pixel_weights, (float*)(ws + p.tadj), n_valid);   // also sums the weights of the valid labels
 
     double best_metric = -1.0;
     std::vector<double> frame_metric;
@@ -344,7 +345,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
         forward(c, p, ws, z);
-        loss_pass(c, g, z_source(p, ws, z), teacher_labels, (const float*)(ws + p.tadj),
+        loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);

@@ -33,7 +33,8 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
 // k_loss.hip
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, float* T, unsigned long long* n_valid);
+void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, const uint8_t* pixel_weights, float* T,
+                   unsigned long long* n_valid);
 // Where the loss kernel finds the low-resolution logits: either the planar tensor [n, C, h, w], or
 // the shares the classifier-fused convolution left behind, [n_parts][padded position][32 classes],
 // to be added in ascending order together with the bias b3; in that case the kernel also writes
@@ -42,7 +43,8 @@ struct ZSrc {
     const float* planar;
     const float* parts; int n_parts; const float* b3; float* z_out;
 };
-void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const float* T, uint8_t* pred,
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* pixel_weights,
+               const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble);
 

@@ -52,3 +52,9 @@ def test_720p_adam_two_steps():
     wl = WL.WORKLOADS["720p"]
     f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
     check_adam(wl, f, lab, p, 2, True, 2e-3, 2e-2)
+
+
+def test_720p_weighted_loss_two_steps():
+    """Per-pixel loss weights (Section 5.2) at the benchmark's shape."""
+    from test_gpu_parity import check_weighted
+    check_weighted(WL.WORKLOADS["720p"], 2, True, 5e-4)

@@ -263,3 +263,50 @@ def test_adam_matrix_core_path():
     wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3, lr=0.01)
     f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
     check_adam(wl, f, lab, p, 3, True, 2e-3, 2e-2)
+
+
+# ------------------------------------------------------------------ weighted cross-entropy (Section 5.2)
+def run_gpu_weighted(wl, feats, labels, params, wts, steps):
+    import torch
+    import paper_2003_10735_amd as st
+    from gpu_util import to_dev_features
+    desc = st.HeadDesc.of(wl)
+    p = torch.from_numpy(params.astype(np.float32)).cuda()
+    losses = torch.full((steps + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    mious = torch.full((steps + 1, wl.n), float("nan"), dtype=torch.float64, device="cuda")
+    st.st_partial_distill(desc, to_dev_features(wl, feats), torch.from_numpy(labels).cuda(), p, steps, wl.lr,
+                          losses=losses, mious=mious, pixel_weights=torch.from_numpy(wts).cuda())
+    torch.cuda.synchronize()
+    return dict(params=p.cpu().numpy(), losses=losses.cpu().numpy(), mious=mious.cpu().numpy())
+
+
+def check_weighted(wl, steps, bf16_operands, tol):
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    wts = WL.object_weight_map(lab, radius=4)
+    assert (wts == 5).any() and (wts == 1).any()
+    d = O.with_pixel_weights(O.desc_of(wl, bf16_operands), wts)
+    o = O.partial_distill_opt(d, WL.features_as_f64(wl, f), lab, p.astype(np.float64), steps,
+                              O.Optim(0, wl.lr, 0.0, 0, 0, 0, 0))
+    g = run_gpu_weighted(wl, f, lab, p, wts, steps)
+    plain = run_gpu(wl, f, lab, p, steps=steps)
+    assert abs(g["losses"][0] - plain["losses"][0]) > 1e-3        # the weights do change the loss
+    assert rel_err(g["losses"], o["losses"]) < tol
+    assert rel_err(g["params"], o["params"]) < tol
+    assert rel_err(g["params"] - p, o["params"] - p) < max(30 * tol, 1e-3)
+    np.testing.assert_allclose(g["mious"], o["mious"], atol=5e-3)
+
+
+def test_weighted_loss_tiny_f32():
+    # class 0 plays the background
+    check_weighted(WL.small_variant(WL.WORKLOADS["tiny"], n_sites=6), 4, None, 1e-4)
+
+
+def test_weighted_loss_ragged_with_ignore_f32():
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=7, w=37, c1=8, c2=8, n_classes=5, n_sites=9,
+                          ignore_index=255, ignore_fraction=0.1, steps=2)
+    check_weighted(wl, 2, None, 1e-4)
+
+
+def test_weighted_loss_matrix_core_path():
+    wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3)
+    check_weighted(wl, 3, True, 5e-4)
