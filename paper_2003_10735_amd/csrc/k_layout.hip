@@ -5,22 +5,46 @@
 
 namespace st {
 
-__global__ void __launch_bounds__(256) k_zero16(uint4* p, size_t n16)
+// Clears a list of regions in one launch: region r owns blocks [first[r], first[r + 1]), each
+// block a fixed run of ZERO_PER_BLOCK 16-byte words.
+constexpr int ZERO_PER_BLOCK = 256 * 8;
+
+__global__ void __launch_bounds__(256) k_zero_regions(ZeroList z)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    for (; i < n16; i += stride) p[i] = z;
+    int r = 0;
+    while (r + 1 < z.n && (int)blockIdx.x >= z.first[r + 1]) ++r;     // block-uniform, n is small
+    uint4* p = (uint4*)z.ptr[r];
+    const size_t base = (size_t)((int)blockIdx.x - z.first[r]) * ZERO_PER_BLOCK;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int k = 0; k < ZERO_PER_BLOCK / 256; ++k) {
+        const size_t i = base + (size_t)k * 256 + threadIdx.x;
+        if (i < z.n16[r]) p[i] = zero;
+    }
+}
+
+void ZeroList::add(void* p, size_t bytes)
+{
+    if (bytes == 0 || n >= MAX) { overflow = overflow || (bytes != 0); return; }
+    ptr[n] = p;
+    n16[n] = (bytes + 15) / 16;
+    first[n + 1] = first[n] + (int)((n16[n] + ZERO_PER_BLOCK - 1) / ZERO_PER_BLOCK);
+    ++n;
+}
+
+// all workspace regions are 16-byte aligned and padded to 16 bytes
+void zero_regions(Ctx& c, const ZeroList& z)
+{
+    if (z.overflow) { c.status = ST_ERR_SHAPE; return; }
+    if (z.n == 0) return;
+    ST_LAUNCH(c, "zero_fill", k_zero_regions, dim3(z.first[z.n]), dim3(256), 0, z);
 }
 
 void zero_bytes(Ctx& c, void* p, size_t bytes)
 {
-    // all workspace regions are 256-byte aligned and padded to 256 bytes
-    const size_t n16 = (bytes + 15) / 16;
-    if (n16 == 0) return;
-    int blocks = (int)((n16 + 255) / 256);
-    if (blocks > 2048) blocks = 2048;
-    ST_LAUNCH(c, "zero_fill", k_zero16, dim3(blocks), dim3(256), 0, (uint4*)p, n16);
+    ZeroList z;
+    z.add(p, bytes);
+    zero_regions(c, z);
 }
 
 // features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when

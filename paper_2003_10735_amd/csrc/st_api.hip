@@ -172,12 +172,45 @@ static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
-// clears everything a call relies on being zero: activation borders and the counters
+// Clears everything a call relies on being zero, in one launch: the counters, and of the
+// activation buffers
+//  * plain kernels: all of them (they write interior cells only and rely on zero borders);
+//  * matrix-core kernels: every position of a1, a2, da1, da2 and of their channel-major copies is
+//    rewritten (zeros on the border) by its producer in every pass, so only the guards in front
+//    of and behind the positions need clearing -- plus the features, whose packing kernel writes
+//    interior cells only.
 static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
 {
-    zero_bytes(c, ws + p.zero_begin, p.zero_end - p.zero_begin);
-    zero_bytes(c, ws + p.counters, 256);
-    zero_bytes(c, ws + p.conf, (size_t)p.g.n * p.g.C * p.g.C * 8);
+    ZeroList z;
+    const Geo& g = p.g;
+    const int n_regions = 2 + 8 + 2 * 2 * (g.c1 / 32 + g.c2 / 32) + 2;
+    if (!p.mfma || n_regions > ZeroList::MAX) {
+        z.add(ws + p.zero_begin, p.zero_end - p.zero_begin);
+    } else {
+        const size_t PP = (size_t)g.padded_positions(), G = (size_t)p.guard;
+        z.add(ws + p.feat - G * g.c_in * 2, (PP + 2 * G) * g.c_in * 2);
+        z.add(ws + p.featT, (size_t)g.c_in * p.PPT * 2);
+        const size_t pm[4] = {p.a1, p.a2, p.da1, p.da2};
+        const int pc[4] = {g.c1, g.c2, g.c1, g.c2};
+        for (int i = 0; i < 4; ++i) {
+            z.add(ws + pm[i] - G * pc[i] * 2, G * pc[i] * 2);
+            z.add(ws + pm[i] + PP * pc[i] * 2, G * pc[i] * 2);
+        }
+        // channel-major copies [C/32][PPT/8][32][8]: per channel block, the column groups of the
+        // head guard and those from the end of the positions (rounded down to a group) on
+        const size_t tm[4] = {p.a1T, p.a2T, p.da1T, p.da2T};
+        const size_t blk = (size_t)p.PPT * 32 * 2;                 // bytes of one channel block
+        const size_t head = G * 32 * 2;                            // guard columns (a multiple of 8)
+        const size_t tail_at = (G + PP / 8 * 8) * 32 * 2;
+        for (int i = 0; i < 4; ++i)
+            for (int b = 0; b < pc[i] / 32; ++b) {
+                z.add(ws + tm[i] + b * blk, head);
+                z.add(ws + tm[i] + b * blk + tail_at, blk - tail_at);
+            }
+    }
+    z.add(ws + p.counters, 256);
+    z.add(ws + p.conf, (size_t)g.n * g.C * g.C * 8);
+    zero_regions(c, z);
 }
 
 // one forward pass of the head: features (already packed) -> low-resolution logits.  The plain

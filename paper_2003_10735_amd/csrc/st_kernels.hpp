@@ -5,6 +5,14 @@
 namespace st {
 
 // k_layout.hip
+// regions to clear, each 16-byte aligned and padded to 16 bytes; one launch clears them all
+struct ZeroList {
+    static constexpr int MAX = 96;
+    void* ptr[MAX]; size_t n16[MAX]; int first[MAX + 1]; int n = 0; bool overflow = false;
+    ZeroList() { first[0] = 0; }
+    void add(void* p, size_t bytes);
+};
+void zero_regions(Ctx& c, const ZeroList& z);
 void zero_bytes(Ctx& c, void* p, size_t bytes);            // p 16-byte aligned, region padded to 16
 void zero_u64(Ctx& c, unsigned long long* p, size_t n);
 void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, char* ws);
