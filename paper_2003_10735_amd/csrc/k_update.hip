@@ -34,6 +34,9 @@ struct UpdateArgs {
     float lr, mu;
     int adam; AdamStep ad;   // adam != 0: vel = first moment m, vel2 = second moment v
     int do_step;     // 0: only refresh the bfloat16 copies
+    // parameter hand-over riding along: with ext_in (do_step == 0) theta is first taken from the
+    // caller's vector (its OIHW order); with ext_out, nb_out more blocks copy theta out to it
+    const float* ext_in; float* ext_out; int nb_out;
     // role (2)
     const float* part3; int blocks3; size_t slot3; int C;
     // block ranges; vec: role (1) handles four parameters per thread over [0, W3) and nb_tail
@@ -46,9 +49,24 @@ struct FinishArgs {
     int n, C; float* loss_out; double* miou_a; double* miou_b; long long* conf_out;
 };
 
+// index in the caller's vector (3x3 weights OIHW) of the internal parameter j ([o][kh][kw][i])
+__device__ __forceinline__ size_t external_index(const UpdateArgs& a, size_t j)
+{
+    if (j < a.po.b1) {
+        const size_t r = j - a.po.W1, i = r % a.c_in, tap = (r / a.c_in) % 9, o = r / ((size_t)a.c_in * 9);
+        return a.po.W1 + (o * a.c_in + i) * 9 + tap;
+    }
+    if (j >= a.po.W2 && j < a.po.b2) {
+        const size_t r = j - a.po.W2, i = r % a.c1, tap = (r / a.c1) % 9, o = r / ((size_t)a.c1 * 9);
+        return a.po.W2 + (o * a.c1 + i) * 9 + tap;
+    }
+    return j;
+}
+
 __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, float g)
 {
-    float w = a.theta[j];
+    float w = a.ext_in ? a.ext_in[external_index(a, j)] : a.theta[j];
+    if (a.ext_in) a.theta[j] = w;
     if (a.do_step) {
         if (a.adam) {
             const float m = __builtin_fmaf(a.ad.beta1, a.vel[j], a.ad.one_minus_beta1 * g);
@@ -89,7 +107,12 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
 // the four lie in the same block).
 __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32x4 g)
 {
-    f32x4 w = *(const f32x4*)(a.theta + j);
+    f32x4 w;
+    if (a.ext_in) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = a.ext_in[external_index(a, j + e)];
+        *(f32x4*)(a.theta + j) = w;
+    } else w = *(const f32x4*)(a.theta + j);
     if (a.do_step) {
         if (a.adam) {
             const f32x4 mo = *(const f32x4*)(a.vel + j), vo = *(const f32x4*)(a.vel2 + j);
@@ -248,8 +271,12 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
             for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
         }
         if (lane == 0) apply_update(a, a.po.W3 + k, acc);
-    } else {
+    } else if (b < a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish) {
         finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3);
+    } else {
+        // parameters back to the caller's order
+        const size_t j = (size_t)(b - a.nb_main - a.nb_tail - a.nb_l3 - a.nb_finish) * 256 + threadIdx.x;
+        if (j < a.po.total) a.ext_out[external_index(a, j)] = a.theta[j];
     }
 }
 
@@ -271,12 +298,13 @@ static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* 
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
 // finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out)
+              double* miou_out, long long* conf_out, const float* ext_in)
 {
     UpdateArgs a;
     a.theta = (float*)(ws + p.theta);
     a.vel = (float*)(ws + p.vel);
     a.vel2 = (float*)(ws + p.vel2);
+    a.ext_in = do_step ? nullptr : ext_in; a.ext_out = nullptr; a.nb_out = 0;
     a.adam = adam ? 1 : 0;
     if (adam) a.ad = *adam; else memset(&a.ad, 0, sizeof(a.ad));
     a.grad = (const float*)(ws + p.grad);
@@ -292,7 +320,7 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
     a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;
     a.part3 = (const float*)(ws + p.grad3);
     a.blocks3 = p.blocks3; a.slot3 = conv3_bwd_slot_floats(p.g); a.C = p.g.C;
-    const bool params = do_step || p.bf16;
+    const bool params = do_step || p.bf16 || a.ext_in;
     const bool l3 = params && p.mfma && do_step;
     // four parameters per thread when every block below W3 starts at a multiple of four and the
     // split copies keep 16-byte alignment
@@ -309,22 +337,33 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
     const int blocks = a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
     if (blocks == 0) return;
-    const char* name = do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
+    const char* name = a.ext_in ? "params_in+weights_to_bf16" : do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
     ST_LAUNCH(c, name, k_step_end, dim3(blocks), dim3(256), 0, a, f);
 }
 
-void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step)
+// takes the caller's parameters (OIHW order) into theta and refreshes the bfloat16 copies
+void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params)
 {
-    step_end(c, p, ws, lr, mu, nullptr, do_step, false, nullptr, nullptr, nullptr);
+    step_end(c, p, ws, 0.f, 0.f, nullptr, false, false, nullptr, nullptr, nullptr, head_params);
 }
 
-void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
+// bookkeeping of a pass without an update; with ext_out the same launch hands theta back to the
+// caller's vector (OIHW order)
+void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                 float* ext_out)
 {
     UpdateArgs a;
     memset(&a, 0, sizeof(a));
     a.nb_finish = p.g.n + 1;
+    if (ext_out) {
+        a.theta = (float*)(ws + p.theta);
+        a.po = p.po; a.c_in = p.g.c_in; a.c1 = p.g.c1; a.c2 = p.g.c2;
+        a.ext_out = ext_out;
+        a.nb_out = cdiv(p.po.total, 256);
+    }
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
-    ST_LAUNCH(c, "finish_pass", k_step_end, dim3(a.nb_finish), dim3(256), 0, a, f);
+    ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end, dim3(a.nb_finish + a.nb_out),
+              dim3(256), 0, a, f);
 }
 
 __global__ void k_miou_from_counts(const unsigned long long* conf, int C, double* out)

@@ -298,8 +298,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     Ctx c{as_stream(stream), ST_OK};
     prepare_workspace(c, p, ws);
     pack_features(c, p, features, desc->feat_dtype, ws);
-    permute_params(c, p, head_params, (float*)(ws + p.theta), 0);
-    update_params(c, p, ws, 0.f, 0.f, false);
+    load_params(c, p, ws, head_params);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred || p.mfma)
@@ -362,19 +361,19 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
 
     prepare_workspace(c, p, ws);
     pack_features(c, p, features, desc->feat_dtype, ws);
-    permute_params(c, p, head_params, theta, 0);
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
     if (use_adam) {
         permute_params(c, p, adam_m, (float*)(ws + p.vel), 0);
         permute_params(c, p, adam_v, (float*)(ws + p.vel2), 0);
     }
-    update_params(c, p, ws, 0.f, 0.f, false);   // bfloat16 copies of the initial weights
+    load_params(c, p, ws, head_params);   // theta in internal order + bfloat16 copies of the initial weights
     label_adjoint(c, g, teacher_labels, pixel_weights, (float*)(ws + p.tadj), n_valid);   // also sums the weights of the valid labels
 
     double best_metric = -1.0;
     std::vector<double> frame_metric;
     int taken = 0;
     bool have_best = false;
+    bool params_out_done = false;
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
         forward(c, p, ws, z);
@@ -389,7 +388,10 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         // along with the optimiser kernel at the end of the step; it needs a launch of its own
         // only when no update follows or when the host must see the metric first.
         const bool finish_now = last || early_exit;
-        if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out);
+        // (the last pass of the fixed-step form also hands the parameters back in the same launch)
+        const bool out_now = last && !early_exit;
+        if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr);
+        params_out_done = params_out_done || out_now;
         bool stop = last;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
@@ -434,7 +436,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     }
     if (early_exit && return_best && have_best)
         ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
-    permute_params(c, p, theta, head_params, 1);
+    if (!params_out_done) permute_params(c, p, theta, head_params, 1);
     if (mu != 0.f) permute_params(c, p, (const float*)(ws + p.vel), velocity, 1);
     if (use_adam) {
         permute_params(c, p, (const float*)(ws + p.vel), adam_m, 1);

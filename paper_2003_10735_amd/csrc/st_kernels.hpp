@@ -61,10 +61,11 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, cons
 //   theta <- theta - step_scale * m / (sqrt(v) * inv_sqrt_bc2 + eps),
 //   step_scale = lr / (1 - beta1^t),  inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
 struct AdamStep { float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_scale, inv_sqrt_bc2; };
-void update_params(Ctx& c, const Plan& p, char* ws, float lr, float mu, bool do_step);
+void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params);
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out);
-void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out);
+              double* miou_out, long long* conf_out, const float* ext_in = nullptr);
+void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                 float* ext_out = nullptr);
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
                         long long* conf, double* miou);
 
