@@ -310,3 +310,60 @@ def test_weighted_loss_ragged_with_ignore_f32():
 def test_weighted_loss_matrix_core_path():
     wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3)
     check_weighted(wl, 3, True, 5e-4)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+@pytest.mark.parametrize("mfma", [False, True])
+def test_all_labels_ignored(mfma):
+    """No valid pixel: loss 0, gradient 0 (the parameters do not move), mean IoU 0, empty counts."""
+    if mfma:
+        wl = WL.small_variant(WL.WORKLOADS["720p"], h=9, w=20, c_in=64, c1=32, c2=64, n_classes=6, steps=2,
+                              ignore_index=255)
+    else:
+        wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=5, w=7, c1=8, c2=8, n_classes=3, steps=2,
+                              ignore_index=255)
+    f, _, p = inputs(wl)
+    lab = np.full((wl.n, wl.H, wl.W), 255, dtype=np.int32)
+    g = run_gpu(wl, f, lab, p)
+    assert np.all(g["losses"] == 0.0) and np.all(g["mious"] == 0.0) and not g["conf"].any()
+    np.testing.assert_array_equal(g["params"], p.astype(np.float32))
+    o = run_oracle(wl, f, lab, p)
+    assert np.all(o["losses"] == 0.0)
+    np.testing.assert_array_equal(o["params"], p.astype(np.float64))
+    check_staged_bit_exact(wl, g, lab)
+
+
+def test_single_class_labels_and_maximum_class_count():
+    """Every pixel of one class (one row of the confusion matrix, mean IoU over one class), with
+    the largest class count the library takes (32)."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=9, c1=8, c2=16, n_classes=32, steps=2, lr=0.05)
+    f, _, p = inputs(wl)
+    lab = np.full((wl.n, wl.H, wl.W), 31, dtype=np.int32)
+    g = run_gpu(wl, f, lab, p)
+    o = run_oracle(wl, f, lab, p)
+    check_staged_bit_exact(wl, g, lab)
+    assert g["conf"][0, :31].sum() == 0 and g["conf"][0, 31].sum() == wl.H * wl.W
+    assert rel_err(g["losses"], o["losses"]) < 1e-4
+    assert rel_err(g["params"], o["params"]) < 1e-4
+    np.testing.assert_allclose(g["mious"], o["mious"], atol=2e-3)
+    assert g["losses"][-1] < g["losses"][0]       # a constant target is learnt quickly
+
+
+def test_workspace_reuse_across_calls_leaves_no_trace():
+    """A workspace that served another call (other data, other optimiser state) gives the same
+    result bit for bit as a fresh one: everything a call relies on is re-established by the call."""
+    import torch
+    import paper_2003_10735_amd as st
+    wl = WL.small_variant(WL.WORKLOADS["720p"], h=12, w=25, c_in=64, c1=64, c2=64, n_classes=5, steps=2)
+    f, lab, p = inputs(wl)
+    ws = st.new_workspace(st.HeadDesc.of(wl))
+    ws.fill_(0xFF)                                  # NaN patterns everywhere
+    a = run_gpu(wl, f, lab, p, workspace=ws)
+    f2, lab2 = WL.make_features(wl, seed=77), WL.make_labels(wl, frame_shift=13)
+    run_gpu(wl, f2, lab2, p, workspace=ws)          # dirty it with another problem
+    b = run_gpu(wl, f, lab, p, workspace=ws)
+    fresh = run_gpu(wl, f, lab, p)
+    for k in ("params", "losses", "mious", "conf", "pred"):
+        np.testing.assert_array_equal(a[k], fresh[k])
+        np.testing.assert_array_equal(b[k], fresh[k])
+    assert np.all(np.isfinite(a["losses"]))
