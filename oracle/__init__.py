@@ -33,6 +33,7 @@ def lib():
         _LIB.sto_softmax_ce.restype = C.c_double
         _LIB.sto_softmax_ce_w.restype = C.c_double
         _LIB.sto_loss_and_grad.restype = C.c_double
+        _LIB.sto_loss_and_grad_full.restype = C.c_double
         _LIB.sto_num_params.restype = C.c_int64
         _LIB.sto_miou.restype = C.c_int
         _LIB.sto_train.restype = C.c_int
@@ -231,6 +232,18 @@ def loss_and_grad(d: Desc, features, labels, params, want_grad=True, want_metric
     loss = lib().sto_loss_and_grad(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params),
                                    _d(grad), _p(pred, C.c_uint8), _p(conf, C.c_int64), _d(mi))
     return float(loss), grad, pred, conf, mi
+
+
+def feature_grad(d: Desc, features, labels, params):
+    """(loss, parameter gradient, d loss / d features [n,c_in,h,w]): the full backward pass, i.e.
+    what partial distillation saves plus what it keeps."""
+    features, params = _f64(features), _f64(params)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    grad = np.empty_like(params)
+    df = np.empty_like(features)
+    loss = lib().sto_loss_and_grad_full(C.byref(d), _d(features), _p(labels, C.c_int32), _d(params),
+                                        _d(grad), _d(df), None, None, None)
+    return float(loss), grad, df
 
 
 def partial_distill(d: Desc, features, labels, params, steps, lr, momentum=0.0, velocity=None):

@@ -539,9 +539,9 @@ void sto_head_forward(const sto_desc* d, const double* features, const double* p
  * parameters only: back-propagation stops at the first trainable layer, so no gradient with
  * respect to the features is ever formed (Section 4.2).  Also returns, when asked, the
  * prediction map, per-frame confusion matrices [n,C,C] and per-frame mean IoU [n]. */
-double sto_loss_and_grad(const sto_desc* d, const double* features, const int32_t* labels,
-                         const double* params, double* grad, uint8_t* pred_out,
-                         int64_t* conf_out, double* miou_out)
+double sto_loss_and_grad_full(const sto_desc* d, const double* features, const int32_t* labels,
+                              const double* params, double* grad, double* dfeatures, uint8_t* pred_out,
+                              int64_t* conf_out, double* miou_out)
 {
     const sto_offsets o = offsets(d);
     const int C = d->n_classes;
@@ -593,10 +593,20 @@ double sto_loss_and_grad(const sto_desc* d, const double* features, const int32_
         if (q) sto_round_bf16(da1, (int64_t)d->n * d->c1 * hw);
         /* layer 1 (3x3): parameters only; the features are frozen, nothing flows past here */
         sto_conv_wgrad(features, da1, grad + o.W1, grad + o.b1, d->n, d->c_in, d->c1, d->h, d->w, 3);
+        /* what partial distillation leaves out (Section 4.2): the gradient with respect to the
+         * features, which an unfrozen front part would need to continue the chain rule */
+        if (dfeatures) sto_conv_dgrad(da1, s.Wq1, dfeatures, d->n, d->c_in, d->c1, d->h, d->w, 3);
         free(da1); free(da2); free(gq); free(g);
     }
     free_state(&s);
     return loss;
+}
+
+double sto_loss_and_grad(const sto_desc* d, const double* features, const int32_t* labels,
+                         const double* params, double* grad, uint8_t* pred_out,
+                         int64_t* conf_out, double* miou_out)
+{
+    return sto_loss_and_grad_full(d, features, labels, params, grad, NULL, pred_out, conf_out, miou_out);
 }
 
 /* k optimiser steps with a fixed step count (Algorithm 1's loop body without the exits):

@@ -237,3 +237,41 @@ def test_training_loop_exits_follow_algorithm_1():
     r_ge = O.train(d, f, lab, p, max_updates=8, lr=0.05, threshold=m[j], strict_break=False)
     r_gt = O.train(d, f, lab, p, max_updates=8, lr=0.05, threshold=m[j], strict_break=True)
     assert r_ge["updates"] == j and r_gt["updates"] > j
+
+
+# ------------------------------------------------------------------ gradient with respect to the features
+def test_feature_gradient_against_autograd_and_finite_differences():
+    """d loss / d features (what an unfrozen front part would receive) against CPU PyTorch
+    autograd through the same head, and against central differences on a few entries."""
+    import torch
+    import torch.nn.functional as F
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], n=2, c_in=3, h=4, w=5, c1=4, c2=3, n_classes=3, n_sites=5,
+                          ignore_index=255, ignore_fraction=0.1)
+    d = O.desc_of(wl)
+    f = WL.features_as_f64(wl, WL.make_features(wl))
+    lab = WL.make_labels(wl)
+    p = WL.make_head_params(wl).astype(np.float64)
+    p += np.random.default_rng(3).standard_normal(p.size) * 0.05
+    loss, grad, df = O.feature_grad(d, f, lab, p)
+    loss2, grad2, _, _, _ = O.loss_and_grad(d, f, lab, p)
+    assert loss == loss2
+    np.testing.assert_array_equal(grad, grad2)
+    sl = WL.param_slices(wl)
+    ft = torch.tensor(f, requires_grad=True)
+    W1 = torch.tensor(p[sl["W1"]].reshape(wl.c1, wl.c_in, 3, 3)); b1 = torch.tensor(p[sl["b1"]])
+    W2 = torch.tensor(p[sl["W2"]].reshape(wl.c2, wl.c1, 3, 3)); b2 = torch.tensor(p[sl["b2"]])
+    W3 = torch.tensor(p[sl["W3"]].reshape(wl.n_classes, wl.c2, 1, 1)); b3 = torch.tensor(p[sl["b3"]])
+    z = F.conv2d(F.relu(F.conv2d(F.relu(F.conv2d(ft, W1, b1, padding=1)), W2, b2, padding=1)), W3, b3)
+    Z = F.interpolate(z, scale_factor=8, mode="bilinear", align_corners=False)
+    lt = torch.tensor(np.where(lab == 255, -100, lab).astype(np.int64))
+    ref = F.cross_entropy(Z, lt, ignore_index=-100)
+    ref.backward()
+    assert abs(loss - ref.item()) < 1e-12
+    np.testing.assert_allclose(df, ft.grad.numpy(), rtol=0, atol=1e-13)
+    rng = np.random.default_rng(4)
+    for _ in range(10):
+        idx = tuple(rng.integers(0, s) for s in f.shape)
+        e = np.zeros_like(f); e[idx] = 1e-6
+        lp = O.loss_and_grad(d, f + e, lab, p, want_grad=False)[0]
+        lm = O.loss_and_grad(d, f - e, lab, p, want_grad=False)[0]
+        assert abs((lp - lm) / 2e-6 - df[idx]) < 1e-7 + 1e-5 * abs(df[idx])
