@@ -70,7 +70,7 @@ def kernel_work(wl):
     conv3 = 2.0 * M * C * wl.c2
     return {
         "conv1_fwd": ("mfma", conv1), "conv12_wgrad": ("mfma", conv1 + conv2),
-        "conv2_fwd": ("mfma", conv2 + conv3), "conv2_dgrad": ("mfma", conv2),
+        "conv2_fwd": ("mfma", conv2 + conv3), "conv2_dgrad": ("mfma", conv2), "conv1_dgrad": ("mfma", conv1),
         "conv3_fwd": ("mfma", conv3), "conv3_wgrad": ("mfma", conv3), "conv3_dgrad": ("mfma", conv3),
         "conv3_bwd": ("mfma", 2 * conv3),
         "upsample_ce_grad": ("alu", 19.0 * C * P),
@@ -98,6 +98,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="720p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--full-backward", action="store_true",
+                    help="also compute d loss / d features in every backward pass (the data-gradient of "
+                         "layer 1 that partial distillation leaves out): the step an unfrozen front part would "
+                         "build on, for the partial-vs-full comparison; default: partial, the headline")
     ap.add_argument("--weighted-loss", action="store_true",
                     help="scale the loss of pixels within 4 px of a non-background (class 0) label by 5 "
                          "(Section 5.2 of the paper); default: unweighted, the headline configuration")
@@ -144,6 +148,7 @@ def main():
 
     use_adam = args.optimizer == "adam"
     pw = torch.from_numpy(WL.object_weight_map(labels, radius=4)).cuda() if args.weighted_loss else None
+    dfeat = torch.empty((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda") if args.full_backward else None
     adam = dict(m=torch.zeros_like(p), v=torch.zeros_like(p), t0=0) if use_adam else None
 
     def one_call():
@@ -154,11 +159,11 @@ def main():
             adam["m"].zero_()
             adam["v"].zero_()
             st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, adam=adam, losses=losses, mious=mious,
-                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw)
+                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw, feature_grad=dfeat)
             return
         st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
                               losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream,
-                              pixel_weights=pw)
+                              pixel_weights=pw, feature_grad=dfeat)
 
     for _ in range(args.warmup):
         one_call()
@@ -249,7 +254,7 @@ def main():
         "config": {"workload": f"{wl.name}: features [{wl.n},{wl.c_in},{wl.h},{wl.w}] {wl.feat_dtype}, head "
                                f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, "
                                f"{wl.steps} {'Adam' if args.optimizer == 'adam' else 'SGD'} steps per key frame (one bench step = one key frame)",
-                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss)},
+                   "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss), "full_backward": bool(args.full_backward)},
         "key_frames_per_s": round(args.steps / elapsed, 3),
         "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
         "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],

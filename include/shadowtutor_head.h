@@ -107,6 +107,13 @@ typedef struct st_distill_opts {
      * is the weighted mean  sum w_p CE_p / sum w_p  over the valid pixels; the metric ignores
      * the weights. */
     const uint8_t* pixel_weights;
+    /* Full backward pass, for comparison with partial distillation (Section 4.2) or for a caller
+     * that owns an unfrozen front part: DEVICE pointer to float32 [n, c_in, h, w], or NULL.  When
+     * given, every backward pass also computes d loss / d features (the data-gradient of the
+     * first layer, which partial distillation leaves out); the tensor holds that of the last
+     * backward pass of the call (untouched if no step is taken).  On the matrix-core path this
+     * needs c1 in multiples of 64 (ST_ERR_SHAPE otherwise). */
+    float* feature_grad;
 } st_distill_opts;
 enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 

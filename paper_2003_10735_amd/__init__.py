@@ -38,7 +38,7 @@ class StDistillOpts(C.Structure):
                 ("strict_break", C.c_int32), ("return_best", C.c_int32),
                 ("optimizer", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t0", C.c_int32),
-                ("pixel_weights", C.c_void_p)]
+                ("pixel_weights", C.c_void_p), ("feature_grad", C.c_void_p)]
 
 
 class StScheduleParams(C.Structure):
@@ -203,18 +203,19 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
                        momentum: float = 0.0, velocity=None, threshold: float = 0.0,
                        strict_break: bool = True, return_best: bool = False, losses=None,
                        mious=None, confusion=None, pred=None, workspace=None, stream=None,
-                       adam=None, pixel_weights=None):
+                       adam=None, pixel_weights=None, feature_grad=None):
     """Runs the library's st_partial_distill; head_params (and the optimiser state) are updated
     in place.  `adam` = dict(m=, v=, t0=0, beta1=0.9, beta2=0.999, eps=1e-8) selects Adam;
-    `pixel_weights` (uint8 [n,8h,8w]) scales every pixel's loss.
+    `pixel_weights` (uint8 [n,8h,8w]) scales every pixel's loss; `feature_grad` (float32
+    [n,c_in,h,w]) receives d loss / d features of the last backward pass.
     Returns (steps_taken, best_metric or None)."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     use_opts = (momentum != 0.0 or threshold > 0.0 or velocity is not None or adam is not None
-                or pixel_weights is not None)
+                or pixel_weights is not None or feature_grad is not None)
     opts = StDistillOpts(momentum, _ptr(velocity), threshold, 1 if strict_break else 0,
                          1 if return_best else 0, ST_OPTIM_SGD, 0.0, 0.0, 0.0, None, None, 0,
-                         _ptr(pixel_weights))
+                         _ptr(pixel_weights), _ptr(feature_grad))
     if adam is not None:
         opts.optimizer = ST_OPTIM_ADAM
         opts.beta1, opts.beta2 = adam.get("beta1", 0.9), adam.get("beta2", 0.999)

@@ -113,6 +113,34 @@ struct DgradProb {
     }
 };
 
+// ---- data gradient of layer 1, straight into the caller's float32 NCHW tensor (no activation in
+//      front of the features, so nothing gates it) ---------------------------------------------
+template <class E, class WE>
+struct FeatDgradProb {
+    static constexpr bool A_K_FAST = true, B_K_FAST = false;
+    Geo g; int ci, co;
+    const E* dy; const WE* W; float* dfeat;
+    __device__ int M() const { return g.positions(); }
+    __device__ int N() const { return ci; }
+    __device__ int K() const { return 9 * co; }
+    __device__ float a(int m, int k) const
+    {
+        const int tap = k / co, o = k - tap * co;
+        return to_f32(dy[(size_t)padded_pos(g, m, 1 - tap / 3, 1 - tap % 3) * co + o]);
+    }
+    __device__ float b(int k, int n) const
+    {
+        const int tap = k / co, o = k - tap * co;
+        return to_f32(W[((size_t)o * 9 + tap) * ci + n]);
+    }
+    __device__ void store(int m, int n, float v) const
+    {
+        const int hw = g.h * g.w;
+        const int img = m / hw, r = m - img * hw;
+        dfeat[((size_t)img * ci + n) * hw + r] = v;
+    }
+};
+
 // ---- weight gradient: dW[o][tap][i] = sum_pos dy[pos][o] * x[pos + tap][i] -------------------
 template <class E, int TAPS>
 struct WgradProb {
@@ -252,6 +280,14 @@ static void fwd_impl(Ctx& c, const Plan& p, char* ws, const WE* W1, const WE* W2
 }
 
 template <class E, class WE>
+static void feat_grad_impl(Ctx& c, const Plan& p, char* ws, const WE* W1, float* dfeat)
+{
+    const Geo& g = p.g;
+    FeatDgradProb<E, WE> d1{g, g.c_in, g.c1, (const E*)(ws + p.da1), W1, dfeat};
+    launch(c, "conv1_dgrad_generic", d1, g.positions(), g.c_in);
+}
+
+template <class E, class WE>
 static void bwd_impl(Ctx& c, const Plan& p, char* ws, const WE* W2, const WE* W3, float* grad)
 {
     const Geo& g = p.g;
@@ -288,6 +324,14 @@ void generic_forward(Ctx& c, const Plan& p, char* ws, float* z)
                              (const bf16*)(ws + p.wq3), theta, z);
     else
         fwd_impl<float, float>(c, p, ws, theta + p.po.W1, theta + p.po.W2, theta + p.po.W3, theta, z);
+}
+
+// d loss / d features [n, c_in, h, w] float32 from da1 (run after generic_backward)
+void generic_feature_grad(Ctx& c, const Plan& p, char* ws, float* dfeat)
+{
+    const float* theta = (const float*)(ws + p.theta);
+    if (p.bf16) feat_grad_impl<bf16, bf16>(c, p, ws, (const bf16*)(ws + p.wq1), dfeat);
+    else feat_grad_impl<float, float>(c, p, ws, theta + p.po.W1, dfeat);
 }
 
 void generic_backward(Ctx& c, const Plan& p, char* ws)

@@ -63,6 +63,8 @@ struct ConvArgs {
     const bf16* W3q;    // [n_cls][cout] bfloat16
     float* zpart;
     int n_cls;
+    // EPI 3: the plain sums go, as float32, straight to a dense [n][cout][h][w] tensor
+    float* dense;
     int PP, Hp, Wp, h, w, cin, cout, PPT, guard;
     int m_tiles, n_tiles, tiles_per_xcd;
 };
@@ -228,6 +230,23 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         mine = sum;
     }
 
+    if (EPI == 3) {
+        // a lane holds 16 channels of one position; for a fixed channel the 32 lanes of a half
+        // wavefront are 32 consecutive positions, i.e. (inside one grid row) consecutive floats
+        const int frame = a.Hp * a.Wp;
+        const int mp = m0 + kgrp * 32 + l32;
+        const int img = mp / frame, rr = mp - img * frame, y = rr / a.Wp, x = rr - y * a.Wp;
+        if (mp < a.PP && y >= 1 && y <= a.h && x >= 1 && x <= a.w) {
+            float* dst = a.dense + ((size_t)img * a.cout * a.h + (y - 1)) * a.w + (x - 1);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ch = n0 + wn * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3);
+                if (ch < a.cout) dst[(size_t)ch * a.h * a.w] = mine[r];
+            }
+        }
+        return;
+    }
+
     // classifier fragments (A operand: rows = classes, k = 16 channels of this tile), fetched
     // now so that they arrive while the tile is being staged
     u32x4 w3f[4];
@@ -256,7 +275,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
             float v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = mine[rg * 4 + e];
-            if (EPI != 1) {
+            if (EPI == 0 || EPI == 2) {
                 const float4 b = *(const float4*)(a.bias + cg);
                 v[0] = fmaxf(v[0] + b.x, 0.f); v[1] = fmaxf(v[1] + b.y, 0.f);
                 v[2] = fmaxf(v[2] + b.z, 0.f); v[3] = fmaxf(v[3] + b.w, 0.f);
@@ -317,14 +336,15 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 bool conv3x3_mfma_supported(int cin, int cout) { return cin % CV_BK == 0 && cout % 32 == 0 && cout >= 32; }
 
 // epi 0: Y = relu(conv + bias); epi 1: Y = conv * [mask > 0]; with W3q / zpart (epi 0, cout a
-// multiple of 64) the block also leaves its share of the classifier's logits
+// multiple of 64) the block also leaves its share of the classifier's logits; epi 3: the plain
+// sums as float32 to the dense tensor `dense` [n][cout][h][w]
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
                   const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer, const bf16* W3q,
-                  float* zpart)
+                  float* zpart, float* dense)
 {
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
-    a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C;
+    a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C; a.dense = dense;
     a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.h = p.g.h; a.w = p.g.w;
     a.cin = cin; a.cout = cout;
     a.PPT = p.PPT; a.guard = p.guard;
@@ -339,7 +359,8 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
         ensure_dynamic_lds((const void*)kernel, smem);
         ST_LAUNCH(c, name, kernel, grid, dim3(512), smem, a);
     };
-    if (epi == 1) go(k_conv3x3_mfma<1, 3>);
+    if (epi == 3) go(k_conv3x3_mfma<3, 4>);
+    else if (epi == 1) go(k_conv3x3_mfma<1, 3>);
     else if (zpart) go(k_conv3x3_mfma<2, 2>);
     else if (layer == 1) go(k_conv3x3_mfma<0, 1>);
     else go(k_conv3x3_mfma<0, 2>);

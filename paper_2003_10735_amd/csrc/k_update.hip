@@ -24,11 +24,12 @@ namespace st {
 //   wq1, wq2, wq3 : for the forward convolutions
 //   wq2t          : W2 with the roles of o and i exchanged and the taps mirrored (tap' = 8 - tap),
 //                   for the data-gradient of layer 2 run as a forward convolution
+//   wq1t          : the same for W1, only when the caller wants the gradient of the features
 // wq3 has theta's order.  So do wq1 and wq2 for the plain tiled kernels (frag == 0); the
 // matrix-core convolutions read wq1, wq2 and wq2t in fragment order (wfrag_index).
 struct UpdateArgs {
     float* theta; float* vel; float* vel2; const float* grad; size_t stride; int splits1, splits2;
-    bf16* wq1; bf16* wq2; bf16* wq2t; bf16* wq3;
+    bf16* wq1; bf16* wq1t; bf16* wq2; bf16* wq2t; bf16* wq3;
     ParamOffsets po; int c_in, c1, c2;
     int frag;        // wq1 / wq2 / wq2t in fragment order
     float lr, mu;
@@ -91,6 +92,7 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
             if (a.frag) {
                 const int i = (int)(r % a.c_in), tap = (int)((r / a.c_in) % 9), o = (int)(r / ((size_t)a.c_in * 9));
                 a.wq1[wfrag_index(o, tap, i, a.c_in)] = q;
+                if (a.wq1t) a.wq1t[wfrag_index(i, 8 - tap, o, a.c1)] = q;
             } else a.wq1[r] = q;
         } else if (j >= a.po.W2 && j < a.po.b2) {
             const size_t r = j - a.po.W2;
@@ -148,6 +150,10 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
             if (a.frag) {
                 const int i = (int)(r % a.c_in), tap = (int)((r / a.c_in) % 9), o = (int)(r / ((size_t)a.c_in * 9));
                 *(bf16x4*)(a.wq1 + wfrag_index(o, tap, i, a.c_in)) = q;
+                if (a.wq1t) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a.wq1t[wfrag_index(i + e, 8 - tap, o, a.c1)] = q[e];
+                }
             } else *(bf16x4*)(a.wq1 + r) = q;
         } else if (j >= a.po.W2 && j < a.po.b2) {
             const size_t r = j - a.po.W2;
@@ -298,7 +304,7 @@ static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* 
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
 // finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out, const float* ext_in)
+              double* miou_out, long long* conf_out, const float* ext_in, bool w1t)
 {
     UpdateArgs a;
     a.theta = (float*)(ws + p.theta);
@@ -312,6 +318,7 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
     a.splits1 = p.mfma ? p.splits1 : 1;
     a.splits2 = p.mfma ? p.splits2 : 1;
     a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
+    a.wq1t = (p.mfma && w1t) ? (bf16*)(ws + p.wq1t) : nullptr;
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
     a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
     a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
@@ -342,9 +349,9 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
 }
 
 // takes the caller's parameters (OIHW order) into theta and refreshes the bfloat16 copies
-void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params)
+void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params, bool w1t)
 {
-    step_end(c, p, ws, 0.f, 0.f, nullptr, false, false, nullptr, nullptr, nullptr, head_params);
+    step_end(c, p, ws, 0.f, 0.f, nullptr, false, false, nullptr, nullptr, nullptr, head_params, w1t);
 }
 
 // bookkeeping of a pass without an update; with ext_out the same launch hands theta back to the

@@ -156,6 +156,7 @@ Plan make_plan(const st_head_desc& d)
     p.best = take(off, p.po.total * 4);
     if (p.bf16) {
         p.wq1 = take(off, (p.po.b1 - p.po.W1) * 2);
+        p.wq1t = take(off, (p.po.b1 - p.po.W1) * 2);
         p.wq2 = take(off, (p.po.b2 - p.po.W2) * 2);
         p.wq2t = take(off, (p.po.b2 - p.po.W2) * 2);
         p.wq3 = take(off, (p.po.b3 - p.po.W3) * 2);
@@ -242,16 +243,25 @@ static ZSrc z_source(const Plan& p, char* ws, float* z)
 }
 
 // partial backward: gradients of the head's parameters only; nothing flows into the features
-static void backward(Ctx& c, const Plan& p, char* ws)
+// (with dfeat, the caller's float32 [n, c_in, h, w] tensor, the chain rule is continued one
+// more layer: what an unfrozen front part would need, and what partial distillation saves)
+static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat)
 {
-    if (!p.mfma) { generic_backward(c, p, ws); return; }
+    if (!p.mfma) {
+        generic_backward(c, p, ws);
+        if (dfeat) generic_feature_grad(c, p, ws, dfeat);
+        return;
+    }
     const Geo& g = p.g;
     float* grad = (float*)(ws + p.grad);
     conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
                    (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
                    (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
-                 (const bf16*)(ws + p.a1), nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
+                 (const bf16*)(ws + p.a1), dfeat ? (bf16*)(ws + p.da1) : nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
+    if (dfeat)
+        conv3x3_mfma(c, "conv1_dgrad_mfma", p, (const bf16*)(ws + p.da1), (const bf16*)(ws + p.wq1t), nullptr, nullptr,
+                     nullptr, nullptr, g.c1, g.c_in, 3, 1, nullptr, nullptr, dfeat);
     wgrad3x3_mfma(c, p, (const bf16*)(ws + p.da1T), (const bf16*)(ws + p.featT), (const bf16*)(ws + p.da2T),
                   (const bf16*)(ws + p.a1T), grad);
 }
@@ -298,7 +308,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     Ctx c{as_stream(stream), ST_OK};
     prepare_workspace(c, p, ws);
     pack_features(c, p, features, desc->feat_dtype, ws);
-    load_params(c, p, ws, head_params);
+    load_params(c, p, ws, head_params, false);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred || p.mfma)
@@ -325,6 +335,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     float adam_eps = 0.f;
     long long adam_t0 = 0;
     const uint8_t* pixel_weights = opts ? opts->pixel_weights : nullptr;
+    float* feature_grad = opts ? opts->feature_grad : nullptr;
     if (opts) {
         if (!isfinite(opts->momentum) || opts->momentum < 0.f || isnan(opts->threshold)) return ST_ERR_ARG;
         if (opts->optimizer != ST_OPTIM_SGD && opts->optimizer != ST_OPTIM_ADAM) return ST_ERR_ARG;
@@ -350,6 +361,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
 
     const Plan p = make_plan(*desc);
     const Geo& g = p.g;
+    // (the matrix-core kernel of the feature gradient needs c1 in multiples of 64)
+    if (feature_grad && p.mfma && !conv3x3_mfma_supported(g.c1, g.c_in)) return ST_ERR_SHAPE;
     char* ws = (char*)workspace;
     Ctx c{as_stream(stream), ST_OK};
 
@@ -366,7 +379,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         permute_params(c, p, adam_m, (float*)(ws + p.vel), 0);
         permute_params(c, p, adam_v, (float*)(ws + p.vel2), 0);
     }
-    load_params(c, p, ws, head_params);   // theta in internal order + bfloat16 copies of the initial weights
+    load_params(c, p, ws, head_params, feature_grad != nullptr);   // theta in internal order + bfloat16 copies
     label_adjoint(c, g, teacher_labels, pixel_weights, (float*)(ws + p.tadj), n_valid);   // also sums the weights of the valid labels
 
     double best_metric = -1.0;
@@ -420,7 +433,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             }
         }
         if (stop) break;
-        backward(c, p, ws);
+        backward(c, p, ws, feature_grad);
         AdamStep ad;
         if (use_adam) {
             // bias corrections of step t in double precision, handed to the kernel as two factors
@@ -431,7 +444,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             ad.step_scale = (float)((double)lr / (1.0 - pow(beta1, t)));
             ad.inv_sqrt_bc2 = (float)(1.0 / sqrt(1.0 - pow(beta2, t)));
         }
-        step_end(c, p, ws, lr, mu, use_adam ? &ad : nullptr, true, !finish_now, loss_out, miou_out, conf_out);
+        step_end(c, p, ws, lr, mu, use_adam ? &ad : nullptr, true, !finish_now, loss_out, miou_out, conf_out, nullptr,
+                 feature_grad != nullptr);
         ++taken;
     }
     if (early_exit && return_best && have_best)

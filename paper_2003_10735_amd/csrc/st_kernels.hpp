@@ -21,12 +21,13 @@ void permute_params(Ctx& c, const Plan& p, const float* src, float* dst, int dir
 // k_conv_generic.hip -- plain tiled kernels (float32 path; bfloat16 shapes the MFMA kernels skip)
 void generic_forward(Ctx& c, const Plan& p, char* ws, float* z);
 void generic_backward(Ctx& c, const Plan& p, char* ws);
+void generic_feature_grad(Ctx& c, const Plan& p, char* ws, float* dfeat);
 
 // k_conv_mfma.hip, k_wgrad_mfma.hip, k_conv3_mfma.hip -- matrix-core kernels of the bfloat16 path
 bool conv3x3_mfma_supported(int cin, int cout);
 void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const bf16* Wq, const float* bias,
                   const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer,
-                  const bf16* W3q = nullptr, float* zpart = nullptr);
+                  const bf16* W3q = nullptr, float* zpart = nullptr, float* dense = nullptr);
 bool wgrad3x3_mfma_supported(int cin, int cout);
 void wgrad_splits_for(const Geo& g, int* splits1, int* splits2);
 void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, const bf16* da2T,
@@ -61,9 +62,10 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, cons
 //   theta <- theta - step_scale * m / (sqrt(v) * inv_sqrt_bc2 + eps),
 //   step_scale = lr / (1 - beta1^t),  inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
 struct AdamStep { float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_scale, inv_sqrt_bc2; };
-void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params);
+void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params, bool w1t);
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out, const float* ext_in = nullptr);
+              double* miou_out, long long* conf_out, const float* ext_in = nullptr,
+              bool w1t = false);
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
                  float* ext_out = nullptr);
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,

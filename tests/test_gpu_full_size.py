@@ -58,3 +58,9 @@ def test_720p_weighted_loss_two_steps():
     """Per-pixel loss weights (Section 5.2) at the benchmark's shape."""
     from test_gpu_parity import check_weighted
     check_weighted(WL.WORKLOADS["720p"], 2, True, 5e-4)
+
+
+def test_720p_feature_gradient():
+    """The full backward pass (what partial distillation leaves out) at the benchmark's shape."""
+    from test_gpu_parity import check_feature_grad
+    check_feature_grad(WL.WORKLOADS["720p"], True, 5e-3)

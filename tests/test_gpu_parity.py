@@ -367,3 +367,58 @@ def test_workspace_reuse_across_calls_leaves_no_trace():
         np.testing.assert_array_equal(a[k], fresh[k])
         np.testing.assert_array_equal(b[k], fresh[k])
     assert np.all(np.isfinite(a["losses"]))
+
+
+# ------------------------------------------------------------------ full backward pass (feature gradient)
+def run_gpu_feature_grad(wl, feats, labels, params, steps):
+    import torch
+    import paper_2003_10735_amd as st
+    from gpu_util import to_dev_features
+    desc = st.HeadDesc.of(wl)
+    p = torch.from_numpy(params.astype(np.float32)).cuda()
+    df = torch.full((wl.n, wl.c_in, wl.h, wl.w), float("nan"), dtype=torch.float32, device="cuda")
+    st.st_partial_distill(desc, to_dev_features(wl, feats), torch.from_numpy(labels).cuda(), p, steps, wl.lr,
+                          feature_grad=df)
+    torch.cuda.synchronize()
+    return p.cpu().numpy(), df.cpu().numpy()
+
+
+def check_feature_grad(wl, bf16_operands, tol):
+    """One step: the feature gradient belongs to the initial parameters, and asking for it must
+    not change the step itself.  On the bfloat16 path the tolerance against the oracle with the
+    same rounding points is wider than for the weights: the operands da2 and da1 are themselves
+    rounded sums, the two sides add in different orders, so a few operand elements round the other
+    way (2^-8 relative each), and an element of d features sums only 9 * c1 products -- it does
+    not average such flips over all positions the way a weight gradient does."""
+    f, lab, p = inputs(wl)
+    params, df = run_gpu_feature_grad(wl, f, lab, p, 1)
+    plain = run_gpu(wl, f, lab, p, steps=1)
+    np.testing.assert_array_equal(params, plain["params"])
+    d = O.desc_of(wl, bf16_operands)
+    _, _, df_o = O.feature_grad(d, WL.features_as_f64(wl, f), lab, p.astype(np.float64))
+    assert np.all(np.isfinite(df))
+    assert rel_err(df, df_o) < tol, rel_err(df, df_o)
+    if bf16_operands:
+        # Against the oracle that rounds nothing only a loose bound holds, by the nature of the
+        # bfloat16 semantics and not of the implementation: where an activation is within rounding
+        # noise of zero its ReLU mask differs between the two, which switches whole elements of
+        # da2 / da1 on or off (the oracle's own two modes differ by 10 % in the maximum norm here,
+        # while the weight gradients, sums over all positions, agree to 1-2 %).
+        _, _, df_p = O.feature_grad(O.desc_of(wl, False), WL.features_as_f64(wl, f), lab, p.astype(np.float64))
+        assert rel_err(df, df_p) < 0.3, rel_err(df, df_p)
+        assert np.median(np.abs(df - df_p)) < 1e-2 * np.abs(df_p).max()
+
+
+def test_feature_grad_tiny_f32():
+    check_feature_grad(WL.WORKLOADS["tiny"], None, 1e-4)
+
+
+def test_feature_grad_ragged_generic_bf16():
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], n=2, c_in=20, h=9, w=37, c1=24, c2=16, n_classes=5, compute="bf16",
+                          feat_dtype="bf16", steps=1)
+    check_feature_grad(wl, True, 5e-3)
+
+
+def test_feature_grad_matrix_core_path():
+    wl = WL.small_variant(WL.WORKLOADS["720p"], n=2, h=20, w=28, c_in=128, c1=64, c2=64, n_classes=7, steps=1)
+    check_feature_grad(wl, True, 5e-3)
