@@ -231,6 +231,44 @@ def main():
                   if kk in ("bound", "achieved", "unit", "frac", "avg_launch_us")}
               for k, v in known.items() if k != dominant}
 
+    # the stand-alone metric call (st_miou: confusion histogram + mean IoU of a class map), the
+    # per-frame pass of a clip; streaming bound: 1 B prediction + 4 B label per pixel
+    pred = torch.zeros((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+    st.st_head_forward(desc, f, p, pred=pred, workspace=ws, stream=stream)
+    conf1 = torch.empty((wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+    m1 = torch.empty(1, dtype=torch.float64, device="cuda")
+    for _ in range(3):
+        st.st_miou(pred, lab, wl.n_classes, wl.ignore_index, confusion=conf1, miou=m1, stream=stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        st.st_miou(pred, lab, wl.n_classes, wl.ignore_index, confusion=conf1, miou=m1, stream=stream)
+    e1.record()
+    torch.cuda.synchronize()
+    miou_us = e0.elapsed_time(e1) / reps * 1e3
+    # the same call once more with an event pair around every launch: the histogram kernel alone
+    st.st_profile_reset()
+    st.st_profile_filter(None)
+    st.st_profile_enable(True)
+    for _ in range(reps):
+        st.st_miou(pred, lab, wl.n_classes, wl.ignore_index, confusion=conf1, miou=m1, stream=stream)
+    torch.cuda.synchronize()
+    mprof = {k: v[1] / v[0] * 1e3 for k, v in st.st_profile_read().items()}
+    st.st_profile_enable(False)
+    st.st_profile_reset()
+    miou_bytes = 5.0 * wl.n * wl.H * wl.W
+    hist_us = mprof["confusion"]
+    miou_pass = {"bound": "hbm", "kernel": "confusion", "avg_launch_us": round(hist_us, 2),
+                 "achieved": round(miou_bytes / hist_us / 1e3, 1), "unit": "GB/s",
+                 "frac": round(miou_bytes / hist_us / 1e3 / PEAK_HBM_GBS, 5),
+                 "us_per_call": round(miou_us, 2),
+                 "launch_us": {k: round(v, 2) for k, v in mprof.items()},
+                 "note": "st_miou = clear + histogram + mean-IoU launches; us_per_call is the whole call "
+                         "issued back to back from Python, avg_launch_us the histogram kernel between its "
+                         "own events; 5 B per pixel"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle as O
@@ -261,6 +299,7 @@ def main():
         "kernel_us": breakdown,
         "roofline": roofline,
         "other_kernels": others,
+        "miou_pass": miou_pass,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

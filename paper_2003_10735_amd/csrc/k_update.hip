@@ -3,6 +3,8 @@
 // kernel (loss, per-frame mean IoU) and the stand-alone confusion-matrix / mean-IoU kernels.
 #include <string.h>
 
+#include <algorithm>
+
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
 
@@ -373,65 +375,131 @@ void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_
               dim3(256), 0, a, f);
 }
 
-__global__ void k_miou_from_counts(const unsigned long long* conf, int C, double* out)
+// Mean IoU (Eq. 1) of a C x C table of counts, any C up to 256: one wavefront per class adds
+// that class's row and column (exact integer sums), then a single thread adds the per-class
+// ratios of the classes that occur as a label in ascending order in float64 and divides by
+// their number; 0 when there is none.
+constexpr int MIOU_THREADS = 1024;
+__global__ void __launch_bounds__(MIOU_THREADS)
+k_miou_from_counts(const unsigned long long* __restrict__ conf, int C, double* __restrict__ out)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    double sum = 0.0;
-    int present = 0;
-    for (int c = 0; c < C; ++c) {
+    __shared__ double iou[256];
+    __shared__ int present[256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c = wave; c < C; c += MIOU_THREADS / 64) {
         unsigned long long row = 0, col = 0;
-        for (int k = 0; k < C; ++k) { row += conf[c * C + k]; col += conf[k * C + c]; }
-        if (row == 0) continue;
-        const unsigned long long inter = conf[c * C + c];
-        sum += (double)inter / (double)(row + col - inter);
-        ++present;
+        for (int k = lane; k < C; k += 64) { row += conf[(size_t)c * C + k]; col += conf[(size_t)k * C + c]; }
+#pragma unroll
+        for (int d = 32; d; d >>= 1) { row += __shfl_xor(row, d, 64); col += __shfl_xor(col, d, 64); }
+        if (lane == 0) {
+            const unsigned long long inter = conf[(size_t)c * C + c];
+            present[c] = row != 0;
+            iou[c] = row ? (double)inter / (double)(row + col - inter) : 0.0;
+        }
     }
-    *out = present ? sum / present : 0.0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double sum = 0.0;
+        int cnt = 0;
+        for (int c = 0; c < C; ++c)
+            if (present[c]) { sum += iou[c]; ++cnt; }
+        *out = cnt ? sum / cnt : 0.0;
+    }
 }
 
 // ------------------------------------------------------------------ stand-alone metric
 // Confusion counts of a class map against labels.  Each block keeps its own C x C table in
-// LDS.  Label maps are piecewise constant, so most wavefronts hold a single (label, prediction)
-// pair: the wavefront first agrees on one bin by ballot and a single lane adds the population
-// count; the few mixed wavefronts repeat that for each distinct bin.  Integer counts, so the
-// order of additions does not matter.
+// LDS and adds it to the result at the end; integer counts, so the order of additions does
+// not matter.  Few, large blocks: the final additions of every block land on the same few
+// cache lines.  Per trip a wavefront takes 1024 consecutive pixels as four label loads of 16
+// bytes and four prediction loads of 4 bytes per lane, each instruction reading one contiguous
+// stretch, all issued before the first is used.  Label maps are piecewise constant, so most
+// wavefronts hold a single (label, prediction) pair: that case is detected with one ballot and
+// costs one LDS addition.  Otherwise every lane merges equal neighbours among its 16 pixels
+// and adds each run to the table itself; LDS resolves lanes that hit the same counter.
+// Tables too large for LDS (more than 128 classes) go to the result directly, one addition
+// per distinct pair of a wavefront and pixel slot.
+constexpr int CONF_THREADS = 1024;
+constexpr int CONF_PER_T = 16;                       // pixels of one thread per trip
+constexpr int CONF_MAX_BLOCKS = 256;
 template <bool LDS_TABLE>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(CONF_THREADS)
 k_confusion(const uint8_t* __restrict__ pred, const int32_t* __restrict__ labels, long long P, int C,
             int ignore, unsigned long long* __restrict__ conf)
 {
     extern __shared__ unsigned int table[];
     if (LDS_TABLE) {
-        for (int i = threadIdx.x; i < C * C; i += 256) table[i] = 0;
+        for (int i = threadIdx.x; i < C * C; i += CONF_THREADS) table[i] = 0;
         __syncthreads();
     }
-    const long long stride = (long long)gridDim.x * 256;
-    const long long n_iter = (P + stride - 1) / stride;
-    for (long long it = 0; it < n_iter; ++it) {
-        const long long i = it * stride + (long long)blockIdx.x * 256 + threadIdx.x;
-        int bin = -1;
-        if (i < P) {
-            const int y = labels[i];
-            const int q = pred[i];
-            if (y != ignore && y >= 0 && y < C && q < C) bin = y * C + q;
-        }
-        // wavefront-level aggregation
-        unsigned long long todo = __ballot(bin >= 0);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int lbin = __shfl(bin, leader, 64);
-            const unsigned long long same = __ballot(bin == lbin);
-            if ((int)(threadIdx.x & 63) == leader) {
-                const unsigned int cnt = (unsigned int)__popcll(same);
-                if (LDS_TABLE) atomicAdd(&table[lbin], cnt);
-                else atomicAdd(&conf[lbin], (unsigned long long)cnt);
+    const bool aligned = (((uintptr_t)labels | (uintptr_t)pred) & 15) == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long trip = (long long)CONF_THREADS * CONF_PER_T;
+    for (long long first = (long long)blockIdx.x * trip; first < P; first += (long long)gridDim.x * trip) {
+        // pixel (k, j) of this lane: wbase + 256 k + 4 lane + j
+        const long long wbase = first + (long long)wave * (64 * CONF_PER_T);
+        if (wbase >= P) continue;
+        int bins[CONF_PER_T];
+        if (aligned && wbase + 64 * CONF_PER_T <= P) {
+            u32x4 lv[4];
+            unsigned int pv[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) lv[k] = *(const u32x4*)(labels + wbase + 256 * k + 4 * lane);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pv[k] = *(const unsigned int*)(pred + wbase + 256 * k + 4 * lane);
+#pragma unroll
+            for (int i = 0; i < CONF_PER_T; ++i) {
+                const int y = (int)lv[i >> 2][i & 3];
+                const int q = (int)((pv[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+                bins[i] = (y != ignore && y >= 0 && y < C && q < C) ? y * C + q : -1;
             }
-            todo &= ~same;
+        } else {
+#pragma unroll
+            for (int i = 0; i < CONF_PER_T; ++i) {
+                const long long at = wbase + 256 * (i >> 2) + 4 * lane + (i & 3);
+                bins[i] = -1;
+                if (at < P) {
+                    const int y = labels[at];
+                    const int q = pred[at];
+                    if (y != ignore && y >= 0 && y < C && q < C) bins[i] = y * C + q;
+                }
+            }
+        }
+        if (LDS_TABLE) {
+            const int b0 = __builtin_amdgcn_readfirstlane(bins[0]);
+            bool same = true;
+#pragma unroll
+            for (int i = 0; i < CONF_PER_T; ++i) same &= bins[i] == b0;
+            if (__ballot(same) == __ballot(true)) {
+                // one pair for the whole wavefront (or nothing to count)
+                if (b0 >= 0 && lane == 0) atomicAdd(&table[b0], 64u * CONF_PER_T);
+            } else {
+                unsigned int run = 1;
+#pragma unroll
+                for (int i = 1; i <= CONF_PER_T; ++i) {
+                    if (i < CONF_PER_T && bins[i] == bins[i - 1]) { ++run; continue; }
+                    if (bins[i - 1] >= 0) atomicAdd(&table[bins[i - 1]], run);
+                    run = 1;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CONF_PER_T; ++i) {
+                const int bin = bins[i];
+                unsigned long long todo = __ballot(bin >= 0);
+                while (todo) {
+                    const int leader = __ffsll((long long)todo) - 1;
+                    const int lbin = __shfl(bin, leader, 64);
+                    const unsigned long long same = __ballot(bin == lbin);
+                    if (lane == leader) atomicAdd(&conf[lbin], (unsigned long long)__popcll(same));
+                    todo &= ~same;
+                }
+            }
         }
     }
     if (LDS_TABLE) {
         __syncthreads();
-        for (int i = threadIdx.x; i < C * C; i += 256)
+        for (int i = threadIdx.x; i < C * C; i += CONF_THREADS)
             if (table[i]) atomicAdd(&conf[i], (unsigned long long)table[i]);
     }
 }
@@ -440,17 +508,15 @@ void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long
                         long long* conf, double* miou)
 {
     zero_u64(c, (unsigned long long*)conf, (size_t)C * C);
-    int blocks = cdiv(P, 256 * 16);
-    if (blocks < 1) blocks = 1;
-    if (blocks > 2048) blocks = 2048;
+    const int blocks = std::min(std::max(cdiv(P, CONF_THREADS * CONF_PER_T), 1), CONF_MAX_BLOCKS);
     const size_t lds = (size_t)C * C * 4;
     if (lds <= 64 * 1024)
-        ST_LAUNCH(c, "confusion", (k_confusion<true>), dim3(blocks), dim3(256), lds, pred, labels, P, C, ignore,
+        ST_LAUNCH(c, "confusion", (k_confusion<true>), dim3(blocks), dim3(CONF_THREADS), lds, pred, labels, P, C, ignore,
                   (unsigned long long*)conf);
     else
-        ST_LAUNCH(c, "confusion", (k_confusion<false>), dim3(blocks), dim3(256), 0, pred, labels, P, C, ignore,
+        ST_LAUNCH(c, "confusion", (k_confusion<false>), dim3(blocks), dim3(CONF_THREADS), 0, pred, labels, P, C, ignore,
                   (unsigned long long*)conf);
-    ST_LAUNCH(c, "miou", k_miou_from_counts, dim3(1), dim3(64), 0, (const unsigned long long*)conf, C, miou);
+    ST_LAUNCH(c, "miou", k_miou_from_counts, dim3(1), dim3(MIOU_THREADS), 0, (const unsigned long long*)conf, C, miou);
 }
 
 }  // namespace st

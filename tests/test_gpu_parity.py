@@ -134,6 +134,24 @@ def test_miou_matches_oracle_bit_exact(P, C, ignore):
     assert m.item() == O.miou(conf_o)[0]
 
 
+def test_miou_unaligned_maps_and_out_of_range_entries():
+    # maps that start off a 16-byte boundary, labels outside [0, C) and predictions >= C: the
+    # vector path must not be taken and such pixels must not be counted
+    P, C = 70001, 11
+    rng = np.random.default_rng(77)
+    pred = rng.integers(0, 14, size=P + 3).astype(np.uint8)
+    lab = rng.integers(-2, 13, size=P + 3).astype(np.int32)
+    lab[1000:40000] = 4
+    pred[500:30000] = 4
+    dp, dl = torch.from_numpy(pred).cuda(), torch.from_numpy(lab).cuda()
+    for off_p, off_l in ((3, 3), (0, 1), (1, 0)):
+        conf, m = st.st_miou(dp[off_p:off_p + P], dl[off_l:off_l + P], C, -1)
+        torch.cuda.synchronize()
+        conf_o = O.confusion(pred[off_p:off_p + P], lab[off_l:off_l + P], C, -1)
+        np.testing.assert_array_equal(conf.cpu().numpy(), conf_o)
+        assert m.item() == O.miou(conf_o)[0]
+
+
 def test_steps_zero_and_determinism():
     wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=9, w=35, c1=8, c2=8, n_classes=5, steps=2)
     f, lab, p = inputs(wl)
