@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--optimizer", choices=("sgd", "adam"), default="sgd",
                     help="sgd: the workload's optimiser (the headline configuration); adam: the "
                          "paper's optimiser (Section 5.2) with beta 0.9 / 0.999, eps 1e-8, state reset per key frame")
+    ap.add_argument("--clients", type=int, default=4,
+                    help="also time the grouped form: this many clients, each with a head and a key frame of "
+                         "its own, trained in one call (reported beside the headline as `grouped`; 0 = skip)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (outside the timed "
                          "region): the known-size reference that scales hardware byte counters")
@@ -269,6 +272,42 @@ def main():
                          "issued back to back from Python, avg_launch_us the histogram kernel between its "
                          "own events; 5 B per pixel"}
 
+    # several clients in one call (one head and one key frame each; the server of Algorithm 3):
+    # the same launches carry `clients` times the work, which fills the chip better
+    grouped = None
+    if args.clients > 0 and wl.n == 1 and not (use_adam or args.weighted_loss or args.full_backward):
+        G = args.clients
+        wg = WL.small_variant(wl, n=G)
+        dg = st.HeadDesc.of(wg)
+        dg.grouped = 1
+        fg_np = WL.make_features(wg)
+        fg = torch.from_numpy(fg_np.view(np.int16)).cuda().view(torch.bfloat16) if fg_np.dtype == np.uint16 \
+            else torch.from_numpy(fg_np).cuda()
+        lg = torch.from_numpy(WL.make_labels(wg)).cuda()
+        pg0 = torch.from_numpy(np.stack([WL.make_head_params(wg, seed=wg.init_seed + 17 * i) for i in range(G)])).cuda()
+        pg = pg0.clone()
+        wsg = st.new_workspace(dg)
+        lossg = torch.zeros((wl.steps + 1, G), dtype=torch.float32, device="cuda")
+
+        def grouped_call():
+            pg.copy_(pg0)
+            st.st_partial_distill(dg, fg, lg, pg, wl.steps, wl.lr, losses=lossg, workspace=wsg, stream=stream)
+
+        for _ in range(3):
+            grouped_call()
+        torch.cuda.synchronize()
+        reps = max(3, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            grouped_call()
+        torch.cuda.synchronize()
+        tg = (time.perf_counter() - t0) / reps
+        grouped = {"clients": G, "head_steps_per_s": round(G * wl.steps / tg, 1),
+                   "us_per_step": round(tg / wl.steps * 1e6, 2), "calls": reps,
+                   "note": "one st_partial_distill call trains `clients` heads on `clients` key frames "
+                           "(desc.grouped = 1); head_steps_per_s counts one optimiser step of one head"}
+        del fg, lg, pg, pg0, wsg
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle as O
@@ -300,6 +339,7 @@ def main():
         "roofline": roofline,
         "other_kernels": others,
         "miou_pass": miou_pass,
+        "grouped": grouped,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

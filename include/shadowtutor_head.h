@@ -63,11 +63,20 @@ enum { ST_COMPUTE_F32 = 0, ST_COMPUTE_BF16 = 1 }; /* st_head_desc.compute */
  * compute = ST_COMPUTE_BF16: convolution operands (features, weights, activations and the
  *   back-propagated gradients) are rounded to bfloat16, products accumulate in float32 on the
  *   matrix cores; master weights, optimiser arithmetic, logits, loss and weight gradients stay
- *   float32.  Shapes with c_in a multiple of 64, c1 and c2 multiples of 32 and c2 one of
- *   64, 128, 256 run on the matrix-core kernels; every other shape runs on plain tiled kernels
+ *   float32.  Shapes with c_in and c1 multiples of 64 and c2 one of 64, 128, 256 run on the
+ *   matrix-core kernels; every other shape runs on plain tiled kernels
  *   with the same rounding points (same results up to the order of float32 additions).
  * Limits: upscale == 8; 2 <= n_classes <= 32; labels outside [0, n_classes) are skipped like
- * ignore_index (they count neither in the loss nor in the metric). */
+ * ignore_index (they count neither in the loss nor in the metric).
+ *
+ * grouped = 0: one head, trained on a mini-batch of n frames (one loss over all of them).
+ * grouped = 1: n clients in one call (the server of Algorithm 3 serves one student per client):
+ *   n heads of the same shape, head f sees frame f only.  Every per-head array then holds n
+ *   consecutive blocks: head_params, velocity, adam_m, adam_v are [n, st_num_params] and losses is
+ *   [steps + 1, n]; the result of head f is what a call with n = 1 on frame f alone gives.  All
+ *   heads take the same number of steps with the same learning rate: threshold must be <= 0, and
+ *   feature_grad NULL (ST_ERR_ARG otherwise).  Runs on the matrix-core kernels only
+ *   (ST_ERR_SHAPE for compute / shapes that do not, see above). */
 typedef struct st_head_desc {
     int32_t n, c_in, h, w;     /* feature map [n, c_in, h, w]                         */
     int32_t c1, c2, n_classes; /* conv3x3 c_in->c1, conv3x3 c1->c2, conv1x1 c2->classes */
@@ -76,6 +85,7 @@ typedef struct st_head_desc {
     int32_t feat_layout;       /* ST_NCHW                                             */
     int32_t compute;           /* ST_COMPUTE_F32 | ST_COMPUTE_BF16                    */
     int32_t ignore_index;      /* label value to skip; -1 = none                      */
+    int32_t grouped;           /* 0: one head for all n frames; 1: n heads, one per frame */
 } st_head_desc;
 
 /* Options of st_partial_distill (NULL = plain gradient descent, fixed step count). */
@@ -121,7 +131,7 @@ enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
  * pointers and each may be NULL.  Entry i of losses / mious describes the parameters before
  * update i+1, entry `steps_taken` the returned ones (k updates = k+1 forwards). */
 typedef struct st_distill_result {
-    float* losses;       /* [steps + 1]                                     */
+    float* losses;       /* [steps + 1]; grouped: [steps + 1, n]            */
     double* mious;       /* [steps + 1, n]  per-frame mean IoU              */
     int64_t* confusion;  /* [n, C, C] of the last forward; row = label, column = prediction */
     uint8_t* pred;       /* [n, 8h, 8w] class map of the last forward       */
@@ -129,7 +139,7 @@ typedef struct st_distill_result {
     double best_metric;  /* HOST, written only when threshold > 0           */
 } st_distill_result;
 
-/* Number of float32 values in head_params:
+/* Number of float32 values in one head's parameters:
  * c1*c_in*9 + c1 + c2*c1*9 + c2 + n_classes*c2 + n_classes.  0 if desc is NULL or invalid. */
 size_t st_num_params(const st_head_desc* desc);
 
@@ -139,7 +149,7 @@ size_t st_workspace_bytes(const st_head_desc* desc);
 /* Forward (Algorithm 1, "Forward"): features -> low-resolution logits and/or the predicted
  * class map (lowest index among the largest up-sampled logits).
  *   features       [n, c_in, h, w], float32 or bfloat16 as desc says; read only
- *   head_params    st_num_params floats; read only
+ *   head_params    st_num_params floats (grouped: n such blocks); read only
  *   logits_lowres  [n, n_classes, h, w] float32, or NULL
  *   pred           [n, 8h, 8w] uint8, or NULL                                              */
 int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
@@ -152,8 +162,8 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
  *   head_params    in/out, updated in place
  *   steps          >= 0 (0: forward + metric only; MAX_UPDATES when threshold > 0)
  *   lr             learning rate, finite
- * The loss is the mean over all valid pixels of all n frames; the metric is per frame (the
- * loop exits of Algorithm 1 use the mean over frames). */
+ * The loss is the mean over all valid pixels of all n frames (grouped: of the head's own frame);
+ * the metric is per frame (the loop exits of Algorithm 1 use the mean over frames). */
 int st_partial_distill(const st_head_desc* desc, const void* features,
                        const int32_t* teacher_labels, float* head_params, int32_t steps,
                        float lr, const st_distill_opts* opts, st_distill_result* out,

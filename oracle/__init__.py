@@ -282,6 +282,33 @@ def partial_distill_opt(d: Desc, features, labels, params, steps, optim: Optim, 
     return dict(params=params, s1=s1, s2=s2, losses=losses, mious=mious, conf=conf, pred=pred)
 
 
+def partial_distill_grouped(d: Desc, features, labels, params, steps, optim: Optim, s1=None,
+                            s2=None, pixel_weights=None):
+    """n clients, each with a student head of its own and one key frame (the server of Algorithm 3
+    keeps one student per client and trains it on that client's frames only).  By definition this
+    is n independent runs of partial_distill_opt on one frame each; nothing is shared.
+    params, s1, s2: [n, num_params]; pixel_weights: uint8 [n,8h,8w] or None.
+    Returns dict(params[n,P], s1, s2, losses[k+1,n], mious[k+1,n], conf[n,C,C], pred[n,8h,8w])."""
+    features = _f64(features)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    params = _f64(params)
+    n = d.n
+    assert params.shape[0] == n and features.shape[0] == n and labels.shape[0] == n
+    runs = []
+    for f in range(n):
+        d1 = desc(1, d.c_in, d.h, d.w, d.c1, d.c2, d.n_classes, d.ignore_index, bool(d.bf16_operands))
+        if pixel_weights is not None:
+            d1 = with_pixel_weights(d1, pixel_weights[f:f + 1])
+        runs.append(partial_distill_opt(d1, features[f:f + 1], labels[f:f + 1], params[f], steps, optim,
+                                        None if s1 is None else s1[f], None if s2 is None else s2[f]))
+    return dict(params=np.stack([r["params"] for r in runs]),
+                s1=np.stack([r["s1"] for r in runs]), s2=np.stack([r["s2"] for r in runs]),
+                losses=np.stack([r["losses"] for r in runs], axis=1),
+                mious=np.concatenate([r["mious"] for r in runs], axis=1),
+                conf=np.concatenate([r["conf"] for r in runs], axis=0),
+                pred=np.concatenate([r["pred"] for r in runs], axis=0))
+
+
 def train(d: Desc, features, labels, params, max_updates, lr, threshold, momentum=0.0,
           velocity=None, strict_break=True):
     """Student training with the skip / best-tracking / early-exit rules.

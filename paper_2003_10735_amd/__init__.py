@@ -30,7 +30,8 @@ EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial
 
 class StHeadDesc(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n", "c_in", "h", "w", "c1", "c2", "n_classes", "upscale",
-                                          "feat_dtype", "feat_layout", "compute", "ignore_index")]
+                                          "feat_dtype", "feat_layout", "compute", "ignore_index",
+                                          "grouped")]
 
 
 class StDistillOpts(C.Structure):
@@ -133,11 +134,12 @@ class HeadDesc:
     ignore_index: int = -1
     upscale: int = 8
     feat_layout: int = ST_NCHW
+    grouped: int = 0        # 1: n heads, one per frame; per-head arrays are [n, ...]
 
     def c(self) -> StHeadDesc:
         return StHeadDesc(self.n, self.c_in, self.h, self.w, self.c1, self.c2, self.n_classes,
                           self.upscale, self.feat_dtype, self.feat_layout, self.compute,
-                          self.ignore_index)
+                          self.ignore_index, self.grouped)
 
     @staticmethod
     def of(wl) -> "HeadDesc":
@@ -190,8 +192,8 @@ def new_workspace(desc: HeadDesc, device="cuda"):
 
 def st_head_forward(desc: HeadDesc, features, head_params, logits_lowres=None, pred=None,
                     workspace=None, stream=None):
-    """features [n,c_in,h,w] (float32 or bfloat16 cuda tensor), head_params float32 [num_params].
-    Fills logits_lowres [n,C,h,w] float32 and/or pred [n,8h,8w] uint8 when given."""
+    """features [n,c_in,h,w] (float32 or bfloat16 cuda tensor), head_params float32 [num_params]
+    ([n, num_params] for a grouped descriptor).  Fills logits_lowres [n,C,h,w] float32 and/or pred [n,8h,8w] uint8 when given."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     _check(lib().st_head_forward(C.byref(d), _ptr(features), _ptr(head_params), _ptr(logits_lowres),
@@ -208,6 +210,8 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
     in place.  `adam` = dict(m=, v=, t0=0, beta1=0.9, beta2=0.999, eps=1e-8) selects Adam;
     `pixel_weights` (uint8 [n,8h,8w]) scales every pixel's loss; `feature_grad` (float32
     [n,c_in,h,w]) receives d loss / d features of the last backward pass.
+    With a grouped descriptor head_params and the optimiser state are [n, num_params] and losses
+    [steps+1, n].
     Returns (steps_taken, best_metric or None)."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)

@@ -35,7 +35,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
                  const unsigned long long* __restrict__ n_valid, int CP, LossTiling lt,
                  const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
                  const bf16* __restrict__ W3q, bf16* __restrict__ da2, bf16* __restrict__ da2T,
-                 float* __restrict__ part, Geo g, int PPT, int guard)
+                 float* __restrict__ part, Geo g, int PPT, int guard, int grp_blocks)
 {
     constexpr int BP = C3B_BP;
     constexpr int OT = C2 / 32;            // channel tiles
@@ -54,7 +54,12 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int PP = g.padded_positions(), frame = g.Hp * g.Wp, hw = g.h * g.w;
-    const int m0 = blockIdx.x * BP;
+    // several heads: blocks are counted per frame (grp_blocks each), so that no block mixes the
+    // positions -- and with them W3 and the partial sums -- of two heads
+    const int head = g.grouped ? blockIdx.x / grp_blocks : 0;
+    const int m0 = g.grouped ? head * frame + (blockIdx.x - head * grp_blocks) * BP : blockIdx.x * BP;
+    const int m_end = g.grouped ? (head + 1) * frame : PP;
+    W3q += (size_t)head * g.C * C2;
 
     // ---- early loads: ReLU mask of this lane's position, a2 fragments of this wavefront's tiles
     const int pm = (wave & 1) * 32 + l32;          // position (inside the block) for the da2 part
@@ -80,9 +85,9 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
         constexpr int NQ = 256 / BP;
         const int mp = m0 + p;
         const int img = min(mp / frame, g.n - 1), rr = mp - img * frame, y = rr / g.Wp, x = rr - y * g.Wp;
-        const bool inside = mp < PP && y >= 1 && y <= g.h && x >= 1 && x <= g.w;
+        const bool inside = mp < m_end && y >= 1 && y <= g.h && x >= 1 && x <= g.w;
         const int cy = inside ? y - 1 : 0, cx = inside ? x - 1 : 0;
-        const unsigned long long nv = *n_valid;
+        const unsigned long long nv = n_valid[head];
         const float inv_n = (inside && nv) ? 1.0f / (float)nv : 0.f;
         // the tiles whose cell window contains (cy, cx): up to 3 tile rows x 2 tile columns
         const int ty_hi = min((cy + 1) / LOSS_TY, lt.tiles_y - 1), tx_hi = min((cx + 1) / LOSS_TX, lt.tiles_x - 1);
@@ -182,11 +187,12 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     // ---- write the da2 tile: position-major rows and channel-major 8-position groups
     for (int q = tid; q < BP * (C2 / 8); q += 256) {
         const int p = q / (C2 / 8), part8 = q % (C2 / 8);
-        if (m0 + p < PP)
+        if (m0 + p < m_end)
             *(uint4*)(da2 + (size_t)(m0 + p) * C2 + part8 * 8) = *(const uint4*)(Os + p * OLD + part8 * 8);
     }
     for (int q = tid; q < (BP / 8) * C2; q += 256) {
         const int o = q % C2, pg = q / C2;
+        if (m0 + pg * 8 >= m_end) continue;
         bf16x8 ov;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ov[e] = Os[(pg * 8 + e) * OLD + o];
@@ -194,7 +200,8 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     }
 }
 
-int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions(), C3B_BP); }
+// blocks (and partial-sum slots) per head
+int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions() / g.heads(), C3B_BP); }
 size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
@@ -202,10 +209,11 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
                     bf16* da2, bf16* da2T, float* part)
 {
     const Geo& g = p.g;
-    const dim3 grid(conv3_bwd_blocks(g));
+    const int grp_blocks = conv3_bwd_blocks(g);
+    const dim3 grid(g.heads() * grp_blocks);
     const int CP = (g.C + 3) / 4 * 4;   // class padding of the loss kernel's slots
 #define ST_C3B(C2) ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2>), grid, dim3(256), 0, slots, T, n_valid, CP, \
-                             p.lt, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard)
+                             p.lt, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard, grp_blocks)
     switch (g.c2) {
     case 64: ST_C3B(64); break;
     case 128: ST_C3B(128); break;

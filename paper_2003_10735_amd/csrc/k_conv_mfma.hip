@@ -67,6 +67,11 @@ struct ConvArgs {
     float* dense;
     int PP, Hp, Wp, h, w, cin, cout, PPT, guard;
     int m_tiles, n_tiles, tiles_per_xcd;
+    // Several heads: positions [k * grp_pp, (k + 1) * grp_pp) use weight set k (Wq, bias and W3q
+    // advance by wq_stride, bias_stride, w3_stride elements per set); position tiles are counted
+    // per set (grp_tiles each) so that no tile mixes two sets.  One head: grp_pp = PP.
+    int grp_pp, grp_tiles;
+    size_t wq_stride, bias_stride, w3_stride;
 };
 
 // TAG only gives every call site (layer 1 forward, layer 2 forward, layer 2 data-gradient) a
@@ -89,7 +94,9 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     const int tile = xcd * a.tiles_per_xcd + slot;
     if (slot >= a.tiles_per_xcd || tile >= a.m_tiles * a.n_tiles) return;
     const int mt = tile / a.n_tiles, nt = tile % a.n_tiles;
-    const int m0 = mt * CV_BM, n0 = nt * CV_BN;
+    const int grp = mt / a.grp_tiles;
+    const int m0 = grp * a.grp_pp + (mt - grp * a.grp_tiles) * CV_BM, n0 = nt * CV_BN;
+    const int m_end = (grp + 1) * a.grp_pp;     // results from here on belong to another tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave & 1, kgrp = wave >> 1;
@@ -107,7 +114,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // this wavefront's block of 32 output channels (clamped: a half tile beyond cout computes
     // a copy of the last block and drops it in the epilogue)
     const int nb = min((n0 >> 5) + wn, (a.cout >> 5) - 1);
-    const bf16* wbase = a.Wq + ((size_t)nb * 9 * kfr + kgrp) * 512 + lane * 8;
+    const bf16* wbase = a.Wq + grp * a.wq_stride + ((size_t)nb * 9 * kfr + kgrp) * 512 + lane * 8;
 
     u32x4 xr[2][XS_PER_T];   // activations on their way to LDS
     u32x4 wr[2][3];          // weight fragments of the three taps of a stage
@@ -236,7 +243,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         const int frame = a.Hp * a.Wp;
         const int mp = m0 + kgrp * 32 + l32;
         const int img = mp / frame, rr = mp - img * frame, y = rr / a.Wp, x = rr - y * a.Wp;
-        if (mp < a.PP && y >= 1 && y <= a.h && x >= 1 && x <= a.w) {
+        if (mp < m_end && y >= 1 && y <= a.h && x >= 1 && x <= a.w) {
             float* dst = a.dense + ((size_t)img * a.cout * a.h + (y - 1)) * a.w + (x - 1);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -251,7 +258,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // now so that they arrive while the tile is being staged
     u32x4 w3f[4];
     if (EPI == 2) {
-        const bf16* w3row = a.W3q + (size_t)min(l32, a.n_cls - 1) * a.cout + n0 + lhi * 8;
+        const bf16* w3row = a.W3q + grp * a.w3_stride + (size_t)min(l32, a.n_cls - 1) * a.cout + n0 + lhi * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const u32x4 v = *(const u32x4*)(w3row + ks * 16);
@@ -267,7 +274,8 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         const int p = kgrp * 32 + l32;
         const int mp = m0 + p;
         const int rr = mp % frame, y = rr / a.Wp, x = rr - y * a.Wp;
-        const bool inside = mp < a.PP && y >= 1 && y <= a.h && x >= 1 && x <= a.w;
+        const bool inside = mp < m_end && y >= 1 && y <= a.h && x >= 1 && x <= a.w;
+        const float* bias = (EPI == 0 || EPI == 2) ? a.bias + grp * a.bias_stride : nullptr;
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             const int c = wn * 32 + rg * 8 + lhi * 4;   // channel inside the tile
@@ -276,7 +284,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = mine[rg * 4 + e];
             if (EPI == 0 || EPI == 2) {
-                const float4 b = *(const float4*)(a.bias + cg);
+                const float4 b = *(const float4*)(bias + cg);
                 v[0] = fmaxf(v[0] + b.x, 0.f); v[1] = fmaxf(v[1] + b.y, 0.f);
                 v[2] = fmaxf(v[2] + b.z, 0.f); v[3] = fmaxf(v[3] + b.w, 0.f);
             } else {
@@ -303,7 +311,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
             zacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w3f[ks]), xf, zacc, 0, 0, 0);
         }
         const int mp = m0 + wave * 32 + l32;
-        if (mp < a.PP) {
+        if (mp < m_end) {
             float* zrow = a.zpart + ((size_t)nt * a.PP + mp) * 32 + lhi * 4;
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq)
@@ -315,7 +323,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         // position-major: 16 bytes = 8 channels of one position
         for (int q = tid; q < CV_BM * (CV_BN / 8); q += NT) {
             const int p = q / (CV_BN / 8), part = q % (CV_BN / 8);
-            if (m0 + p < a.PP && part * 8 < n_valid)
+            if (m0 + p < m_end && part * 8 < n_valid)
                 *(uint4*)(a.Y + (size_t)(m0 + p) * a.cout + n0 + part * 8) = *(const uint4*)(Os + p * CV_OLD + part * 8);
         }
     }
@@ -323,7 +331,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         // channel-major: 16 bytes = 8 consecutive positions of one channel
         for (int q = tid; q < (CV_BM / 8) * CV_BN; q += NT) {
             const int c = q % CV_BN, pg = q / CV_BN;
-            if (c < n_valid) {
+            if (c < n_valid && m0 + pg * 8 < m_end) {
                 bf16x8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = Os[(pg * 8 + e) * CV_OLD + c];
@@ -342,13 +350,21 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
                   const bf16* mask, bf16* Y, bf16* YT, int cin, int cout, int epi, int layer, const bf16* W3q,
                   float* zpart, float* dense)
 {
+    const Geo& g = p.g;
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
     a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C; a.dense = dense;
     a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.h = p.g.h; a.w = p.g.w;
     a.cin = cin; a.cout = cout;
     a.PPT = p.PPT; a.guard = p.guard;
-    a.m_tiles = cdiv(a.PP, CV_BM);
+    // several heads: one weight set per frame (Wq holds them back to back, the biases sit
+    // head_stride floats apart inside the parameter vectors, W3q back to back)
+    a.grp_pp = g.grouped ? g.Hp * g.Wp : a.PP;
+    a.grp_tiles = cdiv(a.grp_pp, CV_BM);
+    a.wq_stride = (size_t)cin * cout * 9;
+    a.bias_stride = p.head_stride;
+    a.w3_stride = (size_t)g.C * cout;
+    a.m_tiles = g.heads() * a.grp_tiles;
     a.n_tiles = cdiv(cout, CV_BN);
     const int tiles = a.m_tiles * a.n_tiles;
     a.tiles_per_xcd = cdiv(tiles, 8);

@@ -120,10 +120,13 @@ void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, 
 //   internal (o*9 + tap)*ci + i   <->   external (o*ci + i)*9 + tap.
 __global__ void __launch_bounds__(256)
 k_permute_params(const float* __restrict__ src, float* __restrict__ dst, ParamOffsets po,
-                 int ci1, int ci2, int dir)
+                 int ci1, int ci2, int dir, size_t head_stride)
 {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= po.total) return;
+    // one head per blockIdx.y: internal blocks head_stride floats apart, external ones back to back
+    src += blockIdx.y * (dir == 0 ? po.total : head_stride);
+    dst += blockIdx.y * (dir == 0 ? head_stride : po.total);
     size_t e = j;
     if (j < po.b1) {
         const size_t r = j - po.W1;
@@ -141,7 +144,8 @@ k_permute_params(const float* __restrict__ src, float* __restrict__ dst, ParamOf
 void permute_params(Ctx& c, const Plan& p, const float* src, float* dst, int dir)
 {
     ST_LAUNCH(c, dir == 0 ? "params_to_internal" : "params_from_internal", k_permute_params,
-              dim3(cdiv(p.po.total, 256)), dim3(256), 0, src, dst, p.po, p.g.c_in, p.g.c1, dir);
+              dim3(cdiv(p.po.total, 256), p.g.heads()), dim3(256), 0, src, dst, p.po, p.g.c_in, p.g.c1, dir,
+              p.head_stride);
 }
 
 }  // namespace st

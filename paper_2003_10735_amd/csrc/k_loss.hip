@@ -120,7 +120,7 @@ k_label_adjoint(const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
     }
     __syncthreads();
     if (n_valid && tid == 0)
-        atomicAdd(n_valid, (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
+        atomicAdd(n_valid + g.head_of(img), (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
     for (int i = tid; i < g.C * LOSS_TX; i += 256) {
         const int lc = i % LOSS_TX, c = i / LOSS_TX;
         const int cx = tx * LOSS_TX + lc;
@@ -186,7 +186,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
             }
             zq[k] = acc;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) bq[k][e] = zs.b3[min(chunk * 4 + e, C - 1)];
+            for (int e = 0; e < 4; ++e) bq[k][e] = zs.b3[g.head_of(img) * zs.b3_stride + min(chunk * 4 + e, C - 1)];
         }
     } else {
 #pragma unroll

@@ -45,11 +45,17 @@ struct UpdateArgs {
     // block ranges; vec: role (1) handles four parameters per thread over [0, W3) and nb_tail
     // blocks handle [W3, total) one by one unless role (2) does
     int nb_main, nb_tail, nb_l3, nb_finish, vec;
+    // several heads (blockIdx.y): floats / elements from one head's block to the next in the
+    // parameter-like vectors (theta, vel, vel2), the caller's vectors, the partial gradients,
+    // the bfloat16 copies and the layer-3 slots
+    size_t hs_param, hs_ext, hs_grad, hs_wq1, hs_wq2, hs_wq3, hs_part3;
 };
 
 struct FinishArgs {
     const float* loss_part; int n_part; const unsigned long long* n_valid; unsigned long long* conf;
     int n, C; float* loss_out; double* miou_a; double* miou_b; long long* conf_out;
+    // per head (blockIdx.y): fph frames and pph tile losses; one head owns all of them
+    int fph, pph;
 };
 
 // index in the caller's vector (3x3 weights OIHW) of the internal parameter j ([o][kh][kw][i])
@@ -169,17 +175,18 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
     }
 }
 
-__device__ void finish_block(const FinishArgs& f, int block)
+__device__ void finish_block(const FinishArgs& f, int block, int head)
 {
     __shared__ double part[256];
     __shared__ unsigned long long cl[32 * 32];
     __shared__ double iou[32];
     __shared__ int present[32];
     const int tid = threadIdx.x;
-    if (block == f.n) {
+    if (block == f.fph) {
         double acc = 0.0;
-        const int per = (f.n_part + 255) / 256;
-        for (int i = tid * per; i < min(f.n_part, (tid + 1) * per); ++i) acc += (double)f.loss_part[i];
+        const int per = (f.pph + 255) / 256;
+        const float* lp = f.loss_part + (size_t)head * f.pph;
+        for (int i = tid * per; i < min(f.pph, (tid + 1) * per); ++i) acc += (double)lp[i];
         part[tid] = acc;
         __syncthreads();
         for (int s = 128; s > 0; s >>= 1) {
@@ -187,11 +194,12 @@ __device__ void finish_block(const FinishArgs& f, int block)
             __syncthreads();
         }
         if (tid == 0 && f.loss_out) {
-            const unsigned long long nv = *f.n_valid;
-            *f.loss_out = nv ? (float)(part[0] / (double)nv) : 0.f;
+            const unsigned long long nv = f.n_valid[head];
+            f.loss_out[head] = nv ? (float)(part[0] / (double)nv) : 0.f;
         }
         return;
     }
+    block += head * f.fph;      // the frame
     const int C = f.C;
     unsigned long long* cf = f.conf + (size_t)block * C * C;
     for (int i = tid; i < C * C; i += 256) {
@@ -225,6 +233,17 @@ __device__ void finish_block(const FinishArgs& f, int block)
 __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
 {
     const int b = blockIdx.x;
+    const int head = blockIdx.y;
+    if (head) {
+        if (a.theta) { a.theta += head * a.hs_param; a.vel += head * a.hs_param; a.vel2 += head * a.hs_param; }
+        if (a.grad) a.grad += head * a.hs_grad;
+        if (a.wq1) { a.wq1 += head * a.hs_wq1; a.wq2 += head * a.hs_wq2; a.wq3 += head * a.hs_wq3; }
+        if (a.wq1t) a.wq1t += head * a.hs_wq1;
+        if (a.wq2t) a.wq2t += head * a.hs_wq2;
+        if (a.ext_in) a.ext_in += head * a.hs_ext;
+        if (a.ext_out) a.ext_out += head * a.hs_ext;
+        if (a.part3) a.part3 += head * a.hs_part3;
+    }
     if (b < a.nb_main) {
         // role (1), four parameters per thread over [0, W3): the partial gradients are added in
         // ascending order of the split, four loads in flight at a time
@@ -280,7 +299,7 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
         }
         if (lane == 0) apply_update(a, a.po.W3 + k, acc);
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish) {
-        finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3);
+        finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3, head);
     } else {
         // parameters back to the caller's order
         const size_t j = (size_t)(b - a.nb_main - a.nb_tail - a.nb_l3 - a.nb_finish) * 256 + threadIdx.x;
@@ -296,11 +315,24 @@ static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* 
     f.n_valid = (const unsigned long long*)(ws + p.counters);
     f.conf = (unsigned long long*)(ws + p.conf);
     f.n = p.g.n; f.C = p.g.C;
+    f.fph = p.g.n / p.g.heads();
+    f.pph = f.n_part / p.g.heads();
     f.loss_out = loss_out;
     f.miou_a = (double*)(ws + p.scal);   // per-frame metric kept in the workspace (host-side loop exits)
     f.miou_b = miou_out;                 // the caller's array (may be null)
     f.conf_out = conf_out;
     return f;
+}
+
+static void head_strides(UpdateArgs& a, const Plan& p)
+{
+    a.hs_param = p.head_stride;
+    a.hs_ext = p.po.total;
+    a.hs_grad = p.grad_stride * p.grad_copies;
+    a.hs_wq1 = p.po.b1 - p.po.W1;
+    a.hs_wq2 = p.po.b2 - p.po.W2;
+    a.hs_wq3 = p.po.b3 - p.po.W3;
+    a.hs_part3 = (size_t)p.blocks3 * conv3_bwd_slot_floats(p.g);
 }
 
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
@@ -342,12 +374,13 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
         a.nb_tail = 0;
     }
     a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 4) : 0;
-    a.nb_finish = finish ? p.g.n + 1 : 0;
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    a.nb_finish = finish ? f.fph + 1 : 0;
+    head_strides(a, p);
     const int blocks = a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
     if (blocks == 0) return;
     const char* name = a.ext_in ? "params_in+weights_to_bf16" : do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
-    ST_LAUNCH(c, name, k_step_end, dim3(blocks), dim3(256), 0, a, f);
+    ST_LAUNCH(c, name, k_step_end, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
 }
 
 // takes the caller's parameters (OIHW order) into theta and refreshes the bfloat16 copies
@@ -363,16 +396,17 @@ void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_
 {
     UpdateArgs a;
     memset(&a, 0, sizeof(a));
-    a.nb_finish = p.g.n + 1;
+    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    a.nb_finish = f.fph + 1;
+    head_strides(a, p);
     if (ext_out) {
         a.theta = (float*)(ws + p.theta);
         a.po = p.po; a.c_in = p.g.c_in; a.c1 = p.g.c1; a.c2 = p.g.c2;
         a.ext_out = ext_out;
         a.nb_out = cdiv(p.po.total, 256);
     }
-    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
-    ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end, dim3(a.nb_finish + a.nb_out),
-              dim3(256), 0, a, f);
+    ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end,
+              dim3(a.nb_finish + a.nb_out, p.g.heads()), dim3(256), 0, a, f);
 }
 
 // Mean IoU (Eq. 1) of a C x C table of counts, any C up to 256: one wavefront per class adds

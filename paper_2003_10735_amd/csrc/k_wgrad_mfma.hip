@@ -36,8 +36,13 @@ struct WgradArgs {
     size_t split_stride;
     int cin, cout, PPT, guard, Wp;
     int units_per_wave;   // 16-position units per wavefront
-    int n_units;          // total units
+    int n_units;          // units of one head's positions
     int o_tiles, i_tiles, splits, items_per_xcd;
+    // Several heads: head k owns the positions from 8-position group k * head_groups8 on and
+    // writes its partial copies head_out_stride floats after head k - 1.  (A head's last unit may
+    // reach into the next frame's first row: dY is zero there, like on every border.)
+    int heads, head_groups8;
+    size_t head_out_stride;
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -61,8 +66,9 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     // positions (all channels) instead of every position of a few channels
     const int tiles = a.o_tiles * a.i_tiles;
     const int item = (bid % 8) * a.items_per_xcd + bid / 8;     // blocks1 is a multiple of 8
-    if (bid / 8 >= a.items_per_xcd || item >= tiles * a.splits) return;
-    const int split = item / tiles, tile = item % tiles;
+    if (bid / 8 >= a.items_per_xcd || item >= tiles * a.splits * a.heads) return;
+    const int hsplit = item / tiles, tile = item % tiles;
+    const int head = hsplit / a.splits, split = hsplit - head * a.splits;
     // output-channel tile fastest: the blocks that stream the same X rows (same split, same
     // input-channel tile) are neighbours in the order, run on one XCD and share them in its L2
     const int ot = tile % a.o_tiles, it = tile / a.o_tiles;
@@ -80,8 +86,9 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     // blocked layout: one 8-position group of 32 channels is 256 elements; lane (l32, lhi) reads
     // channel l32 of group 2u + lhi, so a wavefront's fragment load is one contiguous kilobyte
     const int NG = a.PPT >> 3;
-    const bf16* ya = a.dYT + (((size_t)(o0 >> 5) * NG + (a.guard >> 3) + lhi) << 8) + l32 * 8;
-    const bf16* xb = a.XT + (((size_t)(i0 >> 5) * NG + (a.guard >> 3) + lhi) << 8) + l32 * 8;
+    const int g0 = (a.guard >> 3) + head * a.head_groups8;     // this head's first 8-position group
+    const bf16* ya = a.dYT + (((size_t)(o0 >> 5) * NG + g0 + lhi) << 8) + l32 * 8;
+    const bf16* xb = a.XT + (((size_t)(i0 >> 5) * NG + g0 + lhi) << 8) + l32 * 8;
     const int row_groups = a.Wp >> 3;   // one kernel row = this many 8-position groups
     const bool want_bias = it == 0;
     const int swap_addr = (lane ^ 32) << 2;   // ds_bpermute address of the lane holding the other half
@@ -247,7 +254,7 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     // every row of acc[9] holds the sums over the positions: row 0 lives in lanes 0 .. 31
     if (want_bias && lhi == 0) redb[wave * 32 + l32] = acc[9][0];
     __syncthreads();
-    float* dW = a.dW + (size_t)split * a.split_stride;
+    float* dW = a.dW + head * a.head_out_stride + (size_t)split * a.split_stride;
     for (int q = tid; q < 9 * 32 * 8; q += 256) {
         const int row = q >> 3, part = q & 7;
         const int t = row >> 5, ol = row & 31;
@@ -260,7 +267,7 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
         *(f32x4*)(dW + ((size_t)(o0 + ol) * 9 + t) * a.cin + i0 + part * 4) = sum;
     }
     if (want_bias && tid < 32) {
-        float* db = a.db + (size_t)split * a.split_stride;
+        float* db = a.db + head * a.head_out_stride + (size_t)split * a.split_stride;
         db[o0 + tid] = ((redb[tid] + redb[32 + tid]) + redb[64 + tid]) + redb[96 + tid];
     }
 }
@@ -273,8 +280,9 @@ bool wgrad3x3_mfma_supported(int cin, int cout) { return cin % 32 == 0 && cout %
 void wgrad_splits_for(const Geo& g, int* s1_out, int* s2_out)
 {
     const int n_cu = 256;
-    const int tiles1 = (g.c1 / 32) * (g.c_in / 32), tiles2 = (g.c2 / 32) * (g.c1 / 32);
-    const int n_units = cdiv(g.padded_positions(), 16);
+    // (with several heads every head brings its own set of blocks and its own positions)
+    const int tiles1 = g.heads() * (g.c1 / 32) * (g.c_in / 32), tiles2 = g.heads() * (g.c2 / 32) * (g.c1 / 32);
+    const int n_units = cdiv(g.padded_positions() / g.heads(), 16);
     int best1 = 1, best2 = 1;
     long best_cost = -1;
     for (int s1 = 1; s1 <= 16; ++s1) {
@@ -298,11 +306,14 @@ static WgradArgs wgrad_args(const Plan& p, const bf16* dYT, const bf16* XT, floa
     a.dYT = dYT; a.XT = XT; a.dW = dW; a.db = db;
     a.split_stride = p.grad_stride;
     a.cin = cin; a.cout = cout; a.PPT = p.PPT; a.guard = p.guard; a.Wp = p.g.Wp;
-    a.n_units = cdiv(p.g.padded_positions(), 16);
+    a.heads = p.g.heads();
+    a.n_units = cdiv(p.g.padded_positions() / a.heads, 16);
+    a.head_groups8 = p.g.Hp * p.g.Wp / 8;
+    a.head_out_stride = p.grad_stride * p.grad_copies;
     a.units_per_wave = cdiv(a.n_units, splits * 4);
     a.o_tiles = cout / 32; a.i_tiles = cin / 32;
     a.splits = splits;
-    a.items_per_xcd = cdiv(a.o_tiles * a.i_tiles * splits, 8);
+    a.items_per_xcd = cdiv(a.o_tiles * a.i_tiles * splits * a.heads, 8);
     return a;
 }
 

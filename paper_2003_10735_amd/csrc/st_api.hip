@@ -80,6 +80,7 @@ static int validate(const st_head_desc* d)
     if (d->feat_layout != ST_NCHW) return ST_ERR_ARG;
     if (d->compute != ST_COMPUTE_F32 && d->compute != ST_COMPUTE_BF16) return ST_ERR_ARG;
     if (d->ignore_index < -1) return ST_ERR_ARG;
+    if (d->grouped != 0 && d->grouped != 1) return ST_ERR_ARG;
     // 32-bit indexing inside the kernels
     const long long cmax = std::max(std::max(d->c_in, d->c1), std::max(d->c2, d->n_classes));
     const long long pp = (long long)d->n * (d->h + 2) * (d->w + 2 + 8);
@@ -87,6 +88,12 @@ static int validate(const st_head_desc* d)
     if ((long long)d->n * d->h * d->w * UP * UP >= (1ll << 31)) return ST_ERR_SHAPE;
     if ((long long)d->c1 * d->c_in * 9 >= (1ll << 28) || (long long)d->c2 * d->c1 * 9 >= (1ll << 28))
         return ST_ERR_SHAPE;
+    if (d->grouped) {
+        // one head per frame: matrix-core kernels only, and all heads' parameters in 32-bit reach
+        if (!make_plan(*d).mfma) return ST_ERR_SHAPE;
+        if ((long long)d->n * ((long long)d->c1 * d->c_in * 9 + (long long)d->c2 * d->c1 * 9) >= (1ll << 30))
+            return ST_ERR_SHAPE;
+    }
     return ST_OK;
 }
 
@@ -141,28 +148,30 @@ Plan make_plan(const st_head_desc& d)
     }
     p.zero_end = off;
     const size_t hw = (size_t)g.h * g.w;
+    const size_t heads = (size_t)g.heads();
     p.z = take(off, (size_t)g.n * g.C * hw * 4);
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
     p.tadj = take(off, (size_t)g.n * g.C * hw * 4);
     p.z_parts = p.mfma ? g.c2 / 64 : 0;
     if (p.mfma) p.zpart = take(off, (size_t)p.z_parts * PP * 32 * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
-    p.theta = take(off, p.po.total * 4);
-    p.vel = take(off, p.po.total * 4);
-    p.vel2 = take(off, p.po.total * 4);
     p.grad_stride = (p.po.total + 3) / 4 * 4;
-    p.grad = take(off, p.grad_stride * 4 * p.grad_copies);
-    p.grad3 = take(off, (size_t)std::max(p.blocks3, 1) * conv3_bwd_slot_floats(g) * 4);
-    p.best = take(off, p.po.total * 4);
+    p.head_stride = p.grad_stride;
+    p.theta = take(off, heads * p.head_stride * 4);
+    p.vel = take(off, heads * p.head_stride * 4);
+    p.vel2 = take(off, heads * p.head_stride * 4);
+    p.grad = take(off, heads * p.grad_stride * 4 * p.grad_copies);
+    p.grad3 = take(off, heads * std::max(p.blocks3, 1) * conv3_bwd_slot_floats(g) * 4);
+    p.best = take(off, heads * p.head_stride * 4);
     if (p.bf16) {
-        p.wq1 = take(off, (p.po.b1 - p.po.W1) * 2);
-        p.wq1t = take(off, (p.po.b1 - p.po.W1) * 2);
-        p.wq2 = take(off, (p.po.b2 - p.po.W2) * 2);
-        p.wq2t = take(off, (p.po.b2 - p.po.W2) * 2);
-        p.wq3 = take(off, (p.po.b3 - p.po.W3) * 2);
+        p.wq1 = take(off, heads * (p.po.b1 - p.po.W1) * 2);
+        p.wq1t = take(off, heads * (p.po.b1 - p.po.W1) * 2);
+        p.wq2 = take(off, heads * (p.po.b2 - p.po.W2) * 2);
+        p.wq2t = take(off, heads * (p.po.b2 - p.po.W2) * 2);
+        p.wq3 = take(off, heads * (p.po.b3 - p.po.W3) * 2);
     }
     p.loss_part = take(off, (size_t)loss_blocks(g) * 4);
-    p.counters = take(off, 256);                       // [0] number of valid pixels
+    p.counters = take(off, std::max((size_t)256, heads * 8));   // valid pixels (their weights), one count per head
     p.conf = take(off, (size_t)g.n * g.C * g.C * 8);
     p.scal = take(off, (size_t)g.n * 8);               // per-frame mean IoU of the last pass (double)
     p.total = off;
@@ -209,7 +218,7 @@ static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
                 z.add(ws + tm[i] + b * blk + tail_at, blk - tail_at);
             }
     }
-    z.add(ws + p.counters, 256);
+    z.add(ws + p.counters, std::max((size_t)256, (size_t)g.heads() * 8));
     z.add(ws + p.conf, (size_t)g.n * g.C * g.C * 8);
     zero_regions(c, z);
 }
@@ -234,6 +243,7 @@ static ZSrc z_source(const Plan& p, char* ws, float* z)
 {
     ZSrc zs;
     zs.planar = z; zs.parts = nullptr; zs.n_parts = 0; zs.b3 = nullptr; zs.z_out = nullptr;
+    zs.b3_stride = p.head_stride;
     if (p.mfma) {
         zs.planar = nullptr;
         zs.parts = (const float*)(ws + p.zpart); zs.n_parts = p.z_parts;
@@ -358,6 +368,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     }
     if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
     const bool early_exit = threshold > 0.0;
+    // several heads take the same steps: no per-head loop exits, no feature gradient
+    if (desc->grouped && (early_exit || feature_grad)) return ST_ERR_ARG;
 
     const Plan p = make_plan(*desc);
     const Geo& g = p.g;
@@ -394,7 +406,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);
-        float* loss_out = (out && out->losses) ? out->losses + it : nullptr;
+        float* loss_out = (out && out->losses) ? out->losses + (size_t)it * g.heads() : nullptr;
         double* miou_out = (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr;
         long long* conf_out = (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr;
         // The bookkeeping of this pass (loss, per-frame mIoU, clearing the counts) normally rides

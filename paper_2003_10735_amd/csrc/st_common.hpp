@@ -27,6 +27,9 @@ struct Geo {
     int H, W;        // frame resolution: 8h, 8w
     int c_in, c1, c2, C;
     int ignore_index;
+    int grouped;     // 1: frame f has a head (parameters, loss, pixel count) of its own
+    __host__ __device__ int heads() const { return grouped ? n : 1; }
+    __host__ __device__ int head_of(int img) const { return grouped ? img : 0; }
     __host__ __device__ int positions() const { return n * h * w; }
     __host__ __device__ int padded_positions() const { return n * Hp * Wp; }
     __host__ __device__ long long pixels() const { return (long long)n * H * W; }
@@ -40,6 +43,7 @@ inline Geo make_geo(const st_head_desc& d)
     g.H = d.h * UP; g.W = d.w * UP;
     g.c_in = d.c_in; g.c1 = d.c1; g.c2 = d.c2; g.C = d.n_classes;
     g.ignore_index = d.ignore_index;
+    g.grouped = d.grouped ? 1 : 0;
     return g;
 }
 
@@ -96,10 +100,15 @@ struct Plan {
     bool bf16;          // compute path
     size_t esz;         // bytes per activation element
     bool mfma;          // bf16 path on the matrix-core kernels (else the plain tiled kernels)
-    int splits1, splits2;   // position splits of the layer-1 / layer-2 weight-gradient kernels
-    int blocks3;            // per-block partial slots of the layer-3 backward kernel
+    // With several heads (Geo::grouped) every per-head buffer holds heads() consecutive blocks:
+    // theta, vel, vel2, best (head_stride floats apart), grad (grad_copies * grad_stride floats
+    // apart), grad3 (blocks3 slots apart), the bfloat16 weight copies (their own size apart),
+    // the pixel counters (one each).
+    int splits1, splits2;   // position splits (per head) of the layer-1 / layer-2 weight-gradient kernels
+    int blocks3;            // per-block partial slots (per head) of the layer-3 backward kernel
     int grad_copies;        // max(splits1, splits2): partial gradient copies the update sums
     size_t grad_stride;     // floats between two copies (total rounded up to 16 bytes)
+    size_t head_stride;     // floats between two heads' parameters (total rounded up to 16 bytes)
     int guard;          // guard rows before and after every position-major activation buffer;
                         // also the number of guard columns in front of a channel-major row
     int PPT;            // row pitch (elements) of the channel-major copies

@@ -51,6 +51,7 @@ void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, const uint8_t* p
 struct ZSrc {
     const float* planar;
     const float* parts; int n_parts; const float* b3; float* z_out;
+    size_t b3_stride;     // floats between the biases of two heads (one head per frame)
 };
 void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* pixel_weights,
                const float* T, uint8_t* pred,
@@ -58,6 +59,8 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, cons
                const unsigned long long* n_valid, bool grad, bool assemble);
 
 // k_update.hip
+// (every per-head quantity below -- parameters, optimiser state, partial gradients, weight copies,
+//  the caller's vectors -- holds Geo::heads() blocks; the kernels take the head from blockIdx.y)
 // One Adam step's constants, prepared on the host in double precision:
 //   theta <- theta - step_scale * m / (sqrt(v) * inv_sqrt_bc2 + eps),
 //   step_scale = lr / (1 - beta1^t),  inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).

@@ -57,6 +57,21 @@ def test_bad_descriptors_are_rejected_on_the_host(field, value, status):
     assert L.st_partial_distill(C.byref(cd), dummy, dummy, dummy, 1, 0.1, None, None, dummy, None) == status
 
 
+def test_grouped_descriptor_sizes_and_limits():
+    """One head per frame: the per-head parameter count stays, the workspace holds n heads, and
+    shapes off the matrix-core kernels are refused."""
+    one = st.HeadDesc(4, 256, 90, 160, 128, 128, 19)
+    grp = st.HeadDesc(4, 256, 90, 160, 128, 128, 19, grouped=1)
+    assert st.st_num_params(grp) == st.st_num_params(one) == 445075
+    extra = st.st_workspace_bytes(grp) - st.st_workspace_bytes(one)
+    assert extra >= 3 * 445075 * 4 * 4            # theta, two state vectors, gradient copies of 3 more heads
+    assert st.st_workspace_bytes(st.HeadDesc(1, 256, 90, 160, 128, 128, 19, grouped=1)) > 0
+    # float32 compute, or channel counts the matrix-core kernels do not take
+    assert st.st_workspace_bytes(st.HeadDesc(2, 64, 16, 16, 64, 64, 9, st.ST_F32, st.ST_COMPUTE_F32, grouped=1)) == 0
+    assert st.st_workspace_bytes(st.HeadDesc(2, 20, 16, 16, 24, 16, 9, grouped=1)) == 0
+    assert st.st_workspace_bytes(st.HeadDesc(2, 64, 16, 16, 64, 64, 9, grouped=2)) == 0
+
+
 def test_null_and_argument_errors():
     L = st.lib()
     cd = good().c()

@@ -64,3 +64,16 @@ def test_720p_feature_gradient():
     """The full backward pass (what partial distillation leaves out) at the benchmark's shape."""
     from test_gpu_parity import check_feature_grad
     check_feature_grad(WL.WORKLOADS["720p"], True, 5e-3)
+
+
+def test_720p_four_clients_grouped():
+    """Four clients' key frames and heads in one call, in the launch configuration the benchmark
+    times for the grouped form; every head against its own single-frame oracle run."""
+    import oracle as O
+    from test_gpu_grouped import SGD, check_against_oracle, inputs, run_grouped
+    wl = WL.small_variant(WL.WORKLOADS["720p"], n=4)
+    f, lab, p = inputs(wl)
+    g = run_grouped(wl, f, lab, p, 2)
+    o = O.partial_distill_grouped(O.desc_of(wl, True), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 2, SGD(wl))
+    print("grouped losses", g["losses"].T, "oracle", o["losses"].T)
+    check_against_oracle(wl, g, o, p)

@@ -275,3 +275,33 @@ def test_feature_gradient_against_autograd_and_finite_differences():
         lp = O.loss_and_grad(d, f + e, lab, p, want_grad=False)[0]
         lm = O.loss_and_grad(d, f - e, lab, p, want_grad=False)[0]
         assert abs((lp - lm) / 2e-6 - df[idx]) < 1e-7 + 1e-5 * abs(df[idx])
+
+
+def test_grouped_heads_are_independent_runs():
+    """The grouped form (one head and one frame per client, Algorithm 3) is n separate runs: head
+    f's trace is that of a single-frame run on frame f, whatever the other frames hold, and the
+    per-head columns of the result come in the frames' order."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], n=3, c_in=4, h=3, w=4, c1=5, c2=4, n_classes=3, n_sites=5, steps=2)
+    f = WL.features_as_f64(wl, WL.make_features(wl))
+    lab = WL.make_labels(wl)
+    p = np.stack([WL.make_head_params(wl, seed=11 + i) for i in range(3)]).astype(np.float64)
+    d = O.desc_of(wl)
+    opt = O.Optim(0, 0.05, 0.9, 0, 0, 0, 0)
+    g = O.partial_distill_grouped(d, f, lab, p, 2, opt)
+    assert g["params"].shape == p.shape and g["losses"].shape == (3, 3) and g["mious"].shape == (3, 3)
+    d1 = O.desc(1, wl.c_in, wl.h, wl.w, wl.c1, wl.c2, wl.n_classes)
+    for i in range(3):
+        s = O.partial_distill(d1, f[i:i + 1], lab[i:i + 1], p[i], 2, 0.05, momentum=0.9)
+        np.testing.assert_array_equal(g["params"][i], s["params"])
+        np.testing.assert_array_equal(g["losses"][:, i], s["losses"])
+        np.testing.assert_array_equal(g["mious"][:, i], s["mious"][:, 0])
+        np.testing.assert_array_equal(g["s1"][i], s["velocity"])
+    # other clients' frames do not matter, and it is not the shared-head mini-batch
+    f2, lab2 = f.copy(), lab.copy()
+    f2[1:] *= -0.5
+    lab2[1:] = (lab2[1:] + 1) % wl.n_classes
+    g2 = O.partial_distill_grouped(d, f2, lab2, p, 2, opt)
+    np.testing.assert_array_equal(g2["params"][0], g["params"][0])
+    assert not np.array_equal(g2["params"][1], g["params"][1])
+    shared = O.partial_distill(d, f, lab, p[0], 2, 0.05, momentum=0.9)
+    assert not np.allclose(shared["params"], g["params"][0])
