@@ -9,23 +9,26 @@
 // positions are forced to zero, which keeps the border of the output zero as well).  Guard rows
 // in front of and behind every activation buffer make all reads in-bounds without tests.
 //
-// Block = 512 threads = 8 wavefronts, tile = 128 positions x 64 output channels.  The LDS
-// pipeline is the scarce resource of this kernel (a tile is small, so every byte staged is used
-// only a few times), hence the two operands take different routes:
+// Block = 512 threads = 8 wavefronts, tile = 128 positions x 64 output channels.  A tile is
+// small (every byte staged is used only a few times), and the matrix cores, the LDS read path,
+// the vector-memory path and plain instruction issue are all close to full in the K loop; so the
+// two operands take different routes and the loop is written to issue as little as possible:
 //   * the weights are the MFMA A operand (rows = output channels) and never touch LDS: they are
 //     kept in memory in fragment order (wfrag_index), so a wavefront fetches the fragment it
-//     needs with one coalesced 1 KB load straight into the operand registers, and no two
-//     wavefronts of a block need the same fragment;
+//     needs with one coalesced 1 KB buffer load straight into the operand registers (buffer
+//     descriptor + fixed lane offset + one scalar offset per stage: no address arithmetic), and
+//     no two wavefronts of a block need the same fragment;
 //   * the activations are the B operand (columns = positions) and go through LDS, because the
-//     three taps kw = 0,1,2 of a kernel row read the same slab at row offsets 0,1,2.
+//     three taps kw = 0,1,2 of a kernel row read the same slab at row offsets 0,1,2.  They are
+//     loaded from memory directly into LDS (no registers, no LDS store instructions).
 // Wavefront (wn, kgrp): output channels 32 wn .. +31 of the tile, all 128 positions (four
 // accumulator tiles), and of every 64-channel stage the 16 input channels 16 kgrp .. +15.  The
 // four partial sums per output are exchanged once, through LDS, after the K loop: wavefront
 // (wn, kgrp) ends up owning positions 32 kgrp .. +31 and adds the partials in ascending kgrp.
 // K loop: stages of (one kernel row kh) x (64 input channels): 130 activation rows in LDS (the
-// tile's rows shifted by kh, plus one on each side), rows padded by 16 bytes so that the 16-byte
-// fragment reads of 32 consecutive rows spread over all banks.  Loads run two stages ahead of
-// the matrix cores (global -> registers at stage s-2, registers -> LDS at stage s-1).
+// tile's rows shifted by kh, plus one on each side) of 128 bytes, their 16-byte chunks swizzled
+// by the row number so that the fragment reads of consecutive rows spread over all banks.  Three
+// slabs and three sets of weight registers rotate: loads run two stages ahead of the matrix cores.
 //
 // A lane owns 4 consecutive output channels of one position per register group, which packs
 // into one 8-byte LDS write in the epilogue.  The epilogue stages the tile in LDS and writes it
@@ -41,14 +44,14 @@ namespace st {
 constexpr int CV_BM = 128;
 constexpr int CV_BN = 64;
 constexpr int CV_BK = 64;
-constexpr int CV_LDP = CV_BK + 8;   // LDS row pitch in elements (144 bytes)
+constexpr int CV_NBUF = 3;          // activation slabs in LDS: one in use, two on their way
 constexpr int CV_XS_ROWS = CV_BM + 2;
 constexpr int CV_OLD = CV_BN + 8;   // pitch of the staged output tile
-// dynamic LDS: during the K loop two activation slabs; afterwards the exchanged partial sums
+// dynamic LDS: during the K loop the activation slabs; afterwards the exchanged partial sums
 // (8 owners x 3 sources x 16 registers x 64 lanes, float32) followed by the staged output tile
 constexpr size_t CV_RED_BYTES = (size_t)8 * 3 * 16 * 64 * sizeof(float);
 constexpr size_t CV_SMEM_BYTES = CV_RED_BYTES + (size_t)CV_BM * CV_OLD * sizeof(bf16);
-static_assert((size_t)2 * CV_XS_ROWS * CV_LDP * sizeof(bf16) <= CV_SMEM_BYTES, "K-loop buffers fit");
+static_assert((size_t)CV_NBUF * CV_XS_ROWS * CV_BK * sizeof(bf16) <= CV_SMEM_BYTES, "K-loop buffers fit");
 
 struct ConvArgs {
     const bf16* X;      // [PP][cin] position-major, guards before/after
@@ -81,12 +84,9 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 {
     constexpr int NT = 512;                // threads per block
     // 16-byte chunks per stage: XS_FULL per thread and one more for the first XS_REST threads
-    constexpr int XS_CHUNKS = CV_XS_ROWS * 8;
-    constexpr int XS_FULL = XS_CHUNKS / NT, XS_REST = XS_CHUNKS % NT;
-    constexpr int XS_PER_T = XS_FULL + 1;
-    constexpr int XS_ELEMS = CV_XS_ROWS * CV_LDP;
+    constexpr int XS_BYTES = CV_XS_ROWS * CV_BK * 2;   // one slab: 130 rows of 64 channels, unpadded
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* Xs = (bf16*)smem_raw;                       // [2][XS_ROWS][LDP]
+    // smem_raw during the K loop: [CV_NBUF][XS_ROWS][128 bytes], chunks swizzled
 
     // XCD-aware tile order: consecutive blocks go to different XCDs, so give each XCD a
     // contiguous run of position tiles (neighbours share activation rows in that XCD's L2)
@@ -114,106 +114,138 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // this wavefront's block of 32 output channels (clamped: a half tile beyond cout computes
     // a copy of the last block and drops it in the epilogue)
     const int nb = min((n0 >> 5) + wn, (a.cout >> 5) - 1);
-    const bf16* wbase = a.Wq + grp * a.wq_stride + ((size_t)nb * 9 * kfr + kgrp) * 512 + lane * 8;
 
-    u32x4 xr[2][XS_PER_T];   // activations on their way to LDS
-    u32x4 wr[2][3];          // weight fragments of the three taps of a stage
+    u32x4 wr[3][3];          // weight fragments of the three taps of a stage: in use, and two stages ahead
 
-#define CV_LOAD_X1(SET, S, I)                                                                     \
-    if ((I) < XS_FULL || tid < XS_REST) {                                                         \
-        const int kh_ = (S) / c_chunks, c0_ = ((S) % c_chunks) * CV_BK;                           \
-        const bf16* src_ = a.X + ((long long)m0 - 1 + (long long)(kh_ - 1) * a.Wp) * a.cin + c0_; \
-        const int q = tid + (I) * NT;                                                             \
-        xr[SET][I] = *(const u32x4*)(src_ + (long long)(q >> 3) * a.cin + (q & 7) * 8);           \
-    }
-#define CV_LOAD_X(SET, S) CV_LOAD_X1(SET, S, 0) CV_LOAD_X1(SET, S, 1) CV_LOAD_X1(SET, S, 2)
-#define CV_LOAD_W(SET, S, KW)                                                                     \
+    // ---- activations: global memory -> LDS without passing through registers.  A wavefront-wide
+    // 16-byte load puts lane l's bytes at (LDS base in M0) + 16 l, so one instruction fills eight
+    // consecutive 128-byte rows (64 channels) of a slab.  Rows filled this way cannot be padded;
+    // instead the 16-byte chunk c of row r is kept at chunk position c ^ (r & 7), which spreads
+    // the fragment reads of eight consecutive rows over all banks just as well: the lane that
+    // fills position pc of row r fetches chunk pc ^ (r & 7) from memory.
+    // Wavefront w fills rows 8w .. 8w+7 and 64+8w .. 64+8w+7; wavefront 0 also rows 128, 129.
+    // The loads are written in assembly: the compiler would order every barrier behind all
+    // outstanding loads of this kind, while the pipeline below needs two stages in flight.
+    // (M0 is reserved: the compiler sets it right before each of its own uses and keeps nothing
+    //  in it, and this kernel gives it no such use.)
+    const int lrow = lane >> 3, lpc = lane & 7;
+    const int xo0 = ((wave * 8 + lrow) * a.cin + ((lpc ^ lrow) << 3)) * 2;   // byte offsets inside a slab
+    const int xo1 = xo0 + 64 * a.cin * 2;
+    const int xo2 = ((128 + lrow) * a.cin + ((lpc ^ lrow) << 3)) * 2;
+    const bf16* xg = a.X + ((long long)m0 - 1 - a.Wp) * a.cin;               // first row of the kh = 0 slabs
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave * 1024);   // a scalar: it goes to M0
+    // fragment reads: row J*32 + l32 + KW, chunk kgrp*2 + lhi
+    int rd[3];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) rd[kw] = (l32 + kw) * 128 + (((kgrp * 2 + lhi) ^ ((l32 + kw) & 7)) << 4);
+
+    // The stage being fetched runs two ahead of the one being multiplied.  Its operands are
+    // addressed as (scalar base, advanced once per stage) + (per-lane byte offset, fixed), which
+    // costs no vector instruction and two scalar ones per stage.
+    const char* xsp = (const char*)xg;                                      // activations of the stage
+    // (weights through a buffer descriptor: base in scalar registers, a fixed per-lane offset and
+    //  a scalar offset per stage, so that a weight load needs no address arithmetic at all)
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.Wq + grp * a.wq_stride), 0, (int)(a.wq_stride * 2), 0x00020000);
+    int w_soff = 0;                                                          // weights of the stage
+    unsigned wv[3];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) wv[kw] = (unsigned)((((nb * 9 + kw) * kfr + kgrp) * 512 + lane * 8) * 2);
+    const long long x_step = CV_BK * 2, x_row = ((long long)a.Wp * a.cin - (c_chunks - 1) * CV_BK) * 2;
+    const int w_step = (CV_BK / 16) * 512 * 2, w_row = (2 * kfr + CV_BK / 16) * 512 * 2;
+    int f_cc = 0;
+#define CV_FETCH_NEXT                                                                             \
+    if (++f_cc == c_chunks) { f_cc = 0; xsp += x_row; w_soff += w_row; } else { xsp += x_step; w_soff += w_step; }
+#define CV_DMA(VOFF, LDSADDR)                                                                     \
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(VOFF), "s"(xsp),      \
+                 "s"(LDSADDR) : "memory");
+#define CV_LOAD_X1(BUF, I)                                                                        \
     {                                                                                             \
-        const int kh_ = (S) / c_chunks, kc_ = ((S) % c_chunks) * (CV_BK / 16);                    \
-        wr[SET][KW] = *(const u32x4*)(wbase + ((size_t)(kh_ * 3 + (KW)) * kfr + kc_) * 512);      \
+        if ((I) == 0) CV_DMA(xo0, lds0 + (BUF) * XS_BYTES + wave_lds)                             \
+        if ((I) == 1) CV_DMA(xo1, lds0 + (BUF) * XS_BYTES + 8192 + wave_lds)                      \
+        if ((I) == 2 && wave == 0 && lane < 16) CV_DMA(xo2, lds0 + (BUF) * XS_BYTES + 16384)      \
     }
-#define CV_STORE1(SET, BUF, I)                                                                    \
-    if ((I) < XS_FULL || tid < XS_REST) {                                                         \
-        const int q = tid + (I) * NT;                                                             \
-        *(u32x4*)(Xs + (BUF) * XS_ELEMS + (q >> 3) * CV_LDP + (q & 7) * 8) = xr[SET][I];          \
-    }
+#define CV_LOAD_W(SET, KW) wr[SET][KW] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wv[KW], w_soff, 0);
 #define CV_READ1(DST, J, BUF, KW)                                                                 \
-    DST[J] = *(const bf16x8*)(Xs + (BUF) * XS_ELEMS + ((J) * 32 + l32 + (KW)) * CV_LDP + kgrp * 16 + lhi * 8);
+    DST[J] = *(const bf16x8*)(smem_raw + (BUF) * XS_BYTES + rd[KW] + (J) * 4096);
 #define CV_MMA1(SRC, J, SET, KW)                                                                  \
     acc[J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wr[SET][KW]), SRC[J], acc[J], 0, 0, 0);
-    // One stage S out of LDS buffer BUF and register set SET; meanwhile the activations of
-    // stage S + 2 start their way into set SET, those of stage S + 1 (set 1 - SET) move to the
-    // other buffer, and each weight register is refilled for stage S + 2 as soon as its tap is
-    // done.  The issue order is pinned: the eight wavefronts run in step (a barrier per stage),
-    // so a run of memory instructions would hit the LDS and vector-memory queues from all of
-    // them at once while the matrix cores idle.  Instead every MFMA is followed by at most two
-    // memory instructions, which issue while it executes; the activation fragments of a tap
-    // (fragment sets xa, xb) are read while the tap before it is being multiplied.
-    // (loads and LDS stores are unconditional, with the stage index clamped to the last stage:
-    //  a load under a branch would force a wait for every outstanding load at the join; the
-    //  redundant copies at the tail land where nobody reads any more)
+    // s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)
+#define CV_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | 0x0F70);
+    // One stage out of LDS slab and weight register set B.  With FETCH, the activations and
+    // weights of the stage two ahead start their way into slab / set (B + 2) % 3, which the stage
+    // before this one used last; the loads are spread over the stage, one after every other
+    // MFMA.  Before the barrier that ends the stage every wavefront waits until its own share of
+    // the next stage's slab has landed: everything but the five (wavefront 0: six) loads issued
+    // during this stage, or simply everything when the stage issued none.
 #define CV_F __builtin_amdgcn_sched_barrier(0);
-#define CV_STAGE(S, SET, BUF)                                                                     \
+#define CV_STAGE(B, FETCH)                                                                        \
     {                                                                                             \
-        const int s2_ = min((S) + 2, last);                                                       \
-        CV_READ1(xa, 0, BUF, 0) CV_READ1(xa, 1, BUF, 0) CV_READ1(xa, 2, BUF, 0) CV_READ1(xa, 3, BUF, 0) \
-        CV_READ1(xb, 0, BUF, 1) CV_F                                                              \
-        CV_MMA1(xa, 0, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 0) CV_READ1(xb, 1, BUF, 1) CV_F          \
-        CV_MMA1(xa, 1, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 1) CV_READ1(xb, 2, BUF, 1) CV_F          \
-        CV_MMA1(xa, 2, SET, 0) CV_F CV_LOAD_X1(SET, s2_, 2) CV_READ1(xb, 3, BUF, 1) CV_F          \
-        CV_MMA1(xa, 3, SET, 0) CV_F CV_LOAD_W(SET, s2_, 0) CV_F                                   \
-        CV_MMA1(xb, 0, SET, 1) CV_F CV_READ1(xa, 0, BUF, 2) CV_F                                  \
-        CV_MMA1(xb, 1, SET, 1) CV_F CV_READ1(xa, 1, BUF, 2) CV_F                                  \
-        CV_MMA1(xb, 2, SET, 1) CV_F CV_READ1(xa, 2, BUF, 2) CV_F                                  \
-        CV_MMA1(xb, 3, SET, 1) CV_F CV_READ1(xa, 3, BUF, 2) CV_LOAD_W(SET, s2_, 1) CV_F           \
-        CV_MMA1(xa, 0, SET, 2) CV_F CV_STORE1(1 - (SET), 1 - (BUF), 0) CV_F                       \
-        CV_MMA1(xa, 1, SET, 2) CV_F CV_STORE1(1 - (SET), 1 - (BUF), 1) CV_F                       \
-        CV_MMA1(xa, 2, SET, 2) CV_F CV_STORE1(1 - (SET), 1 - (BUF), 2) CV_F                       \
-        CV_MMA1(xa, 3, SET, 2) CV_F CV_LOAD_W(SET, s2_, 2)                                        \
+        constexpr int N_ = ((B) + 2) % 3;                                                         \
+        CV_READ1(xa, 0, B, 0) CV_READ1(xa, 1, B, 0) CV_READ1(xa, 2, B, 0) CV_READ1(xa, 3, B, 0)   \
+        CV_READ1(xb, 0, B, 1) CV_F                                                                \
+        CV_MMA1(xa, 0, B, 0) CV_F if (FETCH) CV_LOAD_W(N_, 0) CV_READ1(xb, 1, B, 1) CV_F          \
+        CV_MMA1(xa, 1, B, 0) CV_F if (FETCH) CV_LOAD_W(N_, 1) CV_READ1(xb, 2, B, 1) CV_F          \
+        CV_MMA1(xa, 2, B, 0) CV_F if (FETCH) CV_LOAD_W(N_, 2) CV_READ1(xb, 3, B, 1) CV_F          \
+        CV_MMA1(xa, 3, B, 0) CV_F                                                                 \
+        CV_MMA1(xb, 0, B, 1) CV_F if (FETCH) CV_LOAD_X1(N_, 0) CV_READ1(xa, 0, B, 2) CV_F         \
+        CV_MMA1(xb, 1, B, 1) CV_F CV_READ1(xa, 1, B, 2) CV_F                                      \
+        CV_MMA1(xb, 2, B, 1) CV_F if (FETCH) CV_LOAD_X1(N_, 1) CV_READ1(xa, 2, B, 2) CV_F         \
+        CV_MMA1(xb, 3, B, 1) CV_F CV_READ1(xa, 3, B, 2) CV_F                                      \
+        CV_MMA1(xa, 0, B, 2) CV_F if (FETCH) CV_LOAD_X1(N_, 2) CV_F                               \
+        CV_MMA1(xa, 1, B, 2) CV_F                                                                 \
+        CV_MMA1(xa, 2, B, 2) CV_F                                                                 \
+        CV_MMA1(xa, 3, B, 2) CV_F                                                                 \
+        if (FETCH) { CV_FETCH_NEXT CV_VMCNT(5) } else { CV_VMCNT(0) }                             \
         __syncthreads();                                                                          \
     }
-    static_assert(XS_PER_T == 3, "the stage sequence places three activation stores");
 
     bf16x8 xa[4], xb[4];
-    const int last = n_stages - 1;
     {
-        const int s1 = min(1, last);
-        CV_LOAD_X(0, 0)
-        CV_LOAD_W(0, 0, 0) CV_LOAD_W(0, 0, 1) CV_LOAD_W(0, 0, 2)
-        CV_LOAD_X(1, s1)
-        CV_LOAD_W(1, s1, 0) CV_LOAD_W(1, s1, 1) CV_LOAD_W(1, s1, 2)
-        CV_STORE1(0, 0, 0) CV_STORE1(0, 0, 1) CV_STORE1(0, 0, 2)
+        CV_LOAD_W(0, 0) CV_LOAD_W(0, 1) CV_LOAD_W(0, 2)
+        CV_LOAD_X1(0, 0) CV_LOAD_X1(0, 1) CV_LOAD_X1(0, 2)
+        CV_FETCH_NEXT
+        CV_LOAD_W(1, 0) CV_LOAD_W(1, 1) CV_LOAD_W(1, 2)
+        CV_LOAD_X1(1, 0) CV_LOAD_X1(1, 1) CV_LOAD_X1(1, 2)
+        CV_FETCH_NEXT
+        CV_F
+        CV_VMCNT(5)
         __syncthreads();
     }
-    // Two stages per trip, so that register sets and LDS buffers are compile-time choices; an
-    // odd stage count runs its last stage after the loop.  (One loop with an exit in the middle
-    // would do, but the accumulators then live across two different exits and get copied around
-    // every stage.)
-    for (int s = 0; s + 1 < n_stages; s += 2) {
-        CV_STAGE(s, 0, 0)
-        CV_STAGE(s + 1, 1, 1)
+    // the number of stages is a multiple of three (three kernel rows): three stages per trip make
+    // the LDS slab and the weight register set of every stage compile-time choices.  The last
+    // three stages are written out: only the first of them still has something to fetch.
+    for (int s = 0; s + 3 < n_stages; s += 3) {
+        CV_STAGE(0, true)
+        CV_STAGE(1, true)
+        CV_STAGE(2, true)
     }
-    if (n_stages & 1) CV_STAGE(last, 0, 0)
+    CV_STAGE(0, true)
+    CV_STAGE(1, false)
+    CV_STAGE(2, false)
 #undef CV_STAGE
-#undef CV_LOAD_X
+#undef CV_FETCH_NEXT
 #undef CV_LOAD_X1
 #undef CV_LOAD_W
-#undef CV_STORE1
+#undef CV_DMA
 #undef CV_READ1
 #undef CV_MMA1
+#undef CV_VMCNT
 #undef CV_F
 
     // ---- exchange of the partial sums: accumulator tile j of every wavefront goes to the
     //      wavefront (wn, kgrp = j), which adds the four partials in ascending source order
-    float* red = (float*)smem_raw;   // [owner = j * 2 + wn][source slot 0..2][16][64]
+    float* red = (float*)smem_raw;   // [owner = j * 2 + wn][source slot 0..2][4 register groups][64 lanes][4]
     // (all wavefronts are past the last barrier of the K loop: the slabs are free)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (j != kgrp) {
             const int src = kgrp - (kgrp > j ? 1 : 0);
-            float* dst = red + ((size_t)((j * 2 + wn) * 3 + src) * 16) * 64 + lane;
+            float* dst = red + ((size_t)((j * 2 + wn) * 3 + src) * 16) * 64 + lane * 4;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dst[r * 64] = acc[j][r];
+            for (int rq = 0; rq < 4; ++rq)
+                *(f32x4*)(dst + rq * 256) = f32x4{acc[j][rq * 4], acc[j][rq * 4 + 1], acc[j][rq * 4 + 2], acc[j][rq * 4 + 3]};
         }
     }
     f32x16 mine = kgrp == 0 ? acc[0] : kgrp == 1 ? acc[1] : kgrp == 2 ? acc[2] : acc[3];
@@ -225,9 +257,13 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
             f32x16 term;
             if (k == kgrp) term = mine;
             else {
-                const float* srcp = red + ((size_t)((kgrp * 2 + wn) * 3 + (k - (k > kgrp ? 1 : 0))) * 16) * 64 + lane;
+                const float* srcp = red + ((size_t)((kgrp * 2 + wn) * 3 + (k - (k > kgrp ? 1 : 0))) * 16) * 64 + lane * 4;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) term[r] = srcp[r * 64];
+                for (int rq = 0; rq < 4; ++rq) {
+                    const f32x4 v = *(const f32x4*)(srcp + rq * 256);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) term[rq * 4 + e] = v[e];
+                }
             }
             if (k == 0) sum = term;
             else
