@@ -27,7 +27,7 @@
 // (wn, kgrp) ends up owning positions 32 kgrp .. +31 and adds the partials in ascending kgrp.
 // K loop: stages of (one kernel row kh) x (64 input channels): 130 activation rows in LDS (the
 // tile's rows shifted by kh, plus one on each side) of 128 bytes, their 16-byte chunks swizzled
-// by the row number so that the fragment reads of consecutive rows spread over all banks.  Three
+// by the row number so that the fragment reads of 16 consecutive rows spread over all banks.  Three
 // slabs and three sets of weight registers rotate: loads run two stages ahead of the matrix cores.
 //
 // A lane owns 4 consecutive output channels of one position per register group, which packs
@@ -120,25 +120,28 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // ---- activations: global memory -> LDS without passing through registers.  A wavefront-wide
     // 16-byte load puts lane l's bytes at (LDS base in M0) + 16 l, so one instruction fills eight
     // consecutive 128-byte rows (64 channels) of a slab.  Rows filled this way cannot be padded;
-    // instead the 16-byte chunk c of row r is kept at chunk position c ^ (r & 7), which spreads
-    // the fragment reads of eight consecutive rows over all banks just as well: the lane that
-    // fills position pc of row r fetches chunk pc ^ (r & 7) from memory.
+    // instead the 16-byte chunk c of row r is kept at chunk position c ^ ((r >> 1) & 7).  LDS
+    // serves 16 lanes of a 16-byte read per cycle (64 banks): the 16 consecutive rows they read
+    // are 8 even rows (banks 0-31) and 8 odd rows (banks 32-63), and within each group the eight
+    // values of (r >> 1) & 7 differ, so the reads spread over all banks just as padded rows
+    // would.  The lane that fills position pc of row r fetches chunk pc ^ ((r >> 1) & 7).
     // Wavefront w fills rows 8w .. 8w+7 and 64+8w .. 64+8w+7; wavefront 0 also rows 128, 129.
     // The loads are written in assembly: the compiler would order every barrier behind all
     // outstanding loads of this kind, while the pipeline below needs two stages in flight.
     // (M0 is reserved: the compiler sets it right before each of its own uses and keeps nothing
     //  in it, and this kernel gives it no such use.)
     const int lrow = lane >> 3, lpc = lane & 7;
-    const int xo0 = ((wave * 8 + lrow) * a.cin + ((lpc ^ lrow) << 3)) * 2;   // byte offsets inside a slab
+    const int sw01 = (4 * wave + (lrow >> 1)) & 7, sw2 = lrow >> 1;          // (row >> 1) & 7 of the rows filled
+    const int xo0 = ((wave * 8 + lrow) * a.cin + ((lpc ^ sw01) << 3)) * 2;   // byte offsets inside a slab
     const int xo1 = xo0 + 64 * a.cin * 2;
-    const int xo2 = ((128 + lrow) * a.cin + ((lpc ^ lrow) << 3)) * 2;
+    const int xo2 = ((128 + lrow) * a.cin + ((lpc ^ sw2) << 3)) * 2;
     const bf16* xg = a.X + ((long long)m0 - 1 - a.Wp) * a.cin;               // first row of the kh = 0 slabs
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave * 1024);   // a scalar: it goes to M0
     // fragment reads: row J*32 + l32 + KW, chunk kgrp*2 + lhi
     int rd[3];
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) rd[kw] = (l32 + kw) * 128 + (((kgrp * 2 + lhi) ^ ((l32 + kw) & 7)) << 4);
+    for (int kw = 0; kw < 3; ++kw) rd[kw] = (l32 + kw) * 128 + (((kgrp * 2 + lhi) ^ (((l32 + kw) >> 1) & 7)) << 4);
 
     // The stage being fetched runs two ahead of the one being multiplied.  Its operands are
     // addressed as (scalar base, advanced once per stage) + (per-lane byte offset, fixed), which
