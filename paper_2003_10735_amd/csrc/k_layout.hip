@@ -2,6 +2,7 @@
 // permutation between the caller's parameter order (OIHW) and the internal one ([o][kh][kw][i]).
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
+#include "st_begin.hpp"
 
 namespace st {
 
@@ -47,33 +48,13 @@ void zero_bytes(Ctx& c, void* p, size_t bytes)
     zero_regions(c, z);
 }
 
-// features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
-// outT != nullptr, a channel-major copy in the blocked layout of xt_index() for the
-// weight-gradient kernel.
-// One block transposes a 32-channel x 32-column tile of one row through LDS so that both the
-// read (along x) and the write (along c) are contiguous.
+// features -> padded position-major (+ channel-major copy): see pack_features_block
 template <class Tin, class E>
 __global__ void __launch_bounds__(256)
 k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ outT, Geo g, int PPT, int guard)
 {
     __shared__ float tile[32][33];
-    const int x0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-    const int img = blockIdx.z / g.h, y = blockIdx.z % g.h;
-    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
-    for (int k = ty; k < 32; k += 8) {
-        const int c = c0 + k, x = x0 + tx;
-        float v = 0.f;
-        if (c < g.c_in && x < g.w) v = to_f32(f[(((size_t)img * g.c_in + c) * g.h + y) * g.w + x]);
-        tile[k][tx] = v;
-        if (outT && c < g.c_in && x < g.w)
-            outT[xt_index(c, guard + (img * g.Hp + y + 1) * g.Wp + x + 1, PPT / 8)] = from_f32<E>(v);
-    }
-    __syncthreads();
-    for (int k = ty; k < 32; k += 8) {
-        const int x = x0 + k, c = c0 + tx;
-        if (c < g.c_in && x < g.w)
-            out[(((size_t)img * g.Hp + y + 1) * g.Wp + x + 1) * g.c_in + c] = from_f32<E>(tile[tx][k]);
-    }
+    pack_features_block<Tin, E>(f, out, outT, g, PPT, guard, blockIdx.x, blockIdx.y, blockIdx.z, tile);
 }
 
 __global__ void __launch_bounds__(256) k_zero8(unsigned long long* p, size_t n)

@@ -25,6 +25,7 @@
 // results do not change from run to run.
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
+#include "st_begin.hpp"
 
 namespace st {
 
@@ -51,88 +52,15 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// weight with which frame index X (0 .. 8*len-1) contributes to cell `cell` of a line of `len`
-// cells: the tent (1, 3, .. 15, 15, .. 3, 1)/16 around the cell, plus, for the first and last
-// cell, the weight that edge replication folds back onto them
-__device__ __forceinline__ float tap_weight(int X, int cell, int len)
-{
-    const int t = X - 8 * cell + 4;   // 0 .. 15 inside the tent
-    float wgt = 0.f;
-    if (t >= 0 && t < 16) wgt = (t < 8 ? 2 * t + 1 : 31 - 2 * t) * 0.0625f;
-    if (cell == 0 && X < 4) wgt = 1.f;
-    if (cell == len - 1 && X >= 8 * len - 4) wgt = 1.f;
-    return wgt;
-}
-
-// T[img][c][cy][cx] = sum over valid pixels p with label c of wy(p, cy) * wx(p, cx).
-// One block per cell row and run of 32 cells.  First every pixel column that can reach those
-// cells (256 + 2 x 4 columns) adds its 16 rows' y-weights into a per-column table in LDS
-// (the class index is data, so the table cannot live in registers); then one thread per
-// (class, cell) applies the x-weights of the 16 columns under the cell.  All terms are
-// multiples of 1/256 and the sums stay below 2^8 -- below 2^16 with 8-bit pixel weights -- so the
-// result is exact in float32 and does not depend on the order of additions.
+// T = U^T (one-hot valid labels), one block per cell row and run of 32 cells: see label_adjoint_block
 template <int CP>
 __global__ void __launch_bounds__(256)
 k_label_adjoint(const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, float* __restrict__ T,
                 unsigned long long* __restrict__ n_valid, Geo g)
 {
-    constexpr int NCOL = LOSS_TX * 8 + 8;
-    __shared__ float colsum[CP][NCOL + 1];
+    __shared__ float colsum[CP * (LABEL_NCOL + 1)];
     __shared__ unsigned int cnt_part[4];
-    const int tid = threadIdx.x;
-    const int tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
-    const int tx = blockIdx.x % tiles_x, cy = (blockIdx.x / tiles_x) % g.h, img = blockIdx.x / (tiles_x * g.h);
-    const int hw = g.h * g.w;
-    const int32_t* lab = labels + (size_t)img * g.H * g.W;
-    const uint8_t* wm = wmap ? wmap + (size_t)img * g.H * g.W : nullptr;
-    for (int i = tid; i < CP * (NCOL + 1); i += 256) (&colsum[0][0])[i] = 0.f;
-    __syncthreads();
-    const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
-    const int Yt = 8 * cy - 4;                             // frame row of tent position 0
-    unsigned int cnt = 0;     // valid labels (their weights) of this block's own 8 x 256 pixels
-    for (int col = tid; col < NCOL; col += 256) {
-        const int X = X0 + col;
-        const bool xin = X >= 0 && X < g.W;
-        const int Xc = min(max(X, 0), g.W - 1);
-        // the 16 rows under the tent: all loads first (clamped, so none depends on a branch)
-        int ys[16];
-        unsigned int ws[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const size_t at = (size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc;
-            ys[r] = lab[at];
-            ws[r] = wm ? wm[at] : 1u;
-        }
-        const bool own_col = col >= 4 && col < NCOL - 4;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int Y = Yt + r, y = ys[r];
-            if (xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C) {
-                colsum[y][col] += (float)ws[r] * tap_weight(Y, cy, g.h);
-                if (own_col && r >= 4 && r < 12) cnt += ws[r];
-            }
-        }
-    }
-    if (n_valid) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off, 64);
-        if ((tid & 63) == 0) cnt_part[tid >> 6] = cnt;
-    }
-    __syncthreads();
-    if (n_valid && tid == 0)
-        atomicAdd(n_valid + g.head_of(img), (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
-    for (int i = tid; i < g.C * LOSS_TX; i += 256) {
-        const int lc = i % LOSS_TX, c = i / LOSS_TX;
-        const int cx = tx * LOSS_TX + lc;
-        if (cx >= g.w) continue;
-        float acc = 0.f;
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int X = 8 * cx - 4 + t;                  // table column 8 * lc + t
-            if (X >= 0 && X < g.W) acc += tap_weight(X, cx, g.w) * colsum[c][8 * lc + t];
-        }
-        T[((size_t)img * g.C + c) * hw + cy * g.w + cx] = acc;
-    }
+    label_adjoint_block(labels, wmap, T, n_valid, g, blockIdx.x, colsum, cnt_part, CP);
 }
 
 constexpr int LOSS_THREADS = 512;

@@ -7,6 +7,7 @@
 
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
+#include "st_begin.hpp"
 
 namespace st {
 
@@ -230,10 +231,8 @@ __device__ void finish_block(const FinishArgs& f, int block, int head)
     }
 }
 
-__global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
+__device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f, int b, int head)
 {
-    const int b = blockIdx.x;
-    const int head = blockIdx.y;
     if (head) {
         if (a.theta) { a.theta += head * a.hs_param; a.vel += head * a.hs_param; a.vel2 += head * a.hs_param; }
         if (a.grad) a.grad += head * a.hs_grad;
@@ -307,6 +306,53 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
     }
 }
 
+__global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
+{
+    step_end_block(a, f, blockIdx.x, blockIdx.y);
+}
+
+// The launch that opens a call: three kinds of blocks that do not depend on each other,
+//   [0, nb_pack)                   feature packing (pack_features_block),
+//   [nb_pack, nb_pack + nb_label)  U^T of the label map and the pixel counts (label_adjoint_block),
+//   the rest                       the caller's parameters into theta and the bfloat16 operand
+//                                  copies: the blocks of k_step_end, head by head.
+// Run one after the other they are three short launches, each of which leaves most of the chip
+// idle for most of its time.
+struct BeginArgs {
+    const void* features; void* feat; void* featT; int in_bf16, out_bf16, PPT, guard;
+    int pack_x, pack_y, nb_pack;           // pack grid: pack_x column tiles x pack_y channel tiles x rows
+    const int32_t* labels; const uint8_t* wmap; float* T; unsigned long long* n_valid; int CP, nb_label;
+    int nb_update;                         // blocks of the parameter role per head
+    Geo g;
+};
+
+__global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, FinishArgs f)
+{
+    extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
+    int b = blockIdx.x;
+    if (b < q.nb_pack) {
+        float (*tile)[33] = (float (*)[33])dyn_lds;
+        const int bx = b % q.pack_x, by = (b / q.pack_x) % q.pack_y, bz = b / (q.pack_x * q.pack_y);
+        if (q.out_bf16) {
+            if (q.in_bf16) pack_features_block<bf16, bf16>((const bf16*)q.features, (bf16*)q.feat, (bf16*)q.featT, q.g, q.PPT, q.guard, bx, by, bz, tile);
+            else pack_features_block<float, bf16>((const float*)q.features, (bf16*)q.feat, (bf16*)q.featT, q.g, q.PPT, q.guard, bx, by, bz, tile);
+        } else {
+            if (q.in_bf16) pack_features_block<bf16, float>((const bf16*)q.features, (float*)q.feat, (float*)nullptr, q.g, 0, 0, bx, by, bz, tile);
+            else pack_features_block<float, float>((const float*)q.features, (float*)q.feat, (float*)nullptr, q.g, 0, 0, bx, by, bz, tile);
+        }
+        return;
+    }
+    b -= q.nb_pack;
+    if (b < q.nb_label) {
+        float* colsum = dyn_lds;
+        unsigned int* cnt_part = (unsigned int*)(dyn_lds + q.CP * (LABEL_NCOL + 1));
+        label_adjoint_block(q.labels, q.wmap, q.T, q.n_valid, q.g, b, colsum, cnt_part, q.CP);
+        return;
+    }
+    b -= q.nb_label;
+    step_end_block(a, f, b % q.nb_update, b / q.nb_update);
+}
+
 static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
 {
     FinishArgs f;
@@ -337,10 +383,9 @@ static void head_strides(UpdateArgs& a, const Plan& p)
 
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
 // finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
-void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out, const float* ext_in, bool w1t)
+static int step_end_args(const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish,
+                         const float* ext_in, bool w1t, const FinishArgs& f, UpdateArgs& a)
 {
-    UpdateArgs a;
     a.theta = (float*)(ws + p.theta);
     a.vel = (float*)(ws + p.vel);
     a.vel2 = (float*)(ws + p.vel2);
@@ -374,11 +419,19 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
         a.nb_tail = 0;
     }
     a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 4) : 0;
-    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
     a.nb_finish = finish ? f.fph + 1 : 0;
     head_strides(a, p);
-    const int blocks = a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
+    return a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
+}
+
+void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
+              double* miou_out, long long* conf_out, const float* ext_in, bool w1t)
+{
+    UpdateArgs a;
+    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    const int blocks = step_end_args(p, ws, lr, mu, adam, do_step, finish, ext_in, w1t, f, a);
     if (blocks == 0) return;
+    const bool params = do_step || p.bf16 || a.ext_in;
     const char* name = a.ext_in ? "params_in+weights_to_bf16" : do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
     ST_LAUNCH(c, name, k_step_end, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
 }
@@ -387,6 +440,36 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
 void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params, bool w1t)
 {
     step_end(c, p, ws, 0.f, 0.f, nullptr, false, false, nullptr, nullptr, nullptr, head_params, w1t);
+}
+
+// Opens a call in one launch: packs the features, takes the caller's parameters (as load_params)
+// and, with labels, computes T = U^T (one-hot valid labels) and the pixel counts (as
+// label_adjoint; n_valid must be clear).  The workspace must have been cleared before.
+void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_dtype, const float* head_params,
+                bool w1t, const int32_t* labels, const uint8_t* wmap)
+{
+    const Geo& g = p.g;
+    BeginArgs q;
+    memset(&q, 0, sizeof(q));
+    q.features = features; q.feat = ws + p.feat;
+    q.featT = (p.bf16 && p.featT) ? ws + p.featT : nullptr;
+    q.in_bf16 = feat_dtype == ST_BF16; q.out_bf16 = p.bf16 ? 1 : 0;
+    q.PPT = p.PPT; q.guard = p.guard;
+    q.pack_x = cdiv(g.w, 32); q.pack_y = cdiv(g.c_in, 32);
+    q.nb_pack = q.pack_x * q.pack_y * g.n * g.h;
+    q.g = g;
+    q.CP = (g.C + 3) / 4 * 4;
+    if (labels) {
+        q.labels = labels; q.wmap = wmap; q.T = (float*)(ws + p.tadj);
+        q.n_valid = (unsigned long long*)(ws + p.counters);
+        q.nb_label = g.n * g.h * cdiv(g.w, LOSS_TX);
+    }
+    UpdateArgs a;
+    const FinishArgs f = finish_args(p, ws, nullptr, nullptr, nullptr);
+    q.nb_update = step_end_args(p, ws, 0.f, 0.f, nullptr, false, false, head_params, w1t, f, a);
+    const size_t lds = std::max((size_t)32 * 33 * sizeof(float), (size_t)(q.CP * (LABEL_NCOL + 1) + 4) * sizeof(float));
+    ST_LAUNCH(c, labels ? "pack+label_adjoint+params_in" : "pack+params_in", k_call_begin,
+              dim3(q.nb_pack + q.nb_label + q.nb_update * g.heads()), dim3(256), lds, q, a, f);
 }
 
 // bookkeeping of a pass without an update; with ext_out the same launch hands theta back to the

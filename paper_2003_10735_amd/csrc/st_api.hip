@@ -317,8 +317,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     char* ws = (char*)workspace;
     Ctx c{as_stream(stream), ST_OK};
     prepare_workspace(c, p, ws);
-    pack_features(c, p, features, desc->feat_dtype, ws);
-    load_params(c, p, ws, head_params, false);
+    call_begin(c, p, ws, features, desc->feat_dtype, head_params, false, nullptr, nullptr);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
     if (pred || p.mfma)
@@ -385,14 +384,14 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     double* metric_dev = (double*)(ws + p.scal);
 
     prepare_workspace(c, p, ws);
-    pack_features(c, p, features, desc->feat_dtype, ws);
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
     if (use_adam) {
         permute_params(c, p, adam_m, (float*)(ws + p.vel), 0);
         permute_params(c, p, adam_v, (float*)(ws + p.vel2), 0);
     }
-    load_params(c, p, ws, head_params, feature_grad != nullptr);   // theta in internal order + bfloat16 copies
-    label_adjoint(c, g, teacher_labels, pixel_weights, (float*)(ws + p.tadj), n_valid);   // also sums the weights of the valid labels
+    // features packed, theta in internal order + bfloat16 copies, U^T of the labels and the sums
+    // of the weights of the valid labels: one launch
+    call_begin(c, p, ws, features, desc->feat_dtype, head_params, feature_grad != nullptr, teacher_labels, pixel_weights);
 
     double best_metric = -1.0;
     std::vector<double> frame_metric;

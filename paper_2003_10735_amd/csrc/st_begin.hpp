@@ -1,0 +1,124 @@
+// Work that opens a call -- packing the features, the label-dependent half of the gradient --
+// written as per-block device functions, so that it can run either as kernels of its own or as
+// roles of the one launch that opens a call (k_call_begin, next to the optimiser kernel).
+#pragma once
+#include "st_kernels.hpp"
+#include "st_mfma.hpp"
+
+namespace st {
+
+// features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
+// outT != nullptr, a channel-major copy in the blocked layout of xt_index() for the
+// weight-gradient kernel.
+// One block (256 threads) transposes a 32-channel x 32-column tile of one row through LDS so that
+// both the read (along x) and the write (along c) are contiguous.  Block coordinates: column
+// tile bx, channel tile by, row bz = img * h + y.  `tile` is 32 x 33 floats of LDS.
+template <class Tin, class E>
+__device__ __forceinline__ void pack_features_block(const Tin* __restrict__ f, E* __restrict__ out,
+                                                    E* __restrict__ outT, const Geo& g, int PPT, int guard,
+                                                    int bx, int by, int bz, float (*tile)[33])
+{
+    const int x0 = bx * 32, c0 = by * 32;
+    const int img = bz / g.h, y = bz % g.h;
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+    for (int k = ty; k < 32; k += 8) {
+        const int c = c0 + k, x = x0 + tx;
+        float v = 0.f;
+        if (c < g.c_in && x < g.w) v = to_f32(f[(((size_t)img * g.c_in + c) * g.h + y) * g.w + x]);
+        tile[k][tx] = v;
+        if (outT && c < g.c_in && x < g.w)
+            outT[xt_index(c, guard + (img * g.Hp + y + 1) * g.Wp + x + 1, PPT / 8)] = from_f32<E>(v);
+    }
+    __syncthreads();
+    for (int k = ty; k < 32; k += 8) {
+        const int x = x0 + k, c = c0 + tx;
+        if (c < g.c_in && x < g.w)
+            out[(((size_t)img * g.Hp + y + 1) * g.Wp + x + 1) * g.c_in + c] = from_f32<E>(tile[tx][k]);
+    }
+}
+
+// weight with which frame index X (0 .. 8*len-1) contributes to cell `cell` of a line of `len`
+// cells: the tent (1, 3, .. 15, 15, .. 3, 1)/16 around the cell, plus, for the first and last
+// cell, the weight that edge replication folds back onto them
+__device__ __forceinline__ float tap_weight(int X, int cell, int len)
+{
+    const int t = X - 8 * cell + 4;   // 0 .. 15 inside the tent
+    float wgt = 0.f;
+    if (t >= 0 && t < 16) wgt = (t < 8 ? 2 * t + 1 : 31 - 2 * t) * 0.0625f;
+    if (cell == 0 && X < 4) wgt = 1.f;
+    if (cell == len - 1 && X >= 8 * len - 4) wgt = 1.f;
+    return wgt;
+}
+
+// T[img][c][cy][cx] = sum over valid pixels p with label c of wy(p, cy) * wx(p, cx).
+// One block (256 threads) per cell row and run of 32 cells.  First every pixel column that can
+// reach those cells (256 + 2 x 4 columns) adds its 16 rows' y-weights into a per-column table in
+// LDS (the class index is data, so the table cannot live in registers); then one thread per
+// (class, cell) applies the x-weights of the 16 columns under the cell.  All terms are
+// multiples of 1/256 and the sums stay below 2^8 -- below 2^16 with 8-bit pixel weights -- so the
+// result is exact in float32 and does not depend on the order of additions.
+// colsum: CP x (LABEL_NCOL + 1) floats of LDS, CP >= number of classes; cnt_part: 4 words.
+constexpr int LABEL_NCOL = LOSS_TX * 8 + 8;
+__device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ labels,
+                                                    const uint8_t* __restrict__ wmap, float* __restrict__ T,
+                                                    unsigned long long* __restrict__ n_valid, const Geo& g,
+                                                    int block, float* colsum, unsigned int* cnt_part, int CP)
+{
+    constexpr int NCOL = LABEL_NCOL, PITCH = LABEL_NCOL + 1;
+    const int tid = threadIdx.x;
+    const int tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
+    const int tx = block % tiles_x, cy = (block / tiles_x) % g.h, img = block / (tiles_x * g.h);
+    const int hw = g.h * g.w;
+    const int32_t* lab = labels + (size_t)img * g.H * g.W;
+    const uint8_t* wm = wmap ? wmap + (size_t)img * g.H * g.W : nullptr;
+    for (int i = tid; i < CP * PITCH; i += 256) colsum[i] = 0.f;
+    __syncthreads();
+    const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
+    const int Yt = 8 * cy - 4;                             // frame row of tent position 0
+    unsigned int cnt = 0;     // valid labels (their weights) of this block's own 8 x 256 pixels
+    for (int col = tid; col < NCOL; col += 256) {
+        const int X = X0 + col;
+        const bool xin = X >= 0 && X < g.W;
+        const int Xc = min(max(X, 0), g.W - 1);
+        // the 16 rows under the tent: all loads first (clamped, so none depends on a branch)
+        int ys[16];
+        unsigned int ws[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const size_t at = (size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc;
+            ys[r] = lab[at];
+            ws[r] = wm ? wm[at] : 1u;
+        }
+        const bool own_col = col >= 4 && col < NCOL - 4;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int Y = Yt + r, y = ys[r];
+            if (xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C) {
+                colsum[y * PITCH + col] += (float)ws[r] * tap_weight(Y, cy, g.h);
+                if (own_col && r >= 4 && r < 12) cnt += ws[r];
+            }
+        }
+    }
+    if (n_valid) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_down(cnt, off, 64);
+        if ((tid & 63) == 0) cnt_part[tid >> 6] = cnt;
+    }
+    __syncthreads();
+    if (n_valid && tid == 0)
+        atomicAdd(n_valid + g.head_of(img), (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
+    for (int i = tid; i < g.C * LOSS_TX; i += 256) {
+        const int lc = i % LOSS_TX, c = i / LOSS_TX;
+        const int cx = tx * LOSS_TX + lc;
+        if (cx >= g.w) continue;
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int X = 8 * cx - 4 + t;                  // table column 8 * lc + t
+            if (X >= 0 && X < g.W) acc += tap_weight(X, cx, g.w) * colsum[c * PITCH + 8 * lc + t];
+        }
+        T[((size_t)img * g.C + c) * hw + cy * g.w + cx] = acc;
+    }
+}
+
+}  // namespace st
