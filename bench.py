@@ -111,6 +111,10 @@ def main():
     ap.add_argument("--clients", type=int, default=4,
                     help="also time the grouped form: this many clients, each with a head and a key frame of "
                          "its own, trained in one call (reported beside the headline as `grouped`; 0 = skip)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time the calls launched kernel by kernel in the stream; default: `value` is timed "
+                         "with the library's cached HIP graph (st_distill_opts.use_graph), and the "
+                         "kernel-by-kernel rate is reported beside it as `stream_launch`")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (outside the timed "
                          "region): the known-size reference that scales hardware byte counters")
@@ -147,14 +151,18 @@ def main():
     mious = torch.zeros((wl.steps + 1, wl.n), dtype=torch.float64, device="cuda")
     conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
     ws = st.new_workspace(desc)
-    stream = torch.cuda.current_stream()
+    # a stream of the caller's own (the library records its launch graph on it; the NULL stream
+    # cannot be captured), made torch's current stream so that every copy and event below is on it
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()             # the uploads above ran on the default stream
+    torch.cuda.set_stream(stream)
 
     use_adam = args.optimizer == "adam"
     pw = torch.from_numpy(WL.object_weight_map(labels, radius=4)).cuda() if args.weighted_loss else None
     dfeat = torch.empty((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda") if args.full_backward else None
     adam = dict(m=torch.zeros_like(p), v=torch.zeros_like(p), t0=0) if use_adam else None
 
-    def one_call():
+    def one_call(graph=False):
         p.copy_(p0)                      # the head is re-initialised for every key frame
         if vel is not None:
             vel.zero_()
@@ -162,14 +170,18 @@ def main():
             adam["m"].zero_()
             adam["v"].zero_()
             st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, adam=adam, losses=losses, mious=mious,
-                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw, feature_grad=dfeat)
+                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw, feature_grad=dfeat,
+                                  graph=graph)
             return
         st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
                               losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream,
-                              pixel_weights=pw, feature_grad=dfeat)
+                              pixel_weights=pw, feature_grad=dfeat, graph=graph)
 
+    use_graph = not args.no_graph
     for _ in range(args.warmup):
         one_call()
+        if use_graph:
+            one_call(graph=True)
     torch.cuda.synchronize()
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
@@ -193,7 +205,7 @@ def main():
     dominant = max(known, key=lambda k: known[k][1])
     breakdown = {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
 
-    # timed region; only the dominant kernel carries an event pair
+    # timed region, kernel-by-kernel launches; only the dominant kernel carries an event pair
     st.st_profile_filter(dominant)
     st.st_profile_enable(True)
     torch.cuda.synchronize()
@@ -206,8 +218,21 @@ def main():
     st.st_profile_enable(False)
     st.st_profile_reset()
     st.st_profile_filter(None)
-
     elapsed = t1 - t0
+    stream_launch = {"value": round(args.steps * wl.steps / elapsed, 2), "unit": "steps/s",
+                     "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+                     "note": "the same K calls launched kernel by kernel in the stream; the roofline object's "
+                             "event pairs were taken in this pass"}
+    if use_graph:
+        # timed region of the headline: the same K calls through the library's cached launch graph
+        # (no event can ride on a launch inside a graph, hence the separate pass above)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_call(graph=True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        elapsed = t1 - t0
     ms_per_call = elapsed / args.steps * 1e3
     steps_per_s = args.steps * wl.steps / elapsed
     final_losses = losses.cpu().numpy()
@@ -291,7 +316,8 @@ def main():
 
         def grouped_call():
             pg.copy_(pg0)
-            st.st_partial_distill(dg, fg, lg, pg, wl.steps, wl.lr, losses=lossg, workspace=wsg, stream=stream)
+            st.st_partial_distill(dg, fg, lg, pg, wl.steps, wl.lr, losses=lossg, workspace=wsg, stream=stream,
+                                  graph=use_graph)
 
         for _ in range(3):
             grouped_call()
@@ -339,6 +365,8 @@ def main():
         "roofline": roofline,
         "other_kernels": others,
         "miou_pass": miou_pass,
+        "launch": "cached HIP graph (st_distill_opts.use_graph)" if use_graph else "kernel by kernel in the stream",
+        "stream_launch": stream_launch,
         "grouped": grouped,
         "cpu_baseline": cpu_baseline,
     }

@@ -124,6 +124,18 @@ typedef struct st_distill_opts {
      * backward pass of the call (untouched if no step is taken).  On the matrix-core path this
      * needs c1 in multiples of 64 (ST_ERR_SHAPE otherwise). */
     float* feature_grad;
+    /* Launch through a HIP graph.  A step is a handful of short kernels, and in a stream every launch
+     * costs more dispatch time than it does inside a graph.  With use_graph = 1 and threshold <= 0
+     * the library records the call's launches into a graph the first time it sees this exact call
+     * (same descriptor, pointers, step count, learning rate and options, same device), keeps the
+     * instantiated graph in a small per-process cache (the oldest of 8 is dropped) and launches it
+     * on `stream`; later identical calls only launch the cached graph.  The kernels, their order
+     * and their results are those of the plain call; the buffers are read when the graph runs, so
+     * their contents may change between calls.  Needs a stream created by the caller (with the
+     * NULL stream, while that stream is being captured by the caller, or while st_profile_enable
+     * is on, the call runs as if use_graph were 0).  Instantiating a graph allocates host and
+     * driver memory; st_graph_cache_clear() releases it. */
+    int32_t use_graph;
 } st_distill_opts;
 enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 
@@ -212,6 +224,12 @@ int st_schedule_bounds(const st_schedule_params* p, st_schedule_bounds_out* out)
  * (Eq. 4 is n_key_frames * s_net over it, Eq. 9 n_frames over it.)  NaN if p is NULL. */
 double st_schedule_total_time(const st_schedule_params* p, double n_frames, double n_distill_steps,
                               double n_key_frames, double t_c);
+
+/* Destroys every cached launch graph (see st_distill_opts.use_graph).  Synchronises the device. */
+void st_graph_cache_clear(void);
+
+/* Number of launch graphs in the cache. */
+int st_graph_cache_size(void);
 
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* st_strerror(int status);

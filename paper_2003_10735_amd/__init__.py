@@ -25,7 +25,8 @@ ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
            "st_miou", "st_strerror", "st_last_hip_error", "st_version",
            "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read",
-           "st_next_stride", "st_schedule_bounds", "st_schedule_total_time"]
+           "st_next_stride", "st_schedule_bounds", "st_schedule_total_time",
+           "st_graph_cache_clear", "st_graph_cache_size"]
 
 
 class StHeadDesc(C.Structure):
@@ -39,7 +40,7 @@ class StDistillOpts(C.Structure):
                 ("strict_break", C.c_int32), ("return_best", C.c_int32),
                 ("optimizer", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t0", C.c_int32),
-                ("pixel_weights", C.c_void_p), ("feature_grad", C.c_void_p)]
+                ("pixel_weights", C.c_void_p), ("feature_grad", C.c_void_p), ("use_graph", C.c_int32)]
 
 
 class StScheduleParams(C.Structure):
@@ -112,6 +113,7 @@ def lib():
         L.st_schedule_bounds.argtypes = [C.POINTER(StScheduleParams), C.POINTER(StScheduleBounds)]
         L.st_schedule_total_time.restype = C.c_double
         L.st_schedule_total_time.argtypes = [C.POINTER(StScheduleParams)] + [C.c_double] * 4
+        L.st_graph_cache_size.restype = C.c_int
         L.st_profile_enable.argtypes = [C.c_int]
         L.st_profile_filter.argtypes = [C.c_char_p]
         L.st_profile_read.restype = C.c_int
@@ -205,21 +207,22 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
                        momentum: float = 0.0, velocity=None, threshold: float = 0.0,
                        strict_break: bool = True, return_best: bool = False, losses=None,
                        mious=None, confusion=None, pred=None, workspace=None, stream=None,
-                       adam=None, pixel_weights=None, feature_grad=None):
+                       adam=None, pixel_weights=None, feature_grad=None, graph=False):
     """Runs the library's st_partial_distill; head_params (and the optimiser state) are updated
     in place.  `adam` = dict(m=, v=, t0=0, beta1=0.9, beta2=0.999, eps=1e-8) selects Adam;
     `pixel_weights` (uint8 [n,8h,8w]) scales every pixel's loss; `feature_grad` (float32
     [n,c_in,h,w]) receives d loss / d features of the last backward pass.
     With a grouped descriptor head_params and the optimiser state are [n, num_params] and losses
-    [steps+1, n].
+    [steps+1, n].  graph=True launches the call through the library's cached HIP graph
+    (st_distill_opts.use_graph).
     Returns (steps_taken, best_metric or None)."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     use_opts = (momentum != 0.0 or threshold > 0.0 or velocity is not None or adam is not None
-                or pixel_weights is not None or feature_grad is not None)
+                or pixel_weights is not None or feature_grad is not None or graph)
     opts = StDistillOpts(momentum, _ptr(velocity), threshold, 1 if strict_break else 0,
                          1 if return_best else 0, ST_OPTIM_SGD, 0.0, 0.0, 0.0, None, None, 0,
-                         _ptr(pixel_weights), _ptr(feature_grad))
+                         _ptr(pixel_weights), _ptr(feature_grad), 1 if graph else 0)
     if adam is not None:
         opts.optimizer = ST_OPTIM_ADAM
         opts.beta1, opts.beta2 = adam.get("beta1", 0.9), adam.get("beta2", 0.999)
@@ -245,6 +248,14 @@ def st_miou(pred, labels, n_classes: int, ignore_index: int = -1, confusion=None
     _check(lib().st_miou(_ptr(pred), _ptr(labels), pred.numel(), n_classes, ignore_index,
                          _ptr(confusion), _ptr(miou), _stream(stream)), "st_miou")
     return confusion, miou
+
+
+def st_graph_cache_clear():
+    lib().st_graph_cache_clear()
+
+
+def st_graph_cache_size() -> int:
+    return int(lib().st_graph_cache_size())
 
 
 def st_profile_enable(on: bool):

@@ -276,6 +276,30 @@ static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat)
                   (const bf16*)(ws + p.a1T), grad);
 }
 
+// ------------------------------------------------------------------ cached launch graphs
+// One entry per distinct st_partial_distill call (everything the recorded launches depend on).
+struct GraphKey {
+    st_head_desc desc;
+    const void* features; const int32_t* labels; float* params;
+    int32_t steps; float lr;
+    st_distill_opts opts;
+    float* losses; double* mious; int64_t* confusion; uint8_t* pred;
+    void* workspace;
+    int device;
+};
+struct GraphEntry { GraphKey key; hipGraph_t graph; hipGraphExec_t exec; unsigned long long last_use; };
+static std::mutex g_graph_mutex;
+static std::vector<GraphEntry> g_graphs;
+static unsigned long long g_graph_clock = 0;
+constexpr size_t GRAPH_CACHE_MAX = 8;
+
+static void destroy_entry(GraphEntry& e)
+{
+    if (e.exec) (void)hipGraphExecDestroy(e.exec);
+    if (e.graph) (void)hipGraphDestroy(e.graph);
+    e.exec = nullptr; e.graph = nullptr;
+}
+
 }  // namespace st
 
 using namespace st;
@@ -369,6 +393,63 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     const bool early_exit = threshold > 0.0;
     // several heads take the same steps: no per-head loop exits, no feature gradient
     if (desc->grouped && (early_exit || feature_grad)) return ST_ERR_ARG;
+
+    if (opts && opts->use_graph && !early_exit && stream && !g_prof_on) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(as_stream(stream), &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) {
+            GraphKey key;
+            memset(&key, 0, sizeof(key));          // padding bytes take part in the comparison
+            key.desc = *desc;                      // (all int32: no padding)
+            key.features = features; key.labels = teacher_labels; key.params = head_params;
+            key.steps = steps; key.lr = lr;
+            // (field by field: the caller's padding bytes must not take part)
+            key.opts.momentum = opts->momentum; key.opts.velocity = opts->velocity;
+            key.opts.threshold = opts->threshold; key.opts.strict_break = opts->strict_break;
+            key.opts.return_best = opts->return_best; key.opts.optimizer = opts->optimizer;
+            key.opts.beta1 = opts->beta1; key.opts.beta2 = opts->beta2; key.opts.eps = opts->eps;
+            key.opts.adam_m = opts->adam_m; key.opts.adam_v = opts->adam_v; key.opts.adam_t0 = opts->adam_t0;
+            key.opts.pixel_weights = opts->pixel_weights; key.opts.feature_grad = opts->feature_grad;
+            key.opts.use_graph = 1;
+            if (out) { key.losses = out->losses; key.mious = out->mious; key.confusion = out->confusion; key.pred = out->pred; }
+            key.workspace = workspace;
+            if (hipGetDevice(&key.device) != hipSuccess) return ST_ERR_NO_DEVICE;
+            std::lock_guard<std::mutex> lk(g_graph_mutex);
+            GraphEntry* hit = nullptr;
+            for (auto& e : g_graphs)
+                if (memcmp(&e.key, &key, sizeof(key)) == 0) hit = &e;
+            if (!hit) {
+                // record the plain call's launches (nothing runs while the stream is capturing)
+                st_distill_opts plain = *opts;
+                plain.use_graph = 0;
+                if (hipStreamBeginCapture(as_stream(stream), hipStreamCaptureModeRelaxed) != hipSuccess) return ST_ERR_HIP;
+                const int rec = st_partial_distill(desc, features, teacher_labels, head_params, steps, lr, &plain, out,
+                                                   workspace, stream);
+                GraphEntry e;
+                e.key = key; e.graph = nullptr; e.exec = nullptr; e.last_use = 0;
+                const hipError_t end = hipStreamEndCapture(as_stream(stream), &e.graph);
+                if (rec != ST_OK) { destroy_entry(e); return rec; }
+                if (end != hipSuccess || !e.graph) { set_hip_error(end); destroy_entry(e); return ST_ERR_HIP; }
+                const hipError_t inst = hipGraphInstantiate(&e.exec, e.graph, nullptr, nullptr, 0);
+                if (inst != hipSuccess) { set_hip_error(inst); destroy_entry(e); return ST_ERR_HIP; }
+                if (g_graphs.size() >= GRAPH_CACHE_MAX) {
+                    // drop the least recently used one; it may still be running somewhere
+                    size_t old = 0;
+                    for (size_t i = 1; i < g_graphs.size(); ++i)
+                        if (g_graphs[i].last_use < g_graphs[old].last_use) old = i;
+                    (void)hipDeviceSynchronize();
+                    destroy_entry(g_graphs[old]);
+                    g_graphs.erase(g_graphs.begin() + old);
+                }
+                g_graphs.push_back(e);
+                hit = &g_graphs.back();
+            }
+            hit->last_use = ++g_graph_clock;
+            const hipError_t le = hipGraphLaunch(hit->exec, as_stream(stream));
+            if (le != hipSuccess) { set_hip_error(le); return ST_ERR_HIP; }
+            if (out) out->steps_taken = steps;
+            return ST_OK;
+        }
+    }
 
     const Plan p = make_plan(*desc);
     const Geo& g = p.g;
@@ -483,6 +564,21 @@ int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_
     Ctx c{as_stream(stream), ST_OK};
     confusion_and_miou(c, pred, labels, n_pixels, n_classes, ignore_index, (long long*)confusion, miou);
     return c.status;
+}
+
+void st_graph_cache_clear(void)
+{
+    std::lock_guard<std::mutex> lk(g_graph_mutex);
+    if (g_graphs.empty()) return;
+    (void)hipDeviceSynchronize();
+    for (auto& e : g_graphs) destroy_entry(e);
+    g_graphs.clear();
+}
+
+int st_graph_cache_size(void)
+{
+    std::lock_guard<std::mutex> lk(g_graph_mutex);
+    return (int)g_graphs.size();
 }
 
 const char* st_strerror(int status)

@@ -1,0 +1,113 @@
+"""The graph-launch mode of st_partial_distill (st_distill_opts.use_graph): the cached HIP graph
+must give exactly what the plain call gives, on the first launch and on every replay, with other
+GPU work and synchronisations between the replays and with buffer contents that change."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2003_10735_amd as st
+import workloads as WL
+from gpu_util import to_dev_features
+
+pytestmark = pytest.mark.gpu
+
+
+def outputs(bufs):
+    torch.cuda.synchronize()
+    return [b.cpu().numpy().copy() for b in bufs]
+
+
+@pytest.mark.parametrize("mode", ["sgd", "momentum", "adam", "grouped"])
+def test_graph_replays_equal_the_plain_call(mode):
+    grouped = mode == "grouped"
+    wl = WL.small_variant(WL.WORKLOADS["720p"], steps=3, lr=0.02, n_sites=9, n=3 if grouped else 2, c_in=64, h=9,
+                          w=35, c1=64, c2=64, n_classes=6, momentum=0.9 if mode == "momentum" else 0.0)
+    desc = st.HeadDesc.of(wl)
+    desc.grouped = 1 if grouped else 0
+    heads = wl.n if grouped else 1
+    feats = [WL.make_features(wl, seed=wl.feat_seed + i) for i in range(3)]
+    labs = [WL.make_labels(WL.small_variant(wl, label_seed=wl.label_seed + 10 * i)) for i in range(3)]
+    p_np = np.stack([WL.make_head_params(wl, seed=wl.init_seed + 17 * i) for i in range(heads)]).astype(np.float32)
+    if not grouped:
+        p_np = p_np[0]
+    stream = torch.cuda.Stream()
+    ws = st.new_workspace(desc)
+    # fixed buffers: the graph is tied to their addresses, their contents change
+    f = to_dev_features(wl, feats[0]).clone()
+    lab = torch.from_numpy(labs[0]).cuda()
+    p = torch.from_numpy(p_np).cuda()
+    s1, s2 = torch.zeros_like(p), torch.zeros_like(p)
+    steps = 3
+    losses = torch.zeros((steps + 1, heads) if grouped else (steps + 1,), dtype=torch.float32, device="cuda")
+    mious = torch.zeros((steps + 1, wl.n), dtype=torch.float64, device="cuda")
+    conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+    pred = torch.zeros((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+
+    def call(graph):
+        kw = dict(losses=losses, mious=mious, confusion=conf, pred=pred, workspace=ws, stream=stream, graph=graph)
+        if mode == "adam":
+            kw["adam"] = dict(m=s1, v=s2, t0=0)
+        elif mode == "momentum":
+            kw.update(momentum=0.9, velocity=s1)
+        with torch.cuda.stream(stream):
+            taken, _ = st.st_partial_distill(desc, f, lab, p, steps, wl.lr, **kw)
+        assert taken == steps
+        return outputs([p, s1, s2, losses, mious, conf, pred])
+
+    def load(i):
+        torch.cuda.synchronize()
+        f.copy_(to_dev_features(wl, feats[i]))
+        lab.copy_(torch.from_numpy(labs[i]).cuda())
+        p.copy_(torch.from_numpy(p_np).cuda())
+        s1.zero_(); s2.zero_()
+        for b in (losses, mious, conf, pred):
+            b.zero_()
+        torch.cuda.synchronize()
+
+    st.st_graph_cache_clear()
+    want = []
+    for i in range(3):
+        load(i)
+        want.append(call(False))
+    assert st.st_graph_cache_size() == 0
+    assert not np.array_equal(want[0][0], want[1][0])          # the inputs do differ
+    scratch = torch.randn(1 << 20, device="cuda")
+    for rep in range(2):
+        for i in range(3):
+            load(i)
+            scratch = scratch * 1.0001 + 1.0                    # unrelated eager work between the launches
+            got = call(True)
+            torch.cuda.synchronize()
+            for a, b in zip(got, want[i]):
+                np.testing.assert_array_equal(a, b)
+            assert st.st_graph_cache_size() == 1               # recorded once, replayed afterwards
+    # a different call (another step count) gets a graph of its own
+    load(0)
+    with torch.cuda.stream(stream):
+        st.st_partial_distill(desc, f, lab, p, 1, wl.lr, losses=losses, mious=mious, workspace=ws, stream=stream, graph=True)
+    torch.cuda.synchronize()
+    assert st.st_graph_cache_size() == 2
+    st.st_graph_cache_clear()
+    assert st.st_graph_cache_size() == 0
+
+
+def test_graph_mode_falls_back_where_it_cannot_apply():
+    wl = WL.small_variant(WL.WORKLOADS["720p"], steps=2, n=1, c_in=64, h=6, w=10, c1=64, c2=64, n_classes=4, n_sites=5)
+    desc = st.HeadDesc.of(wl)
+    f = to_dev_features(wl, WL.make_features(wl))
+    lab = torch.from_numpy(WL.make_labels(wl)).cuda()
+    p0 = torch.from_numpy(WL.make_head_params(wl)).cuda()
+    st.st_graph_cache_clear()
+    # early exit decides on the host: never recorded
+    p = p0.clone()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        taken, best = st.st_partial_distill(desc, f, lab, p, 2, wl.lr, threshold=2.0, stream=stream, graph=True)
+    torch.cuda.synchronize()
+    assert taken == 2 and st.st_graph_cache_size() == 0
+    ref = p.cpu().numpy()
+    # the same through the plain path
+    q = p0.clone()
+    st.st_partial_distill(desc, f, lab, q, 2, wl.lr, threshold=2.0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(q.cpu().numpy(), ref)
