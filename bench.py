@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # copy-kernel scale factors are recorded under profiles/).  A figure holds only for the kernel
 # source it was measured on: (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "029d9c26feb57bb1ec266e090c5726f6273aec404fa65a37516a12d7b338fc1e", 31.53, 9.43),
-    "conv1_fwd_mfma": ("k_conv_mfma.hip", "2043fe0260c23b9aff56b2ed38514fc7c9a81d0640ab3bd3a5d52cb33f2d31eb", 13.75, 7.55),
-    "upsample_ce_grad": ("k_loss.hip", "8b75b924aa483d9b9ceb99376b56fc188e34da54a9a2c068cc2c9c90dede6f04", 12.26, 3.68),
+    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "7103cba8f94818f9adfd10b899c6271a339317d2c4acb06411186eb46ede5adc", 31.52, 9.43),
+    "conv1_fwd_mfma": ("k_conv_mfma.hip", "cbaf223bc3154ac253ee7cb9335f3a315c76c0de9380afa7d860eb89a656f4d6", 13.74, 7.55),
+    "upsample_ce_grad": ("k_loss.hip", "6b3aeda4014cb3aba0fcce3a0e9a2f3847415747cc65cec9441ea038e6d73f2f", 15.82, 4.72),
 }
 
 
