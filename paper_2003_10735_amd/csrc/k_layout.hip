@@ -1,8 +1,7 @@
-// Layout kernels: zero fill, feature packing (caller's NCHW -> padded position-major), and the
-// permutation between the caller's parameter order (OIHW) and the internal one ([o][kh][kw][i]).
+// Layout kernels: zero fill and the permutation between the caller's parameter order (OIHW) and
+// the internal one ([o][kh][kw][i]).
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
-#include "st_begin.hpp"
 
 namespace st {
 
@@ -41,22 +40,6 @@ void zero_regions(Ctx& c, const ZeroList& z)
     ST_LAUNCH(c, "zero_fill", k_zero_regions, dim3(z.first[z.n]), dim3(256), 0, z);
 }
 
-void zero_bytes(Ctx& c, void* p, size_t bytes)
-{
-    ZeroList z;
-    z.add(p, bytes);
-    zero_regions(c, z);
-}
-
-// features -> padded position-major (+ channel-major copy): see pack_features_block
-template <class Tin, class E>
-__global__ void __launch_bounds__(256)
-k_pack_features(const Tin* __restrict__ f, E* __restrict__ out, E* __restrict__ outT, Geo g, int PPT, int guard)
-{
-    __shared__ float tile[32][33];
-    pack_features_block<Tin, E>(f, out, outT, g, PPT, guard, blockIdx.x, blockIdx.y, blockIdx.z, tile);
-}
-
 __global__ void __launch_bounds__(256) k_zero8(unsigned long long* p, size_t n)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -70,30 +53,6 @@ void zero_u64(Ctx& c, unsigned long long* p, size_t n)
     int blocks = (int)((n + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     ST_LAUNCH(c, "zero_fill", k_zero8, dim3(blocks), dim3(256), 0, p, n);
-}
-
-void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, char* ws)
-{
-    const Geo& g = p.g;
-    dim3 grid(cdiv(g.w, 32), cdiv(g.c_in, 32), g.n * g.h);
-    if (p.bf16) {
-        bf16* out = (bf16*)(ws + p.feat);
-        bf16* outT = p.featT ? (bf16*)(ws + p.featT) : nullptr;
-        if (feat_dtype == ST_BF16)
-            ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, bf16>), grid, dim3(256), 0,
-                      (const bf16*)features, out, outT, g, p.PPT, p.guard);
-        else
-            ST_LAUNCH(c, "pack_features", (k_pack_features<float, bf16>), grid, dim3(256), 0,
-                      (const float*)features, out, outT, g, p.PPT, p.guard);
-    } else {
-        float* out = (float*)(ws + p.feat);
-        if (feat_dtype == ST_BF16)
-            ST_LAUNCH(c, "pack_features", (k_pack_features<bf16, float>), grid, dim3(256), 0,
-                      (const bf16*)features, out, (float*)nullptr, g, 0, 0);
-        else
-            ST_LAUNCH(c, "pack_features", (k_pack_features<float, float>), grid, dim3(256), 0,
-                      (const float*)features, out, (float*)nullptr, g, 0, 0);
-    }
 }
 
 // Parameter permutation.  dir = 0: external (OIHW) -> internal; dir = 1: internal -> external.

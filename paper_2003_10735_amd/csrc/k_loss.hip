@@ -10,7 +10,8 @@
 // operation rounded once in float32.  The predicted class is decided on exactly these values.
 //
 // What depends on the labels but not on the logits is computed once per call
-// (k_label_adjoint): with U the up-sampling operator and Y the one-hot label map,
+// (label_adjoint_block, a role of the launch that opens a call): with U the up-sampling operator
+// and Y the one-hot label map,
 //     T = U^T Y                      (exact in float32: sums of multiples of 1/256)
 // Then, with P the softmax of the up-sampled logits on the valid pixels,
 //     d loss / d z = (U^T P - T) / N_valid
@@ -25,7 +26,6 @@
 // results do not change from run to run.
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
-#include "st_begin.hpp"
 
 namespace st {
 
@@ -50,17 +50,6 @@ __device__ __forceinline__ float wave_sum(float v)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
     return v;
-}
-
-// T = U^T (one-hot valid labels), one block per cell row and run of 32 cells: see label_adjoint_block
-template <int CP>
-__global__ void __launch_bounds__(256)
-k_label_adjoint(const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, float* __restrict__ T,
-                unsigned long long* __restrict__ n_valid, Geo g)
-{
-    __shared__ float colsum[CP * (LABEL_NCOL + 1)];
-    __shared__ unsigned int cnt_part[4];
-    label_adjoint_block(labels, wmap, T, n_valid, g, blockIdx.x, colsum, cnt_part, CP);
 }
 
 constexpr int LOSS_THREADS = 512;
@@ -402,17 +391,6 @@ static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* lab
     case 32: CALL(32); break;                                                                 \
     default: c.status = ST_ERR_SHAPE; break;                                                  \
     }
-
-// T = U^T (one-hot valid labels); once per call.  With n_valid (a cleared counter) the kernel also
-// counts the valid labels: every pixel belongs to the 8 x 256 pixels of exactly one block.
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, const uint8_t* wmap, float* T,
-                   unsigned long long* n_valid)
-{
-    const dim3 grid(g.n * g.h * ((g.w + LOSS_TX - 1) / LOSS_TX));
-#define ST_CALL(CP) ST_LAUNCH(c, "label_adjoint", (k_label_adjoint<CP>), grid, dim3(256), 0, labels, wmap, T, n_valid, g)
-    ST_FOR_CP(ST_CALL)
-#undef ST_CALL
-}
 
 void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* wmap, const float* T,
                uint8_t* pred,

@@ -436,15 +436,9 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
     ST_LAUNCH(c, name, k_step_end, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
 }
 
-// takes the caller's parameters (OIHW order) into theta and refreshes the bfloat16 copies
-void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params, bool w1t)
-{
-    step_end(c, p, ws, 0.f, 0.f, nullptr, false, false, nullptr, nullptr, nullptr, head_params, w1t);
-}
-
-// Opens a call in one launch: packs the features, takes the caller's parameters (as load_params)
-// and, with labels, computes T = U^T (one-hot valid labels) and the pixel counts (as
-// label_adjoint; n_valid must be clear).  The workspace must have been cleared before.
+// Opens a call in one launch: packs the features, takes the caller's parameters (OIHW order)
+// into theta and the bfloat16 copies and, with labels, computes T = U^T (one-hot valid labels)
+// and the pixel counts (n_valid must be clear).  The workspace must have been cleared before.
 void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_dtype, const float* head_params,
                 bool w1t, const int32_t* labels, const uint8_t* wmap)
 {

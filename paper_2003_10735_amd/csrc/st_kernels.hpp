@@ -13,9 +13,7 @@ struct ZeroList {
     void add(void* p, size_t bytes);
 };
 void zero_regions(Ctx& c, const ZeroList& z);
-void zero_bytes(Ctx& c, void* p, size_t bytes);            // p 16-byte aligned, region padded to 16
 void zero_u64(Ctx& c, unsigned long long* p, size_t n);
-void pack_features(Ctx& c, const Plan& p, const void* features, int feat_dtype, char* ws);
 void permute_params(Ctx& c, const Plan& p, const float* src, float* dst, int dir);
 
 // k_conv_generic.hip -- plain tiled kernels (float32 path; bfloat16 shapes the MFMA kernels skip)
@@ -42,8 +40,6 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
 // k_loss.hip
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
-void label_adjoint(Ctx& c, const Geo& g, const int32_t* labels, const uint8_t* pixel_weights, float* T,
-                   unsigned long long* n_valid);
 // Where the loss kernel finds the low-resolution logits: either the planar tensor [n, C, h, w], or
 // the shares the classifier-fused convolution left behind, [n_parts][padded position][32 classes],
 // to be added in ascending order together with the bias b3; in that case the kernel also writes
@@ -65,7 +61,6 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, cons
 //   theta <- theta - step_scale * m / (sqrt(v) * inv_sqrt_bc2 + eps),
 //   step_scale = lr / (1 - beta1^t),  inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
 struct AdamStep { float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_scale, inv_sqrt_bc2; };
-void load_params(Ctx& c, const Plan& p, char* ws, const float* head_params, bool w1t);
 void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_dtype, const float* head_params,
                 bool w1t, const int32_t* labels, const uint8_t* pixel_weights);
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
