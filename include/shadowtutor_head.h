@@ -8,11 +8,12 @@
  *                    (Algorithm 1, "Forward"; Section 2.2: output has the input's spatial size)
  *   ComputeMetric    mean IoU of the predicted class map against the teacher's labels (Eq. 1)
  *   ComputeLoss      mean per-pixel cross-entropy against the teacher's hard labels
- *                    (Algorithm 1, "ComputeLoss"; Section 5.2, without the x5 object weighting)
+ *                    (Algorithm 1, "ComputeLoss"; Section 5.2), optionally weighted per pixel
  *   PartialBackward  chain rule from the loss down to the first trainable layer and no
  *                    further: the frozen front part's output (the feature map) is an input
  *                    and never receives a gradient (Section 4.2)
- *   OptimStep        gradient descent, optionally with momentum (Algorithm 1, "OptimStep")
+ *   OptimStep        gradient descent, optionally with momentum, or Adam (Algorithm 1,
+ *                    "OptimStep"; Section 5.2)
  *
  * The head is  conv3x3(c_in->c1)+bias+ReLU,  conv3x3(c1->c2)+bias+ReLU,  conv1x1(c2->n_classes)
  * +bias,  x8 bilinear up-sampling (pixel centres at half-integers, edge replication).
@@ -184,9 +185,9 @@ int st_partial_distill(const st_head_desc* desc, const void* features,
 /* Mean IoU (Eq. 1) of a class map against labels: IoU_c = |pred_c & label_c| / |pred_c | label_c|
  * averaged over the classes present in the labels (0 when none is).
  *   pred [n_pixels] uint8, labels [n_pixels] int32
- *   confusion [C, C] int64 out (row = label, column = prediction), overwritten; may be NULL
- *             only if workspace is given (C*C*8 bytes are then taken from it)
- *   miou  one double out (device)                                                          */
+ *   confusion [C, C] int64 out (row = label, column = prediction), overwritten; required
+ *   miou  one double out (device); 1 <= n_classes <= 256; labels outside [0, n_classes) and
+ *         predictions >= n_classes are not counted; three short launches, no workspace       */
 int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_t n_classes,
             int32_t ignore_index, int64_t* confusion, double* miou, void* stream);
 
