@@ -22,6 +22,7 @@
 // bias gradient (sums of dY over the positions) comes from one extra MFMA against a fragment of
 // ones in the blocks of the first input-channel tile.
 #include <algorithm>
+#include <vector>
 
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
@@ -274,27 +275,53 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
 
 bool wgrad3x3_mfma_supported(int cin, int cout) { return cin % 32 == 0 && cout % 32 == 0; }
 
-// Position splits of the two layers for the shared launch: tiles1 * s1 + tiles2 * s2 blocks should
-// cover the compute units once, and the longest per-wavefront share (the launch's critical
-// path) should be as short as possible; among equals, fewer partial copies.
+// Position splits of the two layers for the shared launch.  Every block pays a fixed cost (ring
+// fill, the reduction through LDS, the partial-result store: about 22 units' worth) on top of its
+// units, blocks start in launch order on whichever compute unit is free, and every partial copy
+// is read once more by the optimiser kernel.  The search simulates exactly that for every pair of
+// split counts and keeps the shortest; among equals, fewer partial copies.
 void wgrad_splits_for(const Geo& g, int* s1_out, int* s2_out)
 {
-    const int n_cu = 256;
-    // (with several heads every head brings its own set of blocks and its own positions)
+    constexpr int n_cu = 256, fixed_units = 22, reread_units_per_chip = 13;
     const int tiles1 = g.heads() * (g.c1 / 32) * (g.c_in / 32), tiles2 = g.heads() * (g.c2 / 32) * (g.c1 / 32);
     const int n_units = cdiv(g.padded_positions() / g.heads(), 16);
     int best1 = 1, best2 = 1;
     long best_cost = -1;
+    // compute units with the same free time form a group: (time, how many)
+    struct Group { long t; long n; };
+    auto run = [](std::vector<Group>& gs, long blocks, long d) {
+        long makespan = 0;
+        while (blocks > 0) {
+            size_t e = 0;
+            for (size_t i = 1; i < gs.size(); ++i)
+                if (gs[i].t < gs[e].t) e = i;
+            const long k = std::min(gs[e].n, blocks), t = gs[e].t + d;
+            gs[e].n -= k;
+            if (gs[e].n == 0) gs.erase(gs.begin() + e);
+            size_t j = 0;
+            for (; j < gs.size(); ++j)
+                if (gs[j].t == t) break;
+            if (j < gs.size()) gs[j].n += k; else gs.push_back(Group{t, k});
+            makespan = std::max(makespan, t);
+            blocks -= k;
+        }
+        return makespan;
+    };
+    std::vector<Group> gs;
     for (int s1 = 1; s1 <= 16; ++s1) {
-        int s2 = (n_cu - tiles1 * s1) / tiles2;
-        if (s2 < 1) s2 = 1;
-        if (s2 > 16) s2 = 16;
         // keep at least 8 units (128 positions) per wavefront
         if (s1 > 1 && cdiv(n_units, s1 * 4) < 8) break;
-        while (s2 > 1 && cdiv(n_units, s2 * 4) < 8) --s2;
-        const int rounds = cdiv(tiles1 * s1 + tiles2 * s2, n_cu);
-        const long cost = (long)rounds * std::max(cdiv(n_units, s1 * 4), cdiv(n_units, s2 * 4)) * 64 + s1 + s2;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best1 = s1; best2 = s2; }
+        for (int s2 = 1; s2 <= 16; ++s2) {
+            if (s2 > 1 && cdiv(n_units, s2 * 4) < 8) break;
+            const long d1 = cdiv(n_units, s1 * 4) + fixed_units, d2 = cdiv(n_units, s2 * 4) + fixed_units;
+            const long n1 = (long)tiles1 * s1, n2 = (long)tiles2 * s2;
+            // list scheduling on n_cu units, layer 1 first
+            gs.assign(1, Group{0, n_cu});
+            long makespan = run(gs, n1, d1);
+            makespan = std::max(makespan, run(gs, n2, d2));
+            const long cost = (makespan * n_cu + reread_units_per_chip * (n1 + n2)) * 64 + s1 + s2;
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best1 = s1; best2 = s2; }
+        }
     }
     *s1_out = best1; *s2_out = best2;
 }
