@@ -72,12 +72,17 @@ def kernel_work(wl):
         "conv1_fwd": ("mfma", conv1), "conv12_wgrad": ("mfma", conv1 + conv2),
         "conv2_fwd": ("mfma", conv2 + conv3), "conv2_dgrad": ("mfma", conv2), "conv1_dgrad": ("mfma", conv1),
         "conv3_fwd": ("mfma", conv3), "conv3_wgrad": ("mfma", conv3), "conv3_dgrad": ("mfma", conv3),
-        "conv3_bwd": ("mfma", 2 * conv3),
+        # the 1x1 classifier's backward is a skinny contraction (N = classes): a2 read twice (both
+        # layouts), d loss / d z read, da2 written twice (both layouts)
+        "conv3_bwd": ("hbm", (8.0 * wl.c2 + 4.0 * C) * M),
         "upsample_ce_grad": ("alu", 19.0 * C * P),
         "upsample_ce": ("alu", 10.0 * C * P),
         "sgd_update": ("hbm", (22.0 if wl.momentum else 14.0) * wl.n_params),
         "adam_update": ("hbm", 30.0 * wl.n_params),
-        "pack_features": ("hbm", 2.0 * wl.n * wl.c_in * wl.h * wl.w * 2),
+        # the launch that opens a call: features in and out (twice on the matrix-core path: both
+        # layouts), labels in, U^T of the labels out, parameters in and out
+        "pack+label_adjoint": ("hbm", (3.0 if wl.compute == "bf16" else 2.0) * wl.n * wl.c_in * wl.h * wl.w * (2 if wl.feat_dtype == "bf16" else 4)
+                               + 4.0 * P + 4.0 * C * M + 10.0 * wl.n_params),
     }
 
 
@@ -258,6 +263,17 @@ def main():
     others = {k: {kk: vv for kk, vv in roofline_of(k, v[0], v[1]).items()
                   if kk in ("bound", "achieved", "unit", "frac", "avg_launch_us")}
               for k, v in known.items() if k != dominant}
+    # the fused up-sampling + cross-entropy kernel against the other roof as well: as a streaming
+    # kernel it would move 4 C bytes of logits in and 4 C bytes of gradient out per low-resolution
+    # cell and 4 bytes of label per frame pixel (it is the vector ALUs that bind it, not these bytes)
+    for k in others:
+        if k.startswith("upsample_ce"):
+            cells, pixels = wl.n * wl.h * wl.w, wl.n * wl.H * wl.W
+            stream_bytes = (8.0 if k.startswith("upsample_ce_grad") else 4.0) * wl.n_classes * cells + 4.0 * pixels
+            gbs = stream_bytes / (others[k]["avg_launch_us"] * 1e-6) / 1e9
+            others[k]["hbm_achieved_GBs"] = round(gbs, 1)
+            others[k]["hbm_frac"] = round(gbs / PEAK_HBM_GBS, 5)
+            others[k]["binding_roof"] = "alu" if others[k]["frac"] >= others[k]["hbm_frac"] else "hbm"
 
     # the stand-alone metric call (st_miou: confusion histogram + mean IoU of a class map), the
     # per-frame pass of a clip; streaming bound: 1 B prediction + 4 B label per pixel
