@@ -17,7 +17,9 @@ bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 =
 // One block = C3B_BP consecutive padded positions (g is zero on the border).  The block first
 // forms g = d loss / d z for its cells from what the loss kernel left behind -- the per-tile slots
 // of U^T softmax (added in a fixed order: tile rows first), minus U^T of the one-hot labels, over
-// N_valid -- rounds it to bfloat16 and stages it in LDS in both orientations, with W3 transposed.
+// N_valid -- rounds it to bfloat16 and stages it in LDS in both orientations.  W3 comes transposed
+// and padded to 32 classes from the optimiser kernel ([channel][32]), so its MFMA A fragments are
+// 16-byte loads straight from memory.
 // Then
 //   wavefront w computes da2 for positions 32 (w % 2) .. +31 and half of the channel tiles
 //   (K = classes),
@@ -29,12 +31,14 @@ bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 =
 // the block is kept small: the grid then covers the whole chip and each chain is short.
 constexpr int C3B_BP = 64;
 
+// (one or two wavefronts per SIMD are all this kernel asks for: said explicitly, because the
+//  compiler otherwise keeps to 128 registers and then issues the slot loads one at a time)
 template <int C2>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 1)
 k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
                  const unsigned long long* __restrict__ n_valid, int CP, LossTiling lt,
                  const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
-                 const bf16* __restrict__ W3q, bf16* __restrict__ da2, bf16* __restrict__ da2T,
+                 const bf16* __restrict__ W3T, bf16* __restrict__ da2, bf16* __restrict__ da2T,
                  float* __restrict__ part, Geo g, int PPT, int guard, int grp_blocks)
 {
     constexpr int BP = C3B_BP;
@@ -43,12 +47,11 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     constexpr int DW = (OT + 3) / 4;       // dW3 channel tiles per wavefront
     constexpr int KS = BP / 16;            // K steps of the dW3 product
     constexpr int GP = BP + 8;             // pitch of g_cp rows (positions)
-    constexpr int GC = 32 + 8;             // pitch of g_pc / w3t rows (classes)
+    constexpr int GC = 32 + 8;             // pitch of g_pc rows (classes)
     constexpr int OLD = C2 + 8;            // pitch of the output tile
     static_assert(OT % 2 == 0, "two wavefronts share the channel tiles of a position half");
     __shared__ __attribute__((aligned(16))) bf16 g_cp[32 * GP];     // [class][position]
     __shared__ __attribute__((aligned(16))) bf16 g_pc[BP * GC];     // [position][class]
-    __shared__ __attribute__((aligned(16))) bf16 w3t[C2 * GC];      // [channel][class]
     __shared__ __attribute__((aligned(16))) bf16 Os[BP * OLD];      // da2 tile [position][channel]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -59,7 +62,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     const int head = g.grouped ? blockIdx.x / grp_blocks : 0;
     const int m0 = g.grouped ? head * frame + (blockIdx.x - head * grp_blocks) * BP : blockIdx.x * BP;
     const int m_end = g.grouped ? (head + 1) * frame : PP;
-    W3q += (size_t)head * g.C * C2;
+    W3T += (size_t)head * C2 * 32;
 
     // ---- early loads: ReLU mask of this lane's position, a2 fragments of this wavefront's tiles
     const int pm = (wave & 1) * 32 + l32;          // position (inside the block) for the da2 part
@@ -70,6 +73,12 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     for (int t = 0; t < OH; ++t)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(a2 + mrow + (t0 + t) * 32 + rg * 8 + lhi * 4);
+    // W3^T fragments of this wavefront's da2 tiles: rows = channels, k = 16 classes per step
+    bf16x8 wfr[OH][2];
+#pragma unroll
+    for (int t = 0; t < OH; ++t)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) wfr[t][ks] = *(const bf16x8*)(W3T + ((size_t)(t0 + t) * 32 + l32) * 32 + ks * 16 + lhi * 8);
     bf16x8 xf[DW][KS];
 #pragma unroll
     for (int d = 0; d < DW; ++d) {
@@ -107,24 +116,31 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
             }
         const int cstride = LOSS_CH * LOSS_CW;
         const size_t tbase = (size_t)img * g.C * hw + cy * g.w + cx;
+        // all loads of the gather first (their addresses do not depend on each other), then the sums
+        float sv[32 / NQ][6], tv[32 / NQ];
+#pragma unroll
+        for (int k = 0; k < 32 / NQ; ++k) {
+            const int c = min(cq + NQ * k, g.C - 1);     // classes beyond C re-read the last one, unused
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) sv[k][a * 2 + b] = slots[(size_t)off[a][b] + (size_t)c * cstride];
+            tv[k] = T[tbase + (size_t)c * hw];
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < 32 / NQ; ++k) {
             const int cc = cq + NQ * k;
-            const int c = min(cc, g.C - 1);     // classes beyond C re-read the last one, unused
             float v = 0.f;
 #pragma unroll
             for (int a = 0; a < 3; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) v = __builtin_fmaf(wgt[a][b], slots[(size_t)off[a][b] + (size_t)c * cstride], v);
-            v = (v - T[tbase + (size_t)c * hw]) * inv_n;
+                for (int b = 0; b < 2; ++b) v = __builtin_fmaf(wgt[a][b], sv[k][a * 2 + b], v);
+            v = (v - tv[k]) * inv_n;
             const bf16 q = (cc < g.C) ? (bf16)v : (bf16)0.f;
             g_cp[cc * GP + p] = q;
             g_pc[p * GC + cc] = q;
         }
-    }
-    for (int i = tid; i < C2 * 32; i += 256) {
-        const int o = i % C2, c = i / C2;
-        w3t[o * GC + c] = c < g.C ? W3q[(size_t)c * C2 + o] : (bf16)0.f;
     }
     __syncthreads();
 
@@ -140,8 +156,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
             const bf16x8 gf = *(const bf16x8*)(g_pc + pm * GC + ks * 16 + lhi * 8);
 #pragma unroll
             for (int t = 0; t < OH; ++t) {
-                const bf16x8 wf = *(const bf16x8*)(w3t + ((t0 + t) * 32 + l32) * GC + ks * 16 + lhi * 8);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, gf, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[t][ks], gf, acc[t], 0, 0, 0);
             }
         }
         // (a2 is zero on the border, and g is zero there too: border rows of da2 come out zero)
@@ -205,7 +220,7 @@ int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions() / g.heads(
 size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
-                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3q,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
                     bf16* da2, bf16* da2T, float* part)
 {
     const Geo& g = p.g;
@@ -213,7 +228,7 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
     const dim3 grid(g.heads() * grp_blocks);
     const int CP = (g.C + 3) / 4 * 4;   // class padding of the loss kernel's slots
 #define ST_C3B(C2) ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2>), grid, dim3(256), 0, slots, T, n_valid, CP, \
-                             p.lt, a2, a2T, W3q, da2, da2T, part, g, p.PPT, p.guard, grp_blocks)
+                             p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks)
     switch (g.c2) {
     case 64: ST_C3B(64); break;
     case 128: ST_C3B(128); break;

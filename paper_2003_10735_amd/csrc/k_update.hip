@@ -28,11 +28,13 @@ namespace st {
 //   wq2t          : W2 with the roles of o and i exchanged and the taps mirrored (tap' = 8 - tap),
 //                   for the data-gradient of layer 2 run as a forward convolution
 //   wq1t          : the same for W1, only when the caller wants the gradient of the features
+//   wq3t          : W3 transposed, [c2][32] with zero columns beyond the classes: the A fragments of
+//                   the classifier's backward kernel, read straight from memory
 // wq3 has theta's order.  So do wq1 and wq2 for the plain tiled kernels (frag == 0); the
 // matrix-core convolutions read wq1, wq2 and wq2t in fragment order (wfrag_index).
 struct UpdateArgs {
     float* theta; float* vel; float* vel2; const float* grad; size_t stride; int splits1, splits2;
-    bf16* wq1; bf16* wq1t; bf16* wq2; bf16* wq2t; bf16* wq3;
+    bf16* wq1; bf16* wq1t; bf16* wq2; bf16* wq2t; bf16* wq3; bf16* wq3t;
     ParamOffsets po; int c_in, c1, c2;
     int frag;        // wq1 / wq2 / wq2t in fragment order
     float lr, mu;
@@ -110,7 +112,11 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
                 a.wq2[wfrag_index(o, tap, i, a.c1)] = q;
                 a.wq2t[wfrag_index(i, 8 - tap, o, a.c2)] = q;
             } else a.wq2[r] = q;
-        } else if (j >= a.po.W3 && j < a.po.b3) a.wq3[j - a.po.W3] = q;
+        } else if (j >= a.po.W3 && j < a.po.b3) {
+            const size_t r = j - a.po.W3;
+            a.wq3[r] = q;
+            if (a.wq3t) a.wq3t[(r % a.c2) * 32 + r / a.c2] = q;
+        }
     }
 }
 
@@ -239,6 +245,7 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
         if (a.wq1) { a.wq1 += head * a.hs_wq1; a.wq2 += head * a.hs_wq2; a.wq3 += head * a.hs_wq3; }
         if (a.wq1t) a.wq1t += head * a.hs_wq1;
         if (a.wq2t) a.wq2t += head * a.hs_wq2;
+        if (a.wq3t) a.wq3t += head * (size_t)a.c2 * 32;
         if (a.ext_in) a.ext_in += head * a.hs_ext;
         if (a.ext_out) a.ext_out += head * a.hs_ext;
         if (a.part3) a.part3 += head * a.hs_part3;
@@ -401,6 +408,7 @@ static int step_end_args(const Plan& p, char* ws, float lr, float mu, const Adam
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;
     a.wq2t = (p.bf16 && p.wq2t) ? (bf16*)(ws + p.wq2t) : nullptr;
     a.wq3 = p.bf16 ? (bf16*)(ws + p.wq3) : nullptr;
+    a.wq3t = p.wq3t ? (bf16*)(ws + p.wq3t) : nullptr;
     a.po = p.po; a.c_in = p.g.c_in; a.c1 = p.g.c1; a.c2 = p.g.c2;
     a.frag = p.mfma ? 1 : 0;
     a.lr = lr; a.mu = mu; a.do_step = do_step ? 1 : 0;

@@ -169,6 +169,7 @@ Plan make_plan(const st_head_desc& d)
         p.wq2 = take(off, heads * (p.po.b2 - p.po.W2) * 2);
         p.wq2t = take(off, heads * (p.po.b2 - p.po.W2) * 2);
         p.wq3 = take(off, heads * (p.po.b3 - p.po.W3) * 2);
+        if (p.mfma) p.wq3t = take(off, heads * (size_t)g.c2 * 32 * 2);
     }
     p.loss_part = take(off, (size_t)loss_blocks(g) * 4);
     p.counters = take(off, std::max((size_t)256, heads * 8));   // valid pixels (their weights), one count per head
@@ -218,6 +219,7 @@ static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
                 z.add(ws + tm[i] + b * blk + tail_at, blk - tail_at);
             }
     }
+    if (p.wq3t) z.add(ws + p.wq3t, (size_t)g.heads() * g.c2 * 32 * 2);      // rows of the classes beyond C stay zero
     z.add(ws + p.counters, std::max((size_t)256, (size_t)g.heads() * 8));
     z.add(ws + p.conf, (size_t)g.n * g.C * g.C * 8);
     zero_regions(c, z);
@@ -266,7 +268,7 @@ static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat)
     float* grad = (float*)(ws + p.grad);
     conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
                    (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
-                   (const bf16*)(ws + p.wq3), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
+                   (const bf16*)(ws + p.wq3t), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
                  (const bf16*)(ws + p.a1), dfeat ? (bf16*)(ws + p.da1) : nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
     if (dfeat)

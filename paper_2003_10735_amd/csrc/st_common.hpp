@@ -121,6 +121,7 @@ struct Plan {
     size_t zpart; int z_parts;     // shares of the logits left by the classifier-fused convolution
     size_t theta, vel, vel2, grad, best;   // vel: velocity or Adam's m; vel2: Adam's v
     size_t wq1, wq1t, wq2, wq2t, wq3;      // bfloat16 operand copies of the weights
+    size_t wq3t;                           // W3 transposed, [c2][32 classes] (zero beyond C): MFMA A fragments of its backward
     size_t loss_part, counters, conf, scal;
     size_t losses, mious;            // staging when the caller passes no result arrays
     size_t total;

@@ -34,7 +34,7 @@ bool conv3_mfma_supported(int c2, int C);
 int conv3_bwd_blocks(const Geo& g);
 size_t conv3_bwd_slot_floats(const Geo& g);
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
-                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3q,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
                     bf16* da2, bf16* da2T, float* part);
 
 // k_loss.hip
