@@ -129,7 +129,8 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // The loads are written in assembly: the compiler would order every barrier behind all
     // outstanding loads of this kind, while the pipeline below needs two stages in flight.
     // (M0 is reserved: the compiler sets it right before each of its own uses and keeps nothing
-    //  in it, and this kernel gives it no such use.)
+    //  in it, and this kernel gives it no such use.  One wait state separates the scalar write of
+    //  M0 from the load that reads it.)
     const int lrow = lane >> 3, lpc = lane & 7;
     const int sw01 = (4 * wave + (lrow >> 1)) & 7, sw2 = lrow >> 1;          // (row >> 1) & 7 of the rows filled
     const int xo0 = ((wave * 8 + lrow) * a.cin + ((lpc ^ sw01) << 3)) * 2;   // byte offsets inside a slab
@@ -161,7 +162,7 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
 #define CV_FETCH_NEXT                                                                             \
     if (++f_cc == c_chunks) { f_cc = 0; xsp += x_row; w_soff += w_row; } else { xsp += x_step; w_soff += w_step; }
 #define CV_DMA(VOFF, LDSADDR)                                                                     \
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(VOFF), "s"(xsp),      \
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(VOFF), "s"(xsp), \
                  "s"(LDSADDR) : "memory");
 #define CV_LOAD_X1(BUF, I)                                                                        \
     {                                                                                             \
