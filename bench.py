@@ -96,6 +96,22 @@ def call_flops(wl):
     return (wl.steps + 1) * fwd + wl.steps * bwd
 
 
+def step_bytes(wl):
+    """Algorithmic bytes of one optimiser step (one forward, one partial backward, one update) when
+    every tensor is moved once per use: bf16 (or the compute type's) activations and operand
+    weights, float32 logits, gradients and parameters, int32 labels."""
+    e = 2.0 if wl.compute == "bf16" else 4.0
+    M, P, C = wl.n * wl.h * wl.w, wl.n * wl.H * wl.W, wl.n_classes
+    feat, a1, a2 = e * M * wl.c_in, e * M * wl.c1, e * M * wl.c2
+    w1, w2 = 9.0 * wl.c1 * wl.c_in, 9.0 * wl.c2 * wl.c1
+    z = 4.0 * M * C
+    fwd = (feat + e * w1 + a1) + (a1 + e * w2 + a2) + (a2 + z)
+    loss = 2 * z + 4.0 * P
+    bwd = (a2 + z + a2) + (a2 + a1 + 4 * w2) + (a2 + e * w2 + a1) + (feat + a1 + 4 * w1)
+    upd = (22.0 if wl.momentum else 14.0) * wl.n_params
+    return fwd + loss + bwd + upd
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -376,6 +392,13 @@ def main():
                    "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss), "full_backward": bool(args.full_backward)},
         "key_frames_per_s": round(args.steps / elapsed, 3),
         "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
+        # the whole call against both roofs (a call of k steps has k + 1 forwards; its bytes are
+        # counted as k steps' worth, a slight under-count)
+        "whole_call": {"tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
+                       "mfma_frac": round(call_flops(wl) * args.steps / elapsed / 1e12 / (PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32), 5),
+                       "algorithmic_GBs": round(step_bytes(wl) * wl.steps * args.steps / elapsed / 1e9, 1),
+                       "hbm_frac": round(step_bytes(wl) * wl.steps * args.steps / elapsed / 1e9 / PEAK_HBM_GBS, 5),
+                       "algorithmic_MB_per_step": round(step_bytes(wl) / 1e6, 2)},
         "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],
         "kernel_us": breakdown,
         "roofline": roofline,
