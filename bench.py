@@ -9,7 +9,7 @@ Prints ONE JSON line.  Extra objects:
   roofline      the kernel that takes the largest share of the call, its algorithmic work per
                 launch over its average launch duration (HIP events on the launch stream, taken
                 during the timed region), against the chip's published peak
-  cpu_baseline  the CPU oracle (test infrastructure, untuned) on the host cores of this machine
+  cpu_baseline  the CPU oracle (test infrastructure, untuned) on the host cores of the machine
 """
 from __future__ import annotations
 
@@ -141,7 +141,7 @@ def main():
                          "region): the known-size reference that scales hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; sharding is by video stream (one head per "
+        print("bench.py: the library runs on one GPU; sharding is by video stream (one head per "
               "client per GPU, no exchange) and is not part of it. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
