@@ -54,8 +54,10 @@ __device__ __forceinline__ float wave_sum(float v)
 
 constexpr int LOSS_THREADS = 512;
 
+// (up to 24 padded classes the kernel is held to 128 registers, so that two blocks share a
+//  compute unit: the phases of one then fill the barriers and memory waits of the other)
 template <int CP, bool GRAD>
-__global__ void __launch_bounds__(LOSS_THREADS)
+__global__ void __launch_bounds__(LOSS_THREADS, (CP <= 24 ? 4 : 2))
 k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
        unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
