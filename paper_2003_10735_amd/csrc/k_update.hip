@@ -319,17 +319,18 @@ __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
 }
 
 // The launch that opens a call: three kinds of blocks that do not depend on each other,
-//   [0, nb_pack)                   feature packing (pack_features_block),
-//   [nb_pack, nb_pack + nb_label)  U^T of the label map and the pixel counts (label_adjoint_block),
-//   the rest                       the caller's parameters into theta and the bfloat16 operand
-//                                  copies: the blocks of k_step_end, head by head.
+//   first   U^T of the label map and the pixel counts (label_adjoint_block),
+//   then    the caller's parameters into theta and the bfloat16 operand copies: the blocks of
+//           k_step_end, head by head,
+//   last    feature packing (pack_features_block).
 // Run one after the other they are three short launches, each of which leaves most of the chip
 // idle for most of its time.
 struct BeginArgs {
     const void* features; void* feat; void* featT; int in_bf16, out_bf16, PPT, guard;
+    int pack_vec;                          // the 16-byte packing role over the padded grid
     int pack_x, pack_y, nb_pack;           // pack grid: pack_x column tiles x pack_y channel tiles x rows
     const int32_t* labels; const uint8_t* wmap; float* T; unsigned long long* n_valid; int CP, nb_label;
-    int nb_update;                         // blocks of the parameter role per head
+    int nb_update, nb_update_all;          // blocks of the parameter role per head, and of all heads
     Geo g;
 };
 
@@ -337,9 +338,23 @@ __global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, F
 {
     extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
     int b = blockIdx.x;
-    if (b < q.nb_pack) {
+    // (blocks start in index order: the label blocks, each a long chain of dependent steps, go
+    //  first, the short packing blocks last)
+    if (b < q.nb_label) {
+        float* colsum = dyn_lds;
+        unsigned int* cnt_part = (unsigned int*)(dyn_lds + q.CP * (LABEL_NCOL + 1));
+        label_adjoint_block(q.labels, q.wmap, q.T, q.n_valid, q.g, b, colsum, cnt_part, q.CP);
+        return;
+    }
+    b -= q.nb_label;
+    if (b >= q.nb_update_all) {
+        b -= q.nb_update_all;
         float (*tile)[33] = (float (*)[33])dyn_lds;
         const int bx = b % q.pack_x, by = (b / q.pack_x) % q.pack_y, bz = b / (q.pack_x * q.pack_y);
+        if (q.pack_vec) {
+            pack_features_vec_block((const bf16*)q.features, (bf16*)q.feat, (bf16*)q.featT, q.g, q.PPT, q.guard, bx, by, bz, (bf16*)dyn_lds);
+            return;
+        }
         if (q.out_bf16) {
             if (q.in_bf16) pack_features_block<bf16, bf16>((const bf16*)q.features, (bf16*)q.feat, (bf16*)q.featT, q.g, q.PPT, q.guard, bx, by, bz, tile);
             else pack_features_block<float, bf16>((const float*)q.features, (bf16*)q.feat, (bf16*)q.featT, q.g, q.PPT, q.guard, bx, by, bz, tile);
@@ -349,14 +364,6 @@ __global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, F
         }
         return;
     }
-    b -= q.nb_pack;
-    if (b < q.nb_label) {
-        float* colsum = dyn_lds;
-        unsigned int* cnt_part = (unsigned int*)(dyn_lds + q.CP * (LABEL_NCOL + 1));
-        label_adjoint_block(q.labels, q.wmap, q.T, q.n_valid, q.g, b, colsum, cnt_part, q.CP);
-        return;
-    }
-    b -= q.nb_label;
     step_end_block(a, f, b % q.nb_update, b / q.nb_update);
 }
 
@@ -444,6 +451,14 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
     ST_LAUNCH(c, name, k_step_end, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
 }
 
+// Whether the packing role of the call-opening launch writes the whole padded grid of both feature
+// buffers (then only their guards need clearing): matrix-core path, bfloat16 features whose rows
+// are multiples of 16 bytes from a 16-byte aligned start.
+bool pack_covers_borders(const Plan& p, const void* features, int feat_dtype)
+{
+    return p.mfma && feat_dtype == ST_BF16 && p.g.w % 8 == 0 && p.g.c_in % 64 == 0 && ((uintptr_t)features & 15) == 0;
+}
+
 // Opens a call in one launch: packs the features, takes the caller's parameters (OIHW order)
 // into theta and the bfloat16 copies and, with labels, computes T = U^T (one-hot valid labels)
 // and the pixel counts (n_valid must be clear).  The workspace must have been cleared before.
@@ -457,8 +472,14 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
     q.featT = (p.bf16 && p.featT) ? ws + p.featT : nullptr;
     q.in_bf16 = feat_dtype == ST_BF16; q.out_bf16 = p.bf16 ? 1 : 0;
     q.PPT = p.PPT; q.guard = p.guard;
-    q.pack_x = cdiv(g.w, 32); q.pack_y = cdiv(g.c_in, 32);
-    q.nb_pack = q.pack_x * q.pack_y * g.n * g.h;
+    q.pack_vec = pack_covers_borders(p, features, feat_dtype) ? 1 : 0;
+    if (q.pack_vec) {
+        q.pack_x = cdiv(g.Wp, 64); q.pack_y = g.c_in / 64;
+        q.nb_pack = q.pack_x * q.pack_y * g.n * g.Hp;
+    } else {
+        q.pack_x = cdiv(g.w, 32); q.pack_y = cdiv(g.c_in, 32);
+        q.nb_pack = q.pack_x * q.pack_y * g.n * g.h;
+    }
     q.g = g;
     q.CP = (g.C + 3) / 4 * 4;
     if (labels) {
@@ -469,7 +490,9 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
     UpdateArgs a;
     const FinishArgs f = finish_args(p, ws, nullptr, nullptr, nullptr);
     q.nb_update = step_end_args(p, ws, 0.f, 0.f, nullptr, false, false, head_params, w1t, f, a);
-    const size_t lds = std::max((size_t)32 * 33 * sizeof(float), (size_t)(q.CP * (LABEL_NCOL + 1) + 4) * sizeof(float));
+    q.nb_update_all = q.nb_update * g.heads();
+    const size_t lds = std::max(std::max((size_t)32 * 33 * sizeof(float), (size_t)64 * PACKV_PITCH * sizeof(bf16)),
+                                (size_t)(q.CP * (LABEL_NCOL + 1) + 4) * sizeof(float));
     ST_LAUNCH(c, labels ? "pack+label_adjoint+params_in" : "pack+params_in", k_call_begin,
               dim3(q.nb_pack + q.nb_label + q.nb_update * g.heads()), dim3(256), lds, q, a, f);
 }

@@ -188,32 +188,35 @@ static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 //  * plain kernels: all of them (they write interior cells only and rely on zero borders);
 //  * matrix-core kernels: every position of a1, a2, da1, da2 and of their channel-major copies is
 //    rewritten (zeros on the border) by its producer in every pass, so only the guards in front
-//    of and behind the positions need clearing -- plus the features, whose packing kernel writes
-//    interior cells only.
-static void prepare_workspace(Ctx& c, const Plan& p, char* ws)
+//    of and behind the positions need clearing -- plus the features, unless their packing role
+//    covers the padded grid as well (feat_covered).
+static void prepare_workspace(Ctx& c, const Plan& p, char* ws, bool feat_covered)
 {
     ZeroList z;
     const Geo& g = p.g;
-    const int n_regions = 2 + 8 + 2 * 2 * (g.c1 / 32 + g.c2 / 32) + 2;
+    const int n_regions = 2 + 8 + 2 * 2 * (g.c1 / 32 + g.c2 / 32) + 2 * (g.c_in / 32) + 3;
     if (!p.mfma || n_regions > ZeroList::MAX) {
         z.add(ws + p.zero_begin, p.zero_end - p.zero_begin);
     } else {
         const size_t PP = (size_t)g.padded_positions(), G = (size_t)p.guard;
-        z.add(ws + p.feat - G * g.c_in * 2, (PP + 2 * G) * g.c_in * 2);
-        z.add(ws + p.featT, (size_t)g.c_in * p.PPT * 2);
-        const size_t pm[4] = {p.a1, p.a2, p.da1, p.da2};
-        const int pc[4] = {g.c1, g.c2, g.c1, g.c2};
-        for (int i = 0; i < 4; ++i) {
+        if (!feat_covered) {
+            z.add(ws + p.feat - G * g.c_in * 2, (PP + 2 * G) * g.c_in * 2);
+            z.add(ws + p.featT, (size_t)g.c_in * p.PPT * 2);
+        }
+        const size_t pm[5] = {p.a1, p.a2, p.da1, p.da2, p.feat};
+        const int pc[5] = {g.c1, g.c2, g.c1, g.c2, g.c_in};
+        const int nbuf = feat_covered ? 5 : 4;
+        for (int i = 0; i < nbuf; ++i) {
             z.add(ws + pm[i] - G * pc[i] * 2, G * pc[i] * 2);
             z.add(ws + pm[i] + PP * pc[i] * 2, G * pc[i] * 2);
         }
         // channel-major copies [C/32][PPT/8][32][8]: per channel block, the column groups of the
         // head guard and those from the end of the positions (rounded down to a group) on
-        const size_t tm[4] = {p.a1T, p.a2T, p.da1T, p.da2T};
+        const size_t tm[5] = {p.a1T, p.a2T, p.da1T, p.da2T, p.featT};
         const size_t blk = (size_t)p.PPT * 32 * 2;                 // bytes of one channel block
         const size_t head = G * 32 * 2;                            // guard columns (a multiple of 8)
         const size_t tail_at = (G + PP / 8 * 8) * 32 * 2;
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < nbuf; ++i)
             for (int b = 0; b < pc[i] / 32; ++b) {
                 z.add(ws + tm[i] + b * blk, head);
                 z.add(ws + tm[i] + b * blk + tail_at, blk - tail_at);
@@ -342,7 +345,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
     const Plan p = make_plan(*desc);
     char* ws = (char*)workspace;
     Ctx c{as_stream(stream), ST_OK};
-    prepare_workspace(c, p, ws);
+    prepare_workspace(c, p, ws, pack_covers_borders(p, features, desc->feat_dtype));
     call_begin(c, p, ws, features, desc->feat_dtype, head_params, false, nullptr, nullptr);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
     forward(c, p, ws, z);
@@ -466,7 +469,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     unsigned long long* conf = (unsigned long long*)(ws + p.conf);
     double* metric_dev = (double*)(ws + p.scal);
 
-    prepare_workspace(c, p, ws);
+    prepare_workspace(c, p, ws, pack_covers_borders(p, features, desc->feat_dtype));
     if (mu != 0.f) permute_params(c, p, velocity, (float*)(ws + p.vel), 0);
     if (use_adam) {
         permute_params(c, p, adam_m, (float*)(ws + p.vel), 0);

@@ -37,6 +37,66 @@ __device__ __forceinline__ void pack_features_block(const Tin* __restrict__ f, E
     }
 }
 
+// The same for bfloat16 in and out on the matrix-core path, with 16-byte accesses and covering the
+// whole padded grid (zeros on the border), so that nothing of the two feature buffers but their
+// guards needs clearing beforehand.  One block (256 threads): one padded row yp (bz = img * Hp + yp),
+// 64 channels (by), 64 padded columns xp0 .. xp0 + 63 (bx).  Needs w % 8 == 0, c_in % 64 == 0 and a
+// 16-byte aligned source.  `tile` is 64 rows of PACKV_PITCH bfloat16 in LDS.
+constexpr int PACKV_PITCH = 64 + 8;
+__device__ __forceinline__ void pack_features_vec_block(const bf16* __restrict__ f, bf16* __restrict__ out,
+                                                        bf16* __restrict__ outT, const Geo& g, int PPT, int guard,
+                                                        int bx, int by, int bz, bf16* tile)
+{
+    const int xp0 = bx * 64, c0 = by * 64;
+    const int img = bz / g.Hp, yp = bz % g.Hp;
+    const bool row_in = yp >= 1 && yp <= g.h;
+    const int tid = threadIdx.x;
+    // source chunks of 8 columns x = 8q .. 8q + 7 land at padded columns x + 1; the tile's first
+    // padded column (a border or an x = 8k - 1) comes from the chunk before
+    bf16x8 v[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + r * 256, ch = i >> 3, q = i & 7;
+        const int x = xp0 + 8 * q;                         // first column of the chunk
+        v[r] = bf16x8{(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
+        if (row_in && x < g.w) v[r] = *(const bf16x8*)(f + (((size_t)img * g.c_in + c0 + ch) * g.h + (yp - 1)) * g.w + x);
+    }
+    bf16 first = (bf16)0.f;                                // column xp0 - 1 of channel tid (threads 0 .. 63)
+    if (tid < 64 && row_in && xp0 >= 1 && xp0 - 1 < g.w)
+        first = f[(((size_t)img * g.c_in + c0 + tid) * g.h + (yp - 1)) * g.w + xp0 - 1];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + r * 256, ch = i >> 3, q = i & 7;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int xl = 8 * q + e + 1;                  // padded column inside the tile
+            if (xl < 64) tile[ch * PACKV_PITCH + xl] = v[r][e];
+        }
+    }
+    if (tid < 64) tile[tid * PACKV_PITCH] = first;
+    __syncthreads();
+    const size_t prow = ((size_t)img * g.Hp + yp) * g.Wp;  // padded position of column 0 of this row
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + r * 256;
+        {   // position-major: 8 channels of one position
+            const int xl = i >> 3, cq = i & 7;
+            if (xp0 + xl < g.Wp) {
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = tile[(cq * 8 + e) * PACKV_PITCH + xl];
+                *(bf16x8*)(out + (prow + xp0 + xl) * g.c_in + c0 + cq * 8) = o;
+            }
+        }
+        {   // channel-major: 8 positions of one channel
+            const int ch = i >> 3, g8 = i & 7;
+            if (xp0 + 8 * g8 < g.Wp)
+                *(bf16x8*)(outT + xt_index(c0 + ch, guard + (int)prow + xp0 + 8 * g8, PPT / 8)) =
+                    *(const bf16x8*)(tile + ch * PACKV_PITCH + 8 * g8);
+        }
+    }
+}
+
 // weight with which frame index X (0 .. 8*len-1) contributes to cell `cell` of a line of `len`
 // cells: the tent (1, 3, .. 15, 15, .. 3, 1)/16 around the cell, plus, for the first and last
 // cell, the weight that edge replication folds back onto them

@@ -61,6 +61,7 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, cons
 //   theta <- theta - step_scale * m / (sqrt(v) * inv_sqrt_bc2 + eps),
 //   step_scale = lr / (1 - beta1^t),  inv_sqrt_bc2 = 1 / sqrt(1 - beta2^t).
 struct AdamStep { float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_scale, inv_sqrt_bc2; };
+bool pack_covers_borders(const Plan& p, const void* features, int feat_dtype);
 void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_dtype, const float* head_params,
                 bool w1t, const int32_t* labels, const uint8_t* pixel_weights);
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
