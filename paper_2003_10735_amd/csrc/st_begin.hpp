@@ -150,14 +150,27 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
             ws[r] = wm ? wm[at] : 1u;
         }
         const bool own_col = col >= 4 && col < NCOL - 4;
+        // label maps are piecewise constant: rows with the same label are added up in a register
+        // and reach the table once per run (all terms are multiples of 1/256, so any grouping of
+        // the additions gives the same float32 sum)
+        int run_y = -1;
+        float run = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int Y = Yt + r, y = ys[r];
-            if (xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C) {
-                colsum[y * PITCH + col] += (float)ws[r] * tap_weight(Y, cy, g.h);
+            const bool ok = xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C;
+            const int yy = ok ? y : -1;
+            if (yy != run_y) {
+                if (run_y >= 0) colsum[run_y * PITCH + col] += run;
+                run_y = yy;
+                run = 0.f;
+            }
+            if (ok) {
+                run += (float)ws[r] * tap_weight(Y, cy, g.h);
                 if (own_col && r >= 4 && r < 12) cnt += ws[r];
             }
         }
+        if (run_y >= 0) colsum[run_y * PITCH + col] += run;
     }
     if (n_valid) {
 #pragma unroll
