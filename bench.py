@@ -199,10 +199,16 @@ def main():
                               pixel_weights=pw, feature_grad=dfeat, graph=graph)
 
     use_graph = not args.no_graph
+    graph_note = None
     for _ in range(args.warmup):
         one_call()
         if use_graph:
-            one_call(graph=True)
+            try:
+                one_call(graph=True)
+                torch.cuda.synchronize()
+            except (st.StError, RuntimeError) as exc:      # no graph on this system: time the plain launches
+                use_graph = False
+                graph_note = f"graph launch unavailable ({exc}); "
     torch.cuda.synchronize()
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
@@ -404,7 +410,8 @@ def main():
         "roofline": roofline,
         "other_kernels": others,
         "miou_pass": miou_pass,
-        "launch": "cached HIP graph (st_distill_opts.use_graph)" if use_graph else "kernel by kernel in the stream",
+        "launch": "cached HIP graph (st_distill_opts.use_graph)" if use_graph
+                  else (graph_note or "") + "kernel by kernel in the stream",
         "stream_launch": stream_launch,
         "grouped": grouped,
         "cpu_baseline": cpu_baseline,
