@@ -60,7 +60,9 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     const WgradArgs& a = second ? a2 : a1;
     const int bid = second ? blockIdx.x - blocks1 : blockIdx.x;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the wavefront number through readfirstlane: the compiler then keeps everything derived
+    //  from it -- the unit range, the loop counter, the load offsets -- in scalar registers)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lhi = lane >> 5;
     // XCD-aware order: consecutive blocks go to different XCDs; give each XCD a contiguous run
     // of work items in split-major order, so that one XCD's L2 only ever sees about 1/8 of the
@@ -85,12 +87,22 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     const int unit0 = (split * 4 + wave) * a.units_per_wave;
     const int unit1 = min(unit0 + a.units_per_wave, a.n_units);
     // blocked layout: one 8-position group of 32 channels is 256 elements; lane (l32, lhi) reads
-    // channel l32 of group 2u + lhi, so a wavefront's fragment load is one contiguous kilobyte
+    // channel l32 of group 2u + lhi, so a wavefront's fragment load is one contiguous kilobyte.
+    // The operands are read through buffer descriptors: the base (the unit before this
+    // wavefront's first; for X one kernel row further up) sits in scalar registers, the lane
+    // offset is fixed, and every load takes one scalar offset -- no address arithmetic at all
+    // in the vector unit, which the K loop has no issue slots to spare for.
     const int NG = a.PPT >> 3;
     const int g0 = (a.guard >> 3) + head * a.head_groups8;     // this head's first 8-position group
-    const bf16* ya = a.dYT + (((size_t)(o0 >> 5) * NG + g0 + lhi) << 8) + l32 * 8;
-    const bf16* xb = a.XT + (((size_t)(i0 >> 5) * NG + g0 + lhi) << 8) + l32 * 8;
     const int row_groups = a.Wp >> 3;   // one kernel row = this many 8-position groups
+    const int row_bytes = row_groups * 512;
+    const bf16* ybase = a.dYT + (((size_t)(o0 >> 5) * NG + g0) << 8) + (ptrdiff_t)(unit0 - 1) * 512;
+    const bf16* xbase = a.XT + (((size_t)(i0 >> 5) * NG + g0) << 8) + (ptrdiff_t)(unit0 - 1) * 512 -
+                        (ptrdiff_t)row_groups * 256;
+    const int span = (max(unit1 - unit0, 0) + 2) * 1024;       // units unit0 - 1 .. unit1
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc((void*)ybase, 0, span, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)xbase, 0, span + 2 * row_bytes, 0x00020000);
+    const unsigned lane_off = lhi * 512 + l32 * 16;
     const bool want_bias = it == 0;
     const int swap_addr = (lane ^ 32) << 2;   // ds_bpermute address of the lane holding the other half
     const bf16 one = (bf16)1.0f;
@@ -106,10 +118,10 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     u32x4 ry[DEPTH], rx[DEPTH][3];
 #define WG_LOAD(SLOT, U)                                                                        \
     {                                                                                           \
-        const ptrdiff_t g_ = (ptrdiff_t)(U) * 2 * 256;                                          \
-        ry[SLOT] = *(const u32x4*)(ya + g_);                                                    \
+        const int s_ = ((U) - unit0 + 1) * 1024;                                                \
+        ry[SLOT] = __builtin_amdgcn_raw_buffer_load_b128(yrs, lane_off, s_, 0);                 \
         _Pragma("unroll") for (int kh = 0; kh < 3; ++kh)                                        \
-            rx[SLOT][kh] = *(const u32x4*)(xb + g_ + (ptrdiff_t)(kh - 1) * row_groups * 256);   \
+            rx[SLOT][kh] = __builtin_amdgcn_raw_buffer_load_b128(xrs, lane_off, s_ + kh * row_bytes, 0); \
     }
     // The three taps of a kernel row differ by one position.  Moving the reduction index instead
     // of the window,
@@ -149,6 +161,25 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
         ypb[BUF][0] = ymb[BUF][1]; ypb[BUF][1] = ymb[BUF][2]; ypb[BUF][2] = ymb[BUF][3];        \
         ypb[BUF][3] = __builtin_amdgcn_alignbyte(next_, w_[3], 2);                              \
     }
+    // the same in two halves (the fragment at p - 1, then the one at p + 1), for the steady state:
+    // five vector instructions each, which fit behind one MFMA; ten in a row do not
+#define WG_SHIFTED_A(SLOT, BUF)                                                                 \
+    {                                                                                           \
+        const unsigned int prev_ = lhi ? up3_ : carry_prev;                                     \
+        carry_prev = up3_;                                                                      \
+        const u32x4 w_ = ry[SLOT];                                                              \
+        ymb[BUF][0] = __builtin_amdgcn_alignbyte(w_[0], prev_, 2);                              \
+        ymb[BUF][1] = __builtin_amdgcn_alignbyte(w_[1], w_[0], 2);                              \
+        ymb[BUF][2] = __builtin_amdgcn_alignbyte(w_[2], w_[1], 2);                              \
+        ymb[BUF][3] = __builtin_amdgcn_alignbyte(w_[3], w_[2], 2);                              \
+    }
+#define WG_SHIFTED_B(SLOT, BUF)                                                                 \
+    {                                                                                           \
+        const unsigned int next_ = lhi ? dn0_ : carry_next;                                     \
+        carry_next = dn0_;                                                                      \
+        ypb[BUF][0] = ymb[BUF][1]; ypb[BUF][1] = ymb[BUF][2]; ypb[BUF][2] = ymb[BUF][3];        \
+        ypb[BUF][3] = __builtin_amdgcn_alignbyte(next_, ry[SLOT][3], 2);                        \
+    }
 #define WG_MMA(T, Y, KH, SLOT)                                                                  \
     acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(rx[SLOT][KH]), as_bf16x8(Y), acc[T], 0, 0, 0);
 #define WG_F __builtin_amdgcn_sched_barrier(0);
@@ -160,21 +191,22 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
     {                                                                                           \
         const int L_ = ((D) + DEPTH - 1) % DEPTH, N1_ = ((D) + 1) % DEPTH;                      \
         const int N2_ = ((D) + 2) % DEPTH, N3_ = ((D) + 3) % DEPTH, B_ = (D) & 1;               \
-        const ptrdiff_t g_ = (ptrdiff_t)min((U) + DEPTH - 1, unit1) * 2 * 256;                  \
+        const int s_ = (min((U) + DEPTH - 1, unit1) - unit0 + 1) * 1024;                        \
         if (BIAS) acc[9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, as_bf16x8(ry[D]), acc[9], 0, 0, 0); \
         WG_MMA(0, ypb[B_], 0, D) WG_F                                                           \
-        ry[L_] = *(const u32x4*)(ya + g_); WG_F                                                 \
+        ry[L_] = __builtin_amdgcn_raw_buffer_load_b128(yrs, lane_off, s_, 0); WG_F              \
         WG_MMA(1, ry[D], 0, D) WG_F                                                             \
-        rx[L_][0] = *(const u32x4*)(xb + g_ - (ptrdiff_t)row_groups * 256); WG_F                \
+        rx[L_][0] = __builtin_amdgcn_raw_buffer_load_b128(xrs, lane_off, s_, 0); WG_F           \
         WG_MMA(2, ymb[B_], 0, D) WG_F                                                           \
-        rx[L_][1] = *(const u32x4*)(xb + g_); WG_F                                              \
+        rx[L_][1] = __builtin_amdgcn_raw_buffer_load_b128(xrs, lane_off, s_ + row_bytes, 0); WG_F \
         WG_MMA(3, ypb[B_], 1, D) WG_F                                                           \
-        rx[L_][2] = *(const u32x4*)(xb + g_ + (ptrdiff_t)row_groups * 256); WG_F                \
+        rx[L_][2] = __builtin_amdgcn_raw_buffer_load_b128(xrs, lane_off, s_ + 2 * row_bytes, 0); WG_F \
         WG_MMA(4, ry[D], 1, D) WG_F                                                             \
-        WG_SHIFTED(N1_, 1 - B_) WG_F                                                            \
+        WG_SHIFTED_A(N1_, 1 - B_) WG_F                                                          \
         WG_MMA(5, ymb[B_], 1, D) WG_F                                                           \
+        WG_SHIFTED_B(N1_, 1 - B_) WG_F                                                          \
+        WG_MMA(6, ypb[B_], 2, D) WG_F                                                           \
         WG_NEIGHBOURS_ISSUE(N2_, N3_) WG_F                                                      \
-        WG_MMA(6, ypb[B_], 2, D)                                                                \
         WG_MMA(7, ry[D], 2, D)                                                                  \
         WG_MMA(8, ymb[B_], 2, D) WG_F                                                           \
     }
@@ -228,6 +260,8 @@ __global__ void __launch_bounds__(256) k_wgrad3x3_mfma(WgradArgs a1, WgradArgs a
 #undef WG_LOAD
 #undef WG_NEIGHBOURS_ISSUE
 #undef WG_SHIFTED
+#undef WG_SHIFTED_A
+#undef WG_SHIFTED_B
 #undef WG_MMA
 #undef WG_F
 #undef WG_UNIT
