@@ -291,19 +291,47 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
         if (j >= a.po.total) return;
         apply_update(a, j, a.do_step ? a.grad[j] : 0.f);
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3) {
-        // role (2): slot layout [32 classes][c2] weights, then [32] biases
-        const int lane = threadIdx.x & 63;
-        const int k = (b - a.nb_main - a.nb_tail) * 4 + (threadIdx.x >> 6);
+        // role (2): slot layout [32 classes][c2] weights, then [32] biases.  The slots were
+        // written by other compute units, so every load is a round trip to memory: the role is
+        // laid out for few of them.  A block takes 16 consecutive values; its 256 threads split
+        // the slots into 16 contiguous runs (thread = value + 16 * run), every thread adds its
+        // run in ascending order with eight loads in flight, and the 16 partial sums of a value
+        // are added in the order of the runs.
+        __shared__ float run_sum[16][16];
+        const int kk = threadIdx.x & 15, run = threadIdx.x >> 4;
+        const int k = (b - a.nb_main - a.nb_tail) * 16 + kk;
         const int n_w = a.C * a.c2;
-        if (k >= n_w + a.C) return;
+        const bool live = k < n_w + a.C;
         float acc = 0.f;
-        if (a.do_step) {
-            const size_t r = k < n_w ? (size_t)k : (size_t)32 * a.c2 + (k - n_w);
-            for (int s = lane; s < a.blocks3; s += 64) acc += a.part3[(size_t)s * a.slot3 + r];
+        if (a.do_step && live) {
+            const float* src = a.part3 + (k < n_w ? (size_t)k : (size_t)32 * a.c2 + (k - n_w));
+            const int per = (a.blocks3 + 15) / 16;
+            const int s1 = min((run + 1) * per, a.blocks3);
+            int s = run * per;
+            for (; s + 8 <= s1; s += 8) {
+                float v[8];
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+                for (int e = 0; e < 8; ++e) v[e] = src[(size_t)(s + e) * a.slot3];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc += v[e];
+            }
+            if (s < s1) {
+                // the rest of the run, again loaded together (clamped re-loads count as zero)
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = src[(size_t)min(s + e, a.blocks3 - 1) * a.slot3];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc += s + e < s1 ? v[e] : 0.f;
+            }
         }
-        if (lane == 0) apply_update(a, a.po.W3 + k, acc);
+        run_sum[run][kk] = acc;
+        __syncthreads();
+        if (run == 0 && live) {
+            float total = run_sum[0][kk];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) total += run_sum[r][kk];
+            apply_update(a, a.po.W3 + k, total);
+        }
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish) {
         finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3, head);
     } else {
@@ -433,7 +461,7 @@ static int step_end_args(const Plan& p, char* ws, float lr, float mu, const Adam
         a.nb_main = params ? cdiv(l3 ? p.po.W3 : p.po.total, 256) : 0;
         a.nb_tail = 0;
     }
-    a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 4) : 0;
+    a.nb_l3 = l3 ? cdiv(p.g.C * p.g.c2 + p.g.C, 16) : 0;
     a.nb_finish = finish ? f.fph + 1 : 0;
     head_strides(a, p);
     return a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish;
