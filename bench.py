@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # copy-kernel scale factors are recorded under profiles/).  A figure holds only for the kernel
 # source it was measured on: (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "0656ef08bafa8dfbe640f662d203bc75b2394bd1191d655f8d9c8299970b3b52", 33.53, 8.83),
+    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.54, 8.83),
     "conv1_fwd_mfma": ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 13.75, 7.55),
     "upsample_ce_grad": ("k_loss.hip", "297276f9dbef51ee2ee5af0d6dc307fbaf35fb2a9b0a91f9b1861d2b83f321d8", 15.80, 4.72),
 }
