@@ -132,6 +132,11 @@ def main():
     ap.add_argument("--clients", type=int, default=4,
                     help="also time the grouped form: this many clients, each with a head and a key frame of "
                          "its own, trained in one call (reported beside the headline as `grouped`; 0 = skip)")
+    ap.add_argument("--clip-frames", type=int, default=32,
+                    help="also run the temporal-clip schedule on this many 720p frames (every frame: head "
+                         "forward + mean IoU; a frame below the threshold is a key frame and is trained "
+                         "with the early-exit form of Algorithm 1); reported beside the headline as `clip`; "
+                         "0 = skip")
     ap.add_argument("--no-graph", action="store_true",
                     help="time the calls launched kernel by kernel in the stream; default: `value` is timed "
                          "with the library's cached HIP graph (st_distill_opts.use_graph), and the "
@@ -372,6 +377,41 @@ def main():
                            "(desc.grouped = 1); head_steps_per_s counts one optimiser step of one head"}
         del fg, lg, pg, pg0, wsg
 
+    # the temporal clip (Algorithms 3 and 4 around the training step): drifting features, labels
+    # that move two pixels per frame; frames/s and the number of key frames.  Every key-frame
+    # iteration reads its metric back to the host (Algorithm 1 branches on it), so this leg is
+    # bound by those round trips, not by the kernels.
+    clip = None
+    if args.clip_frames > 0 and wl.name == "720p" and not (use_adam or args.weighted_loss or args.full_backward):
+        try:
+            from paper_2003_10735_amd.clip import run_clip
+            wc = WL.WORKLOADS["clip"]
+            wc = WL.small_variant(wc, extra={**wc.extra, "frames": args.clip_frames})
+            dc = st.HeadDesc.of(wc)
+            frames_dev = []
+            for f_np, lab_np in WL.clip_frames(wc):
+                ft = torch.from_numpy(f_np.view(np.int16)).cuda().view(torch.bfloat16) if f_np.dtype == np.uint16 \
+                    else torch.from_numpy(f_np).cuda()
+                frames_dev.append((ft, torch.from_numpy(lab_np).cuda()))
+            thr = float(wc.extra["threshold"])
+            pc = torch.from_numpy(WL.make_head_params(wc)).cuda()
+            wsc = st.new_workspace(dc)
+            run_clip(dc, frames_dev[:2], pc.clone(), threshold=thr, max_updates=wc.steps, lr=wc.lr,
+                     momentum=wc.momentum, workspace=wsc, stream=stream)          # warm-up
+            r = run_clip(dc, frames_dev, pc, threshold=thr, max_updates=wc.steps, lr=wc.lr,
+                         momentum=wc.momentum, workspace=wsc, stream=stream)
+            clip = {"frames": len(frames_dev), "frames_per_s": round(r["frames_per_s"], 1),
+                    "key_frames": int(r["n_key_frames"]), "optimiser_steps": int(sum(r["updates"])),
+                    "threshold": thr, "max_updates": wc.steps,
+                    "first_last_score": [round(r["scores"][0], 4), round(r["scores"][-1], 4)],
+                    "note": "features are noise that drifts (they carry nothing about the labels), so the "
+                            "score stays under the threshold and every frame is a key frame with the full "
+                            "number of steps: the rate is that of forward + metric + early-exit training "
+                            "per frame, inputs resident in HBM"}
+            del frames_dev, wsc
+        except Exception as e:      # the headline line must not depend on this leg
+            clip = {"error": f"{type(e).__name__}: {e}"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle as O
@@ -414,6 +454,7 @@ def main():
                   else (graph_note or "") + "kernel by kernel in the stream",
         "stream_launch": stream_launch,
         "grouped": grouped,
+        "clip": clip,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))
