@@ -181,6 +181,46 @@ Plan make_plan(const st_head_desc& d)
 
 static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
+// Page-locked host memory for the per-iteration metric read-back of the early-exit form (a copy
+// into pageable memory goes through a staging buffer and costs several times as much).  One
+// buffer per calling thread, grown on demand and kept until the process ends; nullptr if the
+// allocation fails (the caller then reads back into ordinary memory).
+// An event per calling thread and device for the same read-back: the host waits for the copy of
+// the metric while the stream already runs the backward pass behind it.
+static hipEvent_t readback_event()
+{
+    static thread_local hipEvent_t ev = nullptr;
+    static thread_local int ev_device = -1;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    if (ev && dev != ev_device) { (void)hipEventDestroy(ev); ev = nullptr; }
+    if (!ev) {
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); ev = nullptr; }
+        ev_device = dev;
+    }
+    return ev;
+}
+
+static double* pinned_metric_buffer(size_t count)
+{
+    static thread_local double* buf = nullptr;
+    static thread_local size_t cap = 0;
+    if (count > cap) {
+        if (buf) (void)hipHostFree(buf);
+        buf = nullptr;
+        cap = 0;
+        const size_t want = std::max(count, (size_t)512);
+        void* ptr = nullptr;
+        if (hipHostMalloc(&ptr, want * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        buf = (double*)ptr;
+        cap = want;
+    }
+    return buf;
+}
+
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 // Clears everything a call relies on being zero, in one launch: the counters, and of the
@@ -503,15 +543,29 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr);
         params_out_done = params_out_done || out_now;
         bool stop = last;
+        // In the early-exit form the backward pass of this iteration is put into the stream before
+        // the host looks at the metric: it only produces gradients (nothing the results depend on
+        // changes before the optimiser step), so the stream works through it while the host waits
+        // for the metric, and it is simply not used when the loop ends here.  (Not with a feature
+        // gradient: that one is an output.)
+        bool backward_queued = false;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
-            frame_metric.resize(g.n);
-            ST_HIP(c, hipMemcpyAsync(frame_metric.data(), metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost,
-                                     c.stream));
-            ST_HIP(c, hipStreamSynchronize(c.stream));
+            double* metric_host = pinned_metric_buffer((size_t)g.n);
+            if (!metric_host) { frame_metric.resize(g.n); metric_host = frame_metric.data(); }
+            ST_HIP(c, hipMemcpyAsync(metric_host, metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost, c.stream));
+            hipEvent_t ev = (!last && !feature_grad) ? readback_event() : nullptr;
+            if (ev) {
+                ST_HIP(c, hipEventRecord(ev, c.stream));
+                backward(c, p, ws, nullptr);
+                backward_queued = true;
+                ST_HIP(c, hipEventSynchronize(ev));
+            } else {
+                ST_HIP(c, hipStreamSynchronize(c.stream));
+            }
             if (c.status != ST_OK) break;
             double metric = 0.0;
-            for (int f = 0; f < g.n; ++f) metric += frame_metric[f];
+            for (int f = 0; f < g.n; ++f) metric += metric_host[f];
             metric /= g.n;
             if (it == 0) {
                 best_metric = metric;
@@ -530,7 +584,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             }
         }
         if (stop) break;
-        backward(c, p, ws, feature_grad);
+        if (!backward_queued) backward(c, p, ws, feature_grad);
         AdamStep ad;
         if (use_adam) {
             // bias corrections of step t in double precision, handed to the kernel as two factors
