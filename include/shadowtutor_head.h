@@ -24,7 +24,9 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Calls return without synchronising, except st_partial_distill with a positive
  *     `threshold`, whose loop exits are decided on the host (one small device-to-host read per
- *     iteration) and which has finished when it returns.
+ *     iteration) and which has finished when it returns.  (While the host waits for that read
+ *     the stream already computes the iteration's gradients; when the loop ends there they are
+ *     left unused in the workspace and no parameter has changed.)
  *   - Dense row-major layouts: features [n, c_in, h, w]; labels / pred [n, 8h, 8w];
  *     low-resolution logits [n, n_classes, h, w].
  *   - head_params is one flat float32 vector: W1 (OIHW) | b1 | W2 (OIHW) | b2 | W3 (OI) | b3.
