@@ -7,6 +7,8 @@
 //   C[m][n] = sum_k A(m, k) * B(k, n),   64 x 64 tile per block, 4 x 4 per thread, K step 16.
 //
 // Each problem is a small struct that says how to fetch A(m,k), B(k,n) and where to store.
+#include <algorithm>
+
 #include "st_kernels.hpp"
 
 namespace st {
@@ -21,9 +23,14 @@ __global__ void __launch_bounds__(256) k_gemm_generic(Prob p)
     const int tid = threadIdx.x;
     const int m0 = blockIdx.x * GB, n0 = blockIdx.y * GB;
     const int tm = (tid / 16) * 4, tn = (tid % 16) * 4;
-    const int M = p.M(), N = p.N(), K = p.K();
+    const int M = p.M(), N = p.N();
+    // blockIdx.z: a share of the reduction range, in whole K steps (weight gradients are split over
+    // the positions, each share goes to a partial copy of its own; everything else has one share)
+    const int k_steps = (p.K() + GK - 1) / GK;
+    const int per = (k_steps + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int k_begin = (int)blockIdx.z * per * GK, K = min(p.K(), ((int)blockIdx.z + 1) * per * GK);
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += GK) {
+    for (int k0 = k_begin; k0 < K; k0 += GK) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int idx = tid + r * 256;
@@ -51,7 +58,7 @@ __global__ void __launch_bounds__(256) k_gemm_generic(Prob p)
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (m0 + tm + i < M && n0 + tn + j < N) p.store(m0 + tm + i, n0 + tn + j, acc[i][j]);
+            if (m0 + tm + i < M && n0 + tn + j < N) p.store(m0 + tm + i, n0 + tn + j, acc[i][j], (int)blockIdx.z);
 }
 
 // position index m in [0, n*h*w) -> padded position (img, y + 1 + dy, x + 1 + dx)
@@ -79,7 +86,7 @@ struct FwdProb {
         return to_f32(x[(size_t)padded_pos(g, m, dy, dx) * ci + i]);
     }
     __device__ float b(int k, int n) const { return to_f32(W[(size_t)n * TAPS * ci + k]); }
-    __device__ void store(int m, int n, float v) const
+    __device__ void store(int m, int n, float v, int) const
     {
         v += bias[n];
         if (relu) v = fmaxf(v, 0.f);
@@ -106,7 +113,7 @@ struct DgradProb {
         const int tap = k / co, o = k - tap * co;
         return to_f32(W[((size_t)o * 9 + tap) * ci + n]);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ void store(int m, int n, float v, int) const
     {
         const size_t at = (size_t)padded_pos(g, m, 0, 0) * ci + n;
         dx[at] = from_f32<E>(to_f32(act[at]) > 0.f ? v : 0.f);
@@ -133,7 +140,7 @@ struct FeatDgradProb {
         const int tap = k / co, o = k - tap * co;
         return to_f32(W[((size_t)o * 9 + tap) * ci + n]);
     }
-    __device__ void store(int m, int n, float v) const
+    __device__ void store(int m, int n, float v, int) const
     {
         const int hw = g.h * g.w;
         const int img = m / hw, r = m - img * hw;
@@ -146,7 +153,7 @@ template <class E, int TAPS>
 struct WgradProb {
     static constexpr bool A_K_FAST = false, B_K_FAST = false;
     Geo g; int ci, co;
-    const E* dy; const E* x; float* dW;
+    const E* dy; const E* x; float* dW; size_t copy_stride;
     __device__ int M() const { return co; }
     __device__ int N() const { return TAPS * ci; }
     __device__ int K() const { return g.positions(); }
@@ -157,7 +164,7 @@ struct WgradProb {
         const int dyy = TAPS == 9 ? tap / 3 - 1 : 0, dxx = TAPS == 9 ? tap % 3 - 1 : 0;
         return to_f32(x[(size_t)padded_pos(g, k, dyy, dxx) * ci + i]);
     }
-    __device__ void store(int m, int n, float v) const { dW[(size_t)m * TAPS * ci + n] = v; }
+    __device__ void store(int m, int n, float v, int share) const { dW[share * copy_stride + (size_t)m * TAPS * ci + n] = v; }
 };
 
 // ---- last layer (1x1) with planar float32 logits / logit gradients ---------------------------
@@ -171,7 +178,7 @@ struct LogitsProb {
     __device__ int K() const { return g.c2; }
     __device__ float a(int m, int k) const { return to_f32(a2[(size_t)padded_pos(g, m, 0, 0) * g.c2 + k]); }
     __device__ float b(int k, int n) const { return to_f32(W3[(size_t)n * g.c2 + k]); }
-    __device__ void store(int m, int n, float v) const
+    __device__ void store(int m, int n, float v, int) const
     {
         const int hw = g.h * g.w, img = m / hw, r = m - img * hw;
         z[((size_t)img * g.C + n) * hw + r] = v + b3[n];
@@ -196,7 +203,7 @@ struct LogitsDgradProb {
         return as_operand<E>(gz[((size_t)img * g.C + k) * hw + r]);
     }
     __device__ float b(int k, int n) const { return to_f32(W3[(size_t)k * g.c2 + n]); }
-    __device__ void store(int m, int n, float v) const
+    __device__ void store(int m, int n, float v, int) const
     {
         const size_t at = (size_t)padded_pos(g, m, 0, 0) * g.c2 + n;
         da2[at] = from_f32<E>(to_f32(a2[at]) > 0.f ? v : 0.f);
@@ -207,7 +214,7 @@ struct LogitsDgradProb {
 template <class E>
 struct LogitsWgradProb {
     static constexpr bool A_K_FAST = true, B_K_FAST = false;
-    Geo g; const float* gz; const E* a2; float* dW3;
+    Geo g; const float* gz; const E* a2; float* dW3; size_t copy_stride;
     __device__ int M() const { return g.C; }
     __device__ int N() const { return g.c2; }
     __device__ int K() const { return g.positions(); }
@@ -217,52 +224,76 @@ struct LogitsWgradProb {
         return as_operand<E>(gz[((size_t)img * g.C + m) * hw + r]);
     }
     __device__ float b(int k, int n) const { return to_f32(a2[(size_t)padded_pos(g, k, 0, 0) * g.c2 + n]); }
-    __device__ void store(int m, int n, float v) const { dW3[(size_t)m * g.c2 + n] = v; }
+    __device__ void store(int m, int n, float v, int share) const { dW3[share * copy_stride + (size_t)m * g.c2 + n] = v; }
 };
 
 template <class Prob>
-static void launch(Ctx& c, const char* name, const Prob& p, int M, int N)
+static void launch(Ctx& c, const char* name, const Prob& p, int M, int N, int shares = 1)
 {
-    ST_LAUNCH(c, name, (k_gemm_generic<Prob>), dim3(cdiv(M, GB), cdiv(N, GB)), dim3(256), 0, p);
+    ST_LAUNCH(c, name, (k_gemm_generic<Prob>), dim3(cdiv(M, GB), cdiv(N, GB), shares), dim3(256), 0, p);
+}
+
+// Position splits of the three weight-gradient products: their outputs are small and their
+// reduction runs over every position, so one share per output tile would leave most of the chip
+// idle for milliseconds.  Enough shares for about a thousand blocks, at most 16 partial copies,
+// at least 128 positions per share.
+void generic_wgrad_splits(const Geo& g, int* splits1, int* splits2, int* splits3)
+{
+    auto pick = [&](int M, int N) {
+        const int tiles = cdiv(M, GB) * cdiv(N, GB);
+        const int by_work = std::max(1, g.positions() / 128);
+        return std::max(1, std::min(std::min(cdiv(1024, tiles), 16), by_work));
+    };
+    *splits1 = pick(g.c1, 9 * g.c_in);
+    *splits2 = pick(g.c2, 9 * g.c1);
+    *splits3 = pick(g.C, g.c2);
 }
 
 // ---- bias gradients ---------------------------------------------------------------------------
 // db[o] = sum over all padded positions of dy[pos][o] (the border holds zeros).  One block per
-// 32 channels; 8 row-lanes per channel walk the positions, then a fixed-order LDS sum.
+// 32 channels and share of the positions (blockIdx.y, partial copy `copy_stride` floats apart);
+// 8 row-lanes per channel walk the share's positions, then a fixed-order LDS sum.
 template <class E>
-__global__ void __launch_bounds__(256) k_bias_grad(const E* __restrict__ dy, float* __restrict__ db, int PP, int co)
+__global__ void __launch_bounds__(256) k_bias_grad(const E* __restrict__ dy, float* __restrict__ db, int PP, int co,
+                                                   size_t copy_stride)
 {
     __shared__ float part[8][33];
     const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
     const int o = blockIdx.x * 32 + tx;
+    const int per = (PP + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int p0 = (int)blockIdx.y * per, p1 = min(PP, p0 + per);
     float acc = 0.f;
     if (o < co)
-        for (int p = ty; p < PP; p += 8) acc += to_f32(dy[(size_t)p * co + o]);
+        for (int p = p0 + ty; p < p1; p += 8) acc += to_f32(dy[(size_t)p * co + o]);
     part[ty][tx] = acc;
     __syncthreads();
     if (ty == 0 && o < co) {
         float s = 0.f;
         for (int r = 0; r < 8; ++r) s += part[r][tx];
-        db[o] = s;
+        db[blockIdx.y * copy_stride + o] = s;
     }
 }
 
-// db3[c] = sum over frames and positions of the operand copy of g[img][c][pos]
+// db3[c] = sum over frames and positions of the operand copy of g[img][c][pos]; blockIdx.y: share
+// of every frame's positions
 template <class E>
-__global__ void __launch_bounds__(256) k_bias_grad_planar(const float* __restrict__ gz, float* __restrict__ db, Geo g)
+__global__ void __launch_bounds__(256) k_bias_grad_planar(const float* __restrict__ gz, float* __restrict__ db, Geo g,
+                                                          size_t copy_stride)
 {
     __shared__ float part[256];
     const int c = blockIdx.x, hw = g.h * g.w;
+    const int per = (hw + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int p0 = (int)blockIdx.y * per, p1 = min(hw, p0 + per);
     float acc = 0.f;
     for (int img = 0; img < g.n; ++img)
-        for (int p = threadIdx.x; p < hw; p += 256) acc += as_operand<E>(gz[((size_t)img * g.C + c) * hw + p]);
+        for (int p = p0 + threadIdx.x; p < p1; p += 256) acc += as_operand<E>(gz[((size_t)img * g.C + c) * hw + p]);
     part[threadIdx.x] = acc;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) db[c] = part[0];
+    if (threadIdx.x == 0) db[blockIdx.y * copy_stride + c] = part[0];
 }
 
 // ------------------------------------------------------------------ host-side entry points
@@ -297,23 +328,24 @@ static void bwd_impl(Ctx& c, const Plan& p, char* ws, const WE* W2, const WE* W3
     E* da2 = (E*)(ws + p.da2);
     E* da1 = (E*)(ws + p.da1);
     // layer 3
-    LogitsWgradProb<E> w3{g, gz, a2, grad + p.po.W3};
-    launch(c, "conv3_wgrad_generic", w3, g.C, g.c2);
-    ST_LAUNCH(c, "bias3_grad", (k_bias_grad_planar<E>), dim3(g.C), dim3(256), 0, gz, grad + p.po.b3, g);
+    LogitsWgradProb<E> w3{g, gz, a2, grad + p.po.W3, p.grad_stride};
+    launch(c, "conv3_wgrad_generic", w3, g.C, g.c2, p.splits3);
+    ST_LAUNCH(c, "bias3_grad", (k_bias_grad_planar<E>), dim3(g.C, p.splits3), dim3(256), 0, gz, grad + p.po.b3, g,
+              p.grad_stride);
     LogitsDgradProb<E, WE> d3{g, gz, W3, a2, da2};
     launch(c, "conv3_dgrad_generic", d3, g.positions(), g.c2);
     // layer 2
-    WgradProb<E, 9> w2{g, g.c1, g.c2, da2, a1, grad + p.po.W2};
-    launch(c, "conv2_wgrad_generic", w2, g.c2, 9 * g.c1);
-    ST_LAUNCH(c, "bias2_grad", (k_bias_grad<E>), dim3(cdiv(g.c2, 32)), dim3(256), 0, (const E*)da2,
-              grad + p.po.b2, g.padded_positions(), g.c2);
+    WgradProb<E, 9> w2{g, g.c1, g.c2, da2, a1, grad + p.po.W2, p.grad_stride};
+    launch(c, "conv2_wgrad_generic", w2, g.c2, 9 * g.c1, p.splits2);
+    ST_LAUNCH(c, "bias2_grad", (k_bias_grad<E>), dim3(cdiv(g.c2, 32), p.splits2), dim3(256), 0, (const E*)da2,
+              grad + p.po.b2, g.padded_positions(), g.c2, p.grad_stride);
     DgradProb<E, WE> d2{g, g.c1, g.c2, da2, W2, a1, da1};
     launch(c, "conv2_dgrad_generic", d2, g.positions(), g.c1);
     // layer 1: parameters only -- the features are frozen, no gradient flows past this layer
-    WgradProb<E, 9> w1{g, g.c_in, g.c1, da1, (const E*)(ws + p.feat), grad + p.po.W1};
-    launch(c, "conv1_wgrad_generic", w1, g.c1, 9 * g.c_in);
-    ST_LAUNCH(c, "bias1_grad", (k_bias_grad<E>), dim3(cdiv(g.c1, 32)), dim3(256), 0, (const E*)da1,
-              grad + p.po.b1, g.padded_positions(), g.c1);
+    WgradProb<E, 9> w1{g, g.c_in, g.c1, da1, (const E*)(ws + p.feat), grad + p.po.W1, p.grad_stride};
+    launch(c, "conv1_wgrad_generic", w1, g.c1, 9 * g.c_in, p.splits1);
+    ST_LAUNCH(c, "bias1_grad", (k_bias_grad<E>), dim3(cdiv(g.c1, 32), p.splits1), dim3(256), 0, (const E*)da1,
+              grad + p.po.b1, g.padded_positions(), g.c1, p.grad_stride);
 }
 
 void generic_forward(Ctx& c, const Plan& p, char* ws, float* z)

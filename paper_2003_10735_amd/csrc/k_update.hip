@@ -15,10 +15,11 @@ namespace st {
 //
 //  (1) optimiser step over the flat parameter buffer: theta <- theta - lr * v, v <- mu * v + g
 //      (mu == 0: v is not touched), or an Adam step (Section 5.2 of the paper; AdamStep).  g is the sum, in ascending order, of the partial gradients
-//      the backward kernels left behind: `splits1` copies for W1/b1 and `splits2` for W2/b2
-//      (position splits of the weight-gradient kernels, `stride` floats apart).
-//  (2) the same for W3/b3 when the classifier's backward kernel left one slot per block: one
-//      wavefront per parameter, lane l adds slots l, l+64, .. in order, then a fixed shuffle tree.
+//      the backward kernels left behind: `splits1` copies for W1/b1, `splits2` for W2/b2 and, on
+//      the plain kernels, `splits3` for W3/b3 (position splits of the weight-gradient kernels,
+//      `stride` floats apart).
+//  (2) the same for W3/b3 when the classifier's backward kernel left one slot per block: 16
+//      threads per parameter, each adding a contiguous run of the slots, then the runs in order.
 //  (3) bookkeeping of the forward pass that preceded the step: block f: mean IoU of frame f from
 //      its confusion counts (copied out when asked, then cleared for the next pass); one more
 //      block: the tile losses added in a fixed order (float64) over the number of valid pixels.
@@ -33,7 +34,7 @@ namespace st {
 // wq3 has theta's order.  So do wq1 and wq2 for the plain tiled kernels (frag == 0); the
 // matrix-core convolutions read wq1, wq2 and wq2t in fragment order (wfrag_index).
 struct UpdateArgs {
-    float* theta; float* vel; float* vel2; const float* grad; size_t stride; int splits1, splits2;
+    float* theta; float* vel; float* vel2; const float* grad; size_t stride; int splits1, splits2, splits3;
     bf16* wq1; bf16* wq1t; bf16* wq2; bf16* wq2t; bf16* wq3; bf16* wq3t;
     ParamOffsets po; int c_in, c1, c2;
     int frag;        // wq1 / wq2 / wq2t in fragment order
@@ -280,7 +281,7 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
         if (j >= limit) return;
         float g = 0.f;
         if (a.do_step) {
-            const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : 1);
+            const int splits = j < a.po.W2 ? a.splits1 : (j < a.po.W3 ? a.splits2 : a.splits3);
             g = a.grad[j];
             for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
         }
@@ -289,7 +290,12 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
         // [W3, total) one by one (only when role (2) is not active)
         const size_t j = a.po.W3 + (size_t)(b - a.nb_main) * 256 + threadIdx.x;
         if (j >= a.po.total) return;
-        apply_update(a, j, a.do_step ? a.grad[j] : 0.f);
+        float g = 0.f;
+        if (a.do_step) {
+            g = a.grad[j];
+            for (int s = 1; s < a.splits3; ++s) g += a.grad[(size_t)s * a.stride + j];
+        }
+        apply_update(a, j, g);
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3) {
         // role (2): slot layout [32 classes][c2] weights, then [32] biases.  The slots were
         // written by other compute units, so every load is a round trip to memory: the role is
@@ -436,8 +442,9 @@ static int step_end_args(const Plan& p, char* ws, float lr, float mu, const Adam
     if (adam) a.ad = *adam; else memset(&a.ad, 0, sizeof(a.ad));
     a.grad = (const float*)(ws + p.grad);
     a.stride = p.grad_stride;
-    a.splits1 = p.mfma ? p.splits1 : 1;
-    a.splits2 = p.mfma ? p.splits2 : 1;
+    a.splits1 = p.splits1;
+    a.splits2 = p.splits2;
+    a.splits3 = p.splits3;
     a.wq1 = p.bf16 ? (bf16*)(ws + p.wq1) : nullptr;
     a.wq1t = (p.mfma && w1t) ? (bf16*)(ws + p.wq1t) : nullptr;
     a.wq2 = p.bf16 ? (bf16*)(ws + p.wq2) : nullptr;

@@ -117,10 +117,11 @@ Plan make_plan(const st_head_desc& d)
     p.mfma = p.bf16 && conv3x3_mfma_supported(g.c_in, g.c1) && conv3x3_mfma_supported(g.c1, g.c2) &&
              wgrad3x3_mfma_supported(g.c_in, g.c1) && wgrad3x3_mfma_supported(g.c1, g.c2) &&
              conv3_mfma_supported(g.c2, g.C);
-    p.splits1 = p.splits2 = 1;
+    p.splits1 = p.splits2 = p.splits3 = 1;
     if (p.mfma) wgrad_splits_for(g, &p.splits1, &p.splits2);
+    else generic_wgrad_splits(g, &p.splits1, &p.splits2, &p.splits3);
     p.blocks3 = p.mfma ? conv3_bwd_blocks(g) : 0;
-    p.grad_copies = std::max(p.splits1, p.splits2);
+    p.grad_copies = std::max(std::max(p.splits1, p.splits2), p.splits3);
     // guard: a 3x3 tap reaches Wp + 1 rows back/ahead of a tile that may overrun the grid by
     // up to 255 positions
     p.guard = (g.Wp + 2 + 256 + 7) / 8 * 8;
@@ -185,22 +186,6 @@ static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 // into pageable memory goes through a staging buffer and costs several times as much).  One
 // buffer per calling thread, grown on demand and kept until the process ends; nullptr if the
 // allocation fails (the caller then reads back into ordinary memory).
-// An event per calling thread and device for the same read-back: the host waits for the copy of
-// the metric while the stream already runs the backward pass behind it.
-static hipEvent_t readback_event()
-{
-    static thread_local hipEvent_t ev = nullptr;
-    static thread_local int ev_device = -1;
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    if (ev && dev != ev_device) { (void)hipEventDestroy(ev); ev = nullptr; }
-    if (!ev) {
-        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); ev = nullptr; }
-        ev_device = dev;
-    }
-    return ev;
-}
-
 static double* pinned_metric_buffer(size_t count)
 {
     static thread_local double* buf = nullptr;
@@ -219,6 +204,22 @@ static double* pinned_metric_buffer(size_t count)
         cap = want;
     }
     return buf;
+}
+
+// An event per calling thread and device for the same read-back: the host waits for the copy of
+// the metric while the stream already runs the backward pass behind it.
+static hipEvent_t readback_event()
+{
+    static thread_local hipEvent_t ev = nullptr;
+    static thread_local int ev_device = -1;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    if (ev && dev != ev_device) { (void)hipEventDestroy(ev); ev = nullptr; }
+    if (!ev) {
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); ev = nullptr; }
+        ev_device = dev;
+    }
+    return ev;
 }
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }

@@ -105,8 +105,10 @@ struct Plan {
     // apart), grad3 (blocks3 slots apart), the bfloat16 weight copies (their own size apart),
     // the pixel counters (one each).
     int splits1, splits2;   // position splits (per head) of the layer-1 / layer-2 weight-gradient kernels
+    int splits3;            // the same for the classifier layer on the plain kernels (the matrix-core
+                            // path leaves per-block slots instead: blocks3)
     int blocks3;            // per-block partial slots (per head) of the layer-3 backward kernel
-    int grad_copies;        // max(splits1, splits2): partial gradient copies the update sums
+    int grad_copies;        // max of the splits: partial gradient copies the update sums
     size_t grad_stride;     // floats between two copies (total rounded up to 16 bytes)
     size_t head_stride;     // floats between two heads' parameters (total rounded up to 16 bytes)
     int guard;          // guard rows before and after every position-major activation buffer;

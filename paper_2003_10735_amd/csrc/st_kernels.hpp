@@ -28,6 +28,7 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
                   const bf16* W3q = nullptr, float* zpart = nullptr, float* dense = nullptr);
 bool wgrad3x3_mfma_supported(int cin, int cout);
 void wgrad_splits_for(const Geo& g, int* splits1, int* splits2);
+void generic_wgrad_splits(const Geo& g, int* splits1, int* splits2, int* splits3);
 void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, const bf16* da2T,
                    const bf16* a1T, float* grad);
 bool conv3_mfma_supported(int c2, int C);
