@@ -40,6 +40,9 @@ RAGGED = [
     dict(n=2, c_in=20, h=9, w=37, c1=24, c2=16, n_classes=5, ignore_index=255, ignore_fraction=0.1),
     dict(n=1, c_in=16, h=3, w=70, c1=16, c2=40, n_classes=21, momentum=0.9),
     dict(n=3, c_in=4, h=1, w=1, c1=4, c2=4, n_classes=2),
+    # enough positions (2 x 33 x 37 = 2442) for the plain path's largest number of partial gradient
+    # copies (16), with a ragged last share
+    dict(n=2, c_in=12, h=33, w=37, c1=16, c2=12, n_classes=4, momentum=0.5),
 ]
 
 
