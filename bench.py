@@ -6,9 +6,11 @@ packing, 8 optimiser steps (9 forwards, 8 partial backwards, 8 updates) and 9 lo
 passes, with all inputs already resident in HBM.  `value` is optimiser steps per second.
 
 Prints ONE JSON line.  Extra objects:
-  roofline      the kernel that takes the largest share of the call, its algorithmic work per
+  roofline      the kernel that takes the largest share of the call (kernels within 3 % of it count
+                as tied and the tie goes to the matrix-core kernel), its algorithmic work per
                 launch over its average launch duration (HIP events on the launch stream, taken
-                during the timed region), against the chip's published peak
+                during the timed region), against the chip's published peak; the other kernels
+                of a step follow in `other_kernels`
   cpu_baseline  the CPU oracle (test infrastructure, untuned) on the host cores of the machine
 """
 from __future__ import annotations
@@ -223,18 +225,24 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # which kernel dominates: one untimed call with an event pair around every launch
+    # which kernel dominates: three untimed calls with an event pair around every launch
     st.st_profile_reset()
     st.st_profile_filter(None)
     st.st_profile_enable(True)
-    one_call()
+    for _ in range(3):
+        one_call()
     torch.cuda.synchronize()
     prof = st.st_profile_read()
     st.st_profile_enable(False)
     st.st_profile_reset()
     work = kernel_work(wl)
     known = {k: v for k, v in prof.items() if any(k.startswith(pre) for pre in work)}
-    dominant = max(known, key=lambda k: known[k][1])
+    # (the weight-gradient launch and the loss kernel take nearly the same time at 720p; kernels
+    #  within 3 % of the largest share count as tied, and a tie goes to the matrix-core kernel, so
+    #  that the object does not flip between two kernels from run to run)
+    top = max(v[1] for v in known.values())
+    tied = [k for k, v in known.items() if v[1] >= 0.97 * top]
+    dominant = max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", known[k][1]))
     breakdown = {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
 
     # timed region, kernel-by-kernel launches; only the dominant kernel carries an event pair
