@@ -134,6 +134,11 @@ def main():
     ap.add_argument("--clients", type=int, default=4,
                     help="also time the grouped form: this many clients, each with a head and a key frame of "
                          "its own, trained in one call (reported beside the headline as `grouped`; 0 = skip)")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="also time this many independent clients, each with its own key frame, head and "
+                         "workspace, whose calls are issued round-robin on streams of their own (the GPU "
+                         "then fills one client's launch gaps with another client's kernels); reported "
+                         "beside the headline as `streams`; 0 = skip")
     ap.add_argument("--clip-frames", type=int, default=32,
                     help="also run the temporal-clip schedule on this many 720p frames (every frame: head "
                          "forward + mean IoU; a frame below the threshold is a key frame and is trained "
@@ -385,6 +390,48 @@ def main():
                            "(desc.grouped = 1); head_steps_per_s counts one optimiser step of one head"}
         del fg, lg, pg, pg0, wsg
 
+    # independent clients on streams of their own: no special mode, just concurrent calls
+    streams_leg = None
+    if args.streams > 1 and wl.n == 1 and not (use_adam or args.weighted_loss or args.full_backward):
+        try:
+            clients = []
+            for i in range(args.streams):
+                wi = WL.small_variant(wl, feat_seed=wl.feat_seed + 101 * (i + 1), label_seed=wl.label_seed + 101 * (i + 1))
+                fi_np = WL.make_features(wi)
+                fi = torch.from_numpy(fi_np.view(np.int16)).cuda().view(torch.bfloat16) if fi_np.dtype == np.uint16 \
+                    else torch.from_numpy(fi_np).cuda()
+                pi0 = torch.from_numpy(WL.make_head_params(wi, seed=wi.init_seed + 17 * i)).cuda()
+                clients.append(dict(f=fi, lab=torch.from_numpy(WL.make_labels(wi)).cuda(), p0=pi0, p=pi0.clone(),
+                                    ws=st.new_workspace(desc), s=torch.cuda.Stream(),
+                                    vel=None if wl.momentum == 0.0 else torch.zeros_like(pi0),
+                                    losses=torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")))
+
+            def client_call(c):
+                with torch.cuda.stream(c["s"]):
+                    c["p"].copy_(c["p0"], non_blocking=True)
+                st.st_partial_distill(desc, c["f"], c["lab"], c["p"], wl.steps, wl.lr, momentum=wl.momentum,
+                                      velocity=c["vel"],
+                                      losses=c["losses"], workspace=c["ws"], stream=c["s"], graph=use_graph)
+
+            for _ in range(3):
+                for c in clients:
+                    client_call(c)
+            torch.cuda.synchronize()
+            reps = max(10, args.steps)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                for c in clients:
+                    client_call(c)
+            torch.cuda.synchronize()
+            ts = time.perf_counter() - t0
+            streams_leg = {"clients": args.streams, "head_steps_per_s": round(reps * args.streams * wl.steps / ts, 1),
+                           "calls": reps * args.streams,
+                           "note": "independent st_partial_distill calls (one key frame, head and workspace per "
+                                   "client) issued round-robin on one stream per client; the sum over the clients"}
+            del clients
+        except Exception as e:      # the headline line must not depend on this leg
+            streams_leg = {"error": f"{type(e).__name__}: {e}"}
+
     # the temporal clip (Algorithms 3 and 4 around the training step): drifting features, labels
     # that move two pixels per frame; frames/s and the number of key frames.  Every key-frame
     # iteration reads its metric back to the host (Algorithm 1 branches on it), so this leg is
@@ -462,6 +509,7 @@ def main():
                   else (graph_note or "") + "kernel by kernel in the stream",
         "stream_launch": stream_launch,
         "grouped": grouped,
+        "streams": streams_leg,
         "clip": clip,
         "cpu_baseline": cpu_baseline,
     }
