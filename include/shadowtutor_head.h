@@ -152,6 +152,8 @@ typedef struct st_distill_result {
     uint8_t* pred;       /* [n, 8h, 8w] class map of the last forward       */
     int32_t steps_taken; /* HOST, written by the call (== steps unless threshold > 0) */
     double best_metric;  /* HOST, written only when threshold > 0           */
+    double first_metric; /* HOST, written only when threshold > 0: the metric (mean over the frames)
+                            before any update, the one Algorithm 1 first compares with THRESHOLD */
 } st_distill_result;
 
 /* Number of float32 values in one head's parameters:

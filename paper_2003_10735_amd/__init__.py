@@ -55,7 +55,8 @@ class StScheduleBounds(C.Structure):
 
 class StDistillResult(C.Structure):
     _fields_ = [("losses", C.c_void_p), ("mious", C.c_void_p), ("confusion", C.c_void_p),
-                ("pred", C.c_void_p), ("steps_taken", C.c_int32), ("best_metric", C.c_double)]
+                ("pred", C.c_void_p), ("steps_taken", C.c_int32), ("best_metric", C.c_double),
+                ("first_metric", C.c_double)]
 
 
 class StWorkspaceLayout(C.Structure):
@@ -65,6 +66,12 @@ class StWorkspaceLayout(C.Structure):
 
 class StKernelStat(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double)]
+
+
+class DistillReturn(tuple):
+    """(steps_taken, best_metric or None) of st_partial_distill; with a threshold also
+    `.first_metric`, the metric before any update."""
+    first_metric = None
 
 
 class StError(RuntimeError):
@@ -215,7 +222,8 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
     With a grouped descriptor head_params and the optimiser state are [n, num_params] and losses
     [steps+1, n].  graph=True launches the call through the library's cached HIP graph
     (st_distill_opts.use_graph).
-    Returns (steps_taken, best_metric or None)."""
+    Returns (steps_taken, best_metric or None); with a threshold the returned tuple also carries
+    `.first_metric`, the metric before any update."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     use_opts = (momentum != 0.0 or threshold > 0.0 or velocity is not None or adam is not None
@@ -234,7 +242,9 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
                                   steps, lr, C.byref(opts) if use_opts else None, C.byref(res),
                                   _ptr(ws), _stream(stream))
     _check(st, "st_partial_distill")
-    return int(res.steps_taken), (float(res.best_metric) if threshold > 0.0 else None)
+    ret = DistillReturn((int(res.steps_taken), (float(res.best_metric) if threshold > 0.0 else None)))
+    ret.first_metric = float(res.first_metric) if threshold > 0.0 else None
+    return ret
 
 
 def st_miou(pred, labels, n_classes: int, ignore_index: int = -1, confusion=None, miou=None,

@@ -3,7 +3,10 @@
 Every frame the head runs forward and is scored against the teacher's label map (mean IoU,
 Eq. 1).  A frame whose score falls below THRESHOLD is a key frame: the head is trained on it
 with Algorithm 1 (at most MAX_UPDATES optimiser steps, leaving as soon as the score reaches the
-threshold) and the updated head serves the following frames.  Only argument marshalling and the
+threshold) and the updated head serves the following frames.  `run_clip` does both with one
+st_partial_distill call per frame (Algorithm 1 scores first and trains only under the
+threshold); `run_clip_strided` keeps the client's head apart from the server's and scores it with
+st_head_forward + st_miou.  Only argument marshalling and the
 loop live here; every computation is a call into the HIP library.
 """
 from __future__ import annotations
@@ -24,32 +27,25 @@ def run_clip(desc: HeadDesc, frames, head_params, *, threshold: float, max_updat
 
     ws = workspace if workspace is not None else new_workspace(desc, head_params.device)
     velocity = torch.zeros_like(head_params) if momentum != 0.0 else None
-    pred = None
-    conf = torch.empty((desc.n_classes, desc.n_classes), dtype=torch.int64, device=head_params.device)
-    miou = torch.empty(1, dtype=torch.float64, device=head_params.device)
     scores, key, updates, trained = [], [], [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_frames = 0
     for features, labels in frames:
-        if pred is None:
-            pred = torch.empty(labels.shape, dtype=torch.uint8, device=labels.device)
-        st_head_forward(desc, features, head_params, pred=pred, workspace=ws, stream=stream)
-        st_miou(pred, labels, desc.n_classes, desc.ignore_index, confusion=conf, miou=miou, stream=stream)
-        score = float(miou.item())          # the schedule is decided on the host
+        # One call per frame is Algorithm 1 as printed: it scores the head on the frame first and
+        # trains only if that score is under the threshold (the schedule is decided on the host,
+        # inside the call, on the metric it reads back).
+        r = st_partial_distill(desc, features, labels, head_params, max_updates, lr,
+                               momentum=momentum, velocity=velocity, threshold=threshold,
+                               strict_break=strict_break, return_best=return_best,
+                               workspace=ws, stream=stream)
+        taken, best = r
+        score = r.first_metric
         scores.append(score)
         is_key = score < threshold
         key.append(is_key)
-        if is_key:
-            taken, best = st_partial_distill(desc, features, labels, head_params, max_updates, lr,
-                                             momentum=momentum, velocity=velocity, threshold=threshold,
-                                             strict_break=strict_break, return_best=return_best,
-                                             workspace=ws, stream=stream)
-            updates.append(taken)
-            trained.append(best)
-        else:
-            updates.append(0)
-            trained.append(None)
+        updates.append(taken if is_key else 0)
+        trained.append(best if is_key else None)
         n_frames += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0

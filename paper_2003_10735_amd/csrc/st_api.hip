@@ -520,7 +520,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     // of the weights of the valid labels: one launch
     call_begin(c, p, ws, features, desc->feat_dtype, head_params, feature_grad != nullptr, teacher_labels, pixel_weights);
 
-    double best_metric = -1.0;
+    double best_metric = -1.0, first_metric = -1.0;
     std::vector<double> frame_metric;
     int taken = 0;
     bool have_best = false;
@@ -569,6 +569,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             for (int f = 0; f < g.n; ++f) metric += metric_host[f];
             metric /= g.n;
             if (it == 0) {
+                first_metric = metric;
                 best_metric = metric;
                 if (return_best) {
                     ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
@@ -611,7 +612,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     if (early_exit) ST_HIP(c, hipStreamSynchronize(c.stream));
     if (out) {
         out->steps_taken = taken;
-        if (early_exit) out->best_metric = best_metric;
+        if (early_exit) { out->best_metric = best_metric; out->first_metric = first_metric; }
     }
     return c.status;
 }

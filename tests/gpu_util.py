@@ -32,10 +32,11 @@ def run_gpu(wl, feats, labels, params, steps=None, velocity=None, threshold=0.0,
     conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
     pred = torch.zeros((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
     ws = workspace if workspace is not None else st.new_workspace(desc)
-    taken, best = st.st_partial_distill(desc, f, lab, p, steps, wl.lr, momentum=wl.momentum, velocity=vel,
-                                        threshold=threshold, strict_break=strict_break,
-                                        return_best=return_best, losses=losses, mious=mious,
-                                        confusion=conf, pred=pred, workspace=ws)
+    ret = st.st_partial_distill(desc, f, lab, p, steps, wl.lr, momentum=wl.momentum, velocity=vel,
+                                threshold=threshold, strict_break=strict_break,
+                                return_best=return_best, losses=losses, mious=mious,
+                                confusion=conf, pred=pred, workspace=ws)
+    taken, best = ret
     torch.cuda.synchronize()
     lay = st.st_get_workspace_layout(desc)
     nz = wl.n * wl.n_classes * wl.h * wl.w
@@ -43,6 +44,7 @@ def run_gpu(wl, feats, labels, params, steps=None, velocity=None, threshold=0.0,
     return dict(params=p.cpu().numpy(), velocity=None if vel is None else vel.cpu().numpy(),
                 losses=losses.cpu().numpy(), mious=mious.cpu().numpy(), conf=conf.cpu().numpy(),
                 pred=pred.cpu().numpy(), z=z.cpu().numpy(), steps_taken=taken, best_metric=best,
+                first_metric=ret.first_metric,
                 workspace=ws, layout=lay)
 
 

@@ -179,11 +179,12 @@ def test_training_loop_exits():
     assert m.max() > m[0] + 0.05
     # already at THRESHOLD: nothing happens
     r = run_gpu(wl, f, lab, p, threshold=float(m[0]), return_best=True)
-    assert r["steps_taken"] == 0
+    assert r["steps_taken"] == 0 and r["first_metric"] == m[0] and r["best_metric"] == m[0]
     np.testing.assert_array_equal(r["params"], p)
     # unreachable THRESHOLD: every update taken, the first strict maximum returned
     r = run_gpu(wl, f, lab, p, threshold=1.5, return_best=True)
-    assert r["steps_taken"] == 8 and r["best_metric"] == m.max()
+    assert r["steps_taken"] == 8 and r["best_metric"] == m.max() and r["first_metric"] == m[0]
+    assert trace["first_metric"] is None          # fixed-step form: no metric is read back
     best_i = int(np.argmax(m))
     ref = run_gpu(wl, f, lab, p, steps=best_i)
     np.testing.assert_array_equal(r["params"], ref["params"])
