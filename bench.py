@@ -461,8 +461,8 @@ def main():
                     "first_last_score": [round(r["scores"][0], 4), round(r["scores"][-1], 4)],
                     "note": "features are noise that drifts (they carry nothing about the labels), so the "
                             "score stays under the threshold and every frame is a key frame with the full "
-                            "number of steps: the rate is that of forward + metric + early-exit training "
-                            "per frame, inputs resident in HBM"}
+                            "number of steps: the rate is that of one early-exit training call per frame "
+                            "(score first, train under the threshold), inputs resident in HBM"}
             del frames_dev, wsc
         except Exception as e:      # the headline line must not depend on this leg
             clip = {"error": f"{type(e).__name__}: {e}"}
