@@ -100,6 +100,31 @@ def test_intermediate_gradient_buffers_f32():
     np.testing.assert_array_equal(gpu["params"], p)      # lr = 0 leaves the parameters alone
 
 
+@pytest.mark.parametrize("compute", ["f32", "bf16"])
+def test_equal_logits_go_to_the_lowest_class(compute):
+    """With a zero classifier every pixel's logits are the biases, exactly: the predicted class
+    is the lowest index among the largest biases (ties are decided the same way everywhere)."""
+    shape = dict(c_in=64, h=9, w=21, c1=64, c2=64, n_classes=7) if compute == "bf16" else \
+        dict(c_in=12, h=9, w=21, c1=16, c2=8, n_classes=7)
+    wl = WL.small_variant(WL.WORKLOADS["720p" if compute == "bf16" else "tiny"], **shape)
+    f, lab, p = inputs(wl)
+    sl = WL.param_slices(wl)
+    desc = st.HeadDesc.of(wl)
+    pred = torch.empty((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+    for b3, want in ((np.zeros(7), 0), (np.array([0, 1, 1, 0, 1, 0, 0.5]), 1), (np.array([-1, -1, -2, -1, -3, -1, -1]), 0),
+                     (np.array([0, 0, 0, 0, 0, 0, 1e-30]), 6)):
+        q = p.copy()
+        q[sl["W3"]] = 0.0
+        q[sl["b3"]] = b3.astype(np.float32)
+        st.st_head_forward(desc, to_dev_features(wl, f), torch.from_numpy(q).cuda(), None, pred)
+        torch.cuda.synchronize()
+        got = pred.cpu().numpy()
+        assert (got == want).all(), (b3, np.unique(got))
+        # and the oracle takes the same decision from the same logits
+        z = np.broadcast_to(b3.astype(np.float32)[None, :, None, None], (wl.n, 7, wl.h, wl.w)).copy()
+        assert (O.predict_from_logits(z) == want).all()
+
+
 def test_head_forward_matches_oracle():
     wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=12, h=10, w=33, c1=16, c2=8, n_classes=6)
     f, lab, p = inputs(wl)
