@@ -111,3 +111,52 @@ def test_graph_mode_falls_back_where_it_cannot_apply():
     st.st_partial_distill(desc, f, lab, q, 2, wl.lr, threshold=2.0)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(q.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("graph", [False, True])
+def test_clients_on_streams_of_their_own_do_not_disturb_each_other(graph):
+    """Three clients (own key frame, head, workspace, stream) whose calls are issued back to back
+    with no synchronisation in between must each get, bit for bit, what a call on its own gets."""
+    wl0 = WL.small_variant(WL.WORKLOADS["720p"], steps=3, lr=0.02, n_sites=9, c_in=64, h=17, w=35, c1=64, c2=64,
+                           n_classes=6)
+    desc = st.HeadDesc.of(wl0)
+    clients = []
+    for i in range(3):
+        wl = WL.small_variant(wl0, feat_seed=wl0.feat_seed + i, label_seed=wl0.label_seed + 10 * i)
+        p0 = torch.from_numpy(WL.make_head_params(wl, seed=wl.init_seed + 17 * i)).cuda()
+        clients.append(dict(f=to_dev_features(wl, WL.make_features(wl)), lab=torch.from_numpy(WL.make_labels(wl)).cuda(),
+                            p0=p0, p=p0.clone(), ws=st.new_workspace(desc), s=torch.cuda.Stream(),
+                            losses=torch.zeros(4, dtype=torch.float32, device="cuda"),
+                            mious=torch.zeros((4, 1), dtype=torch.float64, device="cuda")))
+
+    def call(c):
+        st.st_partial_distill(desc, c["f"], c["lab"], c["p"], 3, wl0.lr, losses=c["losses"], mious=c["mious"],
+                              workspace=c["ws"], stream=c["s"], graph=graph)
+
+    alone = []
+    for c in clients:                      # each on its own, the device idle around it
+        torch.cuda.synchronize()
+        call(c)
+        alone.append(outputs([c["p"], c["losses"], c["mious"]]))
+    for _ in range(3):                     # all together, several rounds in flight at once
+        torch.cuda.synchronize()
+        for c in clients:
+            c["p"].copy_(c["p0"])
+        torch.cuda.synchronize()
+        for _ in range(4):
+            for c in clients:
+                call(c)                    # (round r continues from the parameters of round r - 1)
+        torch.cuda.synchronize()
+    # the same four rounds one client at a time
+    for c, first in zip(clients, alone):
+        together = outputs([c["p"], c["losses"], c["mious"]])
+        c["p"].copy_(c["p0"])
+        for r in range(4):
+            torch.cuda.synchronize()
+            call(c)
+            if r == 0:
+                for a, b in zip(outputs([c["p"], c["losses"], c["mious"]]), first):
+                    np.testing.assert_array_equal(a, b)
+        for a, b in zip(outputs([c["p"], c["losses"], c["mious"]]), together):
+            np.testing.assert_array_equal(a, b)
+    st.st_graph_cache_clear()
