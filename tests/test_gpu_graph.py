@@ -160,3 +160,45 @@ def test_clients_on_streams_of_their_own_do_not_disturb_each_other(graph):
         for a, b in zip(outputs([c["p"], c["losses"], c["mious"]]), together):
             np.testing.assert_array_equal(a, b)
     st.st_graph_cache_clear()
+
+
+def test_two_host_threads_run_the_early_exit_form_side_by_side():
+    """Algorithm 1 with its per-iteration read-back, called from two host threads at once (own
+    stream, workspace and head each): every thread gets what it gets alone."""
+    import threading
+    wl0 = WL.small_variant(WL.WORKLOADS["720p"], steps=4, lr=0.02, n_sites=9, c_in=64, h=13, w=35, c1=64, c2=64,
+                           n_classes=6)
+    desc = st.HeadDesc.of(wl0)
+    clients = []
+    for i in range(2):
+        wl = WL.small_variant(wl0, feat_seed=wl0.feat_seed + i, label_seed=wl0.label_seed + 10 * i)
+        p0 = torch.from_numpy(WL.make_head_params(wl, seed=wl.init_seed + 17 * i)).cuda()
+        clients.append(dict(f=to_dev_features(wl, WL.make_features(wl)), lab=torch.from_numpy(WL.make_labels(wl)).cuda(),
+                            p0=p0, p=p0.clone(), ws=st.new_workspace(desc), s=torch.cuda.Stream(),
+                            mious=torch.zeros((5, 1), dtype=torch.float64, device="cuda"), out=[]))
+
+    def work(c, rounds):
+        for _ in range(rounds):
+            r = st.st_partial_distill(desc, c["f"], c["lab"], c["p"], 4, wl0.lr, threshold=1.5, return_best=True,
+                                      mious=c["mious"], workspace=c["ws"], stream=c["s"])
+            c["out"].append((tuple(r), r.first_metric))
+
+    torch.cuda.synchronize()
+    for c in clients:                                   # one after the other
+        work(c, 3)
+    torch.cuda.synchronize()
+    alone = [(c["p"].cpu().numpy().copy(), list(c["out"])) for c in clients]
+    for c in clients:
+        c["p"].copy_(c["p0"])
+        c["out"].clear()
+    torch.cuda.synchronize()
+    threads = [threading.Thread(target=work, args=(c, 3)) for c in clients]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for c, (p_alone, out_alone) in zip(clients, alone):
+        assert c["out"] == out_alone
+        assert all(o[0][0] == 4 for o in c["out"])      # the threshold is out of reach: all four updates
+        np.testing.assert_array_equal(c["p"].cpu().numpy(), p_alone)
