@@ -6,7 +6,8 @@
 //
 //   C[m][n] = sum_k A(m, k) * B(k, n),   64 x 64 tile per block, 4 x 4 per thread, K step 16.
 //
-// Each problem is a small struct that says how to fetch A(m,k), B(k,n) and where to store.
+// Each problem is a small struct that says where A(m,k) and B(k,n) live -- as the sum of an offset
+// that depends on the row and one that depends on k -- and where to store.
 #include <algorithm>
 
 #include "st_kernels.hpp"
@@ -29,19 +30,45 @@ __global__ void __launch_bounds__(256) k_gemm_generic(Prob p)
     const int k_steps = (p.K() + GK - 1) / GK;
     const int per = (k_steps + (int)gridDim.z - 1) / (int)gridDim.z;
     const int k_begin = (int)blockIdx.z * per * GK, K = min(p.K(), ((int)blockIdx.z + 1) * per * GK);
+
+    // A thread stages four elements of each operand per K step.  An element's address is the sum
+    // of a part that depends on the row (m or n) and a part that depends on k; the thread's rows
+    // never change, so their parts are computed once, and of the k parts only what the step needs.
+    //   K_FAST operand: one k (tid % GK), four rows (tid / GK + 16 r)
+    //   otherwise:      one row (tid % GB), four k (tid / GB + 4 r)
+    const int a_kk = Prob::A_K_FAST ? tid % GK : tid / GB, a_mm = Prob::A_K_FAST ? tid / GK : tid % GB;
+    const int b_kk = Prob::B_K_FAST ? tid % GK : tid / GB, b_nn = Prob::B_K_FAST ? tid / GK : tid % GB;
+    long a_row[4], b_row[4];
+    bool a_in[4], b_in[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int mm = a_mm + (Prob::A_K_FAST ? 16 * r : 0), nn = b_nn + (Prob::B_K_FAST ? 16 * r : 0);
+        a_in[r] = m0 + mm < M;
+        b_in[r] = n0 + nn < N;
+        a_row[r] = a_in[r] ? p.am(m0 + mm) : 0;
+        b_row[r] = b_in[r] ? p.bn(n0 + nn) : 0;
+    }
+    float ra[4], rb[4];
+    // the elements of the step that starts at k0, into registers
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ka = k0 + a_kk + (Prob::A_K_FAST ? 0 : 4 * r), kb = k0 + b_kk + (Prob::B_K_FAST ? 0 : 4 * r);
+            ra[r] = (a_in[r] && ka < K) ? p.a_ld(a_row[r] + p.ak(ka)) : 0.f;
+            rb[r] = (b_in[r] && kb < K) ? p.b_ld(b_row[r] + p.bk(kb)) : 0.f;
+        }
+    };
     float acc[4][4] = {};
+    if (k_begin < K) fetch(k_begin);
     for (int k0 = k_begin; k0 < K; k0 += GK) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int idx = tid + r * 256;
-            int kk, mm;
-            if (Prob::A_K_FAST) { kk = idx % GK; mm = idx / GK; } else { mm = idx % GB; kk = idx / GB; }
-            As[kk][mm] = (m0 + mm < M && k0 + kk < K) ? p.a(m0 + mm, k0 + kk) : 0.f;
-            int nn;
-            if (Prob::B_K_FAST) { kk = idx % GK; nn = idx / GK; } else { nn = idx % GB; kk = idx / GB; }
-            Bs[kk][nn] = (n0 + nn < N && k0 + kk < K) ? p.b(k0 + kk, n0 + nn) : 0.f;
+            As[a_kk + (Prob::A_K_FAST ? 0 : 4 * r)][a_mm + (Prob::A_K_FAST ? 16 * r : 0)] = ra[r];
+            Bs[b_kk + (Prob::B_K_FAST ? 0 : 4 * r)][b_nn + (Prob::B_K_FAST ? 16 * r : 0)] = rb[r];
         }
         __syncthreads();
+        // the next step's elements travel while this one is multiplied
+        if (k0 + GK < K) fetch(k0 + GK);
 #pragma unroll
         for (int kk = 0; kk < GK; ++kk) {
             float a[4], b[4];
@@ -79,13 +106,17 @@ struct FwdProb {
     __device__ int M() const { return g.positions(); }
     __device__ int N() const { return co; }
     __device__ int K() const { return TAPS * ci; }
-    __device__ float a(int m, int k) const
+    __device__ long am(int m) const { return (long)padded_pos(g, m, 0, 0) * ci; }
+    __device__ long ak(int k) const
     {
         const int tap = k / ci, i = k - tap * ci;
         const int dy = TAPS == 9 ? tap / 3 - 1 : 0, dx = TAPS == 9 ? tap % 3 - 1 : 0;
-        return to_f32(x[(size_t)padded_pos(g, m, dy, dx) * ci + i]);
+        return (long)(dy * g.Wp + dx) * ci + i;
     }
-    __device__ float b(int k, int n) const { return to_f32(W[(size_t)n * TAPS * ci + k]); }
+    __device__ float a_ld(long at) const { return to_f32(x[at]); }
+    __device__ long bn(int n) const { return (long)n * TAPS * ci; }
+    __device__ long bk(int k) const { return k; }
+    __device__ float b_ld(long at) const { return to_f32(W[at]); }
     __device__ void store(int m, int n, float v, int) const
     {
         v += bias[n];
@@ -103,16 +134,20 @@ struct DgradProb {
     __device__ int M() const { return g.positions(); }
     __device__ int N() const { return ci; }
     __device__ int K() const { return 9 * co; }
-    __device__ float a(int m, int k) const
+    __device__ long am(int m) const { return (long)padded_pos(g, m, 0, 0) * co; }
+    __device__ long ak(int k) const
     {
         const int tap = k / co, o = k - tap * co;
-        return to_f32(dy[(size_t)padded_pos(g, m, 1 - tap / 3, 1 - tap % 3) * co + o]);
+        return (long)((1 - tap / 3) * g.Wp + (1 - tap % 3)) * co + o;
     }
-    __device__ float b(int k, int n) const
+    __device__ float a_ld(long at) const { return to_f32(dy[at]); }
+    __device__ long bn(int n) const { return n; }
+    __device__ long bk(int k) const
     {
         const int tap = k / co, o = k - tap * co;
-        return to_f32(W[((size_t)o * 9 + tap) * ci + n]);
+        return ((long)o * 9 + tap) * ci;
     }
+    __device__ float b_ld(long at) const { return to_f32(W[at]); }
     __device__ void store(int m, int n, float v, int) const
     {
         const size_t at = (size_t)padded_pos(g, m, 0, 0) * ci + n;
@@ -130,16 +165,20 @@ struct FeatDgradProb {
     __device__ int M() const { return g.positions(); }
     __device__ int N() const { return ci; }
     __device__ int K() const { return 9 * co; }
-    __device__ float a(int m, int k) const
+    __device__ long am(int m) const { return (long)padded_pos(g, m, 0, 0) * co; }
+    __device__ long ak(int k) const
     {
         const int tap = k / co, o = k - tap * co;
-        return to_f32(dy[(size_t)padded_pos(g, m, 1 - tap / 3, 1 - tap % 3) * co + o]);
+        return (long)((1 - tap / 3) * g.Wp + (1 - tap % 3)) * co + o;
     }
-    __device__ float b(int k, int n) const
+    __device__ float a_ld(long at) const { return to_f32(dy[at]); }
+    __device__ long bn(int n) const { return n; }
+    __device__ long bk(int k) const
     {
         const int tap = k / co, o = k - tap * co;
-        return to_f32(W[((size_t)o * 9 + tap) * ci + n]);
+        return ((long)o * 9 + tap) * ci;
     }
+    __device__ float b_ld(long at) const { return to_f32(W[at]); }
     __device__ void store(int m, int n, float v, int) const
     {
         const int hw = g.h * g.w;
@@ -157,13 +196,17 @@ struct WgradProb {
     __device__ int M() const { return co; }
     __device__ int N() const { return TAPS * ci; }
     __device__ int K() const { return g.positions(); }
-    __device__ float a(int m, int k) const { return to_f32(dy[(size_t)padded_pos(g, k, 0, 0) * co + m]); }
-    __device__ float b(int k, int n) const
+    __device__ long am(int m) const { return m; }
+    __device__ long ak(int k) const { return (long)padded_pos(g, k, 0, 0) * co; }
+    __device__ float a_ld(long at) const { return to_f32(dy[at]); }
+    __device__ long bn(int n) const
     {
         const int tap = n / ci, i = n - tap * ci;
         const int dyy = TAPS == 9 ? tap / 3 - 1 : 0, dxx = TAPS == 9 ? tap % 3 - 1 : 0;
-        return to_f32(x[(size_t)padded_pos(g, k, dyy, dxx) * ci + i]);
+        return (long)(dyy * g.Wp + dxx) * ci + i;
     }
+    __device__ long bk(int k) const { return (long)padded_pos(g, k, 0, 0) * ci; }
+    __device__ float b_ld(long at) const { return to_f32(x[at]); }
     __device__ void store(int m, int n, float v, int share) const { dW[share * copy_stride + (size_t)m * TAPS * ci + n] = v; }
 };
 
@@ -176,8 +219,12 @@ struct LogitsProb {
     __device__ int M() const { return g.positions(); }
     __device__ int N() const { return g.C; }
     __device__ int K() const { return g.c2; }
-    __device__ float a(int m, int k) const { return to_f32(a2[(size_t)padded_pos(g, m, 0, 0) * g.c2 + k]); }
-    __device__ float b(int k, int n) const { return to_f32(W3[(size_t)n * g.c2 + k]); }
+    __device__ long am(int m) const { return (long)padded_pos(g, m, 0, 0) * g.c2; }
+    __device__ long ak(int k) const { return k; }
+    __device__ float a_ld(long at) const { return to_f32(a2[at]); }
+    __device__ long bn(int n) const { return (long)n * g.c2; }
+    __device__ long bk(int k) const { return k; }
+    __device__ float b_ld(long at) const { return to_f32(W3[at]); }
     __device__ void store(int m, int n, float v, int) const
     {
         const int hw = g.h * g.w, img = m / hw, r = m - img * hw;
@@ -197,12 +244,16 @@ struct LogitsDgradProb {
     __device__ int M() const { return g.positions(); }
     __device__ int N() const { return g.c2; }
     __device__ int K() const { return g.C; }
-    __device__ float a(int m, int k) const
+    __device__ long am(int m) const
     {
         const int hw = g.h * g.w, img = m / hw, r = m - img * hw;
-        return as_operand<E>(gz[((size_t)img * g.C + k) * hw + r]);
+        return (long)img * g.C * hw + r;
     }
-    __device__ float b(int k, int n) const { return to_f32(W3[(size_t)k * g.c2 + n]); }
+    __device__ long ak(int k) const { return (long)k * g.h * g.w; }
+    __device__ float a_ld(long at) const { return as_operand<E>(gz[at]); }
+    __device__ long bn(int n) const { return n; }
+    __device__ long bk(int k) const { return (long)k * g.c2; }
+    __device__ float b_ld(long at) const { return to_f32(W3[at]); }
     __device__ void store(int m, int n, float v, int) const
     {
         const size_t at = (size_t)padded_pos(g, m, 0, 0) * g.c2 + n;
@@ -218,12 +269,16 @@ struct LogitsWgradProb {
     __device__ int M() const { return g.C; }
     __device__ int N() const { return g.c2; }
     __device__ int K() const { return g.positions(); }
-    __device__ float a(int m, int k) const
+    __device__ long am(int m) const { return (long)m * g.h * g.w; }
+    __device__ long ak(int k) const
     {
         const int hw = g.h * g.w, img = k / hw, r = k - img * hw;
-        return as_operand<E>(gz[((size_t)img * g.C + m) * hw + r]);
+        return (long)img * g.C * hw + r;
     }
-    __device__ float b(int k, int n) const { return to_f32(a2[(size_t)padded_pos(g, k, 0, 0) * g.c2 + n]); }
+    __device__ float a_ld(long at) const { return as_operand<E>(gz[at]); }
+    __device__ long bn(int n) const { return n; }
+    __device__ long bk(int k) const { return (long)padded_pos(g, k, 0, 0) * g.c2; }
+    __device__ float b_ld(long at) const { return to_f32(a2[at]); }
     __device__ void store(int m, int n, float v, int share) const { dW3[share * copy_stride + (size_t)m * g.c2 + n] = v; }
 };
 
