@@ -5,6 +5,7 @@
 
 #include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "st_kernels.hpp"
@@ -57,16 +58,18 @@ void prof_events(Ctx&, const char* name, hipEvent_t* start, hipEvent_t* stop)
     *stop = b;
 }
 
-// kernels that need more than 64 KB of dynamic LDS must be told once (per process)
+// kernels that need more than 64 KB of dynamic LDS must be told once (per process and device)
 void ensure_dynamic_lds(const void* kernel, size_t bytes)
 {
     static std::mutex m;
-    static std::vector<const void*> done;
+    static std::vector<std::pair<const void*, int>> done;
+    int dev = -1;
+    (void)hipGetDevice(&dev);
     std::lock_guard<std::mutex> lk(m);
-    for (const void* k : done)
-        if (k == kernel) return;
+    for (const auto& k : done)
+        if (k.first == kernel && k.second == dev) return;
     (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    done.push_back(kernel);
+    done.push_back({kernel, dev});
 }
 
 // ------------------------------------------------------------------ validation and plan
