@@ -57,3 +57,37 @@ def test_random_shape(seed):
     # every valid pixel is counted exactly once
     valid = (lab != wl.ignore_index).reshape(wl.n, -1).sum(axis=1)
     np.testing.assert_array_equal(conf.cpu().numpy().sum(axis=(1, 2)), valid)
+
+
+@pytest.mark.parametrize("seed", range(200, 208))
+def test_random_shape_with_pixel_weights(seed):
+    """The same random shapes with a random per-pixel weight map (0 .. 5, zeros included: such
+    pixels count for nothing, like ignored ones, but stay in the confusion counts)."""
+    wl, grouped = random_case(seed)
+    heads = wl.n if grouped else 1
+    rng = np.random.default_rng(seed + 5000)
+    f, lab = WL.make_features(wl), WL.make_labels(wl)
+    wts = rng.integers(0, 6, size=lab.shape).astype(np.uint8)
+    p = np.stack([WL.make_head_params(wl, seed=wl.init_seed + 17 * i) for i in range(heads)]).astype(np.float32)
+    desc = st.HeadDesc.of(wl)
+    desc.grouped = grouped
+    print(wl, "grouped", grouped)
+    pt = torch.from_numpy(p if grouped else p[0]).cuda()
+    vel = torch.zeros_like(pt) if wl.momentum else None
+    losses = torch.zeros((wl.steps + 1, heads) if grouped else (wl.steps + 1,), dtype=torch.float32, device="cuda")
+    conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+    st.st_partial_distill(desc, to_dev_features(wl, f), torch.from_numpy(lab).cuda(), pt, wl.steps, wl.lr,
+                          momentum=wl.momentum, velocity=vel, losses=losses, confusion=conf,
+                          pixel_weights=torch.from_numpy(wts).cuda())
+    torch.cuda.synchronize()
+    d = O.desc_of(wl, True)
+    opt = O.Optim(0, wl.lr, wl.momentum, 0, 0, 0, 0)
+    f64 = WL.features_as_f64(wl, f)
+    if grouped:
+        o = O.partial_distill_grouped(d, f64, lab, p.astype(np.float64), wl.steps, opt, pixel_weights=wts)
+    else:
+        o = O.partial_distill_opt(O.with_pixel_weights(d, wts), f64, lab, p[0].astype(np.float64), wl.steps, opt)
+    assert rel_err(losses.cpu().numpy(), o["losses"]) < 5e-4
+    assert rel_err(pt.cpu().numpy(), o["params"]) < 5e-4
+    valid = (lab != wl.ignore_index).reshape(wl.n, -1).sum(axis=1)
+    np.testing.assert_array_equal(conf.cpu().numpy().sum(axis=(1, 2)), valid)
