@@ -27,9 +27,10 @@
  * parameter vector is W1, b1, W2, b2, W3, b3.
  *
  * Parity status: every function here is pinned by tests/test_oracle_*.py
- * (finite differences, closed forms, brute force, an independent library).
- * The values of the trained weights after k steps on the large workloads have
- * no outside pin beyond those: "parity unpinned" for those values.
+ * (finite differences, closed forms, brute force, an independent library),
+ * and so are the losses and trained weights of the k-step loop on the
+ * measured workloads themselves (the same loop replayed with an independent
+ * library's autograd and optimiser in float64).
  */
 #include <math.h>
 #include <stddef.h>

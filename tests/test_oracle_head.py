@@ -305,3 +305,34 @@ def test_grouped_heads_are_independent_runs():
     assert not np.array_equal(g2["params"][1], g["params"][1])
     shared = O.partial_distill(d, f, lab, p[0], 2, 0.05, momentum=0.9)
     assert not np.allclose(shared["params"], g["params"][0])
+
+
+@pytest.mark.parametrize("name,steps", [("720p", 8), ("1080p", 2), ("batch4", 1)])
+def test_full_size_key_frame_matches_library_loop(name, steps):
+    """The measured workloads themselves (1280x720: all eight steps; 1920x1080 with ignored pixels
+    and momentum: two; the batch of four frames with the wider head: one), float64, against the
+    same loop written with CPU PyTorch autograd and torch.optim.SGD: losses of every pass and the
+    trained parameters."""
+    torch.set_num_threads(8)
+    wl = WL.WORKLOADS[name]
+    d = O.desc_of(wl, False)
+    f = WL.features_as_f64(wl, WL.make_features(wl))
+    lab = WL.make_labels(wl)
+    p = WL.make_head_params(wl).astype(np.float64)
+    res = O.partial_distill(d, f, lab, p, steps, wl.lr, momentum=wl.momentum)
+    pt = T(p.copy()).requires_grad_()
+    opt = torch.optim.SGD([pt], lr=wl.lr, momentum=wl.momentum)
+    ft, labt = T(f), T(lab)
+    losses = []
+    for it in range(steps + 1):
+        opt.zero_grad()
+        loss_t, _, _ = torch_loss(d, ft, labt, pt)
+        losses.append(loss_t.item())
+        if it == steps:
+            break
+        loss_t.backward()
+        opt.step()
+    torch.set_num_threads(4)
+    np.testing.assert_allclose(res["losses"], losses, rtol=1e-11)
+    np.testing.assert_allclose(res["params"], pt.detach().numpy(), rtol=0, atol=1e-12)
+    assert np.abs(res["params"] - p).max() > 1e-4        # the steps did move the head
