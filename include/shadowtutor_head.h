@@ -256,10 +256,16 @@ typedef struct st_workspace_layout {
     size_t z;         /* low-resolution logits [n, C, h, w] float32                         */
     size_t g;         /* d loss / d z        [n, C, h, w] float32                           */
     size_t theta;     /* master parameters, internal order (3x3 weights as [o][kh][kw][i])  */
-    size_t grad;      /* parameter gradient, internal order                                 */
+    size_t grad;      /* parameter gradient, internal order, as partial sums: grad_copies   */
+                      /* copies grad_stride floats apart (the weight-gradient kernels split  */
+                      /* the positions; a layer may use fewer copies than grad_copies: the   */
+                      /* unused ones are not written).  On the matrix-core path the          */
+                      /* classifier's share lies elsewhere (one slot per block).             */
     size_t elem_size; /* bytes per activation element: 4 (float32 path) or 2 (bfloat16)     */
     size_t total;     /* == st_workspace_bytes                                              */
     size_t row_pitch; /* cells per padded row: w + 2 rounded up to a multiple of 8          */
+    size_t grad_copies, grad_stride;      /* see grad                                        */
+    size_t splits[3]; /* copies the 3x3 layers 1, 2 and (plain kernels) the classifier use   */
 } st_workspace_layout;
 
 int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out);

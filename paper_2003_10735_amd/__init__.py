@@ -61,7 +61,8 @@ class StDistillResult(C.Structure):
 
 class StWorkspaceLayout(C.Structure):
     _fields_ = [(k, C.c_size_t) for k in ("feat", "a1", "a2", "da1", "da2", "z", "g", "theta",
-                                           "grad", "elem_size", "total", "row_pitch")]
+                                           "grad", "elem_size", "total", "row_pitch", "grad_copies",
+                                           "grad_stride")] + [("splits", C.c_size_t * 3)]
 
 
 class StKernelStat(C.Structure):
@@ -187,7 +188,8 @@ def st_workspace_bytes(desc: HeadDesc) -> int:
 def st_get_workspace_layout(desc: HeadDesc) -> dict:
     d, out = desc.c(), StWorkspaceLayout()
     _check(lib().st_get_workspace_layout(C.byref(d), C.byref(out)), "st_get_workspace_layout")
-    return {k: int(getattr(out, k)) for k, _ in StWorkspaceLayout._fields_}
+    return {k: ([int(v) for v in getattr(out, k)] if k == "splits" else int(getattr(out, k)))
+            for k, _ in StWorkspaceLayout._fields_}
 
 
 def new_workspace(desc: HeadDesc, device="cuda"):

@@ -376,6 +376,8 @@ int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out)
     out->feat = p.feat; out->a1 = p.a1; out->a2 = p.a2; out->da1 = p.da1; out->da2 = p.da2;
     out->z = p.z; out->g = p.gz; out->theta = p.theta; out->grad = p.grad;
     out->elem_size = p.esz; out->total = p.total; out->row_pitch = (size_t)p.g.Wp;
+    out->grad_copies = (size_t)p.grad_copies; out->grad_stride = p.grad_stride;
+    out->splits[0] = (size_t)p.splits1; out->splits[1] = (size_t)p.splits2; out->splits[2] = (size_t)p.splits3;
     return ST_OK;
 }
 

@@ -74,10 +74,11 @@ def test_ragged_shapes(case, compute):
 
 def test_intermediate_gradient_buffers_f32():
     """d loss / d z and the parameter gradient of one step, read back from the workspace."""
-    wl = WL.small_variant(WL.WORKLOADS["tiny"], steps=1, c_in=8, h=6, w=40, c1=8, c2=8, n_classes=4,
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], steps=1, c_in=8, h=16, w=40, c1=8, c2=8, n_classes=4,
                           n_sites=6, lr=0.0)
     f, lab, p = inputs(wl)
     gpu = run_gpu(wl, f, lab, p)
+    assert max(gpu["layout"]["splits"]) > 1          # the weight gradients arrive as partial copies
     d = O.desc_of(wl)
     f64 = WL.features_as_f64(wl, f)
     loss, grad, *_ = O.loss_and_grad(d, f64, lab, p.astype(np.float64))
@@ -89,8 +90,13 @@ def test_intermediate_gradient_buffers_f32():
     assert rel_err(gz, g) < 1e-5
     # gradient in the internal order: 3x3 weights as [o][kh][kw][i]
     n = p.size
-    gi = ws[lay["grad"]:lay["grad"] + 4 * n].view(torch.float32).cpu().numpy()
+    copies = ws[lay["grad"]:lay["grad"] + 4 * lay["grad_copies"] * lay["grad_stride"]].view(torch.float32).cpu().numpy()
+    copies = copies.reshape(lay["grad_copies"], lay["grad_stride"])[:, :n].astype(np.float64)
     sl = WL.param_slices(wl)
+    gi = np.zeros(n)
+    for name in sl:                              # each block of parameters: the sum of its layer's copies
+        layer = {"W1": 0, "b1": 0, "W2": 1, "b2": 1, "W3": 2, "b3": 2}[name]
+        gi[sl[name]] = copies[:lay["splits"][layer], sl[name]].sum(axis=0)
     ref = grad.copy()
     for name, (co, ci) in (("W1", (wl.c1, wl.c_in)), ("W2", (wl.c2, wl.c1))):
         ref[sl[name]] = grad[sl[name]].reshape(co, ci, 3, 3).transpose(0, 2, 3, 1).ravel()
