@@ -27,8 +27,8 @@
  *     iteration) and which has finished when it returns.  (While the host waits for that read
  *     the stream already computes the iteration's gradients; when the loop ends there they are
  *     left unused in the workspace and no parameter has changed.)
- *   - Dense row-major layouts: features [n, c_in, h, w]; labels / pred [n, 8h, 8w];
- *     low-resolution logits [n, n_classes, h, w].
+ *   - Dense row-major layouts: features [n, c_in, h, w] (or [n, h, w, c_in] with feat_layout =
+ *     ST_NHWC); labels / pred [n, 8h, 8w]; low-resolution logits [n, n_classes, h, w].
  *   - head_params is one flat float32 vector: W1 (OIHW) | b1 | W2 (OIHW) | b2 | W3 (OI) | b3.
  *     It is what the server sends back to the client after training ("UpdatedPart").
  *   - Every function returns ST_OK (0) or a negative st_status; nothing throws or aborts.
@@ -58,7 +58,7 @@ typedef enum st_status {
 } st_status;
 
 enum { ST_F32 = 0, ST_BF16 = 1 };                 /* st_head_desc.feat_dtype */
-enum { ST_NCHW = 0 };                             /* st_head_desc.feat_layout */
+enum { ST_NCHW = 0, ST_NHWC = 1 };                /* st_head_desc.feat_layout */
 enum { ST_COMPUTE_F32 = 0, ST_COMPUTE_BF16 = 1 }; /* st_head_desc.compute */
 
 /* Shape of one training problem.
@@ -85,7 +85,7 @@ typedef struct st_head_desc {
     int32_t c1, c2, n_classes; /* conv3x3 c_in->c1, conv3x3 c1->c2, conv1x1 c2->classes */
     int32_t upscale;           /* 8                                                   */
     int32_t feat_dtype;        /* ST_F32 | ST_BF16: element type of `features`        */
-    int32_t feat_layout;       /* ST_NCHW                                             */
+    int32_t feat_layout;       /* ST_NCHW: features [n, c_in, h, w]; ST_NHWC: [n, h, w, c_in] */
     int32_t compute;           /* ST_COMPUTE_F32 | ST_COMPUTE_BF16                    */
     int32_t ignore_index;      /* label value to skip; -1 = none                      */
     int32_t grouped;           /* 0: one head for all n frames; 1: n heads, one per frame */
@@ -121,7 +121,8 @@ typedef struct st_distill_opts {
      * the weights. */
     const uint8_t* pixel_weights;
     /* Full backward pass, for comparison with partial distillation (Section 4.2) or for a caller
-     * that owns an unfrozen front part: DEVICE pointer to float32 [n, c_in, h, w], or NULL.  When
+     * that owns an unfrozen front part: DEVICE pointer to float32 [n, c_in, h, w] (in this order
+     * whatever feat_layout says), or NULL.  When
      * given, every backward pass also computes d loss / d features (the data-gradient of the
      * first layer, which partial distillation leaves out); the tensor holds that of the last
      * backward pass of the call (untouched if no step is taken).  On the matrix-core path this

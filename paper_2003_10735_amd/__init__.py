@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libshadowtutor_head.so")
 ST_OK = 0
 ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_DEVICE = -1, -2, -3, -4, -5, -6
 ST_F32, ST_BF16 = 0, 1
-ST_NCHW = 0
+ST_NCHW, ST_NHWC = 0, 1
 ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
 ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 

@@ -488,10 +488,11 @@ void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamSte
 
 // Whether the packing role of the call-opening launch writes the whole padded grid of both feature
 // buffers (then only their guards need clearing): matrix-core path, bfloat16 features whose rows
-// are multiples of 16 bytes from a 16-byte aligned start.
+// are multiples of 16 bytes from a 16-byte aligned start, in the [n, c_in, h, w] order.
 bool pack_covers_borders(const Plan& p, const void* features, int feat_dtype)
 {
-    return p.mfma && feat_dtype == ST_BF16 && p.g.w % 8 == 0 && p.g.c_in % 64 == 0 && ((uintptr_t)features & 15) == 0;
+    return p.mfma && !p.g.nhwc && feat_dtype == ST_BF16 && p.g.w % 8 == 0 && p.g.c_in % 64 == 0 &&
+           ((uintptr_t)features & 15) == 0;
 }
 
 // Opens a call in one launch: packs the features, takes the caller's parameters (OIHW order)

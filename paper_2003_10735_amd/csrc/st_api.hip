@@ -80,7 +80,7 @@ static int validate(const st_head_desc* d)
     if (d->upscale != UP) return ST_ERR_SHAPE;
     if (d->n_classes < 2 || d->n_classes > 32) return ST_ERR_SHAPE;
     if (d->feat_dtype != ST_F32 && d->feat_dtype != ST_BF16) return ST_ERR_ARG;
-    if (d->feat_layout != ST_NCHW) return ST_ERR_ARG;
+    if (d->feat_layout != ST_NCHW && d->feat_layout != ST_NHWC) return ST_ERR_ARG;
     if (d->compute != ST_COMPUTE_F32 && d->compute != ST_COMPUTE_BF16) return ST_ERR_ARG;
     if (d->ignore_index < -1) return ST_ERR_ARG;
     if (d->grouped != 0 && d->grouped != 1) return ST_ERR_ARG;

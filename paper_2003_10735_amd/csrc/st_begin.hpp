@@ -7,7 +7,8 @@
 
 namespace st {
 
-// features [n, c_in, h, w] (Tin) -> padded position-major [n, Hp, Wp, c_in] (E) and, when
+// features [n, c_in, h, w] (or [n, h, w, c_in]: Geo::nhwc) (Tin) -> padded position-major
+// [n, Hp, Wp, c_in] (E) and, when
 // outT != nullptr, a channel-major copy in the blocked layout of xt_index() for the
 // weight-gradient kernel.
 // One block (256 threads) transposes a 32-channel x 32-column tile of one row through LDS so that
@@ -21,6 +22,27 @@ __device__ __forceinline__ void pack_features_block(const Tin* __restrict__ f, E
     const int x0 = bx * 32, c0 = by * 32;
     const int img = bz / g.h, y = bz % g.h;
     const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+    if (g.nhwc) {
+        // channels are already the fast index: the position-major copy is a straight (padded)
+        // copy, and only the channel-major one goes through the tile
+        for (int k = ty; k < 32; k += 8) {
+            const int x = x0 + k, c = c0 + tx;
+            float v = 0.f;
+            if (c < g.c_in && x < g.w) {
+                v = to_f32(f[(((size_t)img * g.h + y) * g.w + x) * g.c_in + c]);
+                out[(((size_t)img * g.Hp + y + 1) * g.Wp + x + 1) * g.c_in + c] = from_f32<E>(v);
+            }
+            tile[tx][k] = v;
+        }
+        if (!outT) return;
+        __syncthreads();
+        for (int k = ty; k < 32; k += 8) {
+            const int c = c0 + k, x = x0 + tx;
+            if (c < g.c_in && x < g.w)
+                outT[xt_index(c, guard + (img * g.Hp + y + 1) * g.Wp + x + 1, PPT / 8)] = from_f32<E>(tile[k][tx]);
+        }
+        return;
+    }
     for (int k = ty; k < 32; k += 8) {
         const int c = c0 + k, x = x0 + tx;
         float v = 0.f;

@@ -28,6 +28,7 @@ struct Geo {
     int c_in, c1, c2, C;
     int ignore_index;
     int grouped;     // 1: frame f has a head (parameters, loss, pixel count) of its own
+    int nhwc;        // 1: the caller's features are [n, h, w, c_in] instead of [n, c_in, h, w]
     __host__ __device__ int heads() const { return grouped ? n : 1; }
     __host__ __device__ int head_of(int img) const { return grouped ? img : 0; }
     __host__ __device__ int positions() const { return n * h * w; }
@@ -44,6 +45,7 @@ inline Geo make_geo(const st_head_desc& d)
     g.c_in = d.c_in; g.c1 = d.c1; g.c2 = d.c2; g.C = d.n_classes;
     g.ignore_index = d.ignore_index;
     g.grouped = d.grouped ? 1 : 0;
+    g.nhwc = d.feat_layout == ST_NHWC ? 1 : 0;
     return g;
 }
 

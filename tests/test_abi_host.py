@@ -43,7 +43,7 @@ def test_sizes():
 @pytest.mark.parametrize("field,value,status", [
     ("n", 0, st.ST_ERR_SHAPE), ("h", -1, st.ST_ERR_SHAPE), ("upscale", 4, st.ST_ERR_SHAPE),
     ("n_classes", 1, st.ST_ERR_SHAPE), ("n_classes", 33, st.ST_ERR_SHAPE),
-    ("feat_dtype", 7, st.ST_ERR_ARG), ("compute", 2, st.ST_ERR_ARG), ("feat_layout", 1, st.ST_ERR_ARG),
+    ("feat_dtype", 7, st.ST_ERR_ARG), ("compute", 2, st.ST_ERR_ARG), ("feat_layout", 2, st.ST_ERR_ARG),
     ("ignore_index", -2, st.ST_ERR_ARG), ("w", 1 << 24, st.ST_ERR_SHAPE),
 ])
 def test_bad_descriptors_are_rejected_on_the_host(field, value, status):

@@ -131,6 +131,42 @@ def test_equal_logits_go_to_the_lowest_class(compute):
         assert (O.predict_from_logits(z) == want).all()
 
 
+@pytest.mark.parametrize("case", ["f32", "mfma", "mfma_grouped"])
+def test_channels_last_features_give_the_same_call(case):
+    """feat_layout = ST_NHWC: the same features handed over as [n, h, w, c_in] must give, bit for
+    bit, what the [n, c_in, h, w] call gives (only the packing role differs)."""
+    if case == "f32":
+        wl = WL.small_variant(WL.WORKLOADS["tiny"], n=2, c_in=20, h=9, w=37, c1=24, c2=16, n_classes=5, steps=2)
+    else:
+        wl = WL.small_variant(WL.WORKLOADS["720p"], n=2, c_in=64, h=11, w=40, c1=64, c2=64, n_classes=7, steps=2,
+                              n_sites=9)
+    grouped = 1 if case == "mfma_grouped" else 0
+    heads = wl.n if grouped else 1
+    f, lab, _ = inputs(wl)
+    p = np.stack([WL.make_head_params(wl, seed=wl.init_seed + 17 * i) for i in range(heads)]).astype(np.float32)
+    fd = to_dev_features(wl, f)
+    results = []
+    for layout in (st.ST_NCHW, st.ST_NHWC):
+        desc = st.HeadDesc.of(wl)
+        desc.grouped, desc.feat_layout = grouped, layout
+        feats = fd if layout == st.ST_NCHW else fd.permute(0, 2, 3, 1).contiguous()
+        pt = torch.from_numpy(p if grouped else p[0]).cuda()
+        losses = torch.zeros((wl.steps + 1, heads) if grouped else (wl.steps + 1,), dtype=torch.float32, device="cuda")
+        pred = torch.zeros((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+        dfeat = None if (grouped or case == "f32") else torch.zeros((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32,
+                                                                    device="cuda")
+        st.st_partial_distill(desc, feats, torch.from_numpy(lab).cuda(), pt, wl.steps, wl.lr, losses=losses, pred=pred,
+                              feature_grad=dfeat)
+        z = torch.empty((wl.n, wl.n_classes, wl.h, wl.w), dtype=torch.float32, device="cuda")
+        if not grouped:
+            st.st_head_forward(desc, feats, pt, z, None)
+        torch.cuda.synchronize()
+        results.append([t.cpu().numpy() for t in (pt, losses, pred, z)] + ([dfeat.cpu().numpy()] if dfeat is not None else []))
+    for a, b in zip(*results):
+        np.testing.assert_array_equal(a, b)
+    assert np.abs(results[0][0] - (p if grouped else p[0])).max() > 0
+
+
 def test_head_forward_matches_oracle():
     wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=12, h=10, w=33, c1=16, c2=8, n_classes=6)
     f, lab, p = inputs(wl)
