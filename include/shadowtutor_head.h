@@ -140,6 +140,11 @@ typedef struct st_distill_opts {
      * is on, the call runs as if use_graph were 0).  Instantiating a graph allocates host and
      * driver memory; st_graph_cache_clear() releases it. */
     int32_t use_graph;
+    /* With threshold > 0: DEVICE pointer to st_num_params floats (same order as head_params) that
+     * receives best_student of Algorithm 1 whatever return_best says -- so a caller can have the
+     * last parameters in head_params and the best ones here -- or NULL.  Ignored without a
+     * threshold (there the last parameters are the result). */
+    float* best_params;
 } st_distill_opts;
 enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 

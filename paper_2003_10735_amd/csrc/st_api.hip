@@ -413,6 +413,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     double threshold = 0.0;
     float* velocity = nullptr;
     bool strict = true, return_best = false;
+    float* best_params = nullptr;
     bool use_adam = false;
     float *adam_m = nullptr, *adam_v = nullptr;
     double beta1 = 0.0, beta2 = 0.0;
@@ -439,6 +440,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         threshold = opts->threshold;
         strict = opts->strict_break != 0;
         return_best = opts->return_best != 0;
+        best_params = opts->best_params;
     }
     if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
     const bool early_exit = threshold > 0.0;
@@ -461,6 +463,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             key.opts.adam_m = opts->adam_m; key.opts.adam_v = opts->adam_v; key.opts.adam_t0 = opts->adam_t0;
             key.opts.pixel_weights = opts->pixel_weights; key.opts.feature_grad = opts->feature_grad;
             key.opts.use_graph = 1;
+            key.opts.best_params = opts->best_params;
             if (out) { key.losses = out->losses; key.mious = out->mious; key.confusion = out->confusion; key.pred = out->pred; }
             key.workspace = workspace;
             if (hipGetDevice(&key.device) != hipSuccess) return ST_ERR_NO_DEVICE;
@@ -529,6 +532,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     std::vector<double> frame_metric;
     int taken = 0;
     bool have_best = false;
+    const bool keep_best = early_exit && (return_best || best_params);
     bool params_out_done = false;
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
@@ -576,7 +580,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             if (it == 0) {
                 first_metric = metric;
                 best_metric = metric;
-                if (return_best) {
+                if (keep_best) {
                     ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
                     have_best = true;
                 }
@@ -584,7 +588,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             } else {
                 if (metric > best_metric) {
                     best_metric = metric;
-                    if (return_best)
+                    if (keep_best)
                         ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
                 }
                 if (strict ? metric > threshold : metric >= threshold) stop = true;
@@ -606,6 +610,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                  feature_grad != nullptr);
         ++taken;
     }
+    if (early_exit && best_params && have_best) permute_params(c, p, (const float*)(ws + p.best), best_params, 1);
     if (early_exit && return_best && have_best)
         ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
     if (!params_out_done) permute_params(c, p, theta, head_params, 1);

@@ -255,6 +255,15 @@ def test_training_loop_exits():
     best_i = int(np.argmax(m))
     ref = run_gpu(wl, f, lab, p, steps=best_i)
     np.testing.assert_array_equal(r["params"], ref["params"])
+    # the best parameters into a buffer of their own, the last ones in place
+    desc = st.HeadDesc.of(wl)
+    pt, bt = torch.from_numpy(p.copy()).cuda(), torch.zeros(p.size, dtype=torch.float32, device="cuda")
+    taken, best = st.st_partial_distill(desc, to_dev_features(wl, f), torch.from_numpy(lab).cuda(), pt, 8, wl.lr,
+                                        threshold=1.5, return_best=False, best_params=bt)
+    torch.cuda.synchronize()
+    assert taken == 8 and best == m.max()
+    np.testing.assert_array_equal(bt.cpu().numpy(), ref["params"])
+    np.testing.assert_array_equal(pt.cpu().numpy(), trace["params"])
     # reachable THRESHOLD: leave at the first metric strictly above it ('>'), or at it ('>=')
     j = next(i for i in range(1, 9) if m[i] > m[0])
     r_ge = run_gpu(wl, f, lab, p, threshold=float(m[j]), strict_break=False)
