@@ -336,3 +336,37 @@ def test_full_size_key_frame_matches_library_loop(name, steps):
     np.testing.assert_allclose(res["losses"], losses, rtol=1e-11)
     np.testing.assert_allclose(res["params"], pt.detach().numpy(), rtol=0, atol=1e-12)
     assert np.abs(res["params"] - p).max() > 1e-4        # the steps did move the head
+
+
+def test_identity_convolutions_reduce_the_head_to_logistic_regression():
+    """With centre-delta 3x3 kernels and positive features both hidden layers are the identity,
+    and since a 1x1 convolution commutes with the (linear, per-channel) up-sampling the head is
+    multinomial logistic regression on the up-sampled features: loss and the textbook gradient
+    X^T (softmax - onehot) / N for the classifier, written out here in numpy."""
+    C_IN, NC = 4, 3
+    d = tiny(n=2, c_in=C_IN, h=4, w=5, c1=C_IN, c2=C_IN, C=NC)
+    rng = np.random.default_rng(5)
+    f = rng.random((d.n, C_IN, d.h, d.w)) + 0.1
+    lab = rng.integers(0, NC, size=(d.n, 8 * d.h, 8 * d.w)).astype(np.int32)
+    eye = np.zeros((C_IN, C_IN, 3, 3))
+    eye[np.arange(C_IN), np.arange(C_IN), 1, 1] = 1.0
+    W3 = rng.standard_normal((NC, C_IN))
+    b3 = rng.standard_normal(NC)
+    p = np.concatenate([eye.ravel(), np.zeros(C_IN), eye.ravel(), np.zeros(C_IN), W3.ravel(), b3])
+    loss, grad, *_ = O.loss_and_grad(d, f, lab, p)
+    # the design matrix: every frame pixel's up-sampled feature vector (an independent library's
+    # interpolation), one row per pixel
+    X = F.interpolate(T(f), scale_factor=8, mode="bilinear", align_corners=False).numpy()
+    X = X.transpose(0, 2, 3, 1).reshape(-1, C_IN)
+    y = lab.reshape(-1)
+    logits = X @ W3.T + b3
+    logits -= logits.max(axis=1, keepdims=True)
+    P = np.exp(logits)
+    P /= P.sum(axis=1, keepdims=True)
+    N = y.size
+    assert abs(loss - (-np.log(P[np.arange(N), y]).mean())) < 1e-12
+    R = P.copy()
+    R[np.arange(N), y] -= 1.0
+    n3 = NC * C_IN + NC
+    np.testing.assert_allclose(grad[-n3:-NC].reshape(NC, C_IN), R.T @ X / N, atol=1e-13)
+    np.testing.assert_allclose(grad[-NC:], R.sum(axis=0) / N, atol=1e-13)
