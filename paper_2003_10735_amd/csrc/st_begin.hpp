@@ -158,19 +158,31 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
     const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
     const int Yt = 8 * cy - 4;                             // frame row of tent position 0
     unsigned int cnt = 0;     // valid labels (their weights) of this block's own 8 x 256 pixels
-    for (int col = tid; col < NCOL; col += 256) {
-        const int X = X0 + col;
-        const bool xin = X >= 0 && X < g.W;
-        const int Xc = min(max(X, 0), g.W - 1);
-        // the 16 rows under the tent: all loads first (clamped, so none depends on a branch)
-        int ys[16];
-        unsigned int ws[16];
+    // A thread takes table column tid and, the first NCOL - 256 threads, column tid + 256 as
+    // well.  The loads of both columns are issued before either is worked on: one trip to memory
+    // for the block instead of two.
+    static_assert(NCOL > 256 && NCOL <= 512, "one or two columns per thread");
+    const bool second = tid < NCOL - 256;
+    int ys[2][16];
+    unsigned int ws[2][16];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (k == 1 && !second) break;
+        const int Xc = min(max(X0 + tid + 256 * k, 0), g.W - 1);
+        // the 16 rows under the tent (clamped, so that no load depends on a branch of its own)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const size_t at = (size_t)min(max(Yt + r, 0), g.H - 1) * g.W + Xc;
-            ys[r] = lab[at];
-            ws[r] = wm ? wm[at] : 1u;
+            ys[k][r] = lab[at];
+            ws[k][r] = wm ? wm[at] : 1u;
         }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (k == 1 && !second) break;
+        const int col = tid + 256 * k;
+        const int X = X0 + col;
+        const bool xin = X >= 0 && X < g.W;
         const bool own_col = col >= 4 && col < NCOL - 4;
         // label maps are piecewise constant: rows with the same label are added up in a register
         // and reach the table once per run (all terms are multiples of 1/256, so any grouping of
@@ -179,7 +191,7 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
         float run = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int Y = Yt + r, y = ys[r];
+            const int Y = Yt + r, y = ys[k][r];
             const bool ok = xin && Y >= 0 && Y < g.H && y != g.ignore_index && y >= 0 && y < g.C;
             const int yy = ok ? y : -1;
             if (yy != run_y) {
@@ -188,8 +200,8 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
                 run = 0.f;
             }
             if (ok) {
-                run += (float)ws[r] * tap_weight(Y, cy, g.h);
-                if (own_col && r >= 4 && r < 12) cnt += ws[r];
+                run += (float)ws[k][r] * tap_weight(Y, cy, g.h);
+                if (own_col && r >= 4 && r < 12) cnt += ws[k][r];
             }
         }
         if (run_y >= 0) colsum[run_y * PITCH + col] += run;
