@@ -77,3 +77,39 @@ def test_720p_four_clients_grouped():
     o = O.partial_distill_grouped(O.desc_of(wl, True), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 2, SGD(wl))
     print("grouped losses", g["losses"].T, "oracle", o["losses"].T)
     check_against_oracle(wl, g, o, p)
+
+
+def test_720p_graph_launch_equals_the_plain_call():
+    """The benchmark's headline is timed through the cached launch graph on a stream of its own:
+    at the full size, all eight steps, first launch and a replay, it must give bit for bit what
+    the plain call gives (which the test above holds against the oracle)."""
+    import torch
+    import paper_2003_10735_amd as st
+    from gpu_util import to_dev_features
+    wl = WL.WORKLOADS["720p"]
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    desc = st.HeadDesc.of(wl)
+    fd, labd = to_dev_features(wl, f), torch.from_numpy(lab).cuda()
+    stream = torch.cuda.Stream()
+    ws = st.new_workspace(desc)
+    pt = torch.from_numpy(p).cuda()
+    losses = torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")
+    mious = torch.zeros((wl.steps + 1, 1), dtype=torch.float64, device="cuda")
+    conf = torch.zeros((1, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+    pred = torch.zeros((1, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+
+    def run(graph):
+        torch.cuda.synchronize()
+        pt.copy_(torch.from_numpy(p))
+        torch.cuda.synchronize()
+        st.st_partial_distill(desc, fd, labd, pt, wl.steps, wl.lr, losses=losses, mious=mious, confusion=conf,
+                              pred=pred, workspace=ws, stream=stream, graph=graph)
+        torch.cuda.synchronize()
+        return [t.cpu().numpy().copy() for t in (pt, losses, mious, conf, pred)]
+
+    plain = run(False)
+    for _ in range(2):
+        for a, b in zip(run(True), plain):
+            np.testing.assert_array_equal(a, b)
+    assert st.st_graph_cache_size() >= 1
+    st.st_graph_cache_clear()
