@@ -117,3 +117,14 @@ def test_product_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.replace("no CPU fallback", ""), os.path.join(dirpath, fn)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The library runs on one GPU: asked for more, the benchmark says so and stops before it
+    touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
