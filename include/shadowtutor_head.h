@@ -24,9 +24,11 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Calls return without synchronising, except st_partial_distill with a positive
  *     `threshold`, whose loop exits are decided on the host (one small device-to-host read per
- *     iteration) and which has finished when it returns.  (While the host waits for that read
- *     the stream already computes the iteration's gradients; when the loop ends there they are
- *     left unused in the workspace and no parameter has changed.)
+ *     iteration) and which has finished when it returns.  (From the second read on, the stream
+ *     already computes the iteration's gradients while the host waits; when the loop ends there
+ *     they are left unused in the workspace and no parameter has changed.  A call whose first
+ *     metric already reaches the threshold -- the frame is no key frame -- costs one forward
+ *     pass and writes none of the caller's parameter or optimiser vectors.)
  *   - Dense row-major layouts: features [n, c_in, h, w] (or [n, h, w, c_in] with feat_layout =
  *     ST_NHWC); labels / pred [n, 8h, 8w]; low-resolution logits [n, n_classes, h, w].
  *   - head_params is one flat float32 vector: W1 (OIHW) | b1 | W2 (OIHW) | b2 | W3 (OI) | b3.
@@ -101,7 +103,12 @@ typedef struct st_distill_opts {
     int32_t strict_break; /* 1: leave the loop when metric > threshold (as printed);
                              0: when metric >= threshold                                     */
     int32_t return_best;  /* with threshold > 0 -- 1: head_params receives best_student of
-                             Algorithm 1 (strictly-better rule); 0: the last parameters      */
+                             Algorithm 1 (strictly-better rule); 0: the last parameters.
+                             Only the parameters are rolled back to the best iteration: the
+                             optimiser state (velocity, adam_m, adam_v), out->pred,
+                             out->confusion and entry steps_taken of losses / mious always
+                             describe the last pass (Algorithm 1 returns parameters and metric
+                             only; the metric of the returned ones is out->best_metric)      */
     /* Optimiser (Algorithm 1, OptimStep).  ST_OPTIM_SGD: the descent above.  ST_OPTIM_ADAM: the
      * optimiser of the paper's experiments (Section 5.2, learning rate 0.01); the paper gives
      * no further constants, the published defaults are beta1 0.9, beta2 0.999, eps 1e-8.

@@ -228,9 +228,12 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
         float m = Z[0];
 #pragma unroll
         for (int c = 1; c < CP; ++c) m = fmaxf(m, Z[c]);
-        int best = CP - 1;
+        // (only real classes can win: when every real logit is NaN the maximum is the padding's
+        //  value, and then -- as when nothing compares equal at all -- the answer is class 0, never
+        //  an index outside [0, C))
+        int best = 0;
 #pragma unroll
-        for (int c = CP - 2; c >= 0; --c) best = Z[c] == m ? c : best;
+        for (int c = CP - 1; c >= 0; --c) best = (Z[c] == m && (c < CP - 3 || c < C)) ? c : best;
         if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
         if (lab_img) {
             const int y = lab4[i];

@@ -467,15 +467,28 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             if (out) { key.losses = out->losses; key.mious = out->mious; key.confusion = out->confusion; key.pred = out->pred; }
             key.workspace = workspace;
             if (hipGetDevice(&key.device) != hipSuccess) return ST_ERR_NO_DEVICE;
-            std::lock_guard<std::mutex> lk(g_graph_mutex);
-            GraphEntry* hit = nullptr;
-            for (auto& e : g_graphs)
-                if (memcmp(&e.key, &key, sizeof(key)) == 0) hit = &e;
-            if (!hit) {
+            // The cache is locked only to look an entry up and to insert one: recording and
+            // instantiating a graph (milliseconds) runs unlocked, so callers on other streams go on.
+            // (A launch itself happens under the lock, so that no other thread can evict and destroy
+            //  the graph between the look-up and the launch.)
+            auto launch_locked = [&](GraphEntry& e) -> int {
+                e.last_use = ++g_graph_clock;
+                const hipError_t le = hipGraphLaunch(e.exec, as_stream(stream));
+                if (le != hipSuccess) { set_hip_error(le); return ST_ERR_HIP; }
+                if (out) out->steps_taken = steps;
+                return ST_OK;
+            };
+            {
+                std::lock_guard<std::mutex> lk(g_graph_mutex);
+                for (auto& e : g_graphs)
+                    if (memcmp(&e.key, &key, sizeof(key)) == 0) return launch_locked(e);
+            }
+            {
                 // record the plain call's launches (nothing runs while the stream is capturing)
                 st_distill_opts plain = *opts;
                 plain.use_graph = 0;
-                if (hipStreamBeginCapture(as_stream(stream), hipStreamCaptureModeRelaxed) != hipSuccess) return ST_ERR_HIP;
+                const hipError_t begin = hipStreamBeginCapture(as_stream(stream), hipStreamCaptureModeRelaxed);
+                if (begin != hipSuccess) { set_hip_error(begin); return ST_ERR_HIP; }
                 const int rec = st_partial_distill(desc, features, teacher_labels, head_params, steps, lr, &plain, out,
                                                    workspace, stream);
                 GraphEntry e;
@@ -485,6 +498,14 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                 if (end != hipSuccess || !e.graph) { set_hip_error(end); destroy_entry(e); return ST_ERR_HIP; }
                 const hipError_t inst = hipGraphInstantiate(&e.exec, e.graph, nullptr, nullptr, 0);
                 if (inst != hipSuccess) { set_hip_error(inst); destroy_entry(e); return ST_ERR_HIP; }
+                std::lock_guard<std::mutex> lk(g_graph_mutex);
+                GraphEntry* twin = nullptr;      // another thread recorded the same call meanwhile
+                for (auto& other : g_graphs)
+                    if (memcmp(&other.key, &key, sizeof(key)) == 0) twin = &other;
+                if (twin) {
+                    destroy_entry(e);
+                    return launch_locked(*twin);
+                }
                 if (g_graphs.size() >= GRAPH_CACHE_MAX) {
                     // drop the least recently used one; it may still be running somewhere
                     size_t old = 0;
@@ -495,13 +516,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                     g_graphs.erase(g_graphs.begin() + old);
                 }
                 g_graphs.push_back(e);
-                hit = &g_graphs.back();
+                return launch_locked(g_graphs.back());
             }
-            hit->last_use = ++g_graph_clock;
-            const hipError_t le = hipGraphLaunch(hit->exec, as_stream(stream));
-            if (le != hipSuccess) { set_hip_error(le); return ST_ERR_HIP; }
-            if (out) out->steps_taken = steps;
-            return ST_OK;
         }
     }
 
@@ -553,18 +569,20 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr);
         params_out_done = params_out_done || out_now;
         bool stop = last;
-        // In the early-exit form the backward pass of this iteration is put into the stream before
+        // In the early-exit form the backward pass of an iteration is put into the stream before
         // the host looks at the metric: it only produces gradients (nothing the results depend on
         // changes before the optimiser step), so the stream works through it while the host waits
-        // for the metric, and it is simply not used when the loop ends here.  (Not with a feature
-        // gradient: that one is an output.)
+        // for the metric, and it is simply not used when the loop ends here.  Not before the first
+        // metric, though: most frames of a video are not key frames (Table 5: about one in
+        // twenty is), their call ends right there and should cost a forward pass and no more.
+        // (And not with a feature gradient: that one is an output.)
         bool backward_queued = false;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
             double* metric_host = pinned_metric_buffer((size_t)g.n);
             if (!metric_host) { frame_metric.resize(g.n); metric_host = frame_metric.data(); }
             ST_HIP(c, hipMemcpyAsync(metric_host, metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost, c.stream));
-            hipEvent_t ev = (!last && !feature_grad) ? readback_event() : nullptr;
+            hipEvent_t ev = (!last && !feature_grad && it > 0) ? readback_event() : nullptr;
             if (ev) {
                 ST_HIP(c, hipEventRecord(ev, c.stream));
                 backward(c, p, ws, nullptr);
@@ -580,11 +598,11 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             if (it == 0) {
                 first_metric = metric;
                 best_metric = metric;
-                if (keep_best) {
+                if (!(metric < threshold)) stop = true;   // already good enough: no update at all
+                else if (keep_best) {
                     ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
                     have_best = true;
                 }
-                if (!(metric < threshold)) stop = true;   // already good enough: no update at all
             } else {
                 if (metric > best_metric) {
                     best_metric = metric;
@@ -610,12 +628,14 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                  feature_grad != nullptr);
         ++taken;
     }
-    if (early_exit && best_params && have_best) permute_params(c, p, (const float*)(ws + p.best), best_params, 1);
-    if (early_exit && return_best && have_best)
+    if (early_exit && best_params) permute_params(c, p, have_best ? (const float*)(ws + p.best) : theta, best_params, 1);
+    if (early_exit && return_best && have_best && taken > 0)
         ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
-    if (!params_out_done) permute_params(c, p, theta, head_params, 1);
-    if (mu != 0.f) permute_params(c, p, (const float*)(ws + p.vel), velocity, 1);
-    if (use_adam) {
+    // (a call that took no update -- not a key frame -- leaves the caller's vectors as they are)
+    const bool untouched = early_exit && taken == 0;
+    if (!params_out_done && !untouched) permute_params(c, p, theta, head_params, 1);
+    if (mu != 0.f && !untouched) permute_params(c, p, (const float*)(ws + p.vel), velocity, 1);
+    if (use_adam && !untouched) {
         permute_params(c, p, (const float*)(ws + p.vel), adam_m, 1);
         permute_params(c, p, (const float*)(ws + p.vel2), adam_v, 1);
     }
