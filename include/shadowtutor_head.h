@@ -56,7 +56,8 @@ typedef enum st_status {
     ST_ERR_ARG = -3,       /* steps < 0, non-finite lr / momentum, bad enum value */
     ST_ERR_WORKSPACE = -4, /* workspace NULL or misaligned */
     ST_ERR_HIP = -5,       /* a HIP runtime call failed (st_last_hip_error() tells which) */
-    ST_ERR_NO_DEVICE = -6  /* no usable GPU in this process */
+    ST_ERR_NO_DEVICE = -6, /* no usable GPU in this process */
+    ST_ERR_TOO_LARGE = -7  /* st_head_forward_noalloc: the shape needs more than its built-in scratch */
 } st_status;
 
 enum { ST_F32 = 0, ST_BF16 = 1 };                 /* st_head_desc.feat_dtype */
@@ -184,6 +185,22 @@ size_t st_workspace_bytes(const st_head_desc* desc);
  *   pred           [n, 8h, 8w] uint8, or NULL                                              */
 int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
                     float* logits_lowres, uint8_t* pred, void* workspace, void* stream);
+
+/* st_head_forward for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops (most frames of a stream are not key frames
+ * and only need this forward), harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as st_head_forward, but the workspace is a device array built into the library:
+ * ST_NOALLOC_MAX_WORKSPACE_MIB MiB per GPU the library runs on, held from the first call on that
+ * GPU until the process ends (enough for the 1280x720 head 256 -> 128 -> 128 -> 19, which needs
+ * 79 MiB).  The call allocates nothing, on the device or through any library; shapes with
+ * st_workspace_bytes(desc) above the limit are refused with ST_ERR_TOO_LARGE before any GPU work.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ * outside a capture.  Every call on a GPU uses that GPU's one array: calls that overlap on one
+ * GPU (two streams, two threads) race -- serialise them.  The event profile (st_profile_enable)
+ * does not see this call's launches. */
+#define ST_NOALLOC_MAX_WORKSPACE_MIB 96
+int st_head_forward_noalloc(const st_head_desc* desc, const void* features, const float* head_params,
+                            float* logits_lowres, uint8_t* pred, void* stream);
 
 /* Student training on one key frame (Algorithm 1 restricted to the head, Section 4.2):
  * `steps` times { loss, partial backward, optimiser step }, with a forward + metric before the

@@ -16,13 +16,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshadowtutor_head.so")
 
 ST_OK = 0
-ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_DEVICE = -1, -2, -3, -4, -5, -6
+ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_DEVICE, ST_ERR_TOO_LARGE = -1, -2, -3, -4, -5, -6, -7
+ST_NOALLOC_MAX_WORKSPACE_MIB = 96
 ST_F32, ST_BF16 = 0, 1
 ST_NCHW, ST_NHWC = 0, 1
 ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
 ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 
-EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_partial_distill",
+EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_head_forward_noalloc", "st_partial_distill",
            "st_miou", "st_strerror", "st_last_hip_error", "st_version",
            "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read",
            "st_next_stride", "st_schedule_bounds", "st_schedule_total_time",
@@ -103,6 +104,9 @@ def lib():
         L.st_head_forward.restype = C.c_int
         L.st_head_forward.argtypes = [C.POINTER(StHeadDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.st_head_forward_noalloc.restype = C.c_int
+        L.st_head_forward_noalloc.argtypes = [C.POINTER(StHeadDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
         L.st_partial_distill.restype = C.c_int
         L.st_partial_distill.argtypes = [C.POINTER(StHeadDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_int32, C.c_float, C.POINTER(StDistillOpts),
@@ -210,6 +214,14 @@ def st_head_forward(desc: HeadDesc, features, head_params, logits_lowres=None, p
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     _check(lib().st_head_forward(C.byref(d), _ptr(features), _ptr(head_params), _ptr(logits_lowres),
                                  _ptr(pred), _ptr(ws), _stream(stream)), "st_head_forward")
+    return logits_lowres, pred
+
+
+def st_head_forward_noalloc(desc: HeadDesc, features, head_params, logits_lowres=None, pred=None, stream=None):
+    """st_head_forward on the library's built-in scratch: no workspace argument, no allocation."""
+    d = desc.c()
+    _check(lib().st_head_forward_noalloc(C.byref(d), _ptr(features), _ptr(head_params), _ptr(logits_lowres),
+                                         _ptr(pred), _stream(stream)), "st_head_forward_noalloc")
     return logits_lowres, pred
 
 

@@ -40,11 +40,11 @@ static hipEvent_t get_event()
     return e;
 }
 
-void prof_events(Ctx&, const char* name, hipEvent_t* start, hipEvent_t* stop)
+void prof_events(Ctx& c, const char* name, hipEvent_t* start, hipEvent_t* stop)
 {
     *start = nullptr;
     *stop = nullptr;
-    if (!g_prof_on) return;
+    if (!g_prof_on || c.no_profile) return;
     std::lock_guard<std::mutex> lk(g_prof_mutex);
     if (!g_prof_filter.empty() && !strstr(name, g_prof_filter.c_str())) return;
     hipEvent_t a = get_event(), b = get_event();
@@ -58,18 +58,22 @@ void prof_events(Ctx&, const char* name, hipEvent_t* start, hipEvent_t* stop)
     *stop = b;
 }
 
-// kernels that need more than 64 KB of dynamic LDS must be told once (per process and device)
+// kernels that need more than 64 KB of dynamic LDS must be told once (per process and device);
+// a fixed table, so that no call path allocates host memory for it
 void ensure_dynamic_lds(const void* kernel, size_t bytes)
 {
     static std::mutex m;
-    static std::vector<std::pair<const void*, int>> done;
+    constexpr int MAX_DONE = 256;
+    static const void* done_kernel[MAX_DONE];
+    static int done_device[MAX_DONE];
+    static int n_done = 0;
     int dev = -1;
     (void)hipGetDevice(&dev);
     std::lock_guard<std::mutex> lk(m);
-    for (const auto& k : done)
-        if (k.first == kernel && k.second == dev) return;
+    for (int i = 0; i < n_done; ++i)
+        if (done_kernel[i] == kernel && done_device[i] == dev) return;
     (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    done.push_back({kernel, dev});
+    if (n_done < MAX_DONE) { done_kernel[n_done] = kernel; done_device[n_done] = dev; ++n_done; }
 }
 
 // ------------------------------------------------------------------ validation and plan
@@ -227,6 +231,35 @@ static hipEvent_t readback_event()
 
 static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// ------------------------------------------------------------------ built-in scratch
+// Workspace of st_head_forward_noalloc: device memory that exists from the moment the library is
+// loaded, so the call itself allocates nothing.  Every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's name is only a handle: the device address is
+// asked for once per device (hipGetSymbolAddress, with that device current) and kept in a table;
+// the kernels get that address as their workspace argument, exactly like a caller's workspace.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)ST_NOALLOC_MAX_WORKSPACE_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[NOALLOC_MAX_DEVICES];
+
+// the current device's copy of the scratch array (ST_ERR_HIP / ST_ERR_NO_DEVICE on failure)
+static int scratch_of_current_device(char** out)
+{
+    int dev = -1;
+    const hipError_t ge = hipGetDevice(&dev);
+    if (ge != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) { set_hip_error(ge); return ST_ERR_NO_DEVICE; }
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { set_hip_error(e); return ST_ERR_HIP; }
+        g_scratch_ptr[dev] = (char*)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ST_OK;
+}
+
 // Clears everything a call relies on being zero, in one launch: the counters, and of the
 // activation buffers
 //  * plain kernels: all of them (they write interior cells only and rely on zero borders);
@@ -381,16 +414,12 @@ int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out)
     return ST_OK;
 }
 
-int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
-                    float* logits_lowres, uint8_t* pred, void* workspace, void* stream)
+// the launches of a forward call: clearing, packing + parameters, the two convolutions with the
+// classifier, and the pass that leaves the class map
+static int head_forward_launches(const st_head_desc* desc, const Plan& p, const void* features, const float* head_params,
+                                 float* logits_lowres, uint8_t* pred, char* ws, void* stream, bool no_profile)
 {
-    const int v = validate(desc);
-    if (v != ST_OK) return v;
-    if (!features || !head_params) return ST_ERR_NULL;
-    if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
-    const Plan p = make_plan(*desc);
-    char* ws = (char*)workspace;
-    Ctx c{as_stream(stream), ST_OK};
+    Ctx c{as_stream(stream), ST_OK, no_profile};
     prepare_workspace(c, p, ws, pack_covers_borders(p, features, desc->feat_dtype));
     call_begin(c, p, ws, features, desc->feat_dtype, head_params, false, nullptr, nullptr);
     float* z = logits_lowres ? logits_lowres : (float*)(ws + p.z);
@@ -399,6 +428,32 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
         loss_pass(c, p.g, z_source(p, ws, z), nullptr, nullptr, nullptr, pred, nullptr, nullptr, nullptr, nullptr, nullptr,
                   false, false);
     return c.status;
+}
+
+int st_head_forward(const st_head_desc* desc, const void* features, const float* head_params,
+                    float* logits_lowres, uint8_t* pred, void* workspace, void* stream)
+{
+    const int v = validate(desc);
+    if (v != ST_OK) return v;
+    if (!features || !head_params) return ST_ERR_NULL;
+    if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
+    const Plan p = make_plan(*desc);
+    return head_forward_launches(desc, p, features, head_params, logits_lowres, pred, (char*)workspace, stream, false);
+}
+
+int st_head_forward_noalloc(const st_head_desc* desc, const void* features, const float* head_params,
+                            float* logits_lowres, uint8_t* pred, void* stream)
+{
+    const int v = validate(desc);
+    if (v != ST_OK) return v;
+    if (!features || !head_params) return ST_ERR_NULL;
+    const Plan p = make_plan(*desc);
+    if (p.total > NOALLOC_SCRATCH_BYTES) return ST_ERR_TOO_LARGE;
+    char* ws = nullptr;
+    const int sr = scratch_of_current_device(&ws);
+    if (sr != ST_OK) return sr;
+    // (no event profile here: handing out event pairs may create events)
+    return head_forward_launches(desc, p, features, head_params, logits_lowres, pred, ws, stream, true);
 }
 
 int st_partial_distill(const st_head_desc* desc, const void* features, const int32_t* teacher_labels,
@@ -682,6 +737,7 @@ const char* st_strerror(int status)
     case ST_ERR_WORKSPACE: return "workspace missing or not 256-byte aligned";
     case ST_ERR_HIP: return "a HIP runtime call failed";
     case ST_ERR_NO_DEVICE: return "no usable GPU";
+    case ST_ERR_TOO_LARGE: return "shape needs more scratch than the no-allocation entry point has built in";
     default: return "unknown status";
     }
 }

@@ -139,6 +139,7 @@ Plan make_plan(const st_head_desc& d);
 struct Ctx {
     hipStream_t stream;
     int status;   // first failure sticks
+    bool no_profile = false;   // launches of this call never carry profile events
 };
 
 // When the event profile is on and covers `name`, hands out a start/stop event pair that the

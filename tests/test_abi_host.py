@@ -106,7 +106,13 @@ def test_null_and_argument_errors():
     assert L.st_miou(None, None, 0, 3, -1, None, dummy, None) == st.ST_ERR_NULL
     assert L.st_miou(dummy, dummy, 10, 0, -1, dummy, dummy, None) == st.ST_ERR_SHAPE
     assert L.st_get_workspace_layout(C.byref(cd), None) == st.ST_ERR_NULL
-    for s in (0, -1, -2, -3, -4, -5, -6, -99):
+    # the forward entry point on the built-in scratch validates in the same order, then the size
+    na = L.st_head_forward_noalloc
+    assert na(None, dummy, dummy, None, None, None) == st.ST_ERR_NULL
+    assert na(C.byref(cd), None, dummy, None, None, None) == st.ST_ERR_NULL
+    big = st.HeadDesc(1, 256, 135, 240, 128, 128, 19).c()
+    assert na(C.byref(big), dummy, dummy, None, None, None) == st.ST_ERR_TOO_LARGE
+    for s in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert L.st_strerror(s)
 
 
