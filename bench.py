@@ -5,12 +5,21 @@ One bench "step" is one st_partial_distill call on the 1280x720 key-frame worklo
 packing, 8 optimiser steps (9 forwards, 8 partial backwards, 8 updates) and 9 loss/metric
 passes, with all inputs already resident in HBM.  `value` is optimiser steps per second.
 
+Protocol: W warm-up calls; then K = --steps calls between device synchronisations (host clock,
+`wall`), every call between a pair of HIP events on the calling stream, continued until at least
+--min-timed (30) calls are timed.  `ms_per_step` is the median per-call time between the events
+(`ms_per_call` gives min / p90 / max), `value` = optimiser steps per call over it.  The head's
+re-initialisation (one device copy) is inside every timed call.
+
 Prints ONE JSON line.  Extra objects:
   roofline      the kernel that takes the largest share of the call (kernels within 3 % of it count
                 as tied and the tie goes to the matrix-core kernel), its algorithmic work per
                 launch over its average launch duration (HIP events on the launch stream, taken
                 during the timed region), against the chip's published peak; the other kernels
                 of a step follow in `other_kernels`
+  configs       the 1920x1080 key frame and the batch of four frames, same protocol
+  clip, clip_learnable   the temporal-clip schedule: frames per second, key-frame count, time of a
+                key frame and of a frame that is none
   cpu_baseline  the CPU oracle (test infrastructure, untuned) on the host cores of the machine
 """
 from __future__ import annotations
@@ -29,20 +38,18 @@ PEAK_TFLOPS_F32 = 157.3     # MI355X fp32 vector / matrix
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (the passes and their
-# copy-kernel scale factors are recorded under profiles/).  A figure holds only for the kernel
-# source it was measured on: (source file, sha256 of that file at measurement, fetched MiB, written MiB)
+# copy-kernel scale factors are recorded under profiles/).  A figure holds only for the workload and
+# the kernel source it was measured on:
+# (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    "conv12_wgrad_mfma": ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.54, 8.83),
-    "conv1_fwd_mfma": ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 13.75, 7.55),
-    "upsample_ce_grad": ("k_loss.hip", "297276f9dbef51ee2ee5af0d6dc307fbaf35fb2a9b0a91f9b1861d2b83f321d8", 15.80, 4.72),
 }
 
 
-def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel`, or None when there is no measurement for the kernel
-    source as it stands."""
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload`, or None when there is no measurement for
+    the kernel source as it stands."""
     import hashlib
-    entry = MEASURED_TRAFFIC.get(kernel)
+    entry = MEASURED_TRAFFIC.get((workload, kernel))
     if entry is None:
         return None
     src, digest, fetch_mib, write_mib = entry
@@ -114,6 +121,162 @@ def step_bytes(wl):
     return fwd + loss + bwd + upd
 
 
+def upload(feats):
+    import numpy as np
+    import torch
+    if feats.dtype == np.uint16:
+        return torch.from_numpy(feats.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(feats).cuda()
+
+
+class Problem:
+    """One workload's inputs, head and result buffers resident on the GPU, and the call on them."""
+
+    def __init__(self, st, WL, wl, stream, optimizer="sgd", weighted=False, full_backward=False):
+        import numpy as np
+        import torch
+        self.st, self.wl, self.stream = st, wl, stream
+        self.desc = st.HeadDesc.of(wl)
+        self.feats, self.labels, self.params0 = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+        self.f, self.lab = upload(self.feats), torch.from_numpy(self.labels).cuda()
+        self.p0 = torch.from_numpy(self.params0).cuda()
+        self.p = self.p0.clone()
+        self.vel = torch.zeros_like(self.p) if wl.momentum else None
+        self.losses = torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")
+        self.mious = torch.zeros((wl.steps + 1, wl.n), dtype=torch.float64, device="cuda")
+        self.conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
+        self.ws = st.new_workspace(self.desc)
+        self.pw = torch.from_numpy(WL.object_weight_map(self.labels, radius=4)).cuda() if weighted else None
+        self.dfeat = torch.empty((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda") if full_backward else None
+        self.adam = dict(m=torch.zeros_like(self.p), v=torch.zeros_like(self.p), t0=0) if optimizer == "adam" else None
+        torch.cuda.synchronize()
+
+    def call(self, graph=False):
+        """One key frame: the head is re-initialised, then one st_partial_distill call."""
+        wl, st = self.wl, self.st
+        self.p.copy_(self.p0)
+        if self.vel is not None:
+            self.vel.zero_()
+        if self.adam is not None:
+            self.adam["m"].zero_()
+            self.adam["v"].zero_()
+            st.st_partial_distill(self.desc, self.f, self.lab, self.p, wl.steps, wl.lr, adam=self.adam, losses=self.losses,
+                                  mious=self.mious, confusion=self.conf, workspace=self.ws, stream=self.stream,
+                                  pixel_weights=self.pw, feature_grad=self.dfeat, graph=graph)
+            return
+        st.st_partial_distill(self.desc, self.f, self.lab, self.p, wl.steps, wl.lr, momentum=wl.momentum, velocity=self.vel,
+                              losses=self.losses, mious=self.mious, confusion=self.conf, workspace=self.ws,
+                              stream=self.stream, pixel_weights=self.pw, feature_grad=self.dfeat, graph=graph)
+
+
+def timed_calls(fn, n_wall, n_total):
+    """Runs fn() n_total times back to back on torch's current stream with a HIP event before and
+    after every call.  The first n_wall calls are also bracketed by a device synchronisation on
+    both sides and timed with the host clock.  Returns (wall seconds of the first n_wall calls,
+    list of n_total per-call milliseconds between the events)."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_total + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(n_wall):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if n_total > n_wall:
+        ev[n_wall].record()
+        for i in range(n_wall, n_total):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+    return wall, [ev[i].elapsed_time(ev[i + 1]) for i in range(n_total)]
+
+
+def spread(ms):
+    import numpy as np
+    a = np.sort(np.asarray(ms, dtype=np.float64))
+    return {"median": round(float(np.median(a)), 4), "min": round(float(a[0]), 4),
+            "p90": round(float(a[min(len(a) - 1, int(np.ceil(0.9 * len(a))) - 1)]), 4), "max": round(float(a[-1]), 4),
+            "n_timed": int(len(a))}
+
+
+def roofline_of(wl, work, name, launches, total_ms):
+    pre = max((k for k in work if name.startswith(k)), key=len)
+    bound, amount = work[pre]
+    avg_s = total_ms / launches * 1e-3
+    if bound == "mfma":
+        peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
+        achieved, unit = amount / avg_s / 1e12, "TFLOP/s"
+    elif bound == "alu":
+        peak, achieved, unit = PEAK_TFLOPS_F32, amount / avg_s / 1e12, "TFLOP/s"
+    else:
+        peak, achieved, unit = PEAK_HBM_GBS, amount / avg_s / 1e9, "GB/s"
+    return {"bound": bound, "kernel": name, "achieved": round(achieved, 3), "peak": peak,
+            "unit": unit, "frac": round(achieved / peak, 5), "traffic": measured_traffic(name, wl.name),
+            "avg_launch_us": round(avg_s * 1e6, 2), "launches": launches,
+            "work_per_launch": amount}
+
+
+def all_kernel_pass(st, prob, calls):
+    """`calls` untimed calls launched kernel by kernel with an event pair attached to every
+    dispatch: name -> (launches, total ms)."""
+    import torch
+    st.st_profile_reset()
+    st.st_profile_filter(None)
+    st.st_profile_enable(True)
+    for _ in range(calls):
+        prob.call()
+    torch.cuda.synchronize()
+    prof = st.st_profile_read()
+    st.st_profile_enable(False)
+    st.st_profile_reset()
+    return prof
+
+
+def pick_dominant(work, known):
+    """The kernel with the largest share of the call; kernels within 3 % of it count as tied and a
+    tie goes to the matrix-core kernel, so that the choice does not flip from run to run."""
+    top = max(v[1] for v in known.values())
+    tied = [k for k, v in known.items() if v[1] >= 0.97 * top]
+    return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", known[k][1]))
+
+
+def config_leg(st, WL, name, stream, n_timed, use_graph):
+    """Another measured configuration beside the headline: per-call time (median of n_timed calls
+    between HIP events, cached launch graph), convolution TFLOP/s of the whole call against the
+    MFMA peak, and the kernel with the largest share of the call against its own roof."""
+    import torch
+    wl = WL.WORKLOADS[name]
+    prob = Problem(st, WL, wl, stream)
+    prob.call()
+    if use_graph:
+        prob.call(graph=True)
+    torch.cuda.synchronize()
+    work = kernel_work(wl)
+    prof = all_kernel_pass(st, prob, 2)
+    known = {k: v for k, v in prof.items() if any(k.startswith(pre) for pre in work)}
+    dominant = pick_dominant(work, known)
+    _, ms = timed_calls(lambda: prob.call(graph=use_graph), 0, n_timed)
+    sp = spread(ms)
+    t_call = sp["median"] * 1e-3
+    peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
+    tflops = call_flops(wl) / t_call / 1e12
+    gbs = step_bytes(wl) * wl.steps / t_call / 1e9
+    out = {"workload": f"{wl.name}: features [{wl.n},{wl.c_in},{wl.h},{wl.w}] {wl.feat_dtype}, head "
+                       f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, {wl.steps} SGD steps, "
+                       f"momentum {wl.momentum}, lr {wl.lr}",
+           "value": round(wl.steps / t_call, 2), "unit": "steps/s", "ms_per_call": sp, "us_per_optimiser_step":
+           round(t_call / wl.steps * 1e6, 2), "conv_tflops": round(tflops, 2), "mfma_frac": round(tflops / peak, 5),
+           "algorithmic_GBs": round(gbs, 1), "hbm_frac": round(gbs / PEAK_HBM_GBS, 5),
+           "dominant_kernel": roofline_of(wl, work, dominant, *known[dominant]),
+           "kernel_us": {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])},
+           "loss_first_last": [float(prob.losses[0]), float(prob.losses[-1])]}
+    del prob
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +284,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="720p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--min-timed", type=int, default=30,
+                    help="per-call statistics (median, min, p90) are taken over at least this many timed calls, "
+                         "whatever --steps says")
     ap.add_argument("--full-backward", action="store_true",
                     help="also compute d loss / d features in every backward pass (the data-gradient of "
                          "layer 1 that partial distillation leaves out): the step an unfrozen front part would "
@@ -142,8 +308,12 @@ def main():
     ap.add_argument("--clip-frames", type=int, default=32,
                     help="also run the temporal-clip schedule on this many 720p frames (every frame: head "
                          "forward + mean IoU; a frame below the threshold is a key frame and is trained "
-                         "with the early-exit form of Algorithm 1); reported beside the headline as `clip`; "
-                         "0 = skip")
+                         "with the early-exit form of Algorithm 1), once on the configuration's noise features "
+                         "(`clip`: every frame is a key frame) and once on features that carry the labels "
+                         "(`clip_learnable`: most frames are not key frames, as in the paper's videos); 0 = skip")
+    ap.add_argument("--other-configs", default="1080p,batch4",
+                    help="comma-separated workloads measured beside the headline (`configs` in the line); "
+                         "empty = skip")
     ap.add_argument("--no-graph", action="store_true",
                     help="time the calls launched kernel by kernel in the stream; default: `value` is timed "
                          "with the library's cached HIP graph (st_distill_opts.use_graph), and the "
@@ -169,50 +339,20 @@ def main():
     st.lib()   # fails loudly when the HIP library has not been built
     torch.cuda.set_device(0)
     wl = WL.WORKLOADS[args.workload]
-    desc = st.HeadDesc.of(wl)
-
-    feats = WL.make_features(wl)
-    labels = WL.make_labels(wl)
-    params0 = WL.make_head_params(wl)
-    f = torch.from_numpy(feats.view(np.int16)).cuda().view(torch.bfloat16) if feats.dtype == np.uint16 \
-        else torch.from_numpy(feats).cuda()
-    lab = torch.from_numpy(labels).cuda()
-    p0 = torch.from_numpy(params0).cuda()
-    p = p0.clone()
-    vel = torch.zeros_like(p) if wl.momentum else None
-    losses = torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")
-    mious = torch.zeros((wl.steps + 1, wl.n), dtype=torch.float64, device="cuda")
-    conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
-    ws = st.new_workspace(desc)
     # a stream of the caller's own (the library records its launch graph on it; the NULL stream
     # cannot be captured), made torch's current stream so that every copy and event below is on it
     stream = torch.cuda.Stream()
-    torch.cuda.synchronize()             # the uploads above ran on the default stream
+    torch.cuda.synchronize()
     torch.cuda.set_stream(stream)
-
     use_adam = args.optimizer == "adam"
-    pw = torch.from_numpy(WL.object_weight_map(labels, radius=4)).cuda() if args.weighted_loss else None
-    dfeat = torch.empty((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda") if args.full_backward else None
-    adam = dict(m=torch.zeros_like(p), v=torch.zeros_like(p), t0=0) if use_adam else None
-
-    def one_call(graph=False):
-        p.copy_(p0)                      # the head is re-initialised for every key frame
-        if vel is not None:
-            vel.zero_()
-        if use_adam:
-            adam["m"].zero_()
-            adam["v"].zero_()
-            st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, adam=adam, losses=losses, mious=mious,
-                                  confusion=conf, workspace=ws, stream=stream, pixel_weights=pw, feature_grad=dfeat,
-                                  graph=graph)
-            return
-        st.st_partial_distill(desc, f, lab, p, wl.steps, wl.lr, momentum=wl.momentum, velocity=vel,
-                              losses=losses, mious=mious, confusion=conf, workspace=ws, stream=stream,
-                              pixel_weights=pw, feature_grad=dfeat, graph=graph)
+    variant = use_adam or args.weighted_loss or args.full_backward
+    prob = Problem(st, WL, wl, stream, args.optimizer, args.weighted_loss, args.full_backward)
+    desc, f, lab, p, ws = prob.desc, prob.f, prob.lab, prob.p, prob.ws
+    one_call = prob.call
 
     use_graph = not args.no_graph
     graph_note = None
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):
         one_call()
         if use_graph:
             try:
@@ -231,81 +371,52 @@ def main():
         del src, dst
 
     # which kernel dominates: three untimed calls with an event pair around every launch
-    st.st_profile_reset()
-    st.st_profile_filter(None)
-    st.st_profile_enable(True)
-    for _ in range(3):
-        one_call()
-    torch.cuda.synchronize()
-    prof = st.st_profile_read()
-    st.st_profile_enable(False)
-    st.st_profile_reset()
+    prof = all_kernel_pass(st, prob, 3)
     work = kernel_work(wl)
     known = {k: v for k, v in prof.items() if any(k.startswith(pre) for pre in work)}
-    # (the weight-gradient launch and the loss kernel take nearly the same time at 720p; kernels
-    #  within 3 % of the largest share count as tied, and a tie goes to the matrix-core kernel, so
-    #  that the object does not flip between two kernels from run to run)
-    top = max(v[1] for v in known.values())
-    tied = [k for k, v in known.items() if v[1] >= 0.97 * top]
-    dominant = max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", known[k][1]))
+    dominant = pick_dominant(work, known)
     breakdown = {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
 
     # timed region, kernel-by-kernel launches; only the dominant kernel carries an event pair
     st.st_profile_filter(dominant)
     st.st_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_call()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    wall_plain, ms_plain = timed_calls(one_call, args.steps, args.steps)
     dom = st.st_profile_read()[dominant]
     st.st_profile_enable(False)
     st.st_profile_reset()
     st.st_profile_filter(None)
-    elapsed = t1 - t0
-    stream_launch = {"value": round(args.steps * wl.steps / elapsed, 2), "unit": "steps/s",
-                     "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+    sp_plain = spread(ms_plain)
+    stream_launch = {"value": round(wl.steps / (sp_plain["median"] * 1e-3), 2), "unit": "steps/s",
+                     "ms_per_step": sp_plain["median"], "ms_per_call": sp_plain,
                      "note": "the same K calls launched kernel by kernel in the stream; the roofline object's "
                              "event pairs were taken in this pass"}
+    # The headline: K calls (through the library's cached launch graph unless --no-graph) bracketed by
+    # a device synchronisation on both sides for the host clock, every call between a pair of HIP
+    # events on the calling stream; more calls follow until there are at least --min-timed of them.
+    # `value` comes from the median per-call time between the events; the host-clock figure of
+    # the K-call region stands beside it.  The head's re-initialisation (one 1.8 MB device copy) is
+    # inside every timed call.
+    n_total = max(args.steps, args.min_timed)
     if use_graph:
-        # timed region of the headline: the same K calls through the library's cached launch graph
-        # (no event can ride on a launch inside a graph, hence the separate pass above)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            one_call(graph=True)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        elapsed = t1 - t0
-    ms_per_call = elapsed / args.steps * 1e3
-    steps_per_s = args.steps * wl.steps / elapsed
-    final_losses = losses.cpu().numpy()
+        wall, ms_calls = timed_calls(lambda: one_call(graph=True), args.steps, n_total)
+    elif n_total > args.steps:
+        wall, ms_calls = timed_calls(one_call, args.steps, n_total)
+    else:
+        wall, ms_calls = wall_plain, ms_plain
+    sp = spread(ms_calls)
+    t_call = sp["median"] * 1e-3
+    ms_per_call = sp["median"]
+    steps_per_s = wl.steps / t_call
+    final_losses = prob.losses.cpu().numpy()
 
-    def roofline_of(name, launches, total_ms):
-        pre = max((k for k in work if name.startswith(k)), key=len)
-        bound, amount = work[pre]
-        avg_s = total_ms / launches * 1e-3
-        if bound == "mfma":
-            peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
-            achieved, unit = amount / avg_s / 1e12, "TFLOP/s"
-        elif bound == "alu":
-            peak, achieved, unit = PEAK_TFLOPS_F32, amount / avg_s / 1e12, "TFLOP/s"
-        else:
-            peak, achieved, unit = PEAK_HBM_GBS, amount / avg_s / 1e9, "GB/s"
-        return {"bound": bound, "kernel": name, "achieved": round(achieved, 3), "peak": peak,
-                "unit": unit, "frac": round(achieved / peak, 5), "traffic": measured_traffic(name),
-                "avg_launch_us": round(avg_s * 1e6, 2), "launches": launches,
-                "work_per_launch": amount}
-
-    roofline = roofline_of(dominant, dom[0], dom[1])
+    roofline = roofline_of(wl, work, dominant, dom[0], dom[1])
     # the other kernels of a step, from the all-kernel pass (every launch carried an event pair)
-    others = {k: {kk: vv for kk, vv in roofline_of(k, v[0], v[1]).items()
-                  if kk in ("bound", "achieved", "unit", "frac", "avg_launch_us")}
+    others = {k: {kk: vv for kk, vv in roofline_of(wl, work, k, v[0], v[1]).items()
+                  if kk in ("bound", "achieved", "unit", "frac", "avg_launch_us", "traffic")}
               for k, v in known.items() if k != dominant}
     # the fused up-sampling + cross-entropy kernel against the other roof as well: as a streaming
     # kernel it would move 4 C bytes of logits in and 4 C bytes of gradient out per low-resolution
-    # cell and 4 bytes of label per frame pixel (it is the vector ALUs that bind it, not these bytes)
+    # cell and 4 bytes of label per frame pixel
     for k in others:
         if k.startswith("upsample_ce"):
             cells, pixels = wl.n * wl.h * wl.w, wl.n * wl.H * wl.W
@@ -315,8 +426,8 @@ def main():
             others[k]["hbm_frac"] = round(gbs / PEAK_HBM_GBS, 5)
             others[k]["binding_roof"] = "alu" if others[k]["frac"] >= others[k]["hbm_frac"] else "hbm"
 
-    # the stand-alone metric call (st_miou: confusion histogram + mean IoU of a class map), the
-    # per-frame pass of a clip; streaming bound: 1 B prediction + 4 B label per pixel
+    # the stand-alone metric call (st_miou: confusion histogram + mean IoU of a class map);
+    # streaming bound: 1 B prediction + 4 B label per pixel
     pred = torch.zeros((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
     st.st_head_forward(desc, f, p, pred=pred, workspace=ws, stream=stream)
     conf1 = torch.empty((wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
@@ -349,21 +460,24 @@ def main():
                  "frac": round(miou_bytes / hist_us / 1e3 / PEAK_HBM_GBS, 5),
                  "us_per_call": round(miou_us, 2),
                  "launch_us": {k: round(v, 2) for k, v in mprof.items()},
-                 "note": "st_miou = clear + histogram + mean-IoU launches; us_per_call is the whole call "
-                         "issued back to back from Python, avg_launch_us the histogram kernel between its "
-                         "own events; 5 B per pixel"}
+                 "note": "st_miou; us_per_call is the whole call issued back to back from Python, avg_launch_us "
+                         "the histogram kernel between its own events; 5 B per pixel"}
+    # the forward alone (what a frame that is no key frame costs a client): st_head_forward
+    for _ in range(3):
+        st.st_head_forward(desc, f, p, pred=pred, workspace=ws, stream=stream)
+    _, ms_fwd = timed_calls(lambda: st.st_head_forward(desc, f, p, pred=pred, workspace=ws, stream=stream), 0, 30)
+    head_forward = {"ms_per_call": spread(ms_fwd), "frames_per_s": round(1e3 / spread(ms_fwd)["median"], 1),
+                    "note": "st_head_forward (features -> class map), inputs resident in HBM"}
 
     # several clients in one call (one head and one key frame each; the server of Algorithm 3):
     # the same launches carry `clients` times the work, which fills the chip better
     grouped = None
-    if args.clients > 0 and wl.n == 1 and not (use_adam or args.weighted_loss or args.full_backward):
+    if args.clients > 0 and wl.n == 1 and not variant:
         G = args.clients
         wg = WL.small_variant(wl, n=G)
         dg = st.HeadDesc.of(wg)
         dg.grouped = 1
-        fg_np = WL.make_features(wg)
-        fg = torch.from_numpy(fg_np.view(np.int16)).cuda().view(torch.bfloat16) if fg_np.dtype == np.uint16 \
-            else torch.from_numpy(fg_np).cuda()
+        fg = upload(WL.make_features(wg))
         lg = torch.from_numpy(WL.make_labels(wg)).cuda()
         pg0 = torch.from_numpy(np.stack([WL.make_head_params(wg, seed=wg.init_seed + 17 * i) for i in range(G)])).cuda()
         pg = pg0.clone()
@@ -377,31 +491,25 @@ def main():
 
         for _ in range(3):
             grouped_call()
-        torch.cuda.synchronize()
-        reps = max(3, args.steps // 4)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            grouped_call()
-        torch.cuda.synchronize()
-        tg = (time.perf_counter() - t0) / reps
+        reps = max(5, args.steps // 4)
+        _, ms_g = timed_calls(grouped_call, 0, reps)
+        tg = spread(ms_g)["median"] * 1e-3
         grouped = {"clients": G, "head_steps_per_s": round(G * wl.steps / tg, 1),
-                   "us_per_step": round(tg / wl.steps * 1e6, 2), "calls": reps,
+                   "us_per_step": round(tg / wl.steps * 1e6, 2), "ms_per_call": spread(ms_g),
                    "note": "one st_partial_distill call trains `clients` heads on `clients` key frames "
                            "(desc.grouped = 1); head_steps_per_s counts one optimiser step of one head"}
         del fg, lg, pg, pg0, wsg
 
     # independent clients on streams of their own: no special mode, just concurrent calls
     streams_leg = None
-    if args.streams > 1 and wl.n == 1 and not (use_adam or args.weighted_loss or args.full_backward):
+    if args.streams > 1 and wl.n == 1 and not variant:
         try:
             clients = []
             for i in range(args.streams):
                 wi = WL.small_variant(wl, feat_seed=wl.feat_seed + 101 * (i + 1), label_seed=wl.label_seed + 101 * (i + 1))
-                fi_np = WL.make_features(wi)
-                fi = torch.from_numpy(fi_np.view(np.int16)).cuda().view(torch.bfloat16) if fi_np.dtype == np.uint16 \
-                    else torch.from_numpy(fi_np).cuda()
                 pi0 = torch.from_numpy(WL.make_head_params(wi, seed=wi.init_seed + 17 * i)).cuda()
-                clients.append(dict(f=fi, lab=torch.from_numpy(WL.make_labels(wi)).cuda(), p0=pi0, p=pi0.clone(),
+                clients.append(dict(f=upload(WL.make_features(wi)), lab=torch.from_numpy(WL.make_labels(wi)).cuda(),
+                                    p0=pi0, p=pi0.clone(),
                                     ws=st.new_workspace(desc), s=torch.cuda.Stream(),
                                     vel=None if wl.momentum == 0.0 else torch.zeros_like(pi0),
                                     losses=torch.zeros(wl.steps + 1, dtype=torch.float32, device="cuda")))
@@ -432,55 +540,79 @@ def main():
         except Exception as e:      # the headline line must not depend on this leg
             streams_leg = {"error": f"{type(e).__name__}: {e}"}
 
-    # the temporal clip (Algorithms 3 and 4 around the training step): drifting features, labels
-    # that move two pixels per frame; frames/s and the number of key frames.  Every key-frame
-    # iteration reads its metric back to the host (Algorithm 1 branches on it), so this leg is
-    # bound by those round trips, not by the kernels.
-    clip = None
-    if args.clip_frames > 0 and wl.name == "720p" and not (use_adam or args.weighted_loss or args.full_backward):
-        try:
-            from paper_2003_10735_amd.clip import run_clip
-            wc = WL.WORKLOADS["clip"]
-            wc = WL.small_variant(wc, extra={**wc.extra, "frames": args.clip_frames})
-            dc = st.HeadDesc.of(wc)
-            frames_dev = []
-            for f_np, lab_np in WL.clip_frames(wc):
-                ft = torch.from_numpy(f_np.view(np.int16)).cuda().view(torch.bfloat16) if f_np.dtype == np.uint16 \
-                    else torch.from_numpy(f_np).cuda()
-                frames_dev.append((ft, torch.from_numpy(lab_np).cuda()))
-            thr = float(wc.extra["threshold"])
-            pc = torch.from_numpy(WL.make_head_params(wc)).cuda()
-            wsc = st.new_workspace(dc)
-            run_clip(dc, frames_dev[:2], pc.clone(), threshold=thr, max_updates=wc.steps, lr=wc.lr,
-                     momentum=wc.momentum, workspace=wsc, stream=stream)          # warm-up
-            r = run_clip(dc, frames_dev, pc, threshold=thr, max_updates=wc.steps, lr=wc.lr,
-                         momentum=wc.momentum, workspace=wsc, stream=stream)
-            clip = {"frames": len(frames_dev), "frames_per_s": round(r["frames_per_s"], 1),
-                    "key_frames": int(r["n_key_frames"]), "optimiser_steps": int(sum(r["updates"])),
-                    "threshold": thr, "max_updates": wc.steps,
-                    "first_last_score": [round(r["scores"][0], 4), round(r["scores"][-1], 4)],
-                    "note": "features are noise that drifts (they carry nothing about the labels), so the "
-                            "score stays under the threshold and every frame is a key frame with the full "
-                            "number of steps: the rate is that of one early-exit training call per frame "
-                            "(score first, train under the threshold), inputs resident in HBM"}
-            del frames_dev, wsc
-        except Exception as e:      # the headline line must not depend on this leg
-            clip = {"error": f"{type(e).__name__}: {e}"}
+    # The temporal clip (Algorithms 3 and 4 around the training step): labels that move two pixels per
+    # frame, features that drift.  One early-exit call per frame: it scores the head on the frame
+    # (forward + mean IoU) and trains only under the threshold.  Every key-frame iteration reads its
+    # metric back to the host (Algorithm 1 branches on it).  Twice: on the configuration's noise
+    # features every frame is a key frame; on features that carry the labels the trained head serves
+    # the following frames and most frames cost one forward pass, the regime of the paper's videos
+    # (Table 5: about one frame in twenty is a key frame).
+    clip = clip_learnable = None
+    if args.clip_frames > 0 and wl.name == "720p" and not variant:
+        from paper_2003_10735_amd.clip import run_clip
+        for learnable in (False, True):
+            try:
+                wc = WL.WORKLOADS["clip"]
+                wc = WL.small_variant(wc, extra={**wc.extra, "frames": args.clip_frames})
+                dc = st.HeadDesc.of(wc)
+                frames_dev = [(upload(f_np), torch.from_numpy(lab_np).cuda())
+                              for f_np, lab_np in WL.clip_frames(wc, learnable=learnable)]
+                thr = float(wc.extra["threshold"])
+                pc = torch.from_numpy(WL.make_head_params(wc)).cuda()
+                wsc = st.new_workspace(dc)
+                run_clip(dc, frames_dev[:2], pc.clone(), threshold=thr, max_updates=wc.steps, lr=wc.lr,
+                         momentum=wc.momentum, workspace=wsc, stream=stream)          # warm-up
+                r = run_clip(dc, frames_dev, pc, threshold=thr, max_updates=wc.steps, lr=wc.lr,
+                             momentum=wc.momentum, workspace=wsc, stream=stream)
+                key = np.array(r["key_frames"], dtype=bool)
+                fms = np.array(r["frame_ms"])
+                leg = {"frames": len(frames_dev), "frames_per_s": round(r["frames_per_s"], 1),
+                       "key_frames": int(r["n_key_frames"]), "non_key_fraction": round(float(1.0 - key.mean()), 4),
+                       "optimiser_steps": int(sum(r["updates"])),
+                       "ms_per_key_frame": round(float(np.median(fms[key])), 4) if key.any() else None,
+                       "ms_per_non_key_frame": round(float(np.median(fms[~key])), 4) if (~key).any() else None,
+                       "threshold": thr, "max_updates": wc.steps,
+                       "first_last_score": [round(r["scores"][0], 4), round(r["scores"][-1], 4)]}
+                if learnable:
+                    leg["note"] = ("features = noise + a per-class code of each cell's label (not the configuration's "
+                                   "inputs): the head trained on a key frame scores above the threshold on the frames "
+                                   "that follow, which then cost one forward pass + metric + one host read-back each")
+                    clip_learnable = leg
+                else:
+                    leg["note"] = ("the configuration's inputs: noise features say nothing about the labels, so every "
+                                   "frame is a key frame trained for all its steps; one early-exit call per frame")
+                    clip = leg
+                del frames_dev, wsc
+            except Exception as e:      # the headline line must not depend on this leg
+                if learnable:
+                    clip_learnable = {"error": f"{type(e).__name__}: {e}"}
+                else:
+                    clip = {"error": f"{type(e).__name__}: {e}"}
+
+    # the other measured configurations (their own workloads, same protocol, fewer calls)
+    configs = {}
+    if wl.name == "720p" and not variant:
+        for name in [n for n in args.other_configs.split(",") if n]:
+            try:
+                configs[name] = config_leg(st, WL, name, stream, 10 if name == "batch4" else 30, use_graph)
+            except Exception as e:
+                configs[name] = {"error": f"{type(e).__name__}: {e}"}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle as O
         d = O.desc_of(wl)
-        f64 = WL.features_as_f64(wl, feats)
+        f64 = WL.features_as_f64(wl, prob.feats)
         k = wl.steps if wl.name in ("tiny", "720p") else 1
         tc0 = time.perf_counter()
-        O.partial_distill(d, f64, labels, params0.astype(np.float64), k, wl.lr, momentum=wl.momentum)
+        O.partial_distill(d, f64, prob.labels, prob.params0.astype(np.float64), k, wl.lr, momentum=wl.momentum)
         tc1 = time.perf_counter()
         cpu_baseline = {"value": round(k / (tc1 - tc0), 4), "unit": "steps/s", "cores": O.num_threads(),
                         "kind": "oracle",
                         "sample": f"the same {wl.name} key frame, {k} optimiser step(s) "
                                   f"({k + 1} forwards), float64, {tc1 - tc0:.1f} s"}
 
+    peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
     out = {
         "metric": "key-frame partial-distill steps/sec at 1280x720 (fwd+bwd+update)",
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
@@ -491,26 +623,38 @@ def main():
                                f"{wl.c_in}->{wl.c1}->{wl.c2}->{wl.n_classes}, x8 to {wl.H}x{wl.W}, "
                                f"{wl.steps} {'Adam' if args.optimizer == 'adam' else 'SGD'} steps per key frame (one bench step = one key frame)",
                    "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss), "full_backward": bool(args.full_backward)},
-        "key_frames_per_s": round(args.steps / elapsed, 3),
-        "conv_tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
+        "step_definition": "one bench step = one st_partial_distill call = one key frame = "
+                           f"{wl.steps} optimiser steps ({wl.steps + 1} forwards, {wl.steps} partial backwards, {wl.steps} updates); "
+                           "ms_per_step is the median time of such a call between HIP events on the calling stream; "
+                           "`value` counts optimiser steps",
+        "ms_per_key_frame": round(ms_per_call, 4),
+        "ms_per_optimiser_step": round(ms_per_call / wl.steps, 5),
+        "ms_per_call": sp,
+        "wall": {"ms_per_step": round(wall / args.steps * 1e3, 4), "value": round(args.steps * wl.steps / wall, 2),
+                 "note": "host clock around the first K = `steps` calls, device synchronised on both sides"},
+        "key_frames_per_s": round(1.0 / t_call, 3),
+        "conv_tflops": round(call_flops(wl) / t_call / 1e12, 3),
         # the whole call against both roofs (a call of k steps has k + 1 forwards; its bytes are
         # counted as k steps' worth, a slight under-count)
-        "whole_call": {"tflops": round(call_flops(wl) * args.steps / elapsed / 1e12, 3),
-                       "mfma_frac": round(call_flops(wl) * args.steps / elapsed / 1e12 / (PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32), 5),
-                       "algorithmic_GBs": round(step_bytes(wl) * wl.steps * args.steps / elapsed / 1e9, 1),
-                       "hbm_frac": round(step_bytes(wl) * wl.steps * args.steps / elapsed / 1e9 / PEAK_HBM_GBS, 5),
+        "whole_call": {"tflops": round(call_flops(wl) / t_call / 1e12, 3),
+                       "mfma_frac": round(call_flops(wl) / t_call / 1e12 / peak, 5),
+                       "algorithmic_GBs": round(step_bytes(wl) * wl.steps / t_call / 1e9, 1),
+                       "hbm_frac": round(step_bytes(wl) * wl.steps / t_call / 1e9 / PEAK_HBM_GBS, 5),
                        "algorithmic_MB_per_step": round(step_bytes(wl) / 1e6, 2)},
         "loss_first_last": [float(final_losses[0]), float(final_losses[-1])],
         "kernel_us": breakdown,
         "roofline": roofline,
         "other_kernels": others,
         "miou_pass": miou_pass,
+        "head_forward": head_forward,
         "launch": "cached HIP graph (st_distill_opts.use_graph)" if use_graph
                   else (graph_note or "") + "kernel by kernel in the stream",
         "stream_launch": stream_launch,
         "grouped": grouped,
         "streams": streams_leg,
         "clip": clip,
+        "clip_learnable": clip_learnable,
+        "configs": configs,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))

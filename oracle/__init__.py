@@ -263,6 +263,33 @@ def partial_distill(d: Desc, features, labels, params, steps, lr, momentum=0.0, 
     return dict(params=params, velocity=vel, losses=losses, mious=mious, conf=conf, pred=pred)
 
 
+def partial_distill_stepwise(d: Desc, features, labels, params, steps, lr, momentum=0.0, velocity=None,
+                             on_step=None):
+    """The loop of partial_distill written out around loss_and_grad and sgd -- the very routines
+    the C loop calls, in its order -- so that a long run can report between steps
+    (on_step(it, loss) after every pass).  Same dict as partial_distill; a CPU test holds the two
+    bit for bit equal."""
+    features = _f64(features)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    params = _f64(params).copy()
+    vel = (_f64(velocity).copy() if velocity is not None else np.zeros_like(params))
+    losses = np.empty(steps + 1)
+    mious = np.empty((steps + 1, d.n))
+    conf = pred = None
+    for it in range(steps + 1):
+        last = it == steps
+        loss, grad, pred, conf, mi = loss_and_grad(d, features, labels, params, want_grad=not last)
+        losses[it], mious[it] = loss, mi
+        if on_step is not None:
+            on_step(it, loss)
+        if last:
+            break
+        params, v2 = sgd(params, grad, vel if momentum != 0.0 else None, lr, momentum)
+        if v2 is not None:
+            vel = v2
+    return dict(params=params, velocity=vel, losses=losses, mious=mious, conf=conf, pred=pred)
+
+
 def partial_distill_opt(d: Desc, features, labels, params, steps, optim: Optim, s1=None, s2=None):
     """k fixed steps with an explicit optimiser description; s1 / s2 are its state arrays
     (velocity, or Adam's m and v), zero when absent.  Returns the same dict as partial_distill

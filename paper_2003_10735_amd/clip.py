@@ -27,18 +27,21 @@ def run_clip(desc: HeadDesc, frames, head_params, *, threshold: float, max_updat
 
     ws = workspace if workspace is not None else new_workspace(desc, head_params.device)
     velocity = torch.zeros_like(head_params) if momentum != 0.0 else None
-    scores, key, updates, trained = [], [], [], []
+    scores, key, updates, trained, frame_ms = [], [], [], [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_frames = 0
     for features, labels in frames:
-        # One call per frame is Algorithm 1 as printed: it scores the head on the frame first and
-        # trains only if that score is under the threshold (the schedule is decided on the host,
-        # inside the call, on the metric it reads back).
+        # One call per frame is Algorithm 1 as printed: it scores the head on the frame first
+        # (forward + mean IoU) and trains only if that score is under the threshold (the schedule
+        # is decided on the host, inside the call, on the metric it reads back).  A frame that is
+        # no key frame costs that forward pass and nothing else; the call has finished on return.
+        tf = time.perf_counter()
         r = st_partial_distill(desc, features, labels, head_params, max_updates, lr,
                                momentum=momentum, velocity=velocity, threshold=threshold,
                                strict_break=strict_break, return_best=return_best,
                                workspace=ws, stream=stream)
+        frame_ms.append((time.perf_counter() - tf) * 1e3)
         taken, best = r
         score = r.first_metric
         scores.append(score)
@@ -49,7 +52,7 @@ def run_clip(desc: HeadDesc, frames, head_params, *, threshold: float, max_updat
         n_frames += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    return dict(scores=scores, key_frames=key, updates=updates, trained_scores=trained,
+    return dict(scores=scores, key_frames=key, updates=updates, trained_scores=trained, frame_ms=frame_ms,
                 frames_per_s=n_frames / dt if dt > 0 else float("nan"), n_key_frames=sum(key))
 
 

@@ -52,7 +52,7 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-constexpr int LOSS_THREADS = 512;
+constexpr int LOSS_THREADS = 2 * 8 * LOSS_TX;   // two threads per pixel column of the tile
 
 // (up to 24 padded classes the kernel is held to 128 registers, so that two blocks share a
 //  compute unit: the phases of one then fill the barriers and memory waits of the other)
@@ -132,7 +132,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
     // Two threads per pixel column: `half` 0 takes the upper four pixels of the 8 (they
     // interpolate between cell rows qy-1 and qy), half 1 the lower four (rows qy and qy+1).
     // The per-thread instruction stream is the critical path of this kernel, so it is kept short.
-    const int half = tid >> 8, t = tid & 255;
+    const int half = tid >= NT / 2 ? 1 : 0, t = tid - half * (NT / 2);
     const int j = t & 7, tq = t >> 3;
     const int X = (tile_x * LOSS_TX + tq) * 8 + j;
     const bool col_ok = X < g.W;

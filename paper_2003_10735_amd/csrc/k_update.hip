@@ -521,7 +521,7 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
     if (labels) {
         q.labels = labels; q.wmap = wmap; q.T = (float*)(ws + p.tadj);
         q.n_valid = (unsigned long long*)(ws + p.counters);
-        q.nb_label = g.n * g.h * cdiv(g.w, LOSS_TX);
+        q.nb_label = g.n * g.h * cdiv(g.w, LABEL_TX);
     }
     UpdateArgs a;
     const FinishArgs f = finish_args(p, ws, nullptr, nullptr, nullptr);

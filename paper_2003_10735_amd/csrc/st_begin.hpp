@@ -140,7 +140,8 @@ __device__ __forceinline__ float tap_weight(int X, int cell, int len)
 // multiples of 1/256 and the sums stay below 2^8 -- below 2^16 with 8-bit pixel weights -- so the
 // result is exact in float32 and does not depend on the order of additions.
 // colsum: CP x (LABEL_NCOL + 1) floats of LDS, CP >= number of classes; cnt_part: 4 words.
-constexpr int LABEL_NCOL = LOSS_TX * 8 + 8;
+constexpr int LABEL_TX = 32;                 // 8-pixel column groups per block of this role
+constexpr int LABEL_NCOL = LABEL_TX * 8 + 8;
 __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ labels,
                                                     const uint8_t* __restrict__ wmap, float* __restrict__ T,
                                                     unsigned long long* __restrict__ n_valid, const Geo& g,
@@ -148,14 +149,14 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
 {
     constexpr int NCOL = LABEL_NCOL, PITCH = LABEL_NCOL + 1;
     const int tid = threadIdx.x;
-    const int tiles_x = (g.w + LOSS_TX - 1) / LOSS_TX;
+    const int tiles_x = (g.w + LABEL_TX - 1) / LABEL_TX;
     const int tx = block % tiles_x, cy = (block / tiles_x) % g.h, img = block / (tiles_x * g.h);
     const int hw = g.h * g.w;
     const int32_t* lab = labels + (size_t)img * g.H * g.W;
     const uint8_t* wm = wmap ? wmap + (size_t)img * g.H * g.W : nullptr;
     for (int i = tid; i < CP * PITCH; i += 256) colsum[i] = 0.f;
     __syncthreads();
-    const int X0 = tx * LOSS_TX * 8 - 4;                   // frame column of table column 0
+    const int X0 = tx * LABEL_TX * 8 - 4;                  // frame column of table column 0
     const int Yt = 8 * cy - 4;                             // frame row of tent position 0
     unsigned int cnt = 0;     // valid labels (their weights) of this block's own 8 x 256 pixels
     // A thread takes table column tid and, the first NCOL - 256 threads, column tid + 256 as
@@ -214,9 +215,9 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
     __syncthreads();
     if (n_valid && tid == 0)
         atomicAdd(n_valid + g.head_of(img), (unsigned long long)(cnt_part[0] + cnt_part[1] + cnt_part[2] + cnt_part[3]));
-    for (int i = tid; i < g.C * LOSS_TX; i += 256) {
-        const int lc = i % LOSS_TX, c = i / LOSS_TX;
-        const int cx = tx * LOSS_TX + lc;
+    for (int i = tid; i < g.C * LABEL_TX; i += 256) {
+        const int lc = i % LABEL_TX, c = i / LABEL_TX;
+        const int cx = tx * LABEL_TX + lc;
         if (cx >= g.w) continue;
         float acc = 0.f;
 #pragma unroll

@@ -73,7 +73,10 @@ inline ParamOffsets param_offsets(const Geo& g)
 // The fused up-sample + cross-entropy kernel works on tiles of LOSS_TY x LOSS_TX groups of 8x8
 // frame pixels (one thread per pixel column).  A tile touches (LOSS_TY + 2) x (LOSS_TX + 2)
 // low-resolution cells and leaves its share of d loss / d z for them in a slot of its own.
-constexpr int LOSS_TX = 32;             // 8-pixel column groups per tile (256 threads)
+#ifndef ST_LOSS_TX
+#define ST_LOSS_TX 32
+#endif
+constexpr int LOSS_TX = ST_LOSS_TX;     // 8-pixel column groups per tile (two threads per pixel column)
 #ifndef ST_LOSS_TY
 #define ST_LOSS_TY 1
 #endif

@@ -2,12 +2,58 @@
 and through the CPU oracle on identical seeded inputs."""
 from __future__ import annotations
 
+import os
+import time
+
 import numpy as np
 import torch
 
 import oracle as O
 import paper_2003_10735_amd as st
 import workloads as WL
+
+
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def progress(msg):
+    """One line per finished piece of a long test (a frame, a step): printed, and appended to
+    gpurun_out/test_progress.log so that a run whose output is captured still shows that it moves."""
+    line = time.strftime("%H:%M:%S ") + str(msg)
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.join(_ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(_ROOT, "gpurun_out", "test_progress.log"), "a") as fh:
+            fh.write(line + "\n")
+    except OSError:
+        pass
+
+
+def golden_source_digest():
+    """SHA-256 over the oracle's sources and the input generators: what a stored oracle result
+    depends on (the same recipe as tests/golden/make_full_length_expectations.py)."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("oracle/st_oracle.c", "oracle/__init__.py", "workloads/__init__.py"):
+        with open(os.path.join(_ROOT, rel), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def load_golden(name):
+    """The oracle's stored full-length result `name` (written by the committed script
+    tests/golden/make_full_length_expectations.py, which calls only the oracle).  Refuses a file
+    made from other oracle sources or input generators than the tree holds."""
+    g = np.load(os.path.join(_ROOT, "tests", "golden", f"full_length_{name}.npz"))
+    assert str(g["digest"]) == golden_source_digest(), \
+        "tests/golden/full_length_%s.npz is stale: run tests/golden/make_full_length_expectations.py" % name
+    return g
+
+
+def live_oracle():
+    """ST_LIVE_ORACLE=1: the full-length tests run the oracle themselves (minutes of CPU time)
+    instead of reading its stored results."""
+    return os.environ.get("ST_LIVE_ORACLE", "0") not in ("", "0")
 
 
 def to_dev_features(wl, feats):
@@ -48,9 +94,14 @@ def run_gpu(wl, feats, labels, params, steps=None, velocity=None, threshold=0.0,
                 workspace=ws, layout=lay)
 
 
-def run_oracle(wl, feats, labels, params, steps=None, bf16_operands=None, velocity=None):
+def run_oracle(wl, feats, labels, params, steps=None, bf16_operands=None, velocity=None, report=None):
+    """`report`: a tag; the run then goes step by step and leaves a progress line per pass."""
     d = O.desc_of(wl, bf16_operands)
     steps = wl.steps if steps is None else steps
+    if report:
+        return O.partial_distill_stepwise(d, WL.features_as_f64(wl, feats), labels, params.astype(np.float64), steps,
+                                          wl.lr, momentum=wl.momentum, velocity=velocity,
+                                          on_step=lambda it, loss: progress(f"{report}: oracle pass {it} loss {loss:.6f}"))
     return O.partial_distill(d, WL.features_as_f64(wl, feats), labels, params.astype(np.float64), steps,
                              wl.lr, momentum=wl.momentum, velocity=velocity)
 

@@ -6,7 +6,7 @@ import pytest
 
 import oracle as O
 import workloads as WL
-from gpu_util import to_dev_features
+from gpu_util import live_oracle, load_golden, progress, to_dev_features
 
 pytestmark = pytest.mark.gpu
 
@@ -27,6 +27,8 @@ def oracle_clip(wl, frames, params, threshold, bf16_operands=None):
             key.append(True); updates.append(r["updates"])
         else:
             key.append(False); updates.append(0)
+        if wl.h * wl.w > 4096:
+            progress(f"oracle clip frame {len(scores) - 1}: score {m:.4f} updates {updates[-1]}")
     return dict(scores=scores, key_frames=key, updates=updates, params=params)
 
 
@@ -74,15 +76,111 @@ def test_clip_schedule_small_f32():
 
 
 def test_clip_720p_three_frames_bf16():
+    """Three 720p frames whose features carry the labels: the first is a key frame (an untrained
+    head), the trained head then serves the next ones; every decision must be the oracle's."""
     wl = WL.small_variant(WL.WORKLOADS["clip"], extra={"frames": 3, "drift": 0.05, "shift_px": 2, "threshold": 0.75})
     thr = wl.extra["threshold"]
     frames = list(WL.clip_frames(wl, learnable=True))
     p = WL.make_head_params(wl)
     o = oracle_clip(wl, frames, p, thr, bf16_operands=True)
     g = gpu_clip(wl, frames, p, thr)
+    print("scores gpu", g["scores"], "oracle", o["scores"], "updates", g["updates"], o["updates"])
     assert o["key_frames"][0], "an untrained head starts below the threshold"
+    assert all(abs(s - thr) > 1e-2 for s in o["scores"]), "a score inside the tolerance band decides nothing"
     agreed = compare(wl, g, o, thr, 1e-2)
-    assert agreed >= 1
+    assert agreed == len(frames), (agreed, g["scores"], o["scores"])
+    assert g["key_frames"] == o["key_frames"] and g["updates"] == o["updates"]
+    err = float(np.abs(g["params"] - o["params"]).max() / np.abs(o["params"]).max())
+    print("final weights: max error relative to max |w|", err)
+    assert err < 5e-4
+
+
+@pytest.mark.timeout(1500)
+def test_clip_720p_config_32_frames():
+    """The temporal-clip configuration at its own length and on its own inputs: 32 frames of noise
+    features that drift by 0.05 N(0,1) per frame, labels that move 2 px per frame, threshold 0.75,
+    at most 8 steps per key frame.  The features say nothing about the labels, so every frame is
+    a key frame trained for all 8 steps (256 updates of one head in a row): scores, key-frame
+    flags, update counts and the final weights against the oracle's run of the same schedule, with
+    the same rounding points (5e-4) and without (2e-2).  The oracle needs ten minutes for its two
+    runs, so they are read from tests/golden/ (written by the committed script there, from the
+    oracle alone; ST_LIVE_ORACLE=1 runs them here instead); the first frame is also run live and
+    must reproduce the stored score bit for bit."""
+    wl = WL.WORKLOADS["clip"]
+    thr = float(wl.extra["threshold"])
+    frames = list(WL.clip_frames(wl))
+    assert len(frames) == 32
+    p = WL.make_head_params(wl)
+    g = gpu_clip(wl, frames, p, thr)
+    progress("clip 32 frames: gpu scores %s" % np.round(g["scores"], 4).tolist())
+    assert g["n_key_frames"] == 32
+    gold = None if live_oracle() else load_golden("clip")
+    for tag, mode, tol_w, tol_s in (("bf16", True, 5e-4, 5e-3), ("exact", False, 2e-2, 2e-2)):
+        if gold is None:
+            o = oracle_clip(wl, frames, p, thr, bf16_operands=mode)
+            idx = np.arange(p.size)
+            o_par, den_w, den_u = o["params"], np.abs(o["params"]).max(), np.abs(o["params"] - p).max()
+        else:
+            assert int(gold["frames"]) == 32 and float(gold["threshold"]) == thr
+            o = dict(scores=gold[tag + "_scores"].tolist(), key_frames=gold[tag + "_key"].tolist(),
+                     updates=gold[tag + "_updates"].tolist())
+            idx, o_par = gold["index"], gold[tag + "_params"]
+            den_w, den_u = float(gold[tag + "_max_abs_param"]), float(gold[tag + "_max_abs_update"])
+            first = oracle_clip(wl, frames[:1], p, thr, bf16_operands=mode)
+            assert first["scores"][0] == o["scores"][0] and first["updates"][0] == o["updates"][0]
+        assert all(o["key_frames"]) and list(o["updates"]) == [wl.steps] * 32
+        assert g["key_frames"] == list(o["key_frames"]) and g["updates"] == list(o["updates"])
+        np.testing.assert_allclose(g["scores"], o["scores"], rtol=0, atol=tol_s)
+        err = float(np.abs(g["params"][idx] - o_par).max() / den_w)
+        upd = float(np.abs((g["params"][idx] - p[idx]) - (o_par - p[idx])).max() / den_u)
+        progress("clip 32 frames against the %s oracle: final weights after 256 updates: error / max|w| = %.3g, "
+                 "of the update itself %.3g" % (tag, err, upd))
+        assert err < tol_w
+        assert upd < (3e-2 if mode else 1e-1)
+
+
+@pytest.mark.timeout(600)
+def test_720p_early_exit_between_two_trace_values():
+    """Algorithm 1's loop exits at the benchmark's shape: features that carry the labels, THRESHOLD
+    set between two consecutive values of the oracle's own metric trace, so the call must stop at
+    that update; steps taken, best metric, first metric and the returned (best) parameters against
+    the oracle's run of Algorithm 1."""
+    import torch
+    import paper_2003_10735_amd as st
+    wl = WL.small_variant(WL.WORKLOADS["720p"], lr=0.02)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    d = O.desc_of(wl, True)
+    f64 = WL.features_as_f64(wl, f)
+    full = O.train(d, f64, lab, p.astype(np.float64), wl.steps, wl.lr, 1.5)
+    m = full["metrics"]
+    print("oracle metric trace", m.tolist(), flush=True)
+    # the widest gap between consecutive running maxima, not at the very start
+    run = np.maximum.accumulate(m)
+    gaps = [(run[i] - run[i - 1], i) for i in range(2, len(m)) if m[i] == run[i]]
+    gap, j = max(gaps)
+    assert gap > 2e-2, "the trace must rise by more than the metric's tolerance somewhere"
+    thr = float(0.5 * (run[j - 1] + run[j]))
+    o = O.train(d, f64, lab, p.astype(np.float64), wl.steps, wl.lr, thr)
+    assert o["updates"] == j
+    desc = st.HeadDesc.of(wl)
+    pt = torch.from_numpy(p.copy()).cuda()
+    mious = torch.full((wl.steps + 1, 1), float("nan"), dtype=torch.float64, device="cuda")
+    r = st.st_partial_distill(desc, to_dev_features(wl, f), torch.from_numpy(lab).cuda(), pt, wl.steps, wl.lr,
+                              threshold=thr, strict_break=True, return_best=True, mious=mious)
+    torch.cuda.synchronize()
+    taken, best = r
+    gm = mious.cpu().numpy()[:, 0]
+    print("gpu metric trace", gm.tolist(), "taken", taken, "best", best, flush=True)
+    assert taken == o["updates"]
+    np.testing.assert_allclose(gm[:taken + 1], o["metrics"], rtol=0, atol=5e-3)
+    assert np.isnan(gm[taken + 1:]).all()            # nothing ran after the exit
+    assert abs(best - o["best_metric"]) < 5e-3 and abs(r.first_metric - m[0]) < 5e-3
+    assert best == gm[:taken + 1].max()
+    err = float(np.abs(pt.cpu().numpy() - o["params"]).max() / np.abs(o["params"]).max())
+    print("returned parameters: max error relative to max |w|", err)
+    assert err < 5e-4
 
 
 def oracle_clip_strided(wl, frames, params, threshold, min_stride, max_stride, delay):

@@ -275,6 +275,105 @@ def test_training_loop_exits():
     np.testing.assert_allclose(m, ora["metrics"], atol=5e-3)
 
 
+def test_training_loop_comparisons_on_exact_ties():
+    """Algorithm 1's comparisons where the metrics tie exactly.  A step too small to change any
+    predicted class leaves every iteration's metric equal while the parameters move: the
+    strictly-better rule keeps the initial parameters as best_student (a '>=' would return the
+    last ones); a first metric equal to THRESHOLD takes no update; one ulp above it trains."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, n_sites=5,
+                          label_seed=5, steps=3, lr=1e-5)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    trace = run_gpu(wl, f, lab, p)
+    m = trace["mious"][:, 0]
+    assert (m == m[0]).all() and not np.array_equal(trace["params"], p)
+    r = run_gpu(wl, f, lab, p, threshold=1.5, return_best=True)
+    assert r["steps_taken"] == 3 and r["best_metric"] == m[0] and r["first_metric"] == m[0]
+    np.testing.assert_array_equal(r["params"], p)
+    r = run_gpu(wl, f, lab, p, threshold=1.5, return_best=False)
+    np.testing.assert_array_equal(r["params"], trace["params"])
+    r = run_gpu(wl, f, lab, p, threshold=float(m[0]), return_best=True)
+    assert r["steps_taken"] == 0
+    np.testing.assert_array_equal(r["params"], p)
+    r = run_gpu(wl, f, lab, p, threshold=float(np.nextafter(m[0], 2.0)), return_best=True)
+    assert r["steps_taken"] == 3
+    # the oracle scores this problem the same
+    ora = O.train(O.desc_of(wl), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 3, wl.lr, 1.5)
+    assert ora["updates"] == 3 and (ora["metrics"] == ora["metrics"][0]).all()
+    np.testing.assert_allclose(m, ora["metrics"], atol=5e-3)
+
+
+def test_frame_that_needs_no_training_leaves_everything_untouched():
+    """Algorithm 1's skip branch (the common case in a video: most frames are not key frames): a
+    head that already scores at the threshold takes no update, and the call leaves the caller's
+    parameters, velocity and best-parameter buffer's source bit for bit as they were -- on the
+    float32 path and on the matrix-core path."""
+    for kw in (dict(c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, compute="f32", feat_dtype="f32"),
+               dict(c_in=64, h=6, w=12, c1=64, c2=64, n_classes=3, compute="bf16", feat_dtype="bf16")):
+        wl = WL.small_variant(WL.WORKLOADS["tiny"], n_sites=5, label_seed=5, steps=8, lr=0.05, momentum=0.9, **kw)
+        lab = WL.make_labels(wl)
+        f = WL.make_learnable_features(wl, lab)
+        p = WL.make_head_params(wl)
+        trained = run_gpu(wl, f, lab, p)                      # eight steps: a head that scores well
+        m_end = float(trained["mious"][-1, 0])
+        assert m_end > trained["mious"][0, 0] + 0.05
+        desc = st.HeadDesc.of(wl)
+        pt = torch.from_numpy(trained["params"].copy()).cuda()
+        vel = torch.from_numpy(trained["velocity"].copy()).cuda()
+        best = torch.full((p.size,), 7.0, dtype=torch.float32, device="cuda")
+        r = st.st_partial_distill(desc, to_dev_features(wl, f), torch.from_numpy(lab).cuda(), pt, 8, wl.lr,
+                                  momentum=0.9, velocity=vel, threshold=m_end, return_best=True, best_params=best)
+        torch.cuda.synchronize()
+        assert r[0] == 0 and r[1] == m_end and r.first_metric == m_end
+        np.testing.assert_array_equal(pt.cpu().numpy(), trained["params"])
+        np.testing.assert_array_equal(vel.cpu().numpy(), trained["velocity"])
+        np.testing.assert_array_equal(best.cpu().numpy(), trained["params"])     # best_student = the head as given
+
+
+def test_best_is_not_last_with_momentum():
+    """A run whose metric rises and falls again (large step, momentum 0.9).  head_params receives
+    the best iteration's parameters; the velocity, the class map, the confusion counts and the
+    last losses / mious entries are those of the last pass (the header says so)."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, n_sites=5,
+                          label_seed=5, steps=8, lr=0.2, momentum=0.9)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    ora = O.train(O.desc_of(wl), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 8, wl.lr, 1.5, momentum=0.9)
+    mo = ora["metrics"]
+    best_i = int(np.argmax(mo))
+    assert 0 < best_i < 8 and mo[8] < mo[best_i] - 0.1
+    r = run_gpu(wl, f, lab, p, threshold=1.5, return_best=True)
+    m = r["mious"][:, 0]
+    np.testing.assert_allclose(m, mo, atol=2e-2)
+    assert r["steps_taken"] == 8 and int(np.argmax(m)) == best_i and r["best_metric"] == m[best_i]
+    assert rel_err(r["params"], ora["params"]) < 1e-3
+    fixed_best = run_gpu(wl, f, lab, p, steps=best_i)
+    fixed_last = run_gpu(wl, f, lab, p, steps=8)
+    np.testing.assert_array_equal(r["params"], fixed_best["params"])
+    np.testing.assert_array_equal(r["velocity"], fixed_last["velocity"])
+    np.testing.assert_array_equal(r["pred"], fixed_last["pred"])
+    np.testing.assert_array_equal(r["conf"], fixed_last["conf"])
+    assert rel_err(r["velocity"], ora["velocity"]) < 2e-2
+
+
+def test_non_finite_parameters_stay_in_range():
+    """A diverged head (every parameter NaN): the class map stays inside [0, C) -- class 0, the
+    oracle's answer as well -- the confusion counts still hold every valid pixel exactly once,
+    and the loss reports the condition by being non-finite.  Both the float32 and the
+    matrix-core path, with a class count that needs padding."""
+    for kw in (dict(c_in=8, h=6, w=9, c1=8, c2=8, n_classes=5, compute="f32", feat_dtype="f32"),
+               dict(c_in=64, h=6, w=9, c1=64, c2=64, n_classes=19, compute="bf16", feat_dtype="bf16")):
+        wl = WL.small_variant(WL.WORKLOADS["tiny"], n_sites=7, steps=0, **kw)
+        f, lab, p = inputs(wl)
+        g = run_gpu(wl, f, lab, np.full_like(p, np.nan), steps=0)
+        assert not np.isfinite(g["losses"][0])
+        assert (g["pred"] == 0).all()
+        assert g["conf"].sum() == lab.size and (g["conf"][0][:, 1:] == 0).all()
+        np.testing.assert_array_equal(g["pred"], O.predict_from_logits(g["z"]))
+
+
 MFMA_CASES = [
     dict(n=1, c_in=64, h=12, w=40, c1=64, c2=64, n_classes=19),
     dict(n=2, c_in=128, h=9, w=21, c1=64, c2=128, n_classes=21, ignore_index=255, ignore_fraction=0.05,

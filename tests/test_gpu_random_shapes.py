@@ -27,6 +27,28 @@ def random_case(seed):
     return wl, int(rng.integers(0, 2))
 
 
+def check_updates(p0, pt, vel, o, wl):
+    """The weights are dominated by their initial values, so the update itself (and the velocity)
+    is compared as well: a wrong weight or bias gradient on an odd shape shows up here, block by
+    block (W1, b1, W2, b2, W3, b3 of every head), each relative to its own largest entry."""
+    got = pt.cpu().numpy().astype(np.float64).reshape(-1, wl.n_params)
+    want = np.asarray(o["params"]).reshape(-1, wl.n_params)
+    start = np.asarray(p0, dtype=np.float64).reshape(-1, wl.n_params)
+    for name, sl in WL.param_slices(wl).items():
+        for hd in range(got.shape[0]):
+            du = want[hd, sl] - start[hd, sl]
+            if np.abs(du).max() < 1e-9:
+                continue
+            assert rel_err(got[hd, sl] - start[hd, sl], du) < 3e-2, (name, hd)
+    if vel is not None:
+        v, vo = vel.cpu().numpy().reshape(-1, wl.n_params), np.asarray(o["s1"]).reshape(-1, wl.n_params)
+        for name, sl in WL.param_slices(wl).items():
+            for hd in range(v.shape[0]):
+                if np.abs(vo[hd, sl]).max() < 1e-9:
+                    continue
+                assert rel_err(v[hd, sl], vo[hd, sl]) < 3e-2, (name, hd)
+
+
 @pytest.mark.parametrize("seed", range(100, 116))
 def test_random_shape(seed):
     wl, grouped = random_case(seed)
@@ -53,6 +75,7 @@ def test_random_shape(seed):
         o = O.partial_distill_opt(d, f64, lab, p[0].astype(np.float64), wl.steps, opt)
     assert rel_err(losses.cpu().numpy(), o["losses"]) < 5e-4
     assert rel_err(pt.cpu().numpy(), o["params"]) < 5e-4
+    check_updates(p if grouped else p[0], pt, vel, o, wl)
     np.testing.assert_allclose(mious.cpu().numpy(), o["mious"], atol=2e-2)
     # every valid pixel is counted exactly once
     valid = (lab != wl.ignore_index).reshape(wl.n, -1).sum(axis=1)
@@ -89,5 +112,6 @@ def test_random_shape_with_pixel_weights(seed):
         o = O.partial_distill_opt(O.with_pixel_weights(d, wts), f64, lab, p[0].astype(np.float64), wl.steps, opt)
     assert rel_err(losses.cpu().numpy(), o["losses"]) < 5e-4
     assert rel_err(pt.cpu().numpy(), o["params"]) < 5e-4
+    check_updates(p if grouped else p[0], pt, vel, o, wl)
     valid = (lab != wl.ignore_index).reshape(wl.n, -1).sum(axis=1)
     np.testing.assert_array_equal(conf.cpu().numpy().sum(axis=(1, 2)), valid)

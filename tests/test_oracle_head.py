@@ -152,6 +152,20 @@ def test_k_steps_match_library_loop_sgd_and_momentum():
         np.testing.assert_array_equal(res["mious"][-1], mik)
 
 
+@pytest.mark.parametrize("mu", [0.0, 0.9])
+def test_stepwise_loop_is_the_c_loop(mu):
+    """The step-by-step front-end (used where a long run has to report progress) gives bit for bit
+    what the C loop gives."""
+    d = tiny()
+    f, lab, p = random_problem(d, seed=21)
+    a = O.partial_distill(d, f, lab, p, steps=3, lr=0.1, momentum=mu)
+    seen = []
+    b = O.partial_distill_stepwise(d, f, lab, p, steps=3, lr=0.1, momentum=mu, on_step=lambda it, loss: seen.append(it))
+    assert seen == [0, 1, 2, 3]
+    for k in ("params", "velocity", "losses", "mious", "conf", "pred"):
+        np.testing.assert_array_equal(a[k], b[k])
+
+
 def test_partial_means_features_untouched_and_steps0_is_forward_only():
     d = tiny()
     f, lab, p = random_problem(d, seed=13)
@@ -237,6 +251,52 @@ def test_training_loop_exits_follow_algorithm_1():
     r_ge = O.train(d, f, lab, p, max_updates=8, lr=0.05, threshold=m[j], strict_break=False)
     r_gt = O.train(d, f, lab, p, max_updates=8, lr=0.05, threshold=m[j], strict_break=True)
     assert r_ge["updates"] == j and r_gt["updates"] > j
+
+
+def test_training_loop_comparisons_on_exact_ties():
+    """The three comparisons of Algorithm 1 on metrics that tie exactly.  With a step so small that
+    no pixel changes its class, every iteration scores the same while the parameters do move:
+      * best update is strictly-better ('>'): best_student stays the initial one ('>=' would
+        return the last parameters);
+      * the entry test is 'best_metric < THRESHOLD': a first metric equal to THRESHOLD skips the
+        loop ('<=' would train);
+      * the exit is 'metric > THRESHOLD' as printed: a metric equal to THRESHOLD does not leave
+        the loop, the '>=' variant does at the first update."""
+    d, f, lab, p = learnable_problem()
+    lr = 1e-12
+    trace = O.partial_distill(d, f, lab, p, steps=3, lr=lr)
+    m = trace["mious"][:, 0]
+    assert (m == m[0]).all(), "the step must be too small to change any predicted class"
+    assert not np.array_equal(trace["params"], p)
+    r = O.train(d, f, lab, p, max_updates=3, lr=lr, threshold=1.5)
+    assert r["updates"] == 3 and r["best_metric"] == m[0]
+    np.testing.assert_array_equal(r["metrics"], m)
+    np.testing.assert_array_equal(r["params"], p)
+    r = O.train(d, f, lab, p, max_updates=3, lr=lr, threshold=m[0])
+    assert r["updates"] == 0
+    np.testing.assert_array_equal(r["params"], p)
+    above = np.nextafter(m[0], 2.0)
+    r = O.train(d, f, lab, p, max_updates=3, lr=lr, threshold=above)
+    assert r["updates"] == 3                       # below THRESHOLD by one ulp: trains, never exceeds it
+    # exit comparison: learnable run, THRESHOLD exactly at the first metric that beats the start
+    full = O.partial_distill(d, f, lab, p, steps=8, lr=0.05)["mious"][:, 0]
+    j = next(i for i in range(1, 9) if full[i] > full[0])
+    later = next(i for i in range(j + 1, 9) if full[i] > full[j])
+    assert O.train(d, f, lab, p, 8, 0.05, threshold=full[j], strict_break=True)["updates"] == later
+    assert O.train(d, f, lab, p, 8, 0.05, threshold=full[j], strict_break=False)["updates"] == j
+
+
+def test_best_is_not_last_with_momentum():
+    """A run whose metric rises and then falls (large step, momentum): Algorithm 1 returns the
+    parameters of the best iteration, which are those of a fixed-step run of that length."""
+    d, f, lab, p = learnable_problem()
+    r = O.train(d, f, lab, p, max_updates=8, lr=0.2, threshold=1.5, momentum=0.9)
+    m = r["metrics"]
+    best_i = int(np.argmax(m))
+    assert 0 < best_i < 8 and m[8] < m[best_i] - 0.1, m
+    assert r["best_metric"] == m[best_i]
+    ref = O.partial_distill(d, f, lab, p, steps=best_i, lr=0.2, momentum=0.9)
+    np.testing.assert_array_equal(r["params"], ref["params"])
 
 
 # ------------------------------------------------------------------ gradient with respect to the features
