@@ -60,7 +60,7 @@ template <int CP, bool GRAD>
 __global__ void __launch_bounds__(LOSS_THREADS, (CP <= 24 ? 4 : 2))
 k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
-       unsigned long long* __restrict__ conf, Geo g, LossTiling lt)
+       unsigned long long* __restrict__ conf, Geo g, LossTiling lt, int n_tiles)
 {
     static_assert(LOSS_TY == 1, "one row group per tile: the two halves of a block split its 8 pixel rows");
     constexpr int CW = LOSS_CW, CH = LOSS_CH, CWP = CW + 1, NT = LOSS_THREADS;
@@ -72,7 +72,13 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
     __shared__ float wsum[NT / 64];
 
     const int tid = threadIdx.x;
-    const int tile = blockIdx.x % lt.tiles(), img = blockIdx.x / lt.tiles();
+    // XCD-aware tile order: consecutive blocks go to different XCDs, each with an L2 of its own.
+    // Every XCD gets a contiguous run of tiles (a band of rows), so the three tiles that stage the
+    // same row of cells run on one XCD and two of them find the row in its L2.
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || bid >= n_tiles) return;
+    const int tile = bid % lt.tiles(), img = bid / lt.tiles();
     const int tile_x = tile % lt.tiles_x, qy = tile / lt.tiles_x;   // qy: row group = cell row
     const int C = g.C, hw = g.h * g.w;
     const int cx0 = tile_x * LOSS_TX - 1, cy0 = qy - 1;  // cell of local (0, 0)
@@ -295,14 +301,14 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
         float acc = wsum[0];
 #pragma unroll
         for (int w = 1; w < NT / 64; ++w) acc += wsum[w];
-        loss_part[blockIdx.x] = acc;
+        loss_part[bid] = acc;
     }
     if (conf && lab_img)
         for (int i = tid; i < C * C; i += NT)
             if (conf_l[i]) atomicAdd(&conf[(size_t)img * C * C + i], (unsigned long long)conf_l[i]);
 
     if (GRAD) {
-        float* slot = slots + (size_t)blockIdx.x * CP * CH * CW;
+        float* slot = slots + (size_t)bid * CP * CH * CW;
         // cell totals: column group lc gives its left part, lc-1 its centre part, lc-2 its right
         // part; cell row 0 comes from the upper half, row 2 from the lower half, row 1 from both
         // (upper half first).  Cells outside the grid received nothing (their weight went to the
@@ -370,17 +376,18 @@ static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* lab
                         const unsigned long long* n_valid, bool grad, bool assemble)
 {
     const LossTiling lt = loss_tiling(g);
-    const int blocks = g.n * lt.tiles();
+    const int n_tiles = g.n * lt.tiles();
+    const int blocks = (n_tiles + 7) / 8 * 8;      // whole rounds over the eight XCDs
     if (grad) {
         ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred,
-                  slots, loss_part, conf, g, lt);
+                  slots, loss_part, conf, g, lt, n_tiles);
         // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
         if (assemble)
             ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
                       dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
         ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred, slots,
-                  loss_part, conf, g, lt);
+                  loss_part, conf, g, lt, n_tiles);
     }
 }
 
