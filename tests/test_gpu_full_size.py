@@ -22,6 +22,10 @@ def compare_bf16(wl, steps, tight=5e-4):
     assert rel_err(gpu["losses"], ora["losses"]) < 2e-2          # bf16 GEMM inputs: 2e-2 relative
     assert rel_err(gpu["params"], ora["params"]) < 2e-2
     orq = run_oracle(wl, f, lab, p, steps=steps, bf16_operands=True, report=wl.name + " bf16 operands")
+    progress("%s %d steps: against the exact oracle losses %.3g weights %.3g; against the bf16-operand oracle losses %.3g "
+             "weights %.3g update %.3g" % (wl.name, len(gpu["losses"]) - 1, rel_err(gpu["losses"], ora["losses"]),
+                                          rel_err(gpu["params"], ora["params"]), rel_err(gpu["losses"], orq["losses"]),
+                                          rel_err(gpu["params"], orq["params"]), rel_err(gpu["params"] - p, orq["params"] - p)))
     # same rounding points on both sides: what is left is accumulation order
     assert rel_err(gpu["losses"], orq["losses"]) < tight
     assert rel_err(gpu["params"], orq["params"]) < tight
