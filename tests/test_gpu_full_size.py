@@ -83,19 +83,20 @@ def test_batch4_shared_head_all_steps():
         np.testing.assert_allclose(gpu["mious"], gold[tag + "_mious"], atol=5e-3 if tag == "bf16" else 2e-2)
 
 
-def test_720p_adam_two_steps():
-    """The paper's optimiser (Section 5.2) at the benchmark's shape; see check_adam for why the
-    weights are compared where the first gradient is not tiny."""
+def test_720p_adam_all_steps():
+    """The paper's optimiser (Section 5.2: Adam, learning rate 0.01) at the benchmark's shape and
+    the paper's MAX_UPDATES = 8; see check_adam for why the weights are compared where the first
+    gradient is not tiny."""
     from test_gpu_parity import check_adam
     wl = WL.WORKLOADS["720p"]
     f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
-    check_adam(wl, f, lab, p, 2, True, 2e-3, 2e-2)
+    check_adam(wl, f, lab, p, wl.steps, True, 2e-3, 2e-2)
 
 
-def test_720p_weighted_loss_two_steps():
-    """Per-pixel loss weights (Section 5.2) at the benchmark's shape."""
+def test_720p_weighted_loss_all_steps():
+    """Per-pixel loss weights (Section 5.2) at the benchmark's shape, all eight steps."""
     from test_gpu_parity import check_weighted
-    check_weighted(WL.WORKLOADS["720p"], 2, True, 5e-4)
+    check_weighted(WL.WORKLOADS["720p"], WL.WORKLOADS["720p"].steps, True, 5e-4)
 
 
 def test_720p_feature_gradient():
@@ -106,13 +107,13 @@ def test_720p_feature_gradient():
 
 def test_720p_four_clients_grouped():
     """Four clients' key frames and heads in one call, in the launch configuration the benchmark
-    times for the grouped form; every head against its own single-frame oracle run."""
+    times for the grouped form, all eight steps; every head against its own single-frame oracle run."""
     import oracle as O
     from test_gpu_grouped import SGD, check_against_oracle, inputs, run_grouped
     wl = WL.small_variant(WL.WORKLOADS["720p"], n=4)
     f, lab, p = inputs(wl)
-    g = run_grouped(wl, f, lab, p, 2)
-    o = O.partial_distill_grouped(O.desc_of(wl, True), WL.features_as_f64(wl, f), lab, p.astype(np.float64), 2, SGD(wl))
+    g = run_grouped(wl, f, lab, p, wl.steps)
+    o = O.partial_distill_grouped(O.desc_of(wl, True), WL.features_as_f64(wl, f), lab, p.astype(np.float64), wl.steps, SGD(wl))
     print("grouped losses", g["losses"].T, "oracle", o["losses"].T)
     check_against_oracle(wl, g, o, p)
 
