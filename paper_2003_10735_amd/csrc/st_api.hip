@@ -608,10 +608,14 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     for (int it = 0; it <= steps; ++it) {
         const bool last = it == steps;
         forward(c, p, ws, z);
+        // The first pass of the early-exit form only scores the head (loss, class map, counts):
+        // most frames are not key frames and end right there.  A key frame runs the same kernel
+        // once more for the gradient half, below, once the host has seen the metric.
+        const bool score_only = early_exit && it == 0;
         loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
-                  (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last, !p.mfma);
+                  (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last && !score_only, !p.mfma);
         float* loss_out = (out && out->losses) ? out->losses + (size_t)it * g.heads() : nullptr;
         double* miou_out = (out && out->mious) ? out->mious + (size_t)it * g.n : nullptr;
         long long* conf_out = (out && out->confusion && (last || early_exit)) ? (long long*)out->confusion : nullptr;
@@ -668,6 +672,9 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             }
         }
         if (stop) break;
+        if (score_only)   // the gradient half of the pass just scored: no counts, no loss, no class map again
+            loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj), nullptr,
+                      (float*)(ws + p.g_slots), (float*)(ws + p.gz), nullptr, nullptr, n_valid, true, !p.mfma);
         if (!backward_queued) backward(c, p, ws, feature_grad);
         AdamStep ad;
         if (use_adam) {
