@@ -43,26 +43,26 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
     ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.53, 8.83),
-    ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 13.75, 7.55),
-    ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 6.98, 11.32),
-    ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 10.45, 3.77),
+    ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 13.75, 7.55),
+    ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 6.98, 11.32),
+    ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 10.45, 3.77),
     ("720p", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 8.90, 4.71),
     ("720p", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 4.93, 1.82),
     ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 16.99, 11.36),
-    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 74.05, 8.83),
-    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 23.44, 16.59),
-    ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 11.83, 24.88),
-    ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 19.69, 8.29),
+    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.99, 8.83),
+    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 23.45, 16.59),
+    ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 11.82, 24.88),
+    ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 19.69, 8.29),
     ("1080p", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 19.27, 11.14),
     ("1080p", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 10.45, 4.09),
-    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 35.87, 24.95),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.04, 17.49),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 52.00, 60.38),
-    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 45.99, 90.56),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "8cfea77b2504613deea408c3bfd1d6b11bbf622236ce4dcb3ec6914b8ea348b8", 69.00, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 63.31, 74.46),
+    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 35.88, 24.95),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.00, 17.49),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 51.94, 60.38),
+    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 46.96, 90.56),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 69.11, 30.19),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 63.27, 74.39),
     ("batch4", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 31.72, 7.72),
-    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 101.88, 90.68),
+    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 101.89, 90.68),
 }
 
 

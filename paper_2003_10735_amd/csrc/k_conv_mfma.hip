@@ -128,9 +128,12 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
     // Wavefront w fills rows 8w .. 8w+7 and 64+8w .. 64+8w+7; wavefront 0 also rows 128, 129.
     // The loads are written in assembly: the compiler would order every barrier behind all
     // outstanding loads of this kind, while the pipeline below needs two stages in flight.
-    // (M0 is reserved: the compiler sets it right before each of its own uses and keeps nothing
-    //  in it, and this kernel gives it no such use.  One wait state separates the scalar write of
-    //  M0 from the load that reads it.)
+    // (M0 is a reserved register for this compiler: it never allocates a value to it, sets it
+    //  right before each instruction of its own that reads it, and rejects it in an asm clobber
+    //  list ("inline asm clobber list contains reserved registers: m0") -- so the statement
+    //  below cannot declare the write and does not need to: nothing of the compiler's lives in M0
+    //  across it, and each statement sets M0 itself before the one load that reads it.  One wait
+    //  state separates the scalar write of M0 from that load.)
     const int lrow = lane >> 3, lpc = lane & 7;
     const int sw01 = (4 * wave + (lrow >> 1)) & 7, sw2 = lrow >> 1;          // (row >> 1) & 7 of the rows filled
     const int xo0 = ((wave * 8 + lrow) * a.cin + ((lpc ^ sw01) << 3)) * 2;   // byte offsets inside a slab
