@@ -49,18 +49,18 @@ MEASURED_TRAFFIC = {
     ("720p", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 8.90, 4.71),
     ("720p", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 4.93, 1.82),
     ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 16.99, 11.36),
-    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.99, 8.83),
-    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 23.45, 16.59),
+    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 74.05, 8.83),
+    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 23.44, 16.59),
     ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 11.82, 24.88),
     ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 19.69, 8.29),
     ("1080p", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 19.27, 11.14),
     ("1080p", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 10.45, 4.09),
-    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 35.88, 24.95),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.00, 17.49),
+    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 35.87, 24.95),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.04, 17.50),
     ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 51.94, 60.38),
-    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 46.96, 90.56),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 69.11, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 63.27, 74.39),
+    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 46.55, 90.56),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 68.98, 30.19),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 63.29, 74.43),
     ("batch4", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 31.72, 7.72),
     ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "85d41fe6b7fcf0d4b28069ee998d0937ba9ec9e64e84af80d87a71c9e052b233", 101.89, 90.68),
 }
@@ -335,6 +335,8 @@ def main():
     ap.add_argument("--other-configs", default="1080p,batch4",
                     help="comma-separated workloads measured beside the headline (`configs` in the line); "
                          "empty = skip")
+    ap.add_argument("--no-full-compare", action="store_true",
+                    help="skip the partial-against-full comparison leg (`partial_vs_full`)")
     ap.add_argument("--no-graph", action="store_true",
                     help="time the calls launched kernel by kernel in the stream; default: `value` is timed "
                          "with the library's cached HIP graph (st_distill_opts.use_graph), and the "
@@ -619,6 +621,31 @@ def main():
             except Exception as e:
                 configs[name] = {"error": f"{type(e).__name__}: {e}"}
 
+    # Partial against full distillation (Section 4.2; the paper's Table 2 reports 13 ms against 18 ms
+    # per step for its whole student on an RTX 2080 Ti): the same key frame with the data-gradient of
+    # the first trainable layer computed as well -- what an unfrozen front part would build on.
+    partial_vs_full = None
+    if wl.name == "720p" and not variant and not args.no_full_compare:
+        try:
+            pf = Problem(st, WL, wl, stream, full_backward=True)
+            pf.call()
+            if use_graph:
+                pf.call(graph=True)
+            torch.cuda.synchronize()
+            _, ms_f = timed_calls(lambda: pf.call(graph=use_graph), 0, 30)
+            t_full = spread(ms_f)["median"]
+            partial_vs_full = {"partial_us_per_step": round(ms_per_call / wl.steps * 1e3, 2),
+                               "full_us_per_step": round(t_full / wl.steps * 1e3, 2),
+                               "partial_over_full": round(ms_per_call / t_full, 4),
+                               "paper_table_2": {"partial_ms": 13, "full_ms": 18, "partial_over_full": round(13 / 18, 4),
+                                                 "hardware": "RTX 2080 Ti, whole student (the front part is trained too)"},
+                               "note": "full = every backward pass also computes d loss / d features (one more "
+                                       "convolution launch per step); here only the head exists, so only the head's "
+                                       "share of the saving shows"}
+            del pf
+        except Exception as e:
+            partial_vs_full = {"error": f"{type(e).__name__}: {e}"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle as O
@@ -676,6 +703,7 @@ def main():
         "clip": clip,
         "clip_learnable": clip_learnable,
         "configs": configs,
+        "partial_vs_full": partial_vs_full,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(out))
