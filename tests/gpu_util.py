@@ -17,8 +17,9 @@ _ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def progress(msg):
-    """One line per finished piece of a long test (a frame, a step): printed, and appended to
-    gpurun_out/test_progress.log so that a run whose output is captured still shows that it moves."""
+    """One line per finished piece of a long test (a frame, a step): printed, and appended to a
+    log file in the run's output folder, so that a run whose output is captured still shows that
+    it moves."""
     line = time.strftime("%H:%M:%S ") + str(msg)
     print(line, flush=True)
     try:
