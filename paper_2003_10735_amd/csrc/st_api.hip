@@ -370,7 +370,8 @@ struct GraphKey {
     int device;
 };
 struct GraphEntry { GraphKey key; hipGraph_t graph; hipGraphExec_t exec; unsigned long long last_use; };
-static std::mutex g_graph_mutex;
+static std::mutex g_graph_mutex;      // the cache: look-up, insert, launch
+static std::mutex g_capture_mutex;    // recording + instantiating a graph
 static std::vector<GraphEntry> g_graphs;
 static unsigned long long g_graph_clock = 0;
 constexpr size_t GRAPH_CACHE_MAX = 8;
@@ -523,7 +524,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             key.workspace = workspace;
             if (hipGetDevice(&key.device) != hipSuccess) return ST_ERR_NO_DEVICE;
             // The cache is locked only to look an entry up and to insert one: recording and
-            // instantiating a graph (milliseconds) runs unlocked, so callers on other streams go on.
+            // instantiating a graph (milliseconds) runs outside that lock, so callers on other
+            // streams whose graphs exist go on.
             // (A launch itself happens under the lock, so that no other thread can evict and destroy
             //  the graph between the look-up and the launch.)
             auto launch_locked = [&](GraphEntry& e) -> int {
@@ -539,6 +541,9 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                     if (memcmp(&e.key, &key, sizeof(key)) == 0) return launch_locked(e);
             }
             {
+                // One recording at a time (a lock of its own: the cache stays open to look-ups and
+                // launches of other callers meanwhile).
+                std::lock_guard<std::mutex> recording(g_capture_mutex);
                 // record the plain call's launches (nothing runs while the stream is capturing)
                 st_distill_opts plain = *opts;
                 plain.use_graph = 0;

@@ -202,3 +202,46 @@ def test_two_host_threads_run_the_early_exit_form_side_by_side():
         assert c["out"] == out_alone
         assert all(o[0][0] == 4 for o in c["out"])      # the threshold is out of reach: all four updates
         np.testing.assert_array_equal(c["p"].cpu().numpy(), p_alone)
+
+
+def test_two_host_threads_record_and_launch_graphs_side_by_side():
+    """Two host threads (own stream, workspace and head each) whose first graph-mode calls -- the
+    ones that record -- and later launches happen at the same time: every thread gets what it gets
+    alone, and the cache ends up with one graph per distinct call."""
+    import threading
+    st.st_graph_cache_clear()
+    wl0 = WL.small_variant(WL.WORKLOADS["720p"], steps=3, lr=0.02, n_sites=9, c_in=64, h=13, w=35, c1=64, c2=64,
+                           n_classes=6)
+    desc = st.HeadDesc.of(wl0)
+    clients = []
+    for i in range(2):
+        wl = WL.small_variant(wl0, feat_seed=wl0.feat_seed + i, label_seed=wl0.label_seed + 10 * i)
+        p0 = torch.from_numpy(WL.make_head_params(wl, seed=wl.init_seed + 17 * i)).cuda()
+        clients.append(dict(f=to_dev_features(wl, WL.make_features(wl)), lab=torch.from_numpy(WL.make_labels(wl)).cuda(),
+                            p0=p0, p=p0.clone(), ws=st.new_workspace(desc), s=torch.cuda.Stream(),
+                            losses=torch.zeros(4, dtype=torch.float32, device="cuda")))
+
+    def work(c, rounds, graph):
+        for _ in range(rounds):
+            st.st_partial_distill(desc, c["f"], c["lab"], c["p"], 3, wl0.lr, losses=c["losses"], workspace=c["ws"],
+                                  stream=c["s"], graph=graph)
+
+    torch.cuda.synchronize()
+    for c in clients:                                   # one after the other, plain launches
+        work(c, 4, False)
+    torch.cuda.synchronize()
+    alone = [outputs([c["p"], c["losses"]]) for c in clients]
+    for c in clients:
+        c["p"].copy_(c["p0"])
+    torch.cuda.synchronize()
+    threads = [threading.Thread(target=work, args=(c, 4, True)) for c in clients]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for c, ref in zip(clients, alone):
+        for a, b in zip(outputs([c["p"], c["losses"]]), ref):
+            np.testing.assert_array_equal(a, b)
+    assert st.st_graph_cache_size() == 2
+    st.st_graph_cache_clear()
