@@ -500,6 +500,7 @@ def main():
         wg = WL.small_variant(wl, n=G)
         dg = st.HeadDesc.of(wg)
         dg.grouped = 1
+    if args.clients > 0 and wl.n == 1 and not variant and st.st_workspace_bytes(dg) > 0:   # (matrix-core shapes only)
         fg = upload(WL.make_features(wg))
         lg = torch.from_numpy(WL.make_labels(wg)).cuda()
         pg0 = torch.from_numpy(np.stack([WL.make_head_params(wg, seed=wg.init_seed + 17 * i) for i in range(G)])).cuda()
