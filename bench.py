@@ -9,7 +9,8 @@ Protocol: W warm-up calls; then K = --steps calls between device synchronisation
 `wall`), every call between a pair of HIP events on the calling stream, continued until at least
 --min-timed (30) calls are timed.  `ms_per_step` is the median per-call time between the events
 (`ms_per_call` gives min / p90 / max), `value` = optimiser steps per call over it.  The head's
-re-initialisation (one device copy) is inside every timed call.
+re-initialisation (one device copy) runs between the calls, outside the event pairs (inside the
+host-clock region).
 
 Prints ONE JSON line.  Extra objects:
   roofline      the kernel that takes the largest share of the call (kernels within 3 % of it count
@@ -172,15 +173,23 @@ class Problem:
         self.adam = dict(m=torch.zeros_like(self.p), v=torch.zeros_like(self.p), t0=0) if optimizer == "adam" else None
         torch.cuda.synchronize()
 
-    def call(self, graph=False):
-        """One key frame: the head is re-initialised, then one st_partial_distill call."""
-        wl, st = self.wl, self.st
+    def reset(self):
+        """The head (and the optimiser state) as before the key frame."""
         self.p.copy_(self.p0)
         if self.vel is not None:
             self.vel.zero_()
         if self.adam is not None:
             self.adam["m"].zero_()
             self.adam["v"].zero_()
+
+    def call(self, graph=False):
+        """One key frame: the head is re-initialised, then one st_partial_distill call."""
+        self.reset()
+        self.run(graph)
+
+    def run(self, graph=False):
+        wl, st = self.wl, self.st
+        if self.adam is not None:
             st.st_partial_distill(self.desc, self.f, self.lab, self.p, wl.steps, wl.lr, adam=self.adam, losses=self.losses,
                                   mious=self.mious, confusion=self.conf, workspace=self.ws, stream=self.stream,
                                   pixel_weights=self.pw, feature_grad=self.dfeat, graph=graph)
@@ -190,28 +199,33 @@ class Problem:
                               stream=self.stream, pixel_weights=self.pw, feature_grad=self.dfeat, graph=graph)
 
 
-def timed_calls(fn, n_wall, n_total):
+def timed_calls(fn, n_wall, n_total, before=None):
     """Runs fn() n_total times back to back on torch's current stream with a HIP event before and
-    after every call.  The first n_wall calls are also bracketed by a device synchronisation on
-    both sides and timed with the host clock.  Returns (wall seconds of the first n_wall calls,
-    list of n_total per-call milliseconds between the events)."""
+    after every call; `before()` (re-initialising the head) runs ahead of each call, outside its
+    event pair.  The first n_wall calls, their `before()` included, are also bracketed by a device
+    synchronisation on both sides and timed with the host clock.  Returns (wall seconds of the
+    first n_wall calls, list of n_total per-call milliseconds between the events)."""
     import torch
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_total + 1)]
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_total)]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_total)]
+
+    def one(i):
+        if before is not None:
+            before()
+        e0[i].record()
+        fn()
+        e1[i].record()
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ev[0].record()
     for i in range(n_wall):
-        fn()
-        ev[i + 1].record()
+        one(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    if n_total > n_wall:
-        ev[n_wall].record()
-        for i in range(n_wall, n_total):
-            fn()
-            ev[i + 1].record()
-        torch.cuda.synchronize()
-    return wall, [ev[i].elapsed_time(ev[i + 1]) for i in range(n_total)]
+    for i in range(n_wall, n_total):
+        one(i)
+    torch.cuda.synchronize()
+    return wall, [e0[i].elapsed_time(e1[i]) for i in range(n_total)]
 
 
 def spread(ms):
@@ -278,7 +292,7 @@ def config_leg(st, WL, name, stream, n_timed, use_graph):
     prof = all_kernel_pass(st, prob, 2)
     known = {k: v for k, v in prof.items() if any(k.startswith(pre) for pre in work)}
     dominant = pick_dominant(work, known)
-    _, ms = timed_calls(lambda: prob.call(graph=use_graph), 0, n_timed)
+    _, ms = timed_calls(lambda: prob.run(graph=use_graph), 0, n_timed, before=prob.reset)
     sp = spread(ms)
     t_call = sp["median"] * 1e-3
     peak = PEAK_TFLOPS_BF16 if wl.compute == "bf16" else PEAK_TFLOPS_F32
@@ -403,7 +417,7 @@ def main():
     # timed region, kernel-by-kernel launches; only the dominant kernel carries an event pair
     st.st_profile_filter(dominant)
     st.st_profile_enable(True)
-    wall_plain, ms_plain = timed_calls(one_call, args.steps, args.steps)
+    wall_plain, ms_plain = timed_calls(prob.run, args.steps, args.steps, before=prob.reset)
     dom = st.st_profile_read()[dominant]
     st.st_profile_enable(False)
     st.st_profile_reset()
@@ -417,13 +431,13 @@ def main():
     # a device synchronisation on both sides for the host clock, every call between a pair of HIP
     # events on the calling stream; more calls follow until there are at least --min-timed of them.
     # `value` comes from the median per-call time between the events; the host-clock figure of
-    # the K-call region stands beside it.  The head's re-initialisation (one 1.8 MB device copy) is
-    # inside every timed call.
+    # the K-call region stands beside it.  The head's re-initialisation (one 1.8 MB device copy)
+    # runs between the calls: outside the event pairs, inside the host-clock region.
     n_total = max(args.steps, args.min_timed)
     if use_graph:
-        wall, ms_calls = timed_calls(lambda: one_call(graph=True), args.steps, n_total)
+        wall, ms_calls = timed_calls(lambda: prob.run(graph=True), args.steps, n_total, before=prob.reset)
     elif n_total > args.steps:
-        wall, ms_calls = timed_calls(one_call, args.steps, n_total)
+        wall, ms_calls = timed_calls(prob.run, args.steps, n_total, before=prob.reset)
     else:
         wall, ms_calls = wall_plain, ms_plain
     sp = spread(ms_calls)
@@ -508,15 +522,15 @@ def main():
         wsg = st.new_workspace(dg)
         lossg = torch.zeros((wl.steps + 1, G), dtype=torch.float32, device="cuda")
 
-        def grouped_call():
-            pg.copy_(pg0)
+        def grouped_run():
             st.st_partial_distill(dg, fg, lg, pg, wl.steps, wl.lr, losses=lossg, workspace=wsg, stream=stream,
                                   graph=use_graph)
 
         for _ in range(3):
-            grouped_call()
+            pg.copy_(pg0)
+            grouped_run()
         reps = max(5, args.steps // 4)
-        _, ms_g = timed_calls(grouped_call, 0, reps)
+        _, ms_g = timed_calls(grouped_run, 0, reps, before=lambda: pg.copy_(pg0))
         tg = spread(ms_g)["median"] * 1e-3
         grouped = {"clients": G, "head_steps_per_s": round(G * wl.steps / tg, 1),
                    "us_per_step": round(tg / wl.steps * 1e6, 2), "ms_per_call": spread(ms_g),
@@ -633,7 +647,7 @@ def main():
             if use_graph:
                 pf.call(graph=True)
             torch.cuda.synchronize()
-            _, ms_f = timed_calls(lambda: pf.call(graph=use_graph), 0, 30)
+            _, ms_f = timed_calls(lambda: pf.run(graph=use_graph), 0, 30, before=pf.reset)
             t_full = spread(ms_f)["median"]
             partial_vs_full = {"partial_us_per_step": round(ms_per_call / wl.steps * 1e3, 2),
                                "full_us_per_step": round(t_full / wl.steps * 1e3, 2),
@@ -674,7 +688,7 @@ def main():
                    "optimiser_steps_per_call": wl.steps, "lr": wl.lr, "momentum": wl.momentum, "optimizer": args.optimizer, "weighted_loss": bool(args.weighted_loss), "full_backward": bool(args.full_backward)},
         "step_definition": "one bench step = one st_partial_distill call = one key frame = "
                            f"{wl.steps} optimiser steps ({wl.steps + 1} forwards, {wl.steps} partial backwards, {wl.steps} updates); "
-                           "ms_per_step is the median time of such a call between HIP events on the calling stream; "
+                           "ms_per_step is the median time of such a call between HIP events on the calling stream (the head is re-initialised between the calls, outside the events); "
                            "`value` counts optimiser steps",
         "ms_per_key_frame": round(ms_per_call, 4),
         "ms_per_optimiser_step": round(ms_per_call / wl.steps, 5),
