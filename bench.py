@@ -168,7 +168,8 @@ class Problem:
         self.mious = torch.zeros((wl.steps + 1, wl.n), dtype=torch.float64, device="cuda")
         self.conf = torch.zeros((wl.n, wl.n_classes, wl.n_classes), dtype=torch.int64, device="cuda")
         self.ws = st.new_workspace(self.desc)
-        self.pw = torch.from_numpy(WL.object_weight_map(self.labels, radius=4)).cuda() if weighted else None
+        # loss weights of Section 5.2, made on the device from the labels (5 within 4 pixels of an object)
+        self.pw = st.st_object_weights(self.lab, wl.n_classes, 4, ignore_index=wl.ignore_index) if weighted else None
         self.dfeat = torch.empty((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda") if full_backward else None
         self.adam = dict(m=torch.zeros_like(self.p), v=torch.zeros_like(self.p), t0=0) if optimizer == "adam" else None
         torch.cuda.synchronize()
@@ -499,6 +500,29 @@ def main():
                  "launch_us": {k: round(v, 2) for k, v in mprof.items()},
                  "note": "st_miou; us_per_call is the whole call issued back to back from Python, avg_launch_us "
                          "the histogram kernel between its own events; 5 B per pixel"}
+    # the loss-weight map from the labels (st_object_weights, once per key frame when the weighted
+    # loss of Section 5.2 is used); streaming bound: 4 B label in + 1 B weight out per pixel
+    wmap = torch.empty((wl.n, wl.H, wl.W), dtype=torch.uint8, device="cuda")
+    ow_call = lambda: st.st_object_weights(lab, wl.n_classes, 4, ignore_index=wl.ignore_index, weights=wmap, stream=stream)
+    for _ in range(3):
+        ow_call()
+    _, ms_ow = timed_calls(ow_call, 0, 30)
+    st.st_profile_reset()
+    st.st_profile_enable(True)
+    for _ in range(reps):
+        ow_call()
+    torch.cuda.synchronize()
+    ow_us = {k: v[1] / v[0] * 1e3 for k, v in st.st_profile_read().items()}["object_weights"]
+    st.st_profile_enable(False)
+    st.st_profile_reset()
+    ow_bytes = 5.0 * wl.n * wl.H * wl.W
+    weights_pass = {"bound": "hbm", "kernel": "object_weights", "avg_launch_us": round(ow_us, 2),
+                    "achieved": round(ow_bytes / ow_us / 1e3, 1), "unit": "GB/s",
+                    "frac": round(ow_bytes / ow_us / 1e3 / PEAK_HBM_GBS, 5),
+                    "us_per_call": round(spread(ms_ow)["median"] * 1e3, 2),
+                    "note": "st_object_weights, radius 4; us_per_call is the call issued from Python between two events "
+                            "(median of 30), avg_launch_us its one kernel between events attached to the dispatch; "
+                            "5 B per pixel"}
     # the forward alone (what a frame that is no key frame costs a client): st_head_forward
     for _ in range(3):
         st.st_head_forward(desc, f, p, pred=pred, workspace=ws, stream=stream)
@@ -709,6 +733,7 @@ def main():
         "roofline": roofline,
         "other_kernels": others,
         "miou_pass": miou_pass,
+        "weights_pass": weights_pass,
         "head_forward": head_forward,
         "launch": "cached HIP graph (st_distill_opts.use_graph)" if use_graph
                   else (graph_note or "") + "kernel by kernel in the stream",

@@ -225,6 +225,22 @@ int st_partial_distill(const st_head_desc* desc, const void* features,
 int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_t n_classes,
             int32_t ignore_index, int64_t* confusion, double* miou, void* stream);
 
+/* Loss weights from the teacher's label map (Section 5.2: the cross-entropy of pixels near and within
+ * non-background objects is scaled by a factor of 5): weights = `factor` on every pixel that has, in
+ * its own frame, a pixel with an object label at most `radius` columns and at most `radius` rows
+ * away (itself included; the neighbourhood is cut off at the frame's edges), 1 on every other pixel.
+ * The paper gives the factor and not what "near" means: the radius is the caller's choice.  A label
+ * is an object when it lies in [0, n_classes) and is neither `background` nor `ignore_index`.
+ *   labels   [n, height, width] int32, read only
+ *   weights  [n, height, width] uint8 out, overwritten: what st_distill_opts.pixel_weights takes
+ *   0 <= radius <= ST_OBJECT_WEIGHTS_MAX_RADIUS, 1 <= factor <= 255 (ST_ERR_ARG otherwise);
+ *   1 <= n <= 65535, 1 <= height, width <= 2^19, n_classes >= 1 (ST_ERR_SHAPE otherwise).
+ * One launch on `stream`, no workspace; labels and weights must not overlap. */
+#define ST_OBJECT_WEIGHTS_MAX_RADIUS 32
+int st_object_weights(const int32_t* labels, int32_t n, int32_t height, int32_t width, int32_t n_classes,
+                      int32_t background, int32_t ignore_index, int32_t radius, int32_t factor, uint8_t* weights,
+                      void* stream);
+
 /* ---- scheduling arithmetic around the training step (host only, no GPU work) ------------- */
 
 /* Key-frame striding, Algorithm 2: the ratio of the next stride to the current one is linear in

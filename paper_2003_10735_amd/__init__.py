@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libshadowtutor_head.so")
 ST_OK = 0
 ST_ERR_NULL, ST_ERR_SHAPE, ST_ERR_ARG, ST_ERR_WORKSPACE, ST_ERR_HIP, ST_ERR_NO_DEVICE, ST_ERR_TOO_LARGE = -1, -2, -3, -4, -5, -6, -7
 ST_NOALLOC_MAX_WORKSPACE_MIB = 96
+ST_OBJECT_WEIGHTS_MAX_RADIUS = 32
 ST_F32, ST_BF16 = 0, 1
 ST_NCHW, ST_NHWC = 0, 1
 ST_COMPUTE_F32, ST_COMPUTE_BF16 = 0, 1
 ST_OPTIM_SGD, ST_OPTIM_ADAM = 0, 1
 
 EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_head_forward_noalloc", "st_partial_distill",
-           "st_miou", "st_strerror", "st_last_hip_error", "st_version",
+           "st_miou", "st_object_weights", "st_strerror", "st_last_hip_error", "st_version",
            "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read",
            "st_next_stride", "st_schedule_bounds", "st_schedule_total_time",
            "st_graph_cache_clear", "st_graph_cache_size"]
@@ -114,6 +115,8 @@ def lib():
         L.st_miou.restype = C.c_int
         L.st_miou.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p,
                               C.c_void_p, C.c_void_p]
+        L.st_object_weights.restype = C.c_int
+        L.st_object_weights.argtypes = [C.c_void_p] + [C.c_int32] * 8 + [C.c_void_p, C.c_void_p]
         L.st_strerror.restype = C.c_char_p
         L.st_strerror.argtypes = [C.c_int]
         L.st_last_hip_error.restype = C.c_int
@@ -274,6 +277,19 @@ def st_miou(pred, labels, n_classes: int, ignore_index: int = -1, confusion=None
     _check(lib().st_miou(_ptr(pred), _ptr(labels), pred.numel(), n_classes, ignore_index,
                          _ptr(confusion), _ptr(miou), _stream(stream)), "st_miou")
     return confusion, miou
+
+
+def st_object_weights(labels, n_classes: int, radius: int, factor: int = 5, background: int = 0,
+                      ignore_index: int = -1, weights=None, stream=None):
+    """labels int32 [n, H, W] cuda tensor -> uint8 [n, H, W] loss weights (`factor` within `radius`
+    pixels of an object label, 1 elsewhere): the `pixel_weights` of st_partial_distill."""
+    import torch
+    n, H, W = labels.shape
+    if weights is None:
+        weights = torch.empty((n, H, W), dtype=torch.uint8, device=labels.device)
+    _check(lib().st_object_weights(_ptr(labels), n, H, W, n_classes, background, ignore_index, radius, factor,
+                                   _ptr(weights), _stream(stream)), "st_object_weights")
+    return weights
 
 
 def st_graph_cache_clear():

@@ -724,6 +724,20 @@ int st_miou(const uint8_t* pred, const int32_t* labels, int64_t n_pixels, int32_
     return c.status;
 }
 
+int st_object_weights(const int32_t* labels, int32_t n, int32_t height, int32_t width, int32_t n_classes,
+                      int32_t background, int32_t ignore_index, int32_t radius, int32_t factor, uint8_t* weights,
+                      void* stream)
+{
+    // the grid is (column tiles, row tiles, frames): the last two dimensions hold at most 65535 blocks
+    if (n < 1 || n > 65535 || height < 1 || height > (1 << 19) || width < 1 || width > (1 << 19) || n_classes < 1)
+        return ST_ERR_SHAPE;
+    if (radius < 0 || radius > ST_OBJECT_WEIGHTS_MAX_RADIUS || factor < 1 || factor > 255) return ST_ERR_ARG;
+    if (!labels || !weights) return ST_ERR_NULL;
+    Ctx c{as_stream(stream), ST_OK};
+    object_weights(c, labels, n, height, width, n_classes, background, ignore_index, radius, factor, weights);
+    return c.status;
+}
+
 void st_graph_cache_clear(void)
 {
     std::lock_guard<std::mutex> lk(g_graph_mutex);

@@ -73,4 +73,8 @@ void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
                         long long* conf, double* miou);
 
+// k_weights.hip
+void object_weights(Ctx& c, const int32_t* labels, int n, int H, int W, int C, int background, int ignore, int radius,
+                    int factor, uint8_t* out);
+
 }  // namespace st

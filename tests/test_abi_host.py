@@ -112,6 +112,18 @@ def test_null_and_argument_errors():
     assert na(C.byref(cd), None, dummy, None, None, None) == st.ST_ERR_NULL
     big = st.HeadDesc(1, 256, 135, 240, 128, 128, 19).c()
     assert na(C.byref(big), dummy, dummy, None, None, None) == st.ST_ERR_TOO_LARGE
+    # the loss-weight map: shape, then value arguments, then pointers
+    ow = L.st_object_weights
+    assert ow(dummy, 0, 8, 8, 19, 0, -1, 4, 5, dummy, None) == st.ST_ERR_SHAPE
+    assert ow(dummy, 1, 8, 0, 19, 0, -1, 4, 5, dummy, None) == st.ST_ERR_SHAPE
+    assert ow(dummy, 70000, 8, 8, 19, 0, -1, 4, 5, dummy, None) == st.ST_ERR_SHAPE
+    assert ow(dummy, 1, 8, 8, 0, 0, -1, 4, 5, dummy, None) == st.ST_ERR_SHAPE
+    assert ow(dummy, 1, 8, 8, 19, 0, -1, -1, 5, dummy, None) == st.ST_ERR_ARG
+    assert ow(dummy, 1, 8, 8, 19, 0, -1, st.ST_OBJECT_WEIGHTS_MAX_RADIUS + 1, 5, dummy, None) == st.ST_ERR_ARG
+    assert ow(dummy, 1, 8, 8, 19, 0, -1, 4, 0, dummy, None) == st.ST_ERR_ARG
+    assert ow(dummy, 1, 8, 8, 19, 0, -1, 4, 256, dummy, None) == st.ST_ERR_ARG
+    assert ow(None, 1, 8, 8, 19, 0, -1, 4, 5, dummy, None) == st.ST_ERR_NULL
+    assert ow(dummy, 1, 8, 8, 19, 0, -1, 4, 5, None, None) == st.ST_ERR_NULL
     for s in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert L.st_strerror(s)
 
