@@ -93,6 +93,16 @@ def test_720p_adam_all_steps():
     check_adam(wl, f, lab, p, wl.steps, True, 2e-3, 2e-2)
 
 
+def test_720p_paper_recipe_all_steps():
+    """Adam at learning rate 0.01 on the cross-entropy weighted x5 within 4 pixels of an object
+    (Section 5.2: the optimiser and the loss of the paper's experiments), the weight map made by
+    st_object_weights, at the benchmark's shape for all eight steps."""
+    from test_gpu_parity import check_adam
+    wl = WL.WORKLOADS["720p"]
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    check_adam(wl, f, lab, p, wl.steps, True, 2e-3, 2e-2, object_radius=4)
+
+
 def test_720p_weighted_loss_all_steps():
     """Per-pixel loss weights (Section 5.2) at the benchmark's shape, all eight steps."""
     from test_gpu_parity import check_weighted

@@ -407,7 +407,7 @@ def test_matrix_core_path_small_shapes(case):
 
 
 # ------------------------------------------------------------------ Adam (the paper's optimiser, Section 5.2)
-def run_gpu_adam(wl, feats, labels, params, steps, t0=0, m=None, v=None):
+def run_gpu_adam(wl, feats, labels, params, steps, t0=0, m=None, v=None, object_radius=None):
     import torch
     import paper_2003_10735_amd as st
     from gpu_util import to_dev_features
@@ -416,23 +416,31 @@ def run_gpu_adam(wl, feats, labels, params, steps, t0=0, m=None, v=None):
     mt = torch.from_numpy((m if m is not None else np.zeros_like(params)).astype(np.float32)).cuda()
     vt = torch.from_numpy((v if v is not None else np.zeros_like(params)).astype(np.float32)).cuda()
     losses = torch.full((steps + 1,), float("nan"), dtype=torch.float32, device="cuda")
-    taken, _ = st.st_partial_distill(desc, to_dev_features(wl, feats), torch.from_numpy(labels).cuda(), p, steps,
-                                     wl.lr, losses=losses, adam=dict(m=mt, v=vt, t0=t0))
+    lab = torch.from_numpy(labels).cuda()
+    # the loss weights of Section 5.2, made by the library from the labels
+    wts = None if object_radius is None else st.st_object_weights(lab, wl.n_classes, object_radius, factor=5,
+                                                                 ignore_index=wl.ignore_index)
+    taken, _ = st.st_partial_distill(desc, to_dev_features(wl, feats), lab, p, steps,
+                                     wl.lr, losses=losses, adam=dict(m=mt, v=vt, t0=t0), pixel_weights=wts)
     torch.cuda.synchronize()
     assert taken == steps
     return dict(params=p.cpu().numpy(), m=mt.cpu().numpy(), v=vt.cpu().numpy(), losses=losses.cpu().numpy())
 
 
-def check_adam(wl, feats, labels, params, steps, bf16_operands, loss_tol, tol):
+def check_adam(wl, feats, labels, params, steps, bf16_operands, loss_tol, tol, object_radius=None):
     """Adam's update m / (sqrt(v) + eps) is (nearly) the sign of the gradient where the
     gradient is tiny, so two correct implementations whose gradients differ in the last bits
     may move such a parameter in opposite directions.  Elementwise parity of the weights is
     therefore required only where the oracle's own first gradient is not tiny; the losses, the
     second moments (continuous in g) and the share of excused elements are checked as well."""
     d = O.desc_of(wl, bf16_operands)
+    if object_radius is not None:       # with the x5 weighting near objects: the oracle's own map
+        from oracle import object_weights as OW
+        d = O.with_pixel_weights(d, OW.object_weights(labels, wl.n_classes, object_radius, factor=5,
+                                                      ignore_index=wl.ignore_index))
     f64 = WL.features_as_f64(wl, feats)
     o = O.partial_distill_opt(d, f64, labels, params.astype(np.float64), steps, O.adam_optim(wl.lr))
-    g = run_gpu_adam(wl, feats, labels, params, steps)
+    g = run_gpu_adam(wl, feats, labels, params, steps, object_radius=object_radius)
     np.testing.assert_allclose(g["losses"], o["losses"], rtol=loss_tol, atol=loss_tol)
     _, g0, _, _, _ = O.loss_and_grad(d, f64, labels, params.astype(np.float64))
     solid = np.abs(g0) > 1e-3 * np.abs(g0).max()
@@ -460,6 +468,16 @@ def test_adam_matrix_core_path():
     wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3, lr=0.01)
     f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
     check_adam(wl, f, lab, p, 3, True, 2e-3, 2e-2)
+
+
+def test_adam_with_object_weights_matrix_core_path():
+    """The training recipe of the paper's experiments (Section 5.2): Adam at learning rate 0.01
+    on the cross-entropy weighted x5 near and within objects."""
+    wl = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=3, lr=0.01)
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    g, _ = check_adam(wl, f, lab, p, 3, True, 2e-3, 2e-2, object_radius=3)
+    plain = run_gpu_adam(wl, f, lab, p, 3)
+    assert abs(g["losses"][0] - plain["losses"][0]) > 1e-3        # the weights do change the loss
 
 
 # ------------------------------------------------------------------ weighted cross-entropy (Section 5.2)
