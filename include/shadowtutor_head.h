@@ -23,8 +23,9 @@
  *     library neither frees nor keeps any of them after the call returns.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Calls return without synchronising, except st_partial_distill with a positive
- *     `threshold`, whose loop exits are decided on the host (one small device-to-host read per
- *     iteration) and which has finished when it returns.  (From the second read on, the stream
+ *     `threshold`, whose loop exits are decided on the host (every iteration hands its metric to
+ *     the host through a small page-locked buffer the library keeps per calling thread) and which
+ *     has finished when it returns.  (From the second read on, the stream
  *     already computes the iteration's gradients while the host waits; when the loop ends there
  *     they are left unused in the workspace and no parameter has changed.  A call whose first
  *     metric already reaches the threshold -- the frame is no key frame -- costs one forward
@@ -315,6 +316,14 @@ typedef struct st_workspace_layout {
 } st_workspace_layout;
 
 int st_get_workspace_layout(const st_head_desc* desc, st_workspace_layout* out);
+
+/* How st_partial_distill with a positive threshold waits for each iteration's metric.  1 (the
+ * default): the host polls the page-locked buffer the bookkeeping kernel writes, so nothing sits
+ * in the stream between a pass and the kernels queued behind it; a thread whose polls time out
+ * (host memory that is not coherent while a kernel runs) falls back by itself.  0: the host waits
+ * on an event recorded behind the bookkeeping kernel (or on the stream), as on such a platform.
+ * Results are identical either way.  Process-wide; takes effect from the next iteration on. */
+void st_metric_polling(int on);
 
 /* Per-kernel timing: when enabled, every kernel launch of the calls above is bracketed by a
  * pair of HIP events on the caller's stream.  st_profile_read synchronises those events and

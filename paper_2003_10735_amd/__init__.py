@@ -28,7 +28,7 @@ EXPORTS = ["st_num_params", "st_workspace_bytes", "st_head_forward", "st_head_fo
            "st_miou", "st_object_weights", "st_strerror", "st_last_hip_error", "st_version",
            "st_get_workspace_layout", "st_profile_enable", "st_profile_filter", "st_profile_reset", "st_profile_read",
            "st_next_stride", "st_schedule_bounds", "st_schedule_total_time",
-           "st_graph_cache_clear", "st_graph_cache_size"]
+           "st_graph_cache_clear", "st_graph_cache_size", "st_metric_polling"]
 
 
 class StHeadDesc(C.Structure):
@@ -298,6 +298,10 @@ def st_graph_cache_clear():
 
 def st_graph_cache_size() -> int:
     return int(lib().st_graph_cache_size())
+
+
+def st_metric_polling(on: bool):
+    lib().st_metric_polling(1 if on else 0)
 
 
 def st_profile_enable(on: bool):

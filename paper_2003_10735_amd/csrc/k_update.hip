@@ -53,6 +53,8 @@ struct UpdateArgs {
     // parameter-like vectors (theta, vel, vel2), the caller's vectors, the partial gradients,
     // the bfloat16 copies and the layer-3 slots
     size_t hs_param, hs_ext, hs_grad, hs_wq1, hs_wq2, hs_wq3, hs_part3;
+    // early-exit form only: with do_step, receives theta as it was before the step (theta's order), or null
+    float* save_old;
 };
 
 struct FinishArgs {
@@ -60,6 +62,9 @@ struct FinishArgs {
     int n, C; float* loss_out; double* miou_a; double* miou_b; long long* conf_out;
     // per head (blockIdx.y): fph frames and pph tile losses; one head owns all of them
     int fph, pph;
+    // early-exit form only: host memory that also receives the per-frame metric, each value followed by
+    // the pass's token in token_c (or null)
+    double* miou_c; unsigned long long* token_c; unsigned long long token;
 };
 
 // index in the caller's vector (3x3 weights OIHW) of the internal parameter j ([o][kh][kw][i])
@@ -76,11 +81,15 @@ __device__ __forceinline__ size_t external_index(const UpdateArgs& a, size_t j)
     return j;
 }
 
+// (EE: the early-exit form's extras -- save_old here, the host copy of the metric in finish_block --
+//  are compiled in; the kernels of the fixed-step form never look at those fields)
+template <bool EE>
 __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, float g)
 {
     float w = a.ext_in ? a.ext_in[external_index(a, j)] : a.theta[j];
     if (a.ext_in) a.theta[j] = w;
     if (a.do_step) {
+        if (EE && a.save_old) a.save_old[j] = w;
         if (a.adam) {
             const float m = __builtin_fmaf(a.ad.beta1, a.vel[j], a.ad.one_minus_beta1 * g);
             const float v = __builtin_fmaf(a.ad.beta2, a.vel2[j], a.ad.one_minus_beta2 * (g * g));
@@ -123,6 +132,7 @@ __device__ __forceinline__ void apply_update(const UpdateArgs& a, size_t j, floa
 
 // Four consecutive parameters (all block boundaries below W3 are multiples of four here, so
 // the four lie in the same block).
+template <bool EE>
 __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32x4 g)
 {
     f32x4 w;
@@ -132,6 +142,7 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
         *(f32x4*)(a.theta + j) = w;
     } else w = *(const f32x4*)(a.theta + j);
     if (a.do_step) {
+        if (EE && a.save_old) *(f32x4*)(a.save_old + j) = w;
         if (a.adam) {
             const f32x4 mo = *(const f32x4*)(a.vel + j), vo = *(const f32x4*)(a.vel2 + j);
             f32x4 m, v;
@@ -183,6 +194,7 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
     }
 }
 
+template <bool EE>
 __device__ void finish_block(const FinishArgs& f, int block, int head)
 {
     __shared__ double part[256];
@@ -235,13 +247,21 @@ __device__ void finish_block(const FinishArgs& f, int block, int head)
         const double m = cnt ? sum / cnt : 0.0;
         if (f.miou_a) f.miou_a[block] = m;
         if (f.miou_b) f.miou_b[block] = m;
+        if (EE && f.miou_c) {
+            // host memory: the value, then the pass's token as a release at system scope, so a host
+            // that sees the token also sees the value
+            f.miou_c[block] = m;
+            if (f.token_c) __hip_atomic_store(&f.token_c[block], f.token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
+template <bool EE>
 __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f, int b, int head)
 {
     if (head) {
         if (a.theta) { a.theta += head * a.hs_param; a.vel += head * a.hs_param; a.vel2 += head * a.hs_param; }
+        if (EE && a.save_old) a.save_old += head * a.hs_param;
         if (a.grad) a.grad += head * a.hs_grad;
         if (a.wq1) { a.wq1 += head * a.hs_wq1; a.wq2 += head * a.hs_wq2; a.wq3 += head * a.hs_wq3; }
         if (a.wq1t) a.wq1t += head * a.hs_wq1;
@@ -272,7 +292,7 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
                 }
                 for (; s < splits; ++s) g += *(const f32x4*)(gp + (size_t)s * a.stride);
             }
-            apply_update4(a, j, g);
+            apply_update4<EE>(a, j, g);
             return;
         }
         // role (1), one parameter per thread; W3/b3 are left to role (2) when it is active
@@ -285,7 +305,7 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
             g = a.grad[j];
             for (int s = 1; s < splits; ++s) g += a.grad[(size_t)s * a.stride + j];
         }
-        apply_update(a, j, g);
+        apply_update<EE>(a, j, g);
     } else if (b < a.nb_main + a.nb_tail) {
         // [W3, total) one by one (only when role (2) is not active)
         const size_t j = a.po.W3 + (size_t)(b - a.nb_main) * 256 + threadIdx.x;
@@ -295,7 +315,7 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
             g = a.grad[j];
             for (int s = 1; s < a.splits3; ++s) g += a.grad[(size_t)s * a.stride + j];
         }
-        apply_update(a, j, g);
+        apply_update<EE>(a, j, g);
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3) {
         // role (2): slot layout [32 classes][c2] weights, then [32] biases.  The slots were
         // written by other compute units, so every load is a round trip to memory: the role is
@@ -336,10 +356,10 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
             float total = run_sum[0][kk];
 #pragma unroll
             for (int r = 1; r < 16; ++r) total += run_sum[r][kk];
-            apply_update(a, a.po.W3 + k, total);
+            apply_update<EE>(a, a.po.W3 + k, total);
         }
     } else if (b < a.nb_main + a.nb_tail + a.nb_l3 + a.nb_finish) {
-        finish_block(f, b - a.nb_main - a.nb_tail - a.nb_l3, head);
+        finish_block<EE>(f, b - a.nb_main - a.nb_tail - a.nb_l3, head);
     } else {
         // parameters back to the caller's order
         const size_t j = (size_t)(b - a.nb_main - a.nb_tail - a.nb_l3 - a.nb_finish) * 256 + threadIdx.x;
@@ -347,9 +367,10 @@ __device__ __forceinline__ void step_end_block(UpdateArgs a, const FinishArgs& f
     }
 }
 
+template <bool EE>
 __global__ void __launch_bounds__(256) k_step_end(UpdateArgs a, FinishArgs f)
 {
-    step_end_block(a, f, blockIdx.x, blockIdx.y);
+    step_end_block<EE>(a, f, blockIdx.x, blockIdx.y);
 }
 
 // The launch that opens a call: three kinds of blocks that do not depend on each other,
@@ -398,10 +419,12 @@ __global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, F
         }
         return;
     }
-    step_end_block(a, f, b % q.nb_update, b / q.nb_update);
+    step_end_block<false>(a, f, b % q.nb_update, b / q.nb_update);
 }
 
-static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out)
+static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                              double* miou_host = nullptr, unsigned long long* token_host = nullptr,
+                              unsigned long long token = 0)
 {
     FinishArgs f;
     f.loss_part = (const float*)(ws + p.loss_part);
@@ -414,6 +437,8 @@ static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* 
     f.loss_out = loss_out;
     f.miou_a = (double*)(ws + p.scal);   // per-frame metric kept in the workspace (host-side loop exits)
     f.miou_b = miou_out;                 // the caller's array (may be null)
+    f.miou_c = miou_host;                // host memory the device can write (may be null): the loop exits read it
+    f.token_c = token_host; f.token = token;
     f.conf_out = conf_out;
     return f;
 }
@@ -432,9 +457,10 @@ static void head_strides(UpdateArgs& a, const Plan& p)
 // do_step: optimiser step (else only the bfloat16 copies are refreshed);
 // finish: also close the forward pass that preceded it (loss, per-frame mIoU, counts)
 static int step_end_args(const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish,
-                         const float* ext_in, bool w1t, const FinishArgs& f, UpdateArgs& a)
+                         const float* ext_in, bool w1t, const FinishArgs& f, UpdateArgs& a, float* save_old = nullptr)
 {
     a.theta = (float*)(ws + p.theta);
+    a.save_old = do_step ? save_old : nullptr;
     a.vel = (float*)(ws + p.vel);
     a.vel2 = (float*)(ws + p.vel2);
     a.ext_in = do_step ? nullptr : ext_in; a.ext_out = nullptr; a.nb_out = 0;
@@ -475,15 +501,16 @@ static int step_end_args(const Plan& p, char* ws, float lr, float mu, const Adam
 }
 
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
-              double* miou_out, long long* conf_out, const float* ext_in, bool w1t)
+              double* miou_out, long long* conf_out, const float* ext_in, bool w1t, float* save_old)
 {
     UpdateArgs a;
     const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
-    const int blocks = step_end_args(p, ws, lr, mu, adam, do_step, finish, ext_in, w1t, f, a);
+    const int blocks = step_end_args(p, ws, lr, mu, adam, do_step, finish, ext_in, w1t, f, a, save_old);
     if (blocks == 0) return;
     const bool params = do_step || p.bf16 || a.ext_in;
     const char* name = a.ext_in ? "params_in+weights_to_bf16" : do_step ? (adam ? (finish ? "adam_update+finish_pass" : "adam_update") : (finish ? "sgd_update+finish_pass" : "sgd_update")) : (params ? "weights_to_bf16" : "finish_pass");
-    ST_LAUNCH(c, name, k_step_end, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
+    if (a.save_old) ST_LAUNCH(c, name, k_step_end<true>, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
+    else ST_LAUNCH(c, name, k_step_end<false>, dim3(blocks, p.g.heads()), dim3(256), 0, a, f);
 }
 
 // Whether the packing role of the call-opening launch writes the whole padded grid of both feature
@@ -536,11 +563,11 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
 // bookkeeping of a pass without an update; with ext_out the same launch hands theta back to the
 // caller's vector (OIHW order)
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
-                 float* ext_out)
+                 float* ext_out, double* miou_host, unsigned long long* token_host, unsigned long long token)
 {
     UpdateArgs a;
     memset(&a, 0, sizeof(a));
-    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out);
+    const FinishArgs f = finish_args(p, ws, loss_out, miou_out, conf_out, miou_host, token_host, token);
     a.nb_finish = f.fph + 1;
     head_strides(a, p);
     if (ext_out) {
@@ -549,8 +576,12 @@ void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_
         a.ext_out = ext_out;
         a.nb_out = cdiv(p.po.total, 256);
     }
-    ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end,
-              dim3(a.nb_finish + a.nb_out, p.g.heads()), dim3(256), 0, a, f);
+    if (miou_host)
+        ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end<true>,
+                  dim3(a.nb_finish + a.nb_out, p.g.heads()), dim3(256), 0, a, f);
+    else
+        ST_LAUNCH(c, ext_out ? "finish_pass+params_out" : "finish_pass", k_step_end<false>,
+                  dim3(a.nb_finish + a.nb_out, p.g.heads()), dim3(256), 0, a, f);
 }
 
 // Mean IoU (Eq. 1) of a C x C table of counts, any C up to 256: one wavefront per class adds

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+#include <chrono>
 #include <mutex>
 #include <string>
 #include <utility>
@@ -189,28 +191,71 @@ Plan make_plan(const st_head_desc& d)
 
 static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
-// Page-locked host memory for the per-iteration metric read-back of the early-exit form (a copy
-// into pageable memory goes through a staging buffer and costs several times as much).  One
-// buffer per calling thread, grown on demand and kept until the process ends; nullptr if the
-// allocation fails (the caller then reads back into ordinary memory).
-static double* pinned_metric_buffer(size_t count)
+// Page-locked host memory for the per-iteration metric of the early-exit form.  The bookkeeping
+// kernel writes the per-frame metric into it directly and, behind each value, a token the host
+// chose for this pass (a release store at system scope); the host polls the tokens, so nothing
+// sits in the stream between the pass and the backward kernels that follow it.  The buffer is
+// asked for as host-coherent memory; should the tokens not show up within a bounded wait (the
+// memory turned out not to be coherent while a kernel runs), the host synchronises the stream
+// instead and this thread stops polling for good.  Where the device cannot address the buffer at
+// all (`dev` null) the metric is copied into it (a copy into pageable memory would go through a
+// staging buffer and cost several times as much).  One buffer per calling thread, grown on demand
+// and kept until the process ends; `host` null if the allocation fails (the caller then reads
+// back into ordinary memory).
+static std::atomic<bool> g_metric_polling{true};   // st_metric_polling
+
+struct MetricBuffer {
+    double* host = nullptr;                  // [cap] per-frame metric
+    volatile unsigned long long* tok = nullptr;   // [cap] token of the pass that wrote it
+    double* dev = nullptr;                   // the same two arrays as kernels address them
+    unsigned long long* dev_tok = nullptr;
+    size_t cap = 0;
+    unsigned long long next_token = 1;       // never repeats within the buffer's life
+    bool poll = true;
+};
+
+static MetricBuffer& metric_buffer(size_t count)
 {
-    static thread_local double* buf = nullptr;
-    static thread_local size_t cap = 0;
-    if (count > cap) {
-        if (buf) (void)hipHostFree(buf);
-        buf = nullptr;
-        cap = 0;
+    static thread_local MetricBuffer b;
+    if (count > b.cap) {
+        if (b.host) (void)hipHostFree(b.host);
+        b.host = b.dev = nullptr; b.tok = nullptr; b.dev_tok = nullptr; b.cap = 0;
         const size_t want = std::max(count, (size_t)512);
         void* ptr = nullptr;
-        if (hipHostMalloc(&ptr, want * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+        hipError_t e = hipHostMalloc(&ptr, want * 16, hipHostMallocMapped | hipHostMallocCoherent);
+        if (e != hipSuccess) {
             (void)hipGetLastError();
-            return nullptr;
+            b.poll = false;
+            e = hipHostMalloc(&ptr, want * 16, hipHostMallocDefault);
         }
-        buf = (double*)ptr;
-        cap = want;
+        if (e != hipSuccess) { (void)hipGetLastError(); return b; }
+        memset(ptr, 0, want * 16);
+        b.host = (double*)ptr;
+        b.tok = (volatile unsigned long long*)(b.host + want);
+        b.cap = want;
+        void* dptr = nullptr;
+        if (hipHostGetDevicePointer(&dptr, ptr, 0) == hipSuccess) {
+            b.dev = (double*)dptr;
+            b.dev_tok = (unsigned long long*)(b.dev + want);
+        } else (void)hipGetLastError();
     }
-    return buf;
+    return b;
+}
+
+// Waits until the first `count` tokens of the buffer equal `token`, at most `limit_us`.
+static bool wait_for_tokens(const MetricBuffer& b, size_t count, unsigned long long token, double limit_us)
+{
+    const auto t0 = std::chrono::steady_clock::now();
+    for (size_t f = 0; f < count; ++f) {
+        unsigned spins = 0;
+        while (b.tok[f] != token) {
+            if ((++spins & 255u) == 0 &&
+                std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count() > limit_us)
+                return false;
+        }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return true;
 }
 
 // An event per calling thread and device for the same read-back: the host waits for the copy of
@@ -607,7 +652,9 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     double best_metric = -1.0, first_metric = -1.0;
     std::vector<double> frame_metric;
     int taken = 0;
-    bool have_best = false;
+    // best_student of Algorithm 1: while the best parameters so far are the current ones nothing is
+    // copied; the optimiser kernel that overwrites them leaves them in the workspace on its way
+    bool have_best = false, best_is_theta = false;
     const bool keep_best = early_exit && (return_best || best_params);
     bool params_out_done = false;
     for (int it = 0; it <= steps; ++it) {
@@ -630,7 +677,16 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         const bool finish_now = last || early_exit;
         // (the last pass of the fixed-step form also hands the parameters back in the same launch)
         const bool out_now = last && !early_exit;
-        if (finish_now) finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr);
+        // In the early-exit form the bookkeeping kernel also writes the per-frame metric straight
+        // into pinned host memory: the host reads it after the event behind that kernel, and no
+        // copy sits in the stream between the pass and the backward kernels that follow.
+        MetricBuffer* mb = early_exit ? &metric_buffer((size_t)g.n) : nullptr;
+        double* metric_host = mb ? mb->host : nullptr;
+        const bool device_writes = mb && mb->host && mb->dev;
+        const unsigned long long token = device_writes ? mb->next_token++ : 0;
+        if (finish_now)
+            finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr,
+                        device_writes ? mb->dev : nullptr, device_writes ? mb->dev_tok : nullptr, token);
         params_out_done = params_out_done || out_now;
         bool stop = last;
         // In the early-exit form the backward pass of an iteration is put into the stream before
@@ -643,17 +699,29 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         bool backward_queued = false;
         if (early_exit) {
             // Algorithm 1 decides its exits on the metric: one small read-back per iteration
-            double* metric_host = pinned_metric_buffer((size_t)g.n);
-            if (!metric_host) { frame_metric.resize(g.n); metric_host = frame_metric.data(); }
-            ST_HIP(c, hipMemcpyAsync(metric_host, metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost, c.stream));
-            hipEvent_t ev = (!last && !feature_grad && it > 0) ? readback_event() : nullptr;
-            if (ev) {
-                ST_HIP(c, hipEventRecord(ev, c.stream));
-                backward(c, p, ws, nullptr);
-                backward_queued = true;
-                ST_HIP(c, hipEventSynchronize(ev));
+            if (!device_writes) {   // no pinned buffer the device can write: copy the metric
+                if (!metric_host) { frame_metric.resize(g.n); metric_host = frame_metric.data(); }
+                ST_HIP(c, hipMemcpyAsync(metric_host, metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost, c.stream));
+            }
+            const bool speculate = !last && !feature_grad && it > 0;
+            if (device_writes && mb->poll && g_metric_polling.load(std::memory_order_relaxed) && c.status == ST_OK) {
+                if (speculate) { backward(c, p, ws, nullptr); backward_queued = true; }
+                if (!wait_for_tokens(*mb, (size_t)g.n, token, 20000.0)) {
+                    // not seen while the stream runs: wait for the stream, and do so from now on
+                    mb->poll = false;
+                    ST_HIP(c, hipStreamSynchronize(c.stream));
+                    if (c.status == ST_OK && !wait_for_tokens(*mb, (size_t)g.n, token, 0.0)) c.status = ST_ERR_HIP;
+                }
             } else {
-                ST_HIP(c, hipStreamSynchronize(c.stream));
+                hipEvent_t ev = speculate ? readback_event() : nullptr;
+                if (ev) {
+                    ST_HIP(c, hipEventRecord(ev, c.stream));
+                    backward(c, p, ws, nullptr);
+                    backward_queued = true;
+                    ST_HIP(c, hipEventSynchronize(ev));
+                } else {
+                    ST_HIP(c, hipStreamSynchronize(c.stream));
+                }
             }
             if (c.status != ST_OK) break;
             double metric = 0.0;
@@ -663,15 +731,11 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                 first_metric = metric;
                 best_metric = metric;
                 if (!(metric < threshold)) stop = true;   // already good enough: no update at all
-                else if (keep_best) {
-                    ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
-                    have_best = true;
-                }
+                else if (keep_best) have_best = best_is_theta = true;
             } else {
                 if (metric > best_metric) {
                     best_metric = metric;
-                    if (keep_best)
-                        ST_HIP(c, hipMemcpyAsync(ws + p.best, theta, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
+                    if (keep_best) best_is_theta = true;
                 }
                 if (strict ? metric > threshold : metric >= threshold) stop = true;
             }
@@ -692,11 +756,13 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             ad.inv_sqrt_bc2 = (float)(1.0 / sqrt(1.0 - pow(beta2, t)));
         }
         step_end(c, p, ws, lr, mu, use_adam ? &ad : nullptr, true, !finish_now, loss_out, miou_out, conf_out, nullptr,
-                 feature_grad != nullptr);
+                 feature_grad != nullptr, best_is_theta ? (float*)(ws + p.best) : nullptr);
+        best_is_theta = false;
         ++taken;
     }
-    if (early_exit && best_params) permute_params(c, p, have_best ? (const float*)(ws + p.best) : theta, best_params, 1);
-    if (early_exit && return_best && have_best && taken > 0)
+    const bool best_in_workspace = have_best && !best_is_theta;   // else the current parameters are the best
+    if (early_exit && best_params) permute_params(c, p, best_in_workspace ? (const float*)(ws + p.best) : theta, best_params, 1);
+    if (early_exit && return_best && best_in_workspace && taken > 0)
         ST_HIP(c, hipMemcpyAsync(theta, ws + p.best, p.po.total * 4, hipMemcpyDeviceToDevice, c.stream));
     // (a call that took no update -- not a key frame -- leaves the caller's vectors as they are)
     const bool untouched = early_exit && taken == 0;
@@ -771,6 +837,8 @@ const char* st_strerror(int status)
 int st_last_hip_error(void) { return g_last_hip_error; }
 
 const char* st_version(void) { return "0.1"; }
+
+void st_metric_polling(int on) { g_metric_polling.store(on != 0, std::memory_order_relaxed); }
 
 void st_profile_enable(int on)
 {

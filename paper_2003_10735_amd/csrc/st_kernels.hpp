@@ -67,9 +67,12 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
                 bool w1t, const int32_t* labels, const uint8_t* pixel_weights);
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
               double* miou_out, long long* conf_out, const float* ext_in = nullptr,
-              bool w1t = false);
+              bool w1t = false, float* save_old = nullptr);
+// miou_host: host memory the device can write (or null) that also receives the per-frame metric,
+// each value followed by `token` in token_host (a release store at system scope)
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
-                 float* ext_out = nullptr);
+                 float* ext_out = nullptr, double* miou_host = nullptr, unsigned long long* token_host = nullptr,
+                 unsigned long long token = 0);
 void confusion_and_miou(Ctx& c, const uint8_t* pred, const int32_t* labels, long long P, int C, int ignore,
                         long long* conf, double* miou);
 

@@ -358,6 +358,38 @@ def test_best_is_not_last_with_momentum():
     assert rel_err(r["velocity"], ora["velocity"]) < 2e-2
 
 
+def test_early_exit_polling_and_event_wait_agree():
+    """The early-exit loop reads each iteration's metric either by polling the host buffer the
+    bookkeeping kernel writes or by waiting on an event behind it (the fallback of a platform
+    whose host memory is not coherent while a kernel runs): both give the same run, bit for bit
+    -- steps taken, metrics, best parameters, last parameters, velocity."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, n_sites=5,
+                          label_seed=5, steps=8, lr=0.2, momentum=0.9)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    wm = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=4, lr=0.05)
+    fm, labm, pm = inputs(wm)
+    runs = []
+    try:
+        for polling in (True, False, True):
+            st.st_metric_polling(polling)
+            a = run_gpu(wl, f, lab, p, threshold=1.5, return_best=True)
+            b = run_gpu(wl, f, lab, p, threshold=float(a["mious"][2, 0]), strict_break=False)
+            c = run_gpu(wm, fm, labm, pm, threshold=1.5, return_best=False)
+            runs.append((a, b, c))
+    finally:
+        st.st_metric_polling(True)
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert x["steps_taken"] == y["steps_taken"] and x["best_metric"] == y["best_metric"]
+            assert x["first_metric"] == y["first_metric"]
+            for k in ("params", "mious", "losses", "pred", "conf"):
+                np.testing.assert_array_equal(x[k], y[k], err_msg=k)
+    np.testing.assert_array_equal(runs[0][0]["velocity"], runs[1][0]["velocity"])
+    assert 0 < runs[0][1]["steps_taken"] < 8
+
+
 def test_non_finite_parameters_stay_in_range():
     """A diverged head (every parameter NaN): the class map stays inside [0, C) -- class 0, the
     oracle's answer as well -- the confusion counts still hold every valid pixel exactly once,
