@@ -6,8 +6,11 @@
 //            db3[c]         = sum_pos g[c][pos]
 // with g = d loss / d z rounded to bfloat16 where it enters a product.  The class dimension
 // (<= 32) is padded to one 32-row MFMA tile with zeros.
+#include <string.h>
+
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
+#include "st_finish.hpp"
 
 namespace st {
 
@@ -33,14 +36,23 @@ constexpr int C3B_BP = 64;
 
 // (one or two wavefronts per SIMD are all this kernel asks for: said explicitly, because the
 //  compiler otherwise keeps to 128 registers and then issues the slot loads one at a time)
-template <int C2>
+//
+// FIN (early-exit form of the training call): the blocks behind the first `main_blocks` do the
+// bookkeeping of the forward pass that came before (finish_block: loss, per-frame mean IoU, the
+// metric for the host) instead -- it touches nothing this kernel reads or writes, and riding
+// along saves that pass a launch of its own.
+template <int C2, bool FIN>
 __global__ void __launch_bounds__(256, 1)
 k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
                  const unsigned long long* __restrict__ n_valid, int CP, LossTiling lt,
                  const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
                  const bf16* __restrict__ W3T, bf16* __restrict__ da2, bf16* __restrict__ da2T,
-                 float* __restrict__ part, Geo g, int PPT, int guard, int grp_blocks)
+                 float* __restrict__ part, Geo g, int PPT, int guard, int grp_blocks, int main_blocks, FinishArgs fin)
 {
+    if (FIN && (int)blockIdx.x >= main_blocks) {
+        finish_block<true>(fin, (int)blockIdx.x - main_blocks, 0);
+        return;
+    }
     constexpr int BP = C3B_BP;
     constexpr int OT = C2 / 32;            // channel tiles
     constexpr int OH = OT / 2;             // da2 channel tiles per wavefront
@@ -221,14 +233,29 @@ size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
                     const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
-                    bf16* da2, bf16* da2T, float* part)
+                    bf16* da2, bf16* da2T, float* part, const FinishArgs* finish)
 {
     const Geo& g = p.g;
     const int grp_blocks = conv3_bwd_blocks(g);
-    const dim3 grid(g.heads() * grp_blocks);
+    const int main_blocks = g.heads() * grp_blocks;
     const int CP = (g.C + 3) / 4 * 4;   // class padding of the loss kernel's slots
-#define ST_C3B(C2) ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2>), grid, dim3(256), 0, slots, T, n_valid, CP, \
-                             p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks)
+    FinishArgs fin;
+    memset(&fin, 0, sizeof(fin));
+    if (finish) {
+        if (g.grouped) { c.status = ST_ERR_ARG; return; }   // (the riding role serves one head)
+        fin = *finish;
+    }
+    // with `finish`: one more block per frame and one for the loss
+    const dim3 grid(main_blocks + (finish ? fin.fph + 1 : 0));
+#define ST_C3B(C2)                                                                                             \
+    do {                                                                                                       \
+        if (finish)                                                                                            \
+            ST_LAUNCH(c, "conv3_bwd_mfma+finish_pass", (k_conv3_bwd_mfma<C2, true>), grid, dim3(256), 0, slots, T,   \
+                      n_valid, CP, p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin); \
+        else                                                                                                   \
+            ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2, false>), grid, dim3(256), 0, slots, T, n_valid, CP, \
+                      p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin);    \
+    } while (0)
     switch (g.c2) {
     case 64: ST_C3B(64); break;
     case 128: ST_C3B(128); break;

@@ -8,6 +8,7 @@
 #include "st_kernels.hpp"
 #include "st_mfma.hpp"
 #include "st_begin.hpp"
+#include "st_finish.hpp"
 
 namespace st {
 
@@ -57,15 +58,6 @@ struct UpdateArgs {
     float* save_old;
 };
 
-struct FinishArgs {
-    const float* loss_part; int n_part; const unsigned long long* n_valid; unsigned long long* conf;
-    int n, C; float* loss_out; double* miou_a; double* miou_b; long long* conf_out;
-    // per head (blockIdx.y): fph frames and pph tile losses; one head owns all of them
-    int fph, pph;
-    // early-exit form only: host memory that also receives the per-frame metric, each value followed by
-    // the pass's token in token_c (or null)
-    double* miou_c; unsigned long long* token_c; unsigned long long token;
-};
 
 // index in the caller's vector (3x3 weights OIHW) of the internal parameter j ([o][kh][kw][i])
 __device__ __forceinline__ size_t external_index(const UpdateArgs& a, size_t j)
@@ -190,68 +182,6 @@ __device__ __forceinline__ void apply_update4(const UpdateArgs& a, size_t j, f32
 #pragma unroll
                 for (int e = 0; e < 4; ++e) a.wq2t[wfrag_index(i + e, 8 - tap, o, a.c2)] = q[e];
             } else *(bf16x4*)(a.wq2 + r) = q;
-        }
-    }
-}
-
-template <bool EE>
-__device__ void finish_block(const FinishArgs& f, int block, int head)
-{
-    __shared__ double part[256];
-    __shared__ unsigned long long cl[32 * 32];
-    __shared__ double iou[32];
-    __shared__ int present[32];
-    const int tid = threadIdx.x;
-    if (block == f.fph) {
-        double acc = 0.0;
-        const int per = (f.pph + 255) / 256;
-        const float* lp = f.loss_part + (size_t)head * f.pph;
-        for (int i = tid * per; i < min(f.pph, (tid + 1) * per); ++i) acc += (double)lp[i];
-        part[tid] = acc;
-        __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
-            if (tid < s) part[tid] += part[tid + s];
-            __syncthreads();
-        }
-        if (tid == 0 && f.loss_out) {
-            const unsigned long long nv = f.n_valid[head];
-            f.loss_out[head] = nv ? (float)(part[0] / (double)nv) : 0.f;
-        }
-        return;
-    }
-    block += head * f.fph;      // the frame
-    const int C = f.C;
-    unsigned long long* cf = f.conf + (size_t)block * C * C;
-    for (int i = tid; i < C * C; i += 256) {
-        const unsigned long long v = cf[i];
-        cl[i] = v;
-        if (f.conf_out) f.conf_out[(size_t)block * C * C + i] = (long long)v;
-        cf[i] = 0ull;
-    }
-    __syncthreads();
-    // IoU_c = conf[c][c] / (row_c + col_c - conf[c][c]) for classes with row_c > 0, added in
-    // ascending c in float64, divided by their number; 0 when no class is present
-    if (tid < C) {
-        unsigned long long row = 0, col = 0;
-        for (int k = 0; k < C; ++k) { row += cl[tid * C + k]; col += cl[k * C + tid]; }
-        const unsigned long long inter = cl[tid * C + tid];
-        present[tid] = row != 0;
-        iou[tid] = row ? (double)inter / (double)(row + col - inter) : 0.0;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double sum = 0.0;
-        int cnt = 0;
-        for (int c = 0; c < C; ++c)
-            if (present[c]) { sum += iou[c]; ++cnt; }
-        const double m = cnt ? sum / cnt : 0.0;
-        if (f.miou_a) f.miou_a[block] = m;
-        if (f.miou_b) f.miou_b[block] = m;
-        if (EE && f.miou_c) {
-            // host memory: the value, then the pass's token as a release at system scope, so a host
-            // that sees the token also sees the value
-            f.miou_c[block] = m;
-            if (f.token_c) __hip_atomic_store(&f.token_c[block], f.token, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
 }
@@ -422,9 +352,8 @@ __global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, F
     step_end_block<false>(a, f, b % q.nb_update, b / q.nb_update);
 }
 
-static FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
-                              double* miou_host = nullptr, unsigned long long* token_host = nullptr,
-                              unsigned long long token = 0)
+FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                       double* miou_host, unsigned long long* token_host, unsigned long long token)
 {
     FinishArgs f;
     f.loss_part = (const float*)(ws + p.loss_part);

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "st_kernels.hpp"
+#include "st_finish.hpp"
 
 namespace st {
 
@@ -382,7 +383,8 @@ static ZSrc z_source(const Plan& p, char* ws, float* z)
 // partial backward: gradients of the head's parameters only; nothing flows into the features
 // (with dfeat, the caller's float32 [n, c_in, h, w] tensor, the chain rule is continued one
 // more layer: what an unfrozen front part would need, and what partial distillation saves)
-static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat)
+// finish (matrix-core path only): the bookkeeping of the pass before rides on the first launch
+static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat, const FinishArgs* finish = nullptr)
 {
     if (!p.mfma) {
         generic_backward(c, p, ws);
@@ -393,7 +395,7 @@ static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat)
     float* grad = (float*)(ws + p.grad);
     conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
                    (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
-                   (const bf16*)(ws + p.wq3t), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3));
+                   (const bf16*)(ws + p.wq3t), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3), finish);
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
                  (const bf16*)(ws + p.a1), dfeat ? (bf16*)(ws + p.da1) : nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);
     if (dfeat)
@@ -684,7 +686,13 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         double* metric_host = mb ? mb->host : nullptr;
         const bool device_writes = mb && mb->host && mb->dev;
         const unsigned long long token = device_writes ? mb->next_token++ : 0;
-        if (finish_now)
+        // From the second pass on the backward kernels are queued before the host looks at the
+        // metric (below); on the matrix-core path the bookkeeping then rides on the first of them
+        // instead of taking a launch of its own.
+        const bool speculate = early_exit && !last && !feature_grad && it > 0;
+        const bool polled = device_writes && mb->poll && g_metric_polling.load(std::memory_order_relaxed);
+        const bool finish_rides = speculate && polled && p.mfma;
+        if (finish_now && !finish_rides)
             finish_pass(c, p, ws, loss_out, miou_out, conf_out, out_now ? head_params : nullptr,
                         device_writes ? mb->dev : nullptr, device_writes ? mb->dev_tok : nullptr, token);
         params_out_done = params_out_done || out_now;
@@ -703,9 +711,13 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                 if (!metric_host) { frame_metric.resize(g.n); metric_host = frame_metric.data(); }
                 ST_HIP(c, hipMemcpyAsync(metric_host, metric_dev, sizeof(double) * g.n, hipMemcpyDeviceToHost, c.stream));
             }
-            const bool speculate = !last && !feature_grad && it > 0;
-            if (device_writes && mb->poll && g_metric_polling.load(std::memory_order_relaxed) && c.status == ST_OK) {
-                if (speculate) { backward(c, p, ws, nullptr); backward_queued = true; }
+            if (polled && c.status == ST_OK) {
+                if (speculate) {
+                    FinishArgs fin;
+                    if (finish_rides) fin = finish_args(p, ws, loss_out, miou_out, conf_out, mb->dev, mb->dev_tok, token);
+                    backward(c, p, ws, nullptr, finish_rides ? &fin : nullptr);
+                    backward_queued = true;
+                }
                 if (!wait_for_tokens(*mb, (size_t)g.n, token, 20000.0)) {
                     // not seen while the stream runs: wait for the stream, and do so from now on
                     mb->poll = false;

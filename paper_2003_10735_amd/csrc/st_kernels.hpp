@@ -4,6 +4,8 @@
 
 namespace st {
 
+struct FinishArgs;   // st_finish.hpp: arguments of the bookkeeping role
+
 // k_layout.hip
 // regions to clear, each 16-byte aligned and padded to 16 bytes; one launch clears them all
 struct ZeroList {
@@ -34,9 +36,11 @@ void wgrad3x3_mfma(Ctx& c, const Plan& p, const bf16* da1T, const bf16* featT, c
 bool conv3_mfma_supported(int c2, int C);
 int conv3_bwd_blocks(const Geo& g);
 size_t conv3_bwd_slot_floats(const Geo& g);
+// finish: the bookkeeping of the pass that precedes this backward pass rides on the launch (a few more blocks)
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
                     const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
-                    bf16* da2, bf16* da2T, float* part);
+                    bf16* da2, bf16* da2T, float* part,
+                    const FinishArgs* finish = nullptr);
 
 // k_loss.hip
 size_t loss_slot_floats(const Geo& g);
@@ -68,6 +72,10 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
 void step_end(Ctx& c, const Plan& p, char* ws, float lr, float mu, const AdamStep* adam, bool do_step, bool finish, float* loss_out,
               double* miou_out, long long* conf_out, const float* ext_in = nullptr,
               bool w1t = false, float* save_old = nullptr);
+// arguments of the bookkeeping role; miou_host / token_host / token as for finish_pass
+FinishArgs finish_args(const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
+                       double* miou_host = nullptr, unsigned long long* token_host = nullptr,
+                       unsigned long long token = 0);
 // miou_host: host memory the device can write (or null) that also receives the per-frame metric,
 // each value followed by `token` in token_host (a release store at system scope)
 void finish_pass(Ctx& c, const Plan& p, char* ws, float* loss_out, double* miou_out, long long* conf_out,
