@@ -718,7 +718,8 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
                     backward(c, p, ws, nullptr, finish_rides ? &fin : nullptr);
                     backward_queued = true;
                 }
-                if (!wait_for_tokens(*mb, (size_t)g.n, token, 20000.0)) {
+                // (the wait is bounded by far more than a pass can take: 20 ms and 2 us per grid cell)
+                if (!wait_for_tokens(*mb, (size_t)g.n, token, 20000.0 + 2.0 * (double)g.positions())) {
                     // not seen while the stream runs: wait for the stream, and do so from now on
                     mb->poll = false;
                     ST_HIP(c, hipStreamSynchronize(c.stream));

@@ -49,6 +49,26 @@ def test_1080p_ignore_and_momentum_all_steps():
     compare_bf16(WL.WORKLOADS["1080p"], steps=None)
 
 
+@pytest.mark.timeout(600)
+def test_2160p_beyond_the_measured_sizes():
+    """A 3840x2160 key frame (nine times the benchmark's frame: every kernel's grid runs several
+    rounds of blocks, the loss kernel 4 050 tiles), two steps with momentum and ignored pixels,
+    against the oracle's bf16-operand mode."""
+    wl = WL.small_variant(WL.WORKLOADS["1080p"], h=270, w=480, n_sites=120, steps=2)
+    f, lab, p = WL.make_features(wl), WL.make_labels(wl), WL.make_head_params(wl)
+    gpu = run_gpu(wl, f, lab, p, steps=2)
+    check_staged_bit_exact(wl, gpu, lab)
+    orq = run_oracle(wl, f, lab, p, steps=2, bf16_operands=True, report="2160p bf16 operands")
+    progress("2160p 2 steps against the bf16-operand oracle: losses %.3g weights %.3g update %.3g" % (
+        rel_err(gpu["losses"], orq["losses"]), rel_err(gpu["params"], orq["params"]),
+        rel_err(gpu["params"] - p, orq["params"] - p)))
+    assert rel_err(gpu["losses"], orq["losses"]) < 5e-4
+    assert rel_err(gpu["params"], orq["params"]) < 5e-4
+    assert rel_err(gpu["params"] - p, orq["params"] - p) < 3e-2
+    assert rel_err(gpu["velocity"], orq["velocity"]) < 3e-2
+    np.testing.assert_allclose(gpu["mious"], orq["mious"], atol=5e-3)
+
+
 @pytest.mark.timeout(1500)
 def test_batch4_shared_head_all_steps():
     """Four frames, one shared head 320 -> 256 -> 256 -> 21, at its own length: sixteen steps.
