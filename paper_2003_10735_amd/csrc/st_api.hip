@@ -679,9 +679,10 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         const bool finish_now = last || early_exit;
         // (the last pass of the fixed-step form also hands the parameters back in the same launch)
         const bool out_now = last && !early_exit;
-        // In the early-exit form the bookkeeping kernel also writes the per-frame metric straight
-        // into pinned host memory: the host reads it after the event behind that kernel, and no
-        // copy sits in the stream between the pass and the backward kernels that follow.
+        // In the early-exit form the bookkeeping also writes the per-frame metric, and behind it the
+        // pass's token, straight into page-locked host memory; the host polls the token (or, where
+        // that is switched off, waits on an event), so no copy sits in the stream between the pass
+        // and the backward kernels that follow.
         MetricBuffer* mb = early_exit ? &metric_buffer((size_t)g.n) : nullptr;
         double* metric_host = mb ? mb->host : nullptr;
         const bool device_writes = mb && mb->host && mb->dev;
