@@ -18,6 +18,7 @@ constexpr int OW_TH = 16;                    // rows of a tile
 constexpr int OW_WORDS = 4;                  // 64-pixel words of a tile row
 constexpr int OW_TW = 64 * OW_WORDS;         // columns of a tile
 constexpr int OW_THREADS = 1024;
+constexpr int OW_BATCH = 12;                 // label loads a wavefront keeps in flight
 constexpr int OW_ROWS = OW_TH + 2 * ST_OBJECT_WEIGHTS_MAX_RADIUS;   // most mask rows a tile looks at
 static_assert(OW_THREADS * 4 == OW_TH * OW_TW, "four result pixels per thread");
 static_assert(ST_OBJECT_WEIGHTS_MAX_RADIUS < 64, "one neighbouring word per side");
@@ -35,13 +36,14 @@ k_object_weights(const int32_t* __restrict__ labels, int H, int W, int C, int ba
     const int rows = OW_TH + 2 * radius;
 
     // object bits of rows y0 - radius .. y0 + OW_TH + radius - 1, columns x0 - 64 .. x0 + OW_TW + 63;
-    // four loads of a wavefront are in flight before the first ballot needs its labels
+    // OW_BATCH loads of a wavefront are in flight before the first ballot needs its labels (with
+    // a radius of up to 8 that is all a wavefront has to load: one round trip to memory)
     constexpr int WAVES = OW_THREADS / 64;
     const int items = rows * (OW_WORDS + 2);
-    for (int i0 = wave; i0 < items; i0 += 4 * WAVES) {
-        int v[4];
+    for (int i0 = wave; i0 < items; i0 += OW_BATCH * WAVES) {
+        int v[OW_BATCH];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < OW_BATCH; ++k) {
             const int i = i0 + k * WAVES;
             const int row = i / (OW_WORDS + 2), word = i - row * (OW_WORDS + 2);
             const int y = y0 - radius + row, x = x0 - 64 + 64 * word + lane;
@@ -49,7 +51,7 @@ k_object_weights(const int32_t* __restrict__ labels, int H, int W, int C, int ba
             if (i < items && y >= 0 && y < H && x >= 0 && x < W) v[k] = labels[frame + (size_t)y * W + x];
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < OW_BATCH; ++k) {
             const int i = i0 + k * WAVES;               // the same for all lanes of a wavefront
             if (i < items) {
                 const unsigned long long m = __ballot(v[k] >= 0 && v[k] < C && v[k] != background && v[k] != ignore);
