@@ -204,6 +204,38 @@ def test_miou_matches_oracle_bit_exact(P, C, ignore):
     assert m.item() == O.miou(conf_o)[0]
 
 
+@pytest.mark.parametrize("P,C", [(1920 * 1080, 19), (4 * 720 * 1280, 21), (600001, 200)])
+def test_miou_many_blocks_and_reused_result_buffers(P, C):
+    """Frame-sized maps (the histogram runs on up to 256 blocks, spread over all XCDs) with calls
+    in a row into the same result buffers, on maps that change between the calls: every call
+    exact."""
+    rng = np.random.default_rng(P % 1000 + C)
+    pred = rng.integers(0, min(C, 256), size=P).astype(np.uint8)
+    lab = rng.integers(0, C, size=P).astype(np.int32)
+    lab[: P // 2] = lab[0]
+    pred[: P // 3] = pred[0]
+    dp, dl = torch.from_numpy(pred).cuda(), torch.from_numpy(lab).cuda()
+    conf = torch.full((C, C), -7, dtype=torch.int64, device="cuda")
+    m = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    for rep in range(6):
+        if rep:
+            lo, hi = rep * (P // 8), rep * (P // 8) + P // 16
+            lab[lo:hi] = (rep * 3) % C
+            pred[lo + 100:hi + 100] = (rep * 5) % min(C, 256)
+            dp.copy_(torch.from_numpy(pred)); dl.copy_(torch.from_numpy(lab))
+        st.st_miou(dp, dl, C, -1, confusion=conf, miou=m)
+        torch.cuda.synchronize()
+        conf_o = O.confusion(pred, lab, C, -1)
+        np.testing.assert_array_equal(conf.cpu().numpy(), conf_o)
+        assert m.item() == O.miou(conf_o)[0], rep
+    # calls queued back to back without a synchronisation in between
+    for _ in range(20):
+        st.st_miou(dp, dl, C, -1, confusion=conf, miou=m)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(conf.cpu().numpy(), conf_o)
+    assert m.item() == O.miou(conf_o)[0]
+
+
 def test_miou_unaligned_maps_and_out_of_range_entries():
     # maps that start off a 16-byte boundary, labels outside [0, C) and predictions >= C: the
     # vector path must not be taken and such pixels must not be counted
