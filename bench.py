@@ -46,7 +46,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # the kernel source it was measured on:
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.52, 8.83),
+    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.51, 8.83),
     ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 13.75, 7.55),
     ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 6.98, 11.32),
     ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 10.45, 3.77),
@@ -61,12 +61,12 @@ MEASURED_TRAFFIC = {
     ("1080p", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 10.45, 4.09),
     ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 35.89, 24.95),
     ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.01, 17.50),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 51.96, 60.38),
-    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 46.50, 90.56),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 69.09, 30.19),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 51.99, 60.38),
+    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 45.93, 90.56),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "a6528c83dfe46df67caadd75e36e431f9b33a055e451a4a1f0ac84ac1ae20d1b", 69.10, 30.19),
     ("batch4", "upsample_ce_grad"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 63.29, 74.43),
     ("batch4", "upsample_ce"): ("k_loss.hip", "e7a95975f961088702fa08df75facea1175c9dc6c53bebb5d96f37b2d4103083", 31.72, 7.72),
-    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 101.90, 90.68),
+    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 101.91, 90.68),
 }
 
 
