@@ -63,6 +63,17 @@ def test_background_class_and_factor():
     assert (got[1] == 9).sum() == (4 + 8) * (10 + 8)
 
 
+def test_ignore_value_inside_the_class_range_and_first_non_class():
+    lab = sparse_labels(9, 2, 30, 200, 6, 0.01)
+    lab[0, 10, 50:60] = 2       # the ignore value, itself a class index: no object
+    lab[1, 5, 5] = 6            # == n_classes: no class index, no object
+    got, want = run(lab, 6, 3, ignore_index=2)
+    np.testing.assert_array_equal(got, want)
+    got2, want2 = run(lab, 6, 3, ignore_index=-1)
+    np.testing.assert_array_equal(got2, want2)
+    assert (got != got2).any()
+
+
 def test_frames_do_not_leak_into_each_other():
     lab = np.zeros((3, 24, 280), np.int32)
     lab[1, 0, :] = 1            # top row of the middle frame

@@ -40,6 +40,7 @@ def test_against_brute_force(seed, radius):
     lab = random_labels(rng, 2, 7, 11, 5, 0.06, ignore_index=255, p_ignore=0.1)
     lab[0, 0, 0] = 9            # outside [0, n_classes): no object
     lab[1, 6, 10] = -3
+    lab[1, 0, 10] = 5           # the first value that is no class index
     got = OW.object_weights(lab, 5, radius, factor=5, background=0, ignore_index=255)
     np.testing.assert_array_equal(got, brute_force(lab, 5, radius, 5, 0, 255))
 
@@ -96,6 +97,19 @@ def test_background_class_and_frames_are_separate():
     w = OW.object_weights(lab, 3, 1, background=1)          # now class 0 is the object, class 1 background
     assert (w[1] == 5).all()
     assert (w[0] == 5).all()                                 # every pixel has a class-0 neighbour within 1
+
+
+def test_ignore_index_inside_the_class_range_is_no_object():
+    """An ignore value that is itself a class index (here 2 of 0 .. 4) marks nothing, alone or
+    among objects; the same map with no ignore value marks around those pixels as well."""
+    lab = np.zeros((1, 9, 12), np.int32)
+    lab[0, 4, 3] = 2
+    assert (OW.object_weights(lab, 5, 1, ignore_index=2) == 1).all()
+    assert int((OW.object_weights(lab, 5, 1, ignore_index=-1) == 5).sum()) == 9
+    lab[0, 4, 9] = 3
+    w = OW.object_weights(lab, 5, 1, ignore_index=2)
+    assert int((w == 5).sum()) == 9 and w[0, 4, 9] == 5 and w[0, 4, 3] == 1
+    np.testing.assert_array_equal(w, brute_force(lab, 5, 1, 5, 0, 2))
 
 
 def test_monotone_in_the_radius_and_asymmetric_extent():
