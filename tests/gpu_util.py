@@ -114,6 +114,14 @@ def rel_err(a, b):
     return float(np.max(np.abs(a - b)) / (den if den > 0 else 1.0))
 
 
+def update_err(tag, got, want):
+    """Relative error of an update (trained minus initial parameters), logged: the parameters
+    themselves are dominated by their initial values, the update is what a wrong gradient moves."""
+    e = rel_err(got, want)
+    progress(f"update error {tag}: {e:.3g}")
+    return e
+
+
 def check_staged_bit_exact(wl, gpu, labels):
     """From the GPU's own final low-resolution logits the oracle must reproduce the GPU's class
     map, confusion counts and mean IoU bit for bit."""

@@ -7,9 +7,21 @@ import pytest
 
 import workloads as WL
 from gpu_util import (check_pred_against_oracle, check_staged_bit_exact, live_oracle, load_golden, progress, rel_err,
-                      run_gpu, run_oracle)
+                      run_gpu, run_oracle, update_err)
 
 pytestmark = pytest.mark.gpu
+
+
+# Bar on the update (trained minus initial parameters) against the bf16-operand oracle at the
+# full sizes: five times what is measured there (2e-5 .. 2e-4; the parameters themselves are
+# dominated by their initial values and say little).  Small grids cannot carry a bar this tight:
+# there a single activation whose sign the order of additions decides switches a ReLU mask
+# element, which alone moves a gradient entry by about 1 / positions (up to 2e-2 on a few hundred
+# positions, seen on the random shapes), so they keep 3e-2.  What the bar cannot tell at these
+# sizes is a single misplaced rounding point of the bf16 path: planted in the oracle, one moves
+# the 720p update error from 1.9e-4 to 2.4e-4 .. 7.3e-4 (on a few hundred positions: 2e-3 ..
+# 1e-2).  The activations and back-propagated gradients are rounded by being stored as bfloat16.
+FULL_SIZE_UPDATE_BAR = 1e-3
 
 
 def compare_bf16(wl, steps, tight=5e-4):
@@ -29,7 +41,7 @@ def compare_bf16(wl, steps, tight=5e-4):
     # same rounding points on both sides: what is left is accumulation order
     assert rel_err(gpu["losses"], orq["losses"]) < tight
     assert rel_err(gpu["params"], orq["params"]) < tight
-    assert rel_err(gpu["params"] - p, orq["params"] - p) < 3e-2
+    assert update_err(wl.name, gpu["params"] - p, orq["params"] - p) < FULL_SIZE_UPDATE_BAR
     if wl.momentum:
         assert rel_err(gpu["velocity"], orq["velocity"]) < 3e-2
     np.testing.assert_allclose(gpu["mious"], orq["mious"], atol=5e-3)
@@ -64,7 +76,7 @@ def test_2160p_beyond_the_measured_sizes():
         rel_err(gpu["params"] - p, orq["params"] - p)))
     assert rel_err(gpu["losses"], orq["losses"]) < 5e-4
     assert rel_err(gpu["params"], orq["params"]) < 5e-4
-    assert rel_err(gpu["params"] - p, orq["params"] - p) < 3e-2
+    assert update_err("2160p", gpu["params"] - p, orq["params"] - p) < FULL_SIZE_UPDATE_BAR
     assert rel_err(gpu["velocity"], orq["velocity"]) < 3e-2
     np.testing.assert_allclose(gpu["mious"], orq["mious"], atol=5e-3)
 
@@ -93,7 +105,7 @@ def test_batch4_shared_head_all_steps():
     assert gpu["steps_taken"] == 16
     check_staged_bit_exact(wl, gpu, lab)
     idx = gold["index"]
-    for tag, tol, tol_upd in (("bf16", 5e-4, 3e-2), ("exact", 2e-2, 1e-1)):
+    for tag, tol, tol_upd in (("bf16", 5e-4, FULL_SIZE_UPDATE_BAR), ("exact", 2e-2, 1e-1)):
         e_loss = rel_err(gpu["losses"], gold[tag + "_losses"])
         e_par = float(np.abs(gpu["params"][idx] - gold[tag + "_params"]).max() / gold[tag + "_max_abs_param"])
         e_upd = float(np.abs((gpu["params"][idx] - p[idx]) - (gold[tag + "_params"] - p[idx])).max()

@@ -11,7 +11,7 @@ import oracle as O
 import paper_2003_10735_amd as st
 import workloads as WL
 from gpu_util import (check_pred_against_oracle, check_staged_bit_exact, rel_err, run_gpu, run_oracle,
-                      to_dev_features)
+                      to_dev_features, update_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -69,7 +69,7 @@ def test_ragged_shapes(case, compute):
         # against the oracle that rounds the same operands: accumulation order only
         assert rel_err(gpu["losses"], orq["losses"]) < 2e-4
         assert rel_err(gpu["params"], orq["params"]) < 2e-4
-        assert rel_err(gpu["params"] - p, orq["params"] - p) < 2e-2
+        assert update_err(f"ragged {case} bf16", gpu["params"] - p, orq["params"] - p) < 2e-2
 
 
 def test_intermediate_gradient_buffers_f32():
@@ -461,7 +461,7 @@ def test_matrix_core_path_small_shapes(case):
     assert rel_err(gpu["params"], ora["params"]) < 2e-2
     assert rel_err(gpu["losses"], orq["losses"]) < 5e-4
     assert rel_err(gpu["params"], orq["params"]) < 5e-4
-    assert rel_err(gpu["params"] - p, orq["params"] - p) < 3e-2
+    assert update_err(f"mfma case {case}", gpu["params"] - p, orq["params"] - p) < 3e-2
     if wl.momentum:
         assert rel_err(gpu["velocity"], orq["velocity"]) < 3e-2
     # run twice: bit-identical (fixed-order reductions, no floating-point atomics)
