@@ -106,6 +106,83 @@ def test_intermediate_gradient_buffers_f32():
     np.testing.assert_array_equal(gpu["params"], p)      # lr = 0 leaves the parameters alone
 
 
+def test_intermediate_tensors_of_the_bf16_path_element_by_element():
+    """The matrix-core path's own tensors after one step with a zero learning rate, read back from
+    the workspace: both activations and both back-propagated gradients (stored as bfloat16),
+    against a replay with the oracle's primitives that rounds where the
+    bf16 path is defined to round (weights, a1, a2, the logit gradient, da2, da1).  Both sides
+    round the same sums, added in different orders, so nearly every element must agree to the
+    bit, the rest by one bfloat16 step (a sum that falls on the other side of a rounding
+    boundary), and an element may be zero on one side only where a ReLU input is within rounding
+    of zero.  A truncating conversion, a missing ReLU mask or a shifted layout would fail this by
+    orders of magnitude."""
+    wl = WL.small_variant(WL.WORKLOADS["720p"], n=2, c_in=64, h=9, w=21, c1=64, c2=128, n_classes=7, steps=1, lr=0.0,
+                          n_sites=9, ignore_index=255, ignore_fraction=0.05)
+    f, lab, p = inputs(wl)
+    desc = st.HeadDesc.of(wl)
+    ws = st.new_workspace(desc)
+    # (with the feature gradient asked for, the gradient behind layer 1 is also left position-major)
+    dfeat = torch.zeros((wl.n, wl.c_in, wl.h, wl.w), dtype=torch.float32, device="cuda")
+    st.st_partial_distill(desc, to_dev_features(wl, f), torch.from_numpy(lab).cuda(), torch.from_numpy(p).cuda(), 1, 0.0,
+                          workspace=ws, feature_grad=dfeat)
+    torch.cuda.synchronize()
+    lay = st.st_get_workspace_layout(desc)
+    assert lay["elem_size"] == 2
+
+    def grid(off, C):          # [n, h+2, row_pitch, C] bfloat16 -> [n, C, h, w] float64 (inside the zero border)
+        Hp, Wp = wl.h + 2, lay["row_pitch"]
+        t = ws[off:off + 2 * wl.n * Hp * Wp * C].view(torch.bfloat16).reshape(wl.n, Hp, Wp, C)
+        inner = t[:, 1:wl.h + 1, 1:wl.w + 1, :].float().cpu().numpy().astype(np.float64)
+        border = t.float().clone()
+        border[:, 1:wl.h + 1, 1:wl.w + 1, :] = 0
+        assert float(border.abs().max()) == 0.0          # the padding stays zero
+        return inner.transpose(0, 3, 1, 2)
+
+    sl = WL.param_slices(wl)
+    p64 = p.astype(np.float64)
+    W1 = O.round_bf16(p64[sl["W1"]].reshape(wl.c1, wl.c_in, 3, 3))
+    W2 = O.round_bf16(p64[sl["W2"]].reshape(wl.c2, wl.c1, 3, 3))
+    W3 = O.round_bf16(p64[sl["W3"]].reshape(wl.n_classes, wl.c2, 1, 1))
+    x = WL.features_as_f64(wl, f)
+    pre1 = O.conv_fwd(x, W1, p64[sl["b1"]])
+    a1 = O.round_bf16(np.maximum(pre1, 0.0))
+    pre2 = O.conv_fwd(a1, W2, p64[sl["b2"]])
+    a2 = O.round_bf16(np.maximum(pre2, 0.0))
+    z = O.conv_fwd(a2, W3, p64[sl["b3"]])
+    _, G, _ = O.softmax_ce(O.upsample8(z), lab, wl.ignore_index)
+    g = O.upsample8_adjoint(G)
+    da2 = O.round_bf16(O.conv_dgrad(O.round_bf16(g), W3) * (a2 > 0))
+    da1 = O.round_bf16(O.conv_dgrad(da2, W2) * (a1 > 0))
+
+    def compare(name, got, want, exact_share, first_layer=False):
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-300))) - 7)      # one bfloat16 step at `want`
+        diff = np.abs(got - want)
+        one_sided_zero = (got == 0) != (want == 0)
+        same = diff == 0
+        print(name, "identical", same.mean(), "one-sided zeros", int(one_sided_zero.sum()), "of", want.size,
+              "largest difference / largest value", diff.max() / np.abs(want).max())
+        assert same.mean() > exact_share, name
+        assert (want != 0).mean() > 0.05, name            # (not an empty comparison)
+        ok = ~one_sided_zero
+        if first_layer:     # identical inputs on both sides: never more than the one step
+            assert np.all(diff[ok] <= 1.0001 * ulp[ok]), name
+        else:               # inputs that differ by a step here and there move small results by more than their own step
+            assert np.all(diff[ok] <= 1.0001 * ulp[ok] + 2e-3 * np.abs(want).max()), name
+        return one_sided_zero
+
+    z1 = compare("a1", grid(lay["a1"], wl.c1), a1, 0.999, first_layer=True)
+    assert np.all(np.abs(pre1[z1]) < 1e-4)                 # ... only where the sum itself is next to zero
+    z2 = compare("a2", grid(lay["a2"], wl.c2), a2, 0.999)
+    assert np.all(np.abs(pre2[z2]) < 1e-2)
+    # (d loss / d z itself is never assembled on this path: the classifier's backward kernel forms
+    #  it from the loss kernel's per-tile shares and rounds it in registers; da2 is its first image)
+    # a gradient element is zero on one side only through such a mask element (or by falling below bfloat16's range)
+    zd2 = compare("da2", grid(lay["da2"], wl.c2), da2, 0.99)
+    assert zd2.sum() <= z2.sum() + 0.001 * da2.size
+    zd1 = compare("da1", grid(lay["da1"], wl.c1), da1, 0.98)
+    assert zd1.sum() <= z1.sum() + 0.002 * da1.size
+
+
 @pytest.mark.parametrize("compute", ["f32", "bf16"])
 def test_equal_logits_go_to_the_lowest_class(compute):
     """With a zero classifier every pixel's logits are the biases, exactly: the predicted class
