@@ -638,6 +638,14 @@ def main():
                        "ms_per_non_key_frame": round(float(np.median(fms[~key])), 4) if (~key).any() else None,
                        "threshold": thr, "max_updates": wc.steps,
                        "first_last_score": [round(r["scores"][0], 4), round(r["scores"][-1], 4)]}
+                # the same clip from the same head with the caller's word that frames are key frames
+                # (a server that is only sent key frames): the first pass computes its gradients at once
+                rh = run_clip(dc, frames_dev, torch.from_numpy(WL.make_head_params(wc)).cuda(), threshold=thr,
+                              max_updates=wc.steps, lr=wc.lr, momentum=wc.momentum, workspace=wsc, stream=stream,
+                              expect_key_frames=True)
+                leg["with_key_frame_hint"] = {"frames_per_s": round(rh["frames_per_s"], 1),
+                                              "same_schedule": bool(rh["key_frames"] == r["key_frames"]
+                                                                    and rh["updates"] == r["updates"])}
                 if learnable:
                     leg["note"] = ("features = noise + a per-class code of each cell's label (not the configuration's "
                                    "inputs): the head trained on a key frame scores above the threshold on the frames "

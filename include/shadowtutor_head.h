@@ -154,6 +154,13 @@ typedef struct st_distill_opts {
      * last parameters in head_params and the best ones here -- or NULL.  Ignored without a
      * threshold (there the last parameters are the result). */
     float* best_params;
+    /* With threshold > 0: 1 tells the library that the frame is very likely a key frame (a server
+     * that is only sent key frames, Algorithm 3).  The first pass then computes its gradients and
+     * queues the backward pass at once, as every later pass does, instead of scoring the head first
+     * and looking at the metric before anything else is queued; a key frame saves a loss pass and
+     * a wait of the host, a frame whose first metric already reaches the threshold wastes one
+     * backward pass.  Results are the same either way.  0: score first (the default). */
+    int32_t expect_key_frame;
 } st_distill_opts;
 enum { ST_OPTIM_SGD = 0, ST_OPTIM_ADAM = 1 };
 

@@ -43,7 +43,7 @@ class StDistillOpts(C.Structure):
                 ("optimizer", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t0", C.c_int32),
                 ("pixel_weights", C.c_void_p), ("feature_grad", C.c_void_p), ("use_graph", C.c_int32),
-                ("best_params", C.c_void_p)]
+                ("best_params", C.c_void_p), ("expect_key_frame", C.c_int32)]
 
 
 class StScheduleParams(C.Structure):
@@ -232,7 +232,8 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
                        momentum: float = 0.0, velocity=None, threshold: float = 0.0,
                        strict_break: bool = True, return_best: bool = False, losses=None,
                        mious=None, confusion=None, pred=None, workspace=None, stream=None,
-                       adam=None, pixel_weights=None, feature_grad=None, graph=False, best_params=None):
+                       adam=None, pixel_weights=None, feature_grad=None, graph=False, best_params=None,
+                       expect_key_frame=False):
     """Runs the library's st_partial_distill; head_params (and the optimiser state) are updated
     in place.  `adam` = dict(m=, v=, t0=0, beta1=0.9, beta2=0.999, eps=1e-8) selects Adam;
     `pixel_weights` (uint8 [n,8h,8w]) scales every pixel's loss; `feature_grad` (float32
@@ -240,16 +241,19 @@ def st_partial_distill(desc: HeadDesc, features, teacher_labels, head_params, st
     like head_params) receives Algorithm 1's best parameters when a threshold is given.
     With a grouped descriptor head_params and the optimiser state are [n, num_params] and losses
     [steps+1, n].  graph=True launches the call through the library's cached HIP graph
-    (st_distill_opts.use_graph).
+    (st_distill_opts.use_graph).  expect_key_frame=True (with a threshold) makes the first pass compute its
+    gradients at once instead of scoring first (st_distill_opts.expect_key_frame).
     Returns (steps_taken, best_metric or None); with a threshold the returned tuple also carries
     `.first_metric`, the metric before any update."""
     d = desc.c()
     ws = workspace if workspace is not None else new_workspace(desc, features.device)
     use_opts = (momentum != 0.0 or threshold > 0.0 or velocity is not None or adam is not None
-                or pixel_weights is not None or feature_grad is not None or graph or best_params is not None)
+                or pixel_weights is not None or feature_grad is not None or graph or best_params is not None
+                or expect_key_frame)
     opts = StDistillOpts(momentum, _ptr(velocity), threshold, 1 if strict_break else 0,
                          1 if return_best else 0, ST_OPTIM_SGD, 0.0, 0.0, 0.0, None, None, 0,
-                         _ptr(pixel_weights), _ptr(feature_grad), 1 if graph else 0, _ptr(best_params))
+                         _ptr(pixel_weights), _ptr(feature_grad), 1 if graph else 0, _ptr(best_params),
+                         1 if expect_key_frame else 0)
     if adam is not None:
         opts.optimizer = ST_OPTIM_ADAM
         opts.beta1, opts.beta2 = adam.get("beta1", 0.9), adam.get("beta2", 0.999)

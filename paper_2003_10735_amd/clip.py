@@ -18,7 +18,7 @@ from . import (HeadDesc, new_workspace, st_head_forward, st_miou, st_partial_dis
 
 def run_clip(desc: HeadDesc, frames, head_params, *, threshold: float, max_updates: int, lr: float,
              momentum: float = 0.0, strict_break: bool = False, return_best: bool = True,
-             workspace=None, stream=None) -> dict:
+             workspace=None, stream=None, expect_key_frames: bool = False) -> dict:
     """`frames` yields (features, teacher_labels) pairs of cuda tensors ([n,c_in,h,w] bfloat16 or
     float32; [n,8h,8w] int32).  `head_params` (float32 cuda tensor) is updated in place on key
     frames.  Returns per-frame scores before training, which frames were key frames, the
@@ -40,7 +40,7 @@ def run_clip(desc: HeadDesc, frames, head_params, *, threshold: float, max_updat
         r = st_partial_distill(desc, features, labels, head_params, max_updates, lr,
                                momentum=momentum, velocity=velocity, threshold=threshold,
                                strict_break=strict_break, return_best=return_best,
-                               workspace=ws, stream=stream)
+                               workspace=ws, stream=stream, expect_key_frame=expect_key_frames)
         frame_ms.append((time.perf_counter() - tf) * 1e3)
         taken, best = r
         score = r.first_metric

@@ -517,6 +517,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
     float* velocity = nullptr;
     bool strict = true, return_best = false;
     float* best_params = nullptr;
+    bool expect_key_frame = false;
     bool use_adam = false;
     float *adam_m = nullptr, *adam_v = nullptr;
     double beta1 = 0.0, beta2 = 0.0;
@@ -544,6 +545,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         strict = opts->strict_break != 0;
         return_best = opts->return_best != 0;
         best_params = opts->best_params;
+        expect_key_frame = opts->expect_key_frame != 0;
     }
     if (!workspace || !aligned(workspace, 256)) return ST_ERR_WORKSPACE;
     const bool early_exit = threshold > 0.0;
@@ -567,6 +569,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
             key.opts.pixel_weights = opts->pixel_weights; key.opts.feature_grad = opts->feature_grad;
             key.opts.use_graph = 1;
             key.opts.best_params = opts->best_params;
+            key.opts.expect_key_frame = opts->expect_key_frame;
             if (out) { key.losses = out->losses; key.mious = out->mious; key.confusion = out->confusion; key.pred = out->pred; }
             key.workspace = workspace;
             if (hipGetDevice(&key.device) != hipSuccess) return ST_ERR_NO_DEVICE;
@@ -665,7 +668,9 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         // The first pass of the early-exit form only scores the head (loss, class map, counts):
         // most frames are not key frames and end right there.  A key frame runs the same kernel
         // once more for the gradient half, below, once the host has seen the metric.
-        const bool score_only = early_exit && it == 0;
+        // (unless the caller expects a key frame: then the first pass is like every later one)
+        const bool key_hint = early_exit && expect_key_frame;
+        const bool score_only = early_exit && it == 0 && !key_hint;
         loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
@@ -690,7 +695,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         // From the second pass on the backward kernels are queued before the host looks at the
         // metric (below); on the matrix-core path the bookkeeping then rides on the first of them
         // instead of taking a launch of its own.
-        const bool speculate = early_exit && !last && !feature_grad && it > 0;
+        const bool speculate = early_exit && !last && !feature_grad && (it > 0 || key_hint);
         const bool polled = device_writes && mb->poll && g_metric_polling.load(std::memory_order_relaxed);
         const bool finish_rides = speculate && polled && p.mfma;
         if (finish_now && !finish_rides)

@@ -499,6 +499,54 @@ def test_early_exit_polling_and_event_wait_agree():
     assert 0 < runs[0][1]["steps_taken"] < 8
 
 
+def test_key_frame_hint_changes_the_order_of_work_not_the_result():
+    """expect_key_frame makes the first pass compute its gradients and queue the backward pass
+    before the host has seen the metric.  Every outcome of Algorithm 1 -- no update at all, an
+    exit on the way, all updates, best parameters that are not the last -- is the same with and
+    without it, bit for bit; a frame that needs no training leaves the caller's vectors alone."""
+    wl = WL.small_variant(WL.WORKLOADS["tiny"], c_in=8, h=6, w=6, c1=8, c2=8, n_classes=3, n_sites=5,
+                          label_seed=5, steps=8, lr=0.2, momentum=0.9)
+    lab = WL.make_labels(wl)
+    f = WL.make_learnable_features(wl, lab)
+    p = WL.make_head_params(wl)
+    wm = WL.small_variant(WL.WORKLOADS["720p"], h=20, w=28, c_in=64, c1=64, c2=64, n_classes=7, steps=4, lr=0.05)
+    fm, labm, pm = inputs(wm)
+
+    def call(w, feats, labels, params, threshold, hint, **kw):
+        desc = st.HeadDesc.of(w)
+        pt = torch.from_numpy(params.copy()).cuda()
+        vel = torch.zeros_like(pt) if w.momentum else None
+        bt = torch.full_like(pt, 7.0)
+        mious = torch.full((w.steps + 1, w.n), float("nan"), dtype=torch.float64, device="cuda")
+        losses = torch.full((w.steps + 1,), float("nan"), dtype=torch.float32, device="cuda")
+        r = st.st_partial_distill(desc, to_dev_features(w, feats), torch.from_numpy(labels).cuda(), pt, w.steps, w.lr,
+                                  momentum=w.momentum, velocity=vel, threshold=threshold, mious=mious, losses=losses,
+                                  best_params=bt, expect_key_frame=hint, **kw)
+        torch.cuda.synchronize()
+        return dict(ret=tuple(r), first=r.first_metric, params=pt.cpu().numpy(), best=bt.cpu().numpy(),
+                    vel=None if vel is None else vel.cpu().numpy(), mious=mious.cpu().numpy(), losses=losses.cpu().numpy())
+
+    trace = call(wl, f, lab, p, 1.5, False)
+    m = trace["mious"][:, 0]
+    cases = [(wl, f, lab, p, 1.5, dict(return_best=True)), (wl, f, lab, p, 1.5, dict(return_best=False)),
+             (wl, f, lab, p, float(m[0]), dict(return_best=True)),                        # no key frame
+             (wl, f, lab, p, float(m[2]), dict(strict_break=False)),                      # leaves on the way
+             (wm, fm, labm, pm, 1.5, dict(return_best=True))]                              # matrix-core path
+    for w, feats, labels, params, thr, kw in cases:
+        a, b = call(w, feats, labels, params, thr, False, **kw), call(w, feats, labels, params, thr, True, **kw)
+        assert a["ret"] == b["ret"] and a["first"] == b["first"], (thr, kw)
+        taken = a["ret"][0]
+        for k in ("params", "best", "vel"):
+            if a[k] is not None:
+                np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+        np.testing.assert_array_equal(a["mious"][:taken + 1], b["mious"][:taken + 1])
+        np.testing.assert_array_equal(a["losses"][:taken + 1], b["losses"][:taken + 1])
+    nokey = call(wl, f, lab, p, float(m[0]), True, return_best=True)
+    assert nokey["ret"][0] == 0
+    np.testing.assert_array_equal(nokey["params"], p)
+    assert (nokey["vel"] == 0).all()
+
+
 def test_non_finite_parameters_stay_in_range():
     """A diverged head (every parameter NaN): the class map stays inside [0, C) -- class 0, the
     oracle's answer as well -- the confusion counts still hold every valid pixel exactly once,
