@@ -13,7 +13,7 @@ re-initialisation (one device copy) runs between the calls, outside the event pa
 host-clock region).
 
 Prints ONE JSON line.  Extra objects:
-  roofline      the kernel that takes the largest share of the call (kernels within 3 % of it count
+  roofline      the kernel that takes the largest share of the call (kernels within 10 % of it count
                 as tied and the tie goes to the matrix-core kernel), its algorithmic work per
                 launch over its average launch duration (HIP events on the launch stream, taken
                 during the timed region), against the chip's published peak; the other kernels
@@ -274,10 +274,12 @@ def all_kernel_pass(st, prob, calls):
 
 
 def pick_dominant(work, known):
-    """The kernel with the largest share of the call; kernels within 3 % of it count as tied and a
-    tie goes to the matrix-core kernel, so that the choice does not flip from run to run."""
+    """The kernel with the largest share of the call; kernels within 10 % of it count as tied and a
+    tie goes to the matrix-core kernel, so that the choice does not flip from box to box (single
+    kernels vary by +-5 % between boxes, and at 1280x720 the weight-gradient launch and the fused
+    loss kernel are that close; both are reported either way, one here and one in other_kernels)."""
     top = max(v[1] for v in known.values())
-    tied = [k for k, v in known.items() if v[1] >= 0.97 * top]
+    tied = [k for k, v in known.items() if v[1] >= 0.90 * top]
     return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", known[k][1]))
 
 
