@@ -13,8 +13,8 @@ re-initialisation (one device copy) runs between the calls, outside the event pa
 host-clock region).
 
 Prints ONE JSON line.  Extra objects:
-  roofline      the kernel that takes the largest share of the call (kernels within 10 % of it count
-                as tied and the tie goes to the matrix-core kernel), its algorithmic work per
+  roofline      the kernel with the longest launches (kernels within 10 % of it count as tied and the
+                tie goes to the matrix-core kernel), its algorithmic work per
                 launch over its average launch duration (HIP events on the launch stream, taken
                 during the timed region), against the chip's published peak; the other kernels
                 of a step follow in `other_kernels`
@@ -274,13 +274,15 @@ def all_kernel_pass(st, prob, calls):
 
 
 def pick_dominant(work, known):
-    """The kernel with the largest share of the call; kernels within 10 % of it count as tied and a
-    tie goes to the matrix-core kernel, so that the choice does not flip from box to box (single
-    kernels vary by +-5 % between boxes, and at 1280x720 the weight-gradient launch and the fused
-    loss kernel are that close; both are reported either way, one here and one in other_kernels)."""
-    top = max(v[1] for v in known.values())
-    tied = [k for k, v in known.items() if v[1] >= 0.90 * top]
-    return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", known[k][1]))
+    """The kernel with the longest launches (average duration; `known`: name -> (launches, total
+    ms)).  Kernels within 10 % of it count as tied and a tie goes to the matrix-core kernel, so
+    that the choice does not flip from box to box: single kernels vary by +-5 % between boxes, and
+    at 1280x720 the weight-gradient launch and the fused loss kernel are that close (both are
+    reported either way, one in `roofline` and one in `other_kernels`)."""
+    avg = {k: v[1] / v[0] for k, v in known.items()}
+    top = max(avg.values())
+    tied = [k for k in avg if avg[k] >= 0.90 * top]
+    return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", avg[k]))
 
 
 def config_leg(st, WL, name, stream, n_timed, use_graph):
