@@ -61,11 +61,12 @@ struct ConvArgs {
     bf16* Y;            // [PP][cout] or nullptr
     bf16* YT;           // channel-major copy, blocked layout of xt_index(), or nullptr
     // EPI 2: the 1x1 classifier rides along.  Every block adds its 64 channels' share of the
-    // logits of its 128 positions: zpart[n-tile][padded position][32 classes] float32; the
-    // consumer adds the n_tiles shares and the bias.
+    // logits of its 128 positions: zpart[n-tile][padded position][zpitch classes] float32 (zpitch =
+    // the class count rounded up to a multiple of four); the consumer adds the n_tiles shares and
+    // the bias.
     const bf16* W3q;    // [n_cls][cout] bfloat16
     float* zpart;
-    int n_cls;
+    int n_cls, zpitch;
     // EPI 3: the plain sums go, as float32, straight to a dense [n][cout][h][w] tensor
     float* dense;
     int PP, Hp, Wp, h, w, cin, cout, PPT, guard;
@@ -355,10 +356,12 @@ __global__ void __launch_bounds__(512) k_conv3x3_mfma(ConvArgs a)
         }
         const int mp = m0 + wave * 32 + l32;
         if (mp < m_end) {
-            float* zrow = a.zpart + ((size_t)nt * a.PP + mp) * 32 + lhi * 4;
+            // (a lane holds classes 8 gq + 4 lhi .. + 3; the groups beyond the classes are padding)
+            float* zrow = a.zpart + ((size_t)nt * a.PP + mp) * a.zpitch + lhi * 4;
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq)
-                *(f32x4*)(zrow + gq * 8) = f32x4{zacc[gq * 4], zacc[gq * 4 + 1], zacc[gq * 4 + 2], zacc[gq * 4 + 3]};
+                if (gq * 8 + lhi * 4 < a.zpitch)
+                    *(f32x4*)(zrow + gq * 8) = f32x4{zacc[gq * 4], zacc[gq * 4 + 1], zacc[gq * 4 + 2], zacc[gq * 4 + 3]};
         }
     }
     const int n_valid = min(CV_BN, a.cout - n0);
@@ -396,7 +399,7 @@ void conv3x3_mfma(Ctx& c, const char* name, const Plan& p, const bf16* X, const 
     const Geo& g = p.g;
     ConvArgs a;
     a.X = X; a.Wq = Wq; a.bias = bias; a.mask = mask; a.Y = Y; a.YT = YT;
-    a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C; a.dense = dense;
+    a.W3q = W3q; a.zpart = zpart; a.n_cls = p.g.C; a.zpitch = (p.g.C + 3) / 4 * 4; a.dense = dense;
     a.PP = p.g.padded_positions(); a.Hp = p.g.Hp; a.Wp = p.g.Wp; a.h = p.g.h; a.w = p.g.w;
     a.cin = cin; a.cout = cout;
     a.PPT = p.PPT; a.guard = p.guard;

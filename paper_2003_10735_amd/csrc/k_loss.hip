@@ -87,15 +87,16 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
     //      large negative logit: they never win, their softmax term is exactly 0.
     //      All global loads of the prologue are issued before anything waits for one of them.
     constexpr int NZ = (CP * CH * CW + NT - 1) / NT;
-    constexpr int NZQ = (CH * CW * 8 + NT - 1) / NT;     // 16-byte chunks of the 32-class rows
+    constexpr int QC = CP / 4;                            // 16-byte chunks of a cell's row of CP classes
+    constexpr int NZQ = (CH * CW * QC + NT - 1) / NT;
     float zv[NZ];
     f32x4 zq[NZQ], bq[NZQ];
     if (zs.parts) {
         const size_t PP = (size_t)g.padded_positions();
 #pragma unroll
         for (int k = 0; k < NZQ; ++k) {
-            const int i = min(tid + k * NT, CH * CW * 8 - 1);
-            const int cell = i >> 3, chunk = i & 7;
+            const int i = min(tid + k * NT, CH * CW * QC - 1);
+            const int cell = i / QC, chunk = i - cell * QC;
             const int lc = cell % CW, r = cell / CW;
             const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
             const size_t mp = ((size_t)img * g.Hp + cy + 1) * g.Wp + cx + 1;
@@ -105,7 +106,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
 #pragma unroll
             for (int part = 0; part < 4; ++part) {
                 const float wgt = part < zs.n_parts ? 1.f : 0.f;
-                const f32x4 v = *(const f32x4*)(zs.parts + ((size_t)min(part, zs.n_parts - 1) * PP + mp) * 32 + chunk * 4);
+                const f32x4 v = *(const f32x4*)(zs.parts + ((size_t)min(part, zs.n_parts - 1) * PP + mp) * CP + chunk * 4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(wgt, v[e], acc[e]);
             }
@@ -172,13 +173,13 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
 #pragma unroll
         for (int k = 0; k < NZQ; ++k) {
             const int i = tid + k * NT;
-            const int cell = i >> 3, chunk = i & 7;
+            const int cell = i / QC, chunk = i - cell * QC;
             const int lc = cell % CW, r = cell / CW;
-            if (i < CH * CW * 8) {
+            if (i < CH * CW * QC) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int c = chunk * 4 + e;
-                    if (c < CP) zt[c][r][lc] = c < C ? zq[k][e] + bq[k][e] : -1e30f;
+                    zt[c][r][lc] = c < C ? zq[k][e] + bq[k][e] : -1e30f;
                 }
             }
         }

@@ -164,7 +164,7 @@ Plan make_plan(const st_head_desc& d)
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
     p.tadj = take(off, (size_t)g.n * g.C * hw * 4);
     p.z_parts = p.mfma ? g.c2 / 64 : 0;
-    if (p.mfma) p.zpart = take(off, (size_t)p.z_parts * PP * 32 * 4);
+    if (p.mfma) p.zpart = take(off, (size_t)p.z_parts * PP * ((g.C + 3) / 4 * 4) * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
     p.grad_stride = (p.po.total + 3) / 4 * 4;
     p.head_stride = p.grad_stride;

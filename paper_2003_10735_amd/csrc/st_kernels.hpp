@@ -46,7 +46,7 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
 size_t loss_slot_floats(const Geo& g);
 int loss_blocks(const Geo& g);
 // Where the loss kernel finds the low-resolution logits: either the planar tensor [n, C, h, w], or
-// the shares the classifier-fused convolution left behind, [n_parts][padded position][32 classes],
+// the shares the classifier-fused convolution left behind, [n_parts][padded position][classes rounded up to a multiple of four],
 // to be added in ascending order together with the bias b3; in that case the kernel also writes
 // the sums to the planar tensor z_out (each tile its own cells), if given.
 struct ZSrc {
