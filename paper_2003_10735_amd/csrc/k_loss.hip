@@ -58,7 +58,7 @@ constexpr int LOSS_THREADS = 2 * 8 * LOSS_TX;   // two threads per pixel column 
 //  compute unit: the phases of one then fill the barriers and memory waits of the other)
 template <int CP, bool GRAD>
 __global__ void __launch_bounds__(LOSS_THREADS, (CP <= 24 ? 4 : 2))
-k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
+k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
        unsigned long long* __restrict__ conf, Geo g, LossTiling lt, int n_tiles)
 {
@@ -154,7 +154,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
         const int q = tile_x * LOSS_TX + tq;
         if ((q == 0 && j < 4) || (q == g.w - 1 && j >= 4)) { w_mid += w_side; w_side = 0.f; }
     }
-    const int32_t* lab_img = labels ? labels + (size_t)img * g.H * g.W : nullptr;
+    const uint8_t* lab_img = labels ? labels + (size_t)img * g.H * g.W : nullptr;
     uint8_t* pred_img = pred ? pred + (size_t)img * g.H * g.W : nullptr;
     const int Yb = qy * 8 + half * 4;    // first of this thread's four pixel rows
     // labels of this thread's 4 pixels, fetched before the barrier
@@ -162,7 +162,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
     float w4[4] = {1.f, 1.f, 1.f, 1.f};      // loss weight of each pixel
     if (lab_img) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : -1;
+        for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : 255;
         if (wmap) {
             const uint8_t* wm = wmap + (size_t)img * g.H * g.W;
 #pragma unroll
@@ -244,7 +244,7 @@ k_loss(ZSrc zs, const int32_t* __restrict__ labels, const uint8_t* __restrict__ 
         if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
         if (lab_img) {
             const int y = lab4[i];
-            const bool valid = y != g.ignore_index && y >= 0 && y < C;   // y = -1 off the frame
+            const bool valid = y < C;     // (255: ignored, no class index, or off the frame)
             const float mb = -m * 1.44269504088896341f;
             float sum = 0.f;
 #pragma unroll
@@ -371,7 +371,7 @@ size_t loss_slot_floats(const Geo& g)
 int loss_blocks(const Geo& g) { return g.n * loss_tiling(g).tiles(); }
 
 template <int CP>
-static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* wmap,
+static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* labels, const uint8_t* wmap,
                         const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
                         const unsigned long long* n_valid, bool grad, bool assemble)
@@ -405,7 +405,7 @@ static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* lab
     default: c.status = ST_ERR_SHAPE; break;                                                  \
     }
 
-void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* wmap, const float* T,
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* labels, const uint8_t* wmap, const float* T,
                uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble)

@@ -315,6 +315,7 @@ struct BeginArgs {
     int pack_vec;                          // the 16-byte packing role over the padded grid
     int pack_x, pack_y, nb_pack;           // pack grid: pack_x column tiles x pack_y channel tiles x rows
     const int32_t* labels; const uint8_t* wmap; float* T; unsigned long long* n_valid; int CP, nb_label;
+    uint8_t* lab8;                         // the labels as bytes for the loss kernel (written by the label role)
     int nb_update, nb_update_all;          // blocks of the parameter role per head, and of all heads
     Geo g;
 };
@@ -328,7 +329,7 @@ __global__ void __launch_bounds__(256) k_call_begin(BeginArgs q, UpdateArgs a, F
     if (b < q.nb_label) {
         float* colsum = dyn_lds;
         unsigned int* cnt_part = (unsigned int*)(dyn_lds + q.CP * (LABEL_NCOL + 1));
-        label_adjoint_block(q.labels, q.wmap, q.T, q.n_valid, q.g, b, colsum, cnt_part, q.CP);
+        label_adjoint_block(q.labels, q.wmap, q.T, q.n_valid, q.g, b, colsum, cnt_part, q.CP, q.lab8);
         return;
     }
     b -= q.nb_label;
@@ -475,7 +476,7 @@ void call_begin(Ctx& c, const Plan& p, char* ws, const void* features, int feat_
     q.g = g;
     q.CP = (g.C + 3) / 4 * 4;
     if (labels) {
-        q.labels = labels; q.wmap = wmap; q.T = (float*)(ws + p.tadj);
+        q.labels = labels; q.wmap = wmap; q.T = (float*)(ws + p.tadj); q.lab8 = (uint8_t*)(ws + p.lab8);
         q.n_valid = (unsigned long long*)(ws + p.counters);
         q.nb_label = g.n * g.h * cdiv(g.w, LABEL_TX);
     }

@@ -163,6 +163,7 @@ Plan make_plan(const st_head_desc& d)
     p.z = take(off, (size_t)g.n * g.C * hw * 4);
     p.gz = take(off, (size_t)g.n * g.C * hw * 4);
     p.tadj = take(off, (size_t)g.n * g.C * hw * 4);
+    p.lab8 = take(off, (size_t)g.pixels());
     p.z_parts = p.mfma ? g.c2 / 64 : 0;
     if (p.mfma) p.zpart = take(off, (size_t)p.z_parts * PP * ((g.C + 3) / 4 * 4) * 4);
     p.g_slots = take(off, loss_slot_floats(g) * 4);
@@ -671,7 +672,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         // (unless the caller expects a key frame: then the first pass is like every later one)
         const bool key_hint = early_exit && expect_key_frame;
         const bool score_only = early_exit && it == 0 && !key_hint;
-        loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj),
+        loss_pass(c, g, z_source(p, ws, z), (const uint8_t*)(ws + p.lab8), pixel_weights, (const float*)(ws + p.tadj),
                   (out && (last || early_exit)) ? out->pred : nullptr,
                   (float*)(ws + p.g_slots),
                   (float*)(ws + p.gz), (float*)(ws + p.loss_part), conf, n_valid, !last && !score_only, !p.mfma);
@@ -761,7 +762,7 @@ int st_partial_distill(const st_head_desc* desc, const void* features, const int
         }
         if (stop) break;
         if (score_only)   // the gradient half of the pass just scored: no counts, no loss, no class map again
-            loss_pass(c, g, z_source(p, ws, z), teacher_labels, pixel_weights, (const float*)(ws + p.tadj), nullptr,
+            loss_pass(c, g, z_source(p, ws, z), (const uint8_t*)(ws + p.lab8), pixel_weights, (const float*)(ws + p.tadj), nullptr,
                       (float*)(ws + p.g_slots), (float*)(ws + p.gz), nullptr, nullptr, n_valid, true, !p.mfma);
         if (!backward_queued) backward(c, p, ws, feature_grad);
         AdamStep ad;

@@ -145,7 +145,8 @@ constexpr int LABEL_NCOL = LABEL_TX * 8 + 8;
 __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ labels,
                                                     const uint8_t* __restrict__ wmap, float* __restrict__ T,
                                                     unsigned long long* __restrict__ n_valid, const Geo& g,
-                                                    int block, float* colsum, unsigned int* cnt_part, int CP)
+                                                    int block, float* colsum, unsigned int* cnt_part, int CP,
+                                                    uint8_t* __restrict__ lab8)
 {
     constexpr int NCOL = LABEL_NCOL, PITCH = LABEL_NCOL + 1;
     const int tid = threadIdx.x;
@@ -204,6 +205,10 @@ __device__ __forceinline__ void label_adjoint_block(const int32_t* __restrict__ 
                 run += (float)ws[k][r] * tap_weight(Y, cy, g.h);
                 if (own_col && r >= 4 && r < 12) cnt += ws[k][r];
             }
+            // the block's own 8 x 256 pixels as bytes for the loss kernel, which reads them in every
+            // pass: the class, or 255 where the pixel does not count (a quarter of the bytes)
+            if (lab8 && xin && own_col && r >= 4 && r < 12)
+                lab8[(size_t)img * g.H * g.W + (size_t)Y * g.W + X] = ok ? (uint8_t)y : (uint8_t)255;
         }
         if (run_y >= 0) colsum[run_y * PITCH + col] += run;
     }

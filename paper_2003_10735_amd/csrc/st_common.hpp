@@ -125,6 +125,7 @@ struct Plan {
     size_t grad3;                         // per-block partials of dW3 / db3
     size_t zero_begin, zero_end;          // region cleared at the start of every call
     size_t z, g_slots, gz, tadj;   // tadj: U^T of the one-hot labels, [n, C, h, w] float32
+    size_t lab8;                   // the labels as bytes, [n, 8h, 8w]: the class, or 255 for a pixel that does not count
     size_t zpart; int z_parts;     // shares of the logits left by the classifier-fused convolution
     size_t theta, vel, vel2, grad, best;   // vel: velocity or Adam's m; vel2: Adam's v
     size_t wq1, wq1t, wq2, wq2t, wq3;      // bfloat16 operand copies of the weights

@@ -54,7 +54,8 @@ struct ZSrc {
     const float* parts; int n_parts; const float* b3; float* z_out;
     size_t b3_stride;     // floats between the biases of two heads (one head per frame)
 };
-void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const int32_t* labels, const uint8_t* pixel_weights,
+// labels8: the labels as bytes (class, or 255 where the pixel does not count), or null: no loss, prediction only
+void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* labels8, const uint8_t* pixel_weights,
                const float* T, uint8_t* pred,
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble);
