@@ -46,26 +46,26 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # the kernel source it was measured on:
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.53, 8.83),
+    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.52, 8.83),
     ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 13.75, 7.55),
     ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 6.99, 9.91),
     ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 10.45, 3.77),
-    ("720p", "upsample_ce_grad"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 4.75, 4.71),
-    ("720p", "upsample_ce"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 3.02, 1.82),
+    ("720p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 4.73, 4.71),
+    ("720p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 3.02, 1.82),
     ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 16.99, 11.36),
-    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 74.01, 8.83),
-    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.45, 16.59),
+    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 74.03, 8.83),
+    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.46, 16.59),
     ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 11.83, 21.77),
     ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 19.69, 8.29),
-    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 10.09, 11.14),
-    ("1080p", "upsample_ce"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 6.31, 4.09),
-    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 35.89, 24.95),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.00, 17.47),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 51.97, 60.38),
-    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 41.96, 83.02),
+    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 10.07, 11.14),
+    ("1080p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 6.31, 4.09),
+    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 35.88, 24.95),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 266.99, 17.46),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 51.85, 60.38),
+    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 42.01, 83.02),
     ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 69.10, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 41.58, 73.24),
-    ("batch4", "upsample_ce"): ("k_loss.hip", "5ec9bb0d8f6357895878f4cc45a21e9fc9b580c65e81f212435471eb0cd7a65b", 23.14, 7.72),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 41.37, 73.62),
+    ("batch4", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 23.14, 7.72),
     ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 101.91, 90.68),
 }
 

@@ -101,14 +101,23 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
             const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
             const size_t mp = ((size_t)img * g.Hp + cy + 1) * g.Wp + cx + 1;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            // at most four shares (256 channels); absent ones re-read the last with weight 0, so
-            // that no load sits under a branch
+            // one, two or four shares (64, 128, 256 channels), added in ascending order; within a
+            // group of two an absent share re-reads the last with weight 0, so that the loads of a
+            // group are issued together
+            const float* zp = zs.parts + mp * CP + chunk * 4;
+            const size_t share = PP * CP;
+            {
+                const f32x4 v0 = *(const f32x4*)zp;
+                const f32x4 v1 = *(const f32x4*)(zp + (zs.n_parts > 1 ? share : 0));
+                const float w1 = zs.n_parts > 1 ? 1.f : 0.f;
 #pragma unroll
-            for (int part = 0; part < 4; ++part) {
-                const float wgt = part < zs.n_parts ? 1.f : 0.f;
-                const f32x4 v = *(const f32x4*)(zs.parts + ((size_t)min(part, zs.n_parts - 1) * PP + mp) * CP + chunk * 4);
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(w1, v1[e], __builtin_fmaf(1.f, v0[e], acc[e]));
+            }
+            if (zs.n_parts > 2) {
+                const f32x4 v2 = *(const f32x4*)(zp + 2 * share);
+                const f32x4 v3 = *(const f32x4*)(zp + 3 * share);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(wgt, v[e], acc[e]);
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(1.f, v3[e], __builtin_fmaf(1.f, v2[e], acc[e]));
             }
             zq[k] = acc;
 #pragma unroll
