@@ -46,27 +46,27 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # the kernel source it was measured on:
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.52, 8.83),
+    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.77, 8.83),
     ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 13.75, 7.55),
-    ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 6.99, 9.91),
+    ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 6.99, 6.13),
     ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 10.45, 3.77),
     ("720p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 4.73, 4.71),
     ("720p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 3.02, 1.82),
-    ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 16.99, 11.36),
-    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 74.03, 8.83),
-    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.46, 16.59),
-    ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 11.83, 21.77),
+    ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 13.20, 11.36),
+    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.85, 8.83),
+    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.48, 16.59),
+    ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 11.83, 13.48),
     ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 19.69, 8.29),
     ("1080p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 10.07, 11.14),
     ("1080p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 6.31, 4.09),
-    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 35.88, 24.95),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 266.99, 17.46),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 51.85, 60.38),
-    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 42.01, 83.02),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 69.10, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 41.37, 73.62),
+    ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 27.54, 24.95),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.29, 17.50),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 52.08, 60.38),
+    ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 40.96, 52.83),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 69.09, 30.19),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 41.46, 73.57),
     ("batch4", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 23.14, 7.72),
-    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "e653286eab18ad31e189748a8708c57d7e1db4ee00bb73579aa5fec677d610a4", 101.91, 90.68),
+    ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 71.52, 90.68),
 }
 
 
@@ -106,9 +106,9 @@ def kernel_work(wl):
         "conv1_fwd": ("mfma", conv1), "conv12_wgrad": ("mfma", conv1 + conv2),
         "conv2_fwd": ("mfma", conv2 + conv3), "conv2_dgrad": ("mfma", conv2), "conv1_dgrad": ("mfma", conv1),
         "conv3_fwd": ("mfma", conv3), "conv3_wgrad": ("mfma", conv3), "conv3_dgrad": ("mfma", conv3),
-        # the 1x1 classifier's backward is a skinny contraction (N = classes): a2 read twice (both
-        # layouts), d loss / d z read, da2 written twice (both layouts)
-        "conv3_bwd": ("hbm", (8.0 * wl.c2 + 4.0 * C) * M),
+        # the 1x1 classifier's backward is a skinny contraction (N = classes): a2 read,
+        # d loss / d z read, da2 written twice (both layouts)
+        "conv3_bwd": ("hbm", (6.0 * wl.c2 + 4.0 * C) * M),
         "upsample_ce_grad": ("alu", 19.0 * C * P),
         "upsample_ce": ("alu", 10.0 * C * P),
         "sgd_update": ("hbm", (22.0 if wl.momentum else 14.0) * wl.n_params),

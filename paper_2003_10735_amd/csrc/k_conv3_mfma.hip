@@ -14,6 +14,9 @@
 
 namespace st {
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
 bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 == 256) && C <= 32; }
 
 // ------------------------------------------------------------------ backward
@@ -45,7 +48,7 @@ template <int C2, bool FIN>
 __global__ void __launch_bounds__(256, 1)
 k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
                  const unsigned long long* __restrict__ n_valid, int CP, LossTiling lt,
-                 const bf16* __restrict__ a2, const bf16* __restrict__ a2T,
+                 const bf16* __restrict__ a2,
                  const bf16* __restrict__ W3T, bf16* __restrict__ da2, bf16* __restrict__ da2T,
                  float* __restrict__ part, Geo g, int PPT, int guard, int grp_blocks, int main_blocks, FinishArgs fin)
 {
@@ -65,6 +68,7 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     __shared__ __attribute__((aligned(16))) bf16 g_cp[32 * GP];     // [class][position]
     __shared__ __attribute__((aligned(16))) bf16 g_pc[BP * GC];     // [position][class]
     __shared__ __attribute__((aligned(16))) bf16 Os[BP * OLD];      // da2 tile [position][channel]
+    __shared__ __attribute__((aligned(16))) bf16 A2s[BP * OLD];     // a2 tile [position][channel]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -76,30 +80,27 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
     const int m_end = g.grouped ? (head + 1) * frame : PP;
     W3T += (size_t)head * C2 * 32;
 
-    // ---- early loads: ReLU mask of this lane's position, a2 fragments of this wavefront's tiles
+    // ---- early loads: the block's a2 tile (position-major, 16 bytes per load) on its way to LDS.
+    //      Both uses take it from there: the ReLU mask of the da2 part, and the dW3 part, whose
+    //      reduction runs over the positions and therefore wants 8 consecutive positions of one
+    //      channel per lane -- the transposing LDS read hands out exactly that, so the layer-2
+    //      convolution need not leave a channel-major copy of a2 behind.
     const int pm = (wave & 1) * 32 + l32;          // position (inside the block) for the da2 part
     const int t0 = (wave >> 1) * OH;               // first channel tile of the da2 part
-    const size_t mrow = (size_t)min(m0 + pm, PP - 1) * C2;
-    bf16x4 mk[OH][4];
+    constexpr int A2_CHUNKS = BP * (C2 / 8) / 256; // 16-byte chunks of the tile per thread
+    u32x4 a2v[A2_CHUNKS];
 #pragma unroll
-    for (int t = 0; t < OH; ++t)
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(a2 + mrow + (t0 + t) * 32 + rg * 8 + lhi * 4);
+    for (int k = 0; k < A2_CHUNKS; ++k) {
+        const int q = tid + 256 * k, p = q / (C2 / 8), part8 = q - p * (C2 / 8);
+        // (rows past the last position repeat it: d loss / d z is zero there)
+        a2v[k] = *(const u32x4*)(a2 + (size_t)min(m0 + p, PP - 1) * C2 + part8 * 8);
+    }
     // W3^T fragments of this wavefront's da2 tiles: rows = channels, k = 16 classes per step
     bf16x8 wfr[OH][2];
 #pragma unroll
     for (int t = 0; t < OH; ++t)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) wfr[t][ks] = *(const bf16x8*)(W3T + ((size_t)(t0 + t) * 32 + l32) * 32 + ks * 16 + lhi * 8);
-    bf16x8 xf[DW][KS];
-#pragma unroll
-    for (int d = 0; d < DW; ++d) {
-        const int t = min(wave + 4 * d, OT - 1);
-        const bf16* xrow = a2T + xt_index(t * 32 + l32, guard + m0 + lhi * 8, PPT / 8);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xf[d][ks] = *(const bf16x8*)(xrow + ks * 512);   // two 8-position groups per step
-    }
-
     // ---- stage g (both orientations) and W3^T
     {
         const int p = tid & (BP - 1), cq = tid / BP;     // this thread: one position, every fourth class
@@ -154,7 +155,19 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
             g_pc[p * GC + cc] = q;
         }
     }
+#pragma unroll
+    for (int k = 0; k < A2_CHUNKS; ++k) {
+        const int q = tid + 256 * k, p = q / (C2 / 8), part8 = q - p * (C2 / 8);
+        *(u32x4*)(A2s + p * OLD + part8 * 8) = a2v[k];
+    }
     __syncthreads();
+
+    // ReLU mask of this lane's position
+    bf16x4 mk[OH][4];
+#pragma unroll
+    for (int t = 0; t < OH; ++t)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) mk[t][rg] = *(const bf16x4*)(A2s + pm * OLD + (t0 + t) * 32 + rg * 8 + lhi * 4);
 
     // ---- da2: D[o][pos] = sum_c W3T[o][c] * g[c][pos], two K steps cover 32 classes
     {
@@ -195,7 +208,14 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const bf16x8 gf = *(const bf16x8*)(g_cp + l32 * GP + ks * 16 + lhi * 8);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, xf[d][ks], acc, 0, 0, 0);
+                // B fragment: lane = channel l32 of tile t, positions 16 ks + 8 lhi .. + 7.  In a
+                // group of 16 lanes, lane r names the row (position r / 4, channels 4 (r % 4) .. + 3)
+                // and lane i receives channel i of positions 0 .. 3 of the group's rows: two reads.
+                const bf16* row = A2s + (ks * 16 + lhi * 8 + ((lane & 15) >> 2)) * OLD + t * 32 + (lane & 16) + 4 * (lane & 3);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)row);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(row + 4 * OLD));
+                const s16x8 xs = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, __builtin_bit_cast(bf16x8, xs), acc, 0, 0, 0);
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -232,7 +252,7 @@ int conv3_bwd_blocks(const Geo& g) { return cdiv(g.padded_positions() / g.heads(
 size_t conv3_bwd_slot_floats(const Geo& g) { return (size_t)32 * g.c2 + 32; }
 
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
-                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* W3T,
                     bf16* da2, bf16* da2T, float* part, const FinishArgs* finish)
 {
     const Geo& g = p.g;
@@ -251,10 +271,10 @@ void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
     do {                                                                                                       \
         if (finish)                                                                                            \
             ST_LAUNCH(c, "conv3_bwd_mfma+finish_pass", (k_conv3_bwd_mfma<C2, true>), grid, dim3(256), 0, slots, T,   \
-                      n_valid, CP, p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin); \
+                      n_valid, CP, p.lt, a2, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin); \
         else                                                                                                   \
             ST_LAUNCH(c, "conv3_bwd_mfma", (k_conv3_bwd_mfma<C2, false>), grid, dim3(256), 0, slots, T, n_valid, CP, \
-                      p.lt, a2, a2T, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin);    \
+                      p.lt, a2, W3T, da2, da2T, part, g, p.PPT, p.guard, grp_blocks, main_blocks, fin);    \
     } while (0)
     switch (g.c2) {
     case 64: ST_C3B(64); break;

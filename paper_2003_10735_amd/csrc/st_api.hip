@@ -153,7 +153,6 @@ Plan make_plan(const st_head_desc& d)
     if (p.mfma) {
         p.featT = take(off, (size_t)g.c_in * p.PPT * 2);
         p.a1T = take(off, (size_t)g.c1 * p.PPT * 2);
-        p.a2T = take(off, (size_t)g.c2 * p.PPT * 2);
         p.da1T = take(off, (size_t)g.c1 * p.PPT * 2);
         p.da2T = take(off, (size_t)g.c2 * p.PPT * 2);
     }
@@ -336,12 +335,13 @@ static void prepare_workspace(Ctx& c, const Plan& p, char* ws, bool feat_covered
         }
         // channel-major copies [C/32][PPT/8][32][8]: per channel block, the column groups of the
         // head guard and those from the end of the positions (rounded down to a group) on
-        const size_t tm[5] = {p.a1T, p.a2T, p.da1T, p.da2T, p.featT};
+        const size_t tm[4] = {p.a1T, p.da1T, p.da2T, p.featT};
+        const int tc[4] = {g.c1, g.c1, g.c2, g.c_in};
         const size_t blk = (size_t)p.PPT * 32 * 2;                 // bytes of one channel block
         const size_t head = G * 32 * 2;                            // guard columns (a multiple of 8)
         const size_t tail_at = (G + PP / 8 * 8) * 32 * 2;
-        for (int i = 0; i < nbuf; ++i)
-            for (int b = 0; b < pc[i] / 32; ++b) {
+        for (int i = 0; i < nbuf - 1; ++i)
+            for (int b = 0; b < tc[i] / 32; ++b) {
                 z.add(ws + tm[i] + b * blk, head);
                 z.add(ws + tm[i] + b * blk + tail_at, blk - tail_at);
             }
@@ -364,7 +364,7 @@ static void forward(Ctx& c, const Plan& p, char* ws, float* z)
     conv3x3_mfma(c, "conv1_fwd_mfma", p, (const bf16*)(ws + p.feat), (const bf16*)(ws + p.wq1), theta + p.po.b1,
                  nullptr, (bf16*)(ws + p.a1), (bf16*)(ws + p.a1T), g.c_in, g.c1, 0, 1);
     conv3x3_mfma(c, "conv2_fwd_logits_mfma", p, (const bf16*)(ws + p.a1), (const bf16*)(ws + p.wq2),
-                 theta + p.po.b2, nullptr, (bf16*)(ws + p.a2), (bf16*)(ws + p.a2T), g.c1, g.c2, 0, 2,
+                 theta + p.po.b2, nullptr, (bf16*)(ws + p.a2), nullptr, g.c1, g.c2, 0, 2,
                  (const bf16*)(ws + p.wq3), (float*)(ws + p.zpart));
 }
 
@@ -395,7 +395,7 @@ static void backward(Ctx& c, const Plan& p, char* ws, float* dfeat, const Finish
     const Geo& g = p.g;
     float* grad = (float*)(ws + p.grad);
     conv3_bwd_mfma(c, p, (const float*)(ws + p.g_slots), (const float*)(ws + p.tadj),
-                   (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2), (const bf16*)(ws + p.a2T),
+                   (const unsigned long long*)(ws + p.counters), (const bf16*)(ws + p.a2),
                    (const bf16*)(ws + p.wq3t), (bf16*)(ws + p.da2), (bf16*)(ws + p.da2T), (float*)(ws + p.grad3), finish);
     conv3x3_mfma(c, "conv2_dgrad_mfma", p, (const bf16*)(ws + p.da2), (const bf16*)(ws + p.wq2t), nullptr,
                  (const bf16*)(ws + p.a1), dfeat ? (bf16*)(ws + p.da1) : nullptr, (bf16*)(ws + p.da1T), g.c2, g.c1, 1, 2);

@@ -121,7 +121,7 @@ struct Plan {
     int PPT;            // row pitch (elements) of the channel-major copies
     // byte offsets
     size_t feat, a1, a2, da1, da2;
-    size_t featT, a1T, a2T, da1T, da2T;   // channel-major copies [C][PPT] for the weight-gradient kernels
+    size_t featT, a1T, da1T, da2T;        // channel-major copies [C][PPT] for the weight-gradient kernels
     size_t grad3;                         // per-block partials of dW3 / db3
     size_t zero_begin, zero_end;          // region cleared at the start of every call
     size_t z, g_slots, gz, tadj;   // tadj: U^T of the one-hot labels, [n, C, h, w] float32

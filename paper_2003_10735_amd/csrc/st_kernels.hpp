@@ -38,7 +38,7 @@ int conv3_bwd_blocks(const Geo& g);
 size_t conv3_bwd_slot_floats(const Geo& g);
 // finish: the bookkeeping of the pass that precedes this backward pass rides on the launch (a few more blocks)
 void conv3_bwd_mfma(Ctx& c, const Plan& p, const float* slots, const float* T,
-                    const unsigned long long* n_valid, const bf16* a2, const bf16* a2T, const bf16* W3T,
+                    const unsigned long long* n_valid, const bf16* a2, const bf16* W3T,
                     bf16* da2, bf16* da2T, float* part,
                     const FinishArgs* finish = nullptr);
 
