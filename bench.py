@@ -46,26 +46,26 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # the kernel source it was measured on:
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.77, 8.83),
+    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.78, 8.83),
     ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 13.75, 7.55),
     ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 6.99, 6.13),
     ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 10.45, 3.77),
-    ("720p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 4.73, 4.71),
-    ("720p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 3.02, 1.82),
+    ("720p", "upsample_ce_grad"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 4.73, 4.71),
+    ("720p", "upsample_ce"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 3.01, 1.82),
     ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 13.20, 11.36),
     ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.85, 8.83),
     ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.48, 16.59),
     ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 11.83, 13.48),
     ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 19.69, 8.29),
-    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 10.07, 11.14),
-    ("1080p", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 6.31, 4.09),
+    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 10.07, 11.14),
+    ("1080p", "upsample_ce"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 6.30, 4.09),
     ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 27.54, 24.95),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 267.29, 17.50),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 52.08, 60.38),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 269.26, 17.76),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 52.07, 60.38),
     ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 40.96, 52.83),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 69.09, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 41.46, 73.57),
-    ("batch4", "upsample_ce"): ("k_loss.hip", "c0b12c474743771cd1e07040b4ce0d814e6ec3b8c1b2489c6a573fc7195f503f", 23.14, 7.72),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 68.98, 30.19),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 30.13, 22.21),
+    ("batch4", "upsample_ce"): ("k_loss.hip", "f9b76d88581485d063848b45905a5df3ea87c4cffd9b32eadb75c2d85a3d01c6", 23.12, 7.72),
     ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "627e48c869a93c67767c61d3849b7a7cb44f09402da30ab6ab8e6595a588fdd9", 71.52, 90.68),
 }
 

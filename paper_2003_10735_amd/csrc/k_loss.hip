@@ -36,6 +36,14 @@ __device__ __forceinline__ float lerp1(float a, float b, float t)
     return __builtin_fmaf(t, d, a);
 }
 
+// a product that stays a product: a following addition is not contracted into it, so that the
+// addition can take its cross-lane operand directly (one instruction instead of move + fma)
+__device__ __forceinline__ float mul_rounded(float a, float b)
+{
+#pragma clang fp contract(off)
+    return a * b;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
 {
@@ -56,7 +64,10 @@ constexpr int LOSS_THREADS = 2 * 8 * LOSS_TX;   // two threads per pixel column 
 
 // (up to 24 padded classes the kernel is held to 128 registers, so that two blocks share a
 //  compute unit: the phases of one then fill the barriers and memory waits of the other)
-template <int CP, bool GRAD>
+// CP: classes rounded up to a multiple of four (the layout of the logit shares, of the staged
+// cells and of the slots); CA: the number of classes itself, CP - 3 .. CP -- the per-pixel
+// arithmetic runs over exactly these, so a padded class costs no instruction.
+template <int CP, int CA, bool GRAD>
 __global__ void __launch_bounds__(LOSS_THREADS, (CP <= 24 ? 4 : 2))
 k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ wmap, const float* __restrict__ T,
        uint8_t* __restrict__ pred, float* __restrict__ slots, float* __restrict__ loss_part,
@@ -220,36 +231,34 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
 
     // x-interpolated logits on this half's upper cell row and their difference to the lower one
     // (the y interpolation is fma(fy, difference, upper row): same roundings as lerp1)
-    float Hu[CP], D[CP];
+    float Hu[CA], D[CA];
 #pragma unroll
-    for (int c = 0; c < CP; ++c) {
+    for (int c = 0; c < CA; ++c) {
         Hu[c] = lerp1(zt[c][half][cl], zt[c][half][cl + 1], fx);
         const float Hl = lerp1(zt[c][half + 1][cl], zt[c][half + 1][cl + 1], fx);
         D[c] = __fsub_rn(Hl, Hu[c]);
     }
-    float Vu[GRAD ? CP : 1], Vl[GRAD ? CP : 1];    // U^T along y: upper / lower cell row of the half
+    float Vu[GRAD ? CA : 1], Vl[GRAD ? CA : 1];    // U^T along y: upper / lower cell row of the half
     if (GRAD) {
 #pragma unroll
-        for (int c = 0; c < CP; ++c) { Vu[c] = 0.f; Vl[c] = 0.f; }
+        for (int c = 0; c < CA; ++c) { Vu[c] = 0.f; Vl[c] = 0.f; }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         // weight of the lower cell row: (9, 11, 13, 15) / 16 in the upper half, (1, 3, 5, 7) / 16 below
         const float fy = half ? (2 * i + 1) * 0.0625f : (2 * i + 9) * 0.0625f;
         const int Y = Yb + i;
-        float Z[CP];
+        float Z[CA];
 #pragma unroll
-        for (int c = 0; c < CP; ++c) Z[c] = __builtin_fmaf(fy, D[c], Hu[c]);
+        for (int c = 0; c < CA; ++c) Z[c] = __builtin_fmaf(fy, D[c], Hu[c]);
         // prediction: the largest logit, lowest index among equals
         float m = Z[0];
 #pragma unroll
-        for (int c = 1; c < CP; ++c) m = fmaxf(m, Z[c]);
-        // (only real classes can win: when every real logit is NaN the maximum is the padding's
-        //  value, and then -- as when nothing compares equal at all -- the answer is class 0, never
-        //  an index outside [0, C))
+        for (int c = 1; c < CA; ++c) m = fmaxf(m, Z[c]);
+        // (when nothing compares equal to the maximum -- NaN logits -- the answer is class 0)
         int best = 0;
 #pragma unroll
-        for (int c = CP - 1; c >= 0; --c) best = (Z[c] == m && (c < CP - 3 || c < C)) ? c : best;
+        for (int c = CA - 1; c >= 0; --c) best = Z[c] == m ? c : best;
         if (pred_img && col_ok) pred_img[(size_t)Y * g.W + X] = (uint8_t)best;
         if (lab_img) {
             const int y = lab4[i];
@@ -257,7 +266,7 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
             const float mb = -m * 1.44269504088896341f;
             float sum = 0.f;
 #pragma unroll
-            for (int c = 0; c < CP; ++c) {
+            for (int c = 0; c < CA; ++c) {
                 Z[c] = __builtin_amdgcn_exp2f(__builtin_fmaf(Z[c], 1.44269504088896341f, mb));
                 sum += Z[c];
             }
@@ -269,7 +278,7 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
                 const float rs = valid ? w4[i] * __builtin_amdgcn_rcpf(sum) : 0.f;
                 const float wa = (1.f - fy) * rs, wb = fy * rs;
 #pragma unroll
-                for (int c = 0; c < CP; ++c) {
+                for (int c = 0; c < CA; ++c) {
                     Vu[c] = __builtin_fmaf(wa, Z[c], Vu[c]);
                     Vl[c] = __builtin_fmaf(wb, Z[c], Vl[c]);
                 }
@@ -281,24 +290,27 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
         // border row itself
         if (qy == 0 && half == 0) {
 #pragma unroll
-            for (int c = 0; c < CP; ++c) { Vl[c] += Vu[c]; Vu[c] = 0.f; }
+            for (int c = 0; c < CA; ++c) { Vl[c] += Vu[c]; Vu[c] = 0.f; }
         }
         if (qy == g.h - 1 && half == 1) {
 #pragma unroll
-            for (int c = 0; c < CP; ++c) { Vu[c] += Vl[c]; Vl[c] = 0.f; }
+            for (int c = 0; c < CA; ++c) { Vu[c] += Vl[c]; Vl[c] = 0.f; }
         }
         // adjoint of the x interpolation, reduced over the group's 8 columns: columns 0-3 feed
         // the left and the centre cell, columns 4-7 the centre and the right cell
+        float2* my_contrib = (float2*)&contrib[half][0][0][tq][0] + (j >> 2);
 #pragma unroll
-        for (int c = 0; c < CP; ++c) {
+        for (int c = 0; c < CA; ++c) {
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 const float v = r == 0 ? Vu[c] : Vl[c];
-                const float side = quad_sum(v * w_side);   // lanes 0-3: left cell, lanes 4-7: right cell
-                const float mid = group8_sum(v * w_mid);
+                float side = quad_sum(mul_rounded(v, w_side));   // lanes 0-3: left cell, lanes 4-7: right cell
+                float mid = group8_sum(mul_rounded(v, w_mid));
+                // (the sums are complete before the branch: inside it the cross-lane operand and
+                //  its addition would be two instructions)
+                asm volatile("" : "+v"(side), "+v"(mid));
                 // lane 0 of the group writes (left, centre), lane 4 writes (right, unused)
-                if ((j & 3) == 0)
-                    *(float2*)&contrib[half][c][r][tq][j >> 1] = make_float2(side, j == 0 ? mid : 0.f);
+                if ((j & 3) == 0) my_contrib[(c * 2 + r) * (LOSS_TX * 2)] = make_float2(side, j == 0 ? mid : 0.f);
             }
         }
     }
@@ -329,7 +341,7 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int rr = r - hf;
-                if (rr < 0 || rr > 1) continue;
+                if (rr < 0 || rr > 1 || c >= CA) continue;    // (a padded class: nothing was handed over)
                 if (lc < LOSS_TX) v += contrib[hf][c][rr][lc][0];
                 if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[hf][c][rr][lc - 1][1];
                 if (lc >= 2) v += contrib[hf][c][rr][lc - 2][2];
@@ -379,7 +391,7 @@ size_t loss_slot_floats(const Geo& g)
 
 int loss_blocks(const Geo& g) { return g.n * loss_tiling(g).tiles(); }
 
-template <int CP>
+template <int CP, int CA>
 static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* labels, const uint8_t* wmap,
                         const float* T,
                         uint8_t* pred, float* slots, float* gz, float* loss_part, unsigned long long* conf,
@@ -389,14 +401,14 @@ static void loss_launch(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* lab
     const int n_tiles = g.n * lt.tiles();
     const int blocks = (n_tiles + 7) / 8 * 8;      // whole rounds over the eight XCDs
     if (grad) {
-        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred,
+        ST_LAUNCH(c, "upsample_ce_grad", (k_loss<CP, CA, true>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred,
                   slots, loss_part, conf, g, lt, n_tiles);
         // the matrix-core backward kernel adds the slots itself; the plain path wants g assembled
         if (assemble)
             ST_LAUNCH(c, "assemble_dz", (k_assemble_g<CP>), dim3(cdiv((long long)g.n * g.C * g.h * g.w, 256)),
                       dim3(256), 0, (const float*)slots, T, n_valid, gz, g, lt);
     } else {
-        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred, slots,
+        ST_LAUNCH(c, "upsample_ce", (k_loss<CP, CA, false>), dim3(blocks), dim3(LOSS_THREADS), 0, zs, labels, wmap, T, pred, slots,
                   loss_part, conf, g, lt, n_tiles);
     }
 }
@@ -419,9 +431,17 @@ void loss_pass(Ctx& c, const Geo& g, const ZSrc& zs, const uint8_t* labels, cons
                float* slots, float* gz, float* loss_part, unsigned long long* conf,
                const unsigned long long* n_valid, bool grad, bool assemble)
 {
-#define ST_CALL(CP) loss_launch<CP>(c, g, zs, labels, wmap, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble)
+#define ST_ARGS c, g, zs, labels, wmap, T, pred, slots, gz, loss_part, conf, n_valid, grad, assemble
+#define ST_CALL(CP)                                                                           \
+    switch (CP - g.C) {                                                                       \
+    case 0: loss_launch<CP, CP>(ST_ARGS); break;                                              \
+    case 1: loss_launch<CP, CP - 1>(ST_ARGS); break;                                          \
+    case 2: loss_launch<CP, CP - 2>(ST_ARGS); break;                                          \
+    default: loss_launch<CP, CP - 3>(ST_ARGS); break;                                         \
+    }
     ST_FOR_CP(ST_CALL)
 #undef ST_CALL
+#undef ST_ARGS
 }
 
 }  // namespace st
