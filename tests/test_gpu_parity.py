@@ -11,7 +11,7 @@ import oracle as O
 import paper_2003_10735_amd as st
 import workloads as WL
 from gpu_util import (check_pred_against_oracle, check_staged_bit_exact, rel_err, run_gpu, run_oracle,
-                      to_dev_features, update_err)
+                      progress, to_dev_features, update_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -593,6 +593,31 @@ def test_matrix_core_path_small_shapes(case):
     again = run_gpu(wl, f, lab, p)
     for k in ("params", "losses", "mious", "conf", "pred"):
         np.testing.assert_array_equal(gpu[k], again[k])
+
+
+@pytest.mark.parametrize("path", ["f32", "mfma"])
+def test_every_class_count(path):
+    """2 .. 32 classes, each on both paths: the fused loss kernel is compiled once per class count
+    (its arithmetic runs over exactly the classes that exist, its buffers over the count rounded
+    up to a multiple of four), so every count is a kernel of its own.  Small grids with a ragged
+    tile edge, ignored pixels, two steps: losses and parameters against the oracle; predictions,
+    confusion counts and mean IoU bit for bit from the call's own final logits."""
+    for C in range(2, 33):
+        if path == "f32":
+            wl = WL.small_variant(WL.WORKLOADS["tiny"], steps=2, lr=0.05, n_sites=11, n=1, c_in=6, h=4, w=35, c1=8,
+                                  c2=8, n_classes=C, ignore_index=255, ignore_fraction=0.05)
+        else:
+            wl = WL.small_variant(WL.WORKLOADS["720p"], steps=2, lr=0.02, n_sites=11, n=1, c_in=64, h=4, w=35, c1=32,
+                                  c2=64, n_classes=C, ignore_index=255, ignore_fraction=0.05)
+        f, lab, p = inputs(wl)
+        gpu = run_gpu(wl, f, lab, p)
+        check_staged_bit_exact(wl, gpu, lab)
+        ora = run_oracle(wl, f, lab, p, bf16_operands=(path == "mfma"))
+        tol = 1e-4 if path == "f32" else 5e-4
+        assert rel_err(gpu["losses"], ora["losses"]) < tol, C
+        assert rel_err(gpu["params"], ora["params"]) < tol, C
+        assert update_err(f"{C} classes {path}", gpu["params"] - p, ora["params"] - p) < (2e-3 if path == "f32" else 3e-2), C
+        progress(f"every class count: {path} C={C} ok")
 
 
 # ------------------------------------------------------------------ Adam (the paper's optimiser, Section 5.2)
