@@ -220,14 +220,14 @@ k_conv3_bwd_mfma(const float* __restrict__ slots, const float* __restrict__ T,
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int c = (r >> 2) * 8 + lhi * 4 + (r & 3);
-                slot[c * C2 + t * 32 + l32] = acc[r];
+                if (c < g.C) slot[c * C2 + t * 32 + l32] = acc[r];    // (rows beyond the classes are never read)
             }
         }
     }
     if (tid < 32) {
         float s = 0.f;
         for (int p = 0; p < BP; ++p) s += (float)g_cp[tid * GP + p];
-        slot[32 * C2 + tid] = s;
+        if (tid < g.C) slot[32 * C2 + tid] = s;
     }
     __syncthreads();
 
