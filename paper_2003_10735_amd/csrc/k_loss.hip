@@ -36,14 +36,6 @@ __device__ __forceinline__ float lerp1(float a, float b, float t)
     return __builtin_fmaf(t, d, a);
 }
 
-// a product that stays a product: a following addition is not contracted into it, so that the
-// addition can take its cross-lane operand directly (one instruction instead of move + fma)
-__device__ __forceinline__ float mul_rounded(float a, float b)
-{
-#pragma clang fp contract(off)
-    return a * b;
-}
-
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
 {
@@ -304,8 +296,8 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 const float v = r == 0 ? Vu[c] : Vl[c];
-                float side = quad_sum(mul_rounded(v, w_side));   // lanes 0-3: left cell, lanes 4-7: right cell
-                float mid = group8_sum(mul_rounded(v, w_mid));
+                float side = quad_sum(v * w_side);   // lanes 0-3: left cell, lanes 4-7: right cell
+                float mid = group8_sum(v * w_mid);
                 // (the sums are complete before the branch: inside it the cross-lane operand and
                 //  its addition would be two instructions)
                 asm volatile("" : "+v"(side), "+v"(mid));
