@@ -200,7 +200,7 @@ int st_head_forward(const st_head_desc* desc, const void* features, const float*
  * results as st_head_forward, but the workspace is a device array built into the library:
  * ST_NOALLOC_MAX_WORKSPACE_MIB MiB per GPU the library runs on, held from the first call on that
  * GPU until the process ends (enough for the 1280x720 head 256 -> 128 -> 128 -> 19, which needs
- * 79 MiB).  The call allocates nothing, on the device or through any library; shapes with
+ * 75 MiB).  The call allocates nothing, on the device or through any library; shapes with
  * st_workspace_bytes(desc) above the limit are refused with ST_ERR_TOO_LARGE before any GPU work.
  * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
  * outside a capture.  Every call on a GPU uses that GPU's one array: calls that overlap on one
