@@ -31,8 +31,10 @@ bool conv3_mfma_supported(int c2, int C) { return (c2 == 64 || c2 == 128 || c2 =
 //   (K = classes),
 //   wavefront w computes dW3 for channel tiles w, w+4, ..  over all positions (K = positions),
 // so no sum crosses wavefronts.  Partial dW3 / db3 go to one slot per block; the optimiser
-// kernel adds the slots in order.  All global loads a wavefront needs later (ReLU mask, a2
-// fragments) are issued before the first barrier, so their latency overlaps the staging.
+// kernel adds the slots in order (only the rows of real classes are stored).  The block's a2
+// tile is loaded once, position-major, before the first barrier (its latency overlaps the
+// staging of g) and kept in LDS: the ReLU mask is read from it directly, the dW3 operand
+// through the transposing LDS read.
 // The work per position is small and every phase is a chain of dependent memory round trips, so
 // the block is kept small: the grid then covers the whole chip and each chain is short.
 constexpr int C3B_BP = 64;
