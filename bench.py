@@ -274,15 +274,16 @@ def all_kernel_pass(st, prob, calls):
 
 
 def pick_dominant(work, known):
-    """The kernel with the longest launches (average duration; `known`: name -> (launches, total
-    ms)).  Kernels within 10 % of it count as tied and a tie goes to the matrix-core kernel, so
-    that the choice does not flip from box to box: single kernels vary by +-5 % between boxes, and
-    at 1280x720 the weight-gradient launch and the fused loss kernel are that close (both are
-    reported either way, one in `roofline` and one in `other_kernels`)."""
-    avg = {k: v[1] / v[0] for k, v in known.items()}
-    top = max(avg.values())
-    tied = [k for k in avg if avg[k] >= 0.90 * top]
-    return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", avg[k]))
+    """The kernel with the largest share of a call's GPU time (`known`: name -> (launches, total
+    ms); a kernel that runs once per call, like the one that opens it, does not win on the length
+    of its single launch).  Kernels within 10 % of the largest share count as tied and a tie goes
+    to the matrix-core kernel, so that the choice does not flip from box to box: single kernels
+    vary by +-5 % between boxes (both candidates are reported either way, one in `roofline` and
+    the others in `other_kernels`)."""
+    total = {k: v[1] for k, v in known.items()}
+    top = max(total.values())
+    tied = [k for k in total if total[k] >= 0.90 * top]
+    return max(tied, key=lambda k: (work[max((q for q in work if k.startswith(q)), key=len)][0] == "mfma", total[k]))
 
 
 def config_leg(st, WL, name, stream, n_timed, use_graph):
