@@ -46,26 +46,26 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # the kernel source it was measured on:
 # (workload, kernel) -> (source file, sha256 of that file at measurement, fetched MiB, written MiB)
 MEASURED_TRAFFIC = {
-    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.77, 8.83),
+    ("720p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 33.76, 8.83),
     ("720p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 13.75, 7.55),
     ("720p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 6.99, 6.13),
     ("720p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 10.45, 3.77),
-    ("720p", "upsample_ce_grad"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 4.73, 4.71),
-    ("720p", "upsample_ce"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 3.09, 1.79),
+    ("720p", "upsample_ce_grad"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 4.73, 4.71),
+    ("720p", "upsample_ce"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 3.09, 1.79),
     ("720p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "d34a21526a2abea318af286f76d053408f182efe714831ab42011bb3a90ac2a3", 13.22, 9.81),
-    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.86, 8.83),
-    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.49, 16.59),
+    ("1080p", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 73.85, 8.83),
+    ("1080p", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 23.48, 16.59),
     ("1080p", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 11.83, 13.48),
     ("1080p", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 19.69, 8.29),
-    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 10.07, 11.14),
-    ("1080p", "upsample_ce"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 6.48, 4.02),
+    ("1080p", "upsample_ce_grad"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 10.07, 11.14),
+    ("1080p", "upsample_ce"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 6.48, 4.02),
     ("1080p", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "d34a21526a2abea318af286f76d053408f182efe714831ab42011bb3a90ac2a3", 27.57, 21.56),
-    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 269.35, 17.72),
-    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 52.00, 60.38),
+    ("batch4", "conv12_wgrad_mfma"): ("k_wgrad_mfma.hip", "3f1113211612b411a441d3e271631c0d813b618f43bc6021537d53e99dc1f2bd", 268.59, 17.78),
+    ("batch4", "conv1_fwd_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 51.96, 60.38),
     ("batch4", "conv2_fwd_logits_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 40.96, 52.83),
-    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 69.13, 30.19),
-    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 30.13, 22.21),
-    ("batch4", "upsample_ce"): ("k_loss.hip", "ef1331f734bcd6da0bb6780c28615f355589739d151c90f81e0dec7a73cf98ae", 23.45, 7.61),
+    ("batch4", "conv2_dgrad_mfma"): ("k_conv_mfma.hip", "4fcaaea68e64f5ed6fbf36846280e453fa4afd196b9118763448bf90be1356f7", 68.98, 30.19),
+    ("batch4", "upsample_ce_grad"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 30.14, 22.21),
+    ("batch4", "upsample_ce"): ("k_loss.hip", "424dc624335d093c3f6a4e8de9fe08d0b1e2d3f6305e078e10999d0c9a77d705", 23.46, 7.61),
     ("batch4", "conv3_bwd_mfma"): ("k_conv3_mfma.hip", "d34a21526a2abea318af286f76d053408f182efe714831ab42011bb3a90ac2a3", 71.54, 80.27),
 }
 

@@ -93,7 +93,7 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
     constexpr int QC = CP / 4;                            // 16-byte chunks of a cell's row of CP classes
     constexpr int NZQ = (CH * CW * QC + NT - 1) / NT;
     float zv[NZ];
-    f32x4 zq[NZQ], bq[NZQ];
+    f32x4 zr[NZQ][4], bq[NZQ];
     if (zs.parts) {
         const size_t PP = (size_t)g.padded_positions();
 #pragma unroll
@@ -103,26 +103,18 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
             const int lc = cell % CW, r = cell / CW;
             const int cx = min(max(cx0 + lc, 0), g.w - 1), cy = min(max(cy0 + r, 0), g.h - 1);
             const size_t mp = ((size_t)img * g.Hp + cy + 1) * g.Wp + cx + 1;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            // one, two or four shares (64, 128, 256 channels), added in ascending order; within a
-            // group of two an absent share re-reads the last with weight 0, so that the loads of a
-            // group are issued together
+            // one, two or four shares (64, 128, 256 channels); within a group of two an absent
+            // share re-reads the last one (it is then not added), so that the loads of a group are
+            // issued together.  Only loaded here: the sums wait until every load of the prologue
+            // is on its way.
             const float* zp = zs.parts + mp * CP + chunk * 4;
             const size_t share = PP * CP;
-            {
-                const f32x4 v0 = *(const f32x4*)zp;
-                const f32x4 v1 = *(const f32x4*)(zp + (zs.n_parts > 1 ? share : 0));
-                const float w1 = zs.n_parts > 1 ? 1.f : 0.f;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(w1, v1[e], __builtin_fmaf(1.f, v0[e], acc[e]));
-            }
+            zr[k][0] = *(const f32x4*)zp;
+            zr[k][1] = *(const f32x4*)(zp + (zs.n_parts > 1 ? share : 0));
             if (zs.n_parts > 2) {
-                const f32x4 v2 = *(const f32x4*)(zp + 2 * share);
-                const f32x4 v3 = *(const f32x4*)(zp + 3 * share);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(1.f, v3[e], __builtin_fmaf(1.f, v2[e], acc[e]));
+                zr[k][2] = *(const f32x4*)(zp + 2 * share);
+                zr[k][3] = *(const f32x4*)(zp + 3 * share);
             }
-            zq[k] = acc;
 #pragma unroll
             for (int e = 0; e < 4; ++e) bq[k][e] = zs.b3[g.head_of(img) * zs.b3_stride + min(chunk * 4 + e, C - 1)];
         }
@@ -140,11 +132,16 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
     float tv[NTT];
     const bool want_tz = T && loss_part;
 #pragma unroll
-    for (int k = 0; k < NTT; ++k) {
-        const int i = tid + k * NT;
-        const int lc = i % LOSS_TX, c = i / LOSS_TX;
-        const int cx = tile_x * LOSS_TX + lc;
-        tv[k] = (want_tz && c < C && cx < g.w) ? T[((size_t)img * C + c) * hw + qy * g.w + cx] : 0.f;
+    for (int k = 0; k < NTT; ++k) tv[k] = 0.f;
+    if (want_tz) {
+        // (clamped addresses: the values of cells and classes that do not exist are dropped below)
+#pragma unroll
+        for (int k = 0; k < NTT; ++k) {
+            const int i = tid + k * NT;
+            const int lc = i % LOSS_TX, c = i / LOSS_TX;
+            const int cx = tile_x * LOSS_TX + lc;
+            tv[k] = T[((size_t)img * C + min(c, C - 1)) * hw + qy * g.w + min(cx, g.w - 1)];
+        }
     }
     for (int i = tid; i < C * C; i += NT) conf_l[i] = 0;
 
@@ -170,15 +167,30 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
     uint8_t* pred_img = pred ? pred + (size_t)img * g.H * g.W : nullptr;
     const int Yb = qy * 8 + half * 4;    // first of this thread's four pixel rows
     // labels of this thread's 4 pixels, fetched before the barrier
-    int lab4[4];
-    float w4[4] = {1.f, 1.f, 1.f, 1.f};      // loss weight of each pixel
+    int lab4[4] = {255, 255, 255, 255};
+    int wraw[4] = {1, 1, 1, 1};              // loss weight of each pixel
     if (lab_img) {
+        const size_t at = (size_t)Yb * g.W + min(X, g.W - 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lab4[i] = col_ok ? lab_img[(size_t)(Yb + i) * g.W + X] : 255;
+        for (int i = 0; i < 4; ++i) lab4[i] = lab_img[at + (size_t)i * g.W];
         if (wmap) {
             const uint8_t* wm = wmap + (size_t)img * g.H * g.W;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) w4[i] = col_ok ? (float)wm[(size_t)(Yb + i) * g.W + X] : 0.f;
+            for (int i = 0; i < 4; ++i) wraw[i] = wm[at + (size_t)i * g.W];
+        }
+    }
+    // ---- every load of the prologue is issued; from here on their values are used
+    float w4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        lab4[i] = col_ok ? lab4[i] : 255;
+        w4[i] = col_ok ? (float)wraw[i] : 0.f;
+    }
+    if (want_tz) {
+#pragma unroll
+        for (int k = 0; k < NTT; ++k) {
+            const int i = tid + k * NT;
+            if (i / LOSS_TX >= C || tile_x * LOSS_TX + i % LOSS_TX >= g.w) tv[k] = 0.f;
         }
     }
     if (zs.parts) {
@@ -187,11 +199,22 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
             const int i = tid + k * NT;
             const int cell = i / QC, chunk = i - cell * QC;
             const int lc = cell % CW, r = cell / CW;
+            // the shares in ascending order (each addition rounded on its own), then the bias
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[e] = __builtin_fmaf(1.f, zr[k][0][e], acc[e]);
+                if (zs.n_parts > 1) acc[e] = __builtin_fmaf(1.f, zr[k][1][e], acc[e]);
+            }
+            if (zs.n_parts > 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(1.f, zr[k][3][e], __builtin_fmaf(1.f, zr[k][2][e], acc[e]));
+            }
             if (i < CH * CW * QC) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int c = chunk * 4 + e;
-                    zt[c][r][lc] = c < C ? zq[k][e] + bq[k][e] : -1e30f;
+                    zt[c][r][lc] = c < C ? acc[e] + bq[k][e] : -1e30f;
                 }
             }
         }
@@ -327,18 +350,37 @@ k_loss(ZSrc zs, const uint8_t* __restrict__ labels, const uint8_t* __restrict__ 
         // part; cell row 0 comes from the upper half, row 2 from the lower half, row 1 from both
         // (upper half first).  Cells outside the grid received nothing (their weight went to the
         // border cells above).
-        for (int i = tid; i < CP * CH * CW; i += NT) {
-            const int lc = i % CW, r = (i / CW) % CH, c = i / (CW * CH);
-            float v = 0.f;
+        // A thread keeps one cell (row r, column lc) and walks over the classes, NT / (CH * CW) of
+        // them per trip of the block: everything that depends on the cell is computed once.
+        constexpr int CELLS = CH * CW, CSTEP = NT / CELLS;
+        const int cg = tid / CELLS, cell = tid - cg * CELLS;
+        const int r = cell / CW, lc = cell - r * CW;
+        const int hfA = r == 2 ? 1 : 0, rrA = r - hfA;        // first contributing (half, row of the half)
+        const bool pairB = r == 1;                             // row 1 also gets the lower half's row 0
+        const bool s0 = lc < LOSS_TX, s1 = lc >= 1 && lc <= LOSS_TX, s2 = lc >= 2;
+        const int i0 = min(lc, LOSS_TX - 1) * 4, i1 = min(max(lc - 1, 0), LOSS_TX - 1) * 4 + 1, i2 = max(lc - 2, 0) * 4 + 2;
+        if (cg < CSTEP) {
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const int rr = r - hf;
-                if (rr < 0 || rr > 1 || c >= CA) continue;    // (a padded class: nothing was handed over)
-                if (lc < LOSS_TX) v += contrib[hf][c][rr][lc][0];
-                if (lc >= 1 && lc - 1 < LOSS_TX) v += contrib[hf][c][rr][lc - 1][1];
-                if (lc >= 2) v += contrib[hf][c][rr][lc - 2][2];
+            for (int k = 0; k < (CP + CSTEP - 1) / CSTEP; ++k) {
+                const int c = cg + k * CSTEP;
+                if (c >= CP) break;
+                float v = 0.f;
+                if (c < CA) {                                  // (a padded class: nothing was handed over)
+                    const float* A = &contrib[hfA][c][rrA][0][0];
+                    const float a0 = A[i0], a1 = A[i1], a2 = A[i2];
+                    v += s0 ? a0 : 0.f;
+                    v += s1 ? a1 : 0.f;
+                    v += s2 ? a2 : 0.f;
+                    if (pairB) {
+                        const float* B = &contrib[1][c][0][0][0];
+                        const float b0 = B[i0], b1 = B[i1], b2 = B[i2];
+                        v += s0 ? b0 : 0.f;
+                        v += s1 ? b1 : 0.f;
+                        v += s2 ? b2 : 0.f;
+                    }
+                }
+                slot[c * CELLS + cell] = v;
             }
-            slot[i] = v;
         }
     }
 }
